@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark: Moonwalk gradient steps per second on one MI355X.
+
+One "step" is one full moonwalk_grad call (Phase I forward, loss, Phase II reverse, Phase III
+forward vijp sweep with weight and bias gradients) on one batch of synthetic input that is
+already resident in HBM. Default workload: the deep square MLP (depth 64, width 1024, batch
+256, leaky slope 0.1, re-seed interval 4).
+
+Prints ONE JSON line. `value` is gradient steps/s of moonwalk_grad; the same line carries
+TFLOP/s (10 B sum d_in d_out flop per step), the library's own backprop_grad timed the same
+way, itemised and peak device bytes of both, the roofline of the dominant kernel measured live
+with HIP events, and the fp64 CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="deep_square")
+    ap.add_argument("--depth", type=int, default=None, help="truncate the configuration to this many layers")
+    ap.add_argument("--reseed", type=int, default=None, help="override the re-seed interval K")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backprop", action="store_true")
+    ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return start.elapsed_time(stop) / steps, wall * 1e3 / steps   # ms/step by events, by wall clock
+
+
+def cpu_baseline(wl, flops):
+    """The fp64 oracle's Moonwalk step as it stands, on the host cores (right inverses excluded,
+    as for the GPU). Sample: whole steps of the same workload, at least one, about 10-30 s."""
+    from oracle import moonwalk_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ps = [O.right_inverse(W) for W in wl.W]
+    n, elapsed = 0, 0.0
+    while n < 1 or (elapsed < 10.0 and n < 50):
+        t0 = time.perf_counter()
+        O.moonwalk(wl.W, wl.b, wl.alphas, wl.x, wl.t, reseed_interval=wl.reseed_interval,
+                   loss_scale=wl.loss_scale, Ps=Ps)
+        elapsed += time.perf_counter() - t0
+        n += 1
+    per = elapsed / n
+    return {"value": 1.0 / per, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} full fp64 oracle Moonwalk step(s) of the same workload (numpy, right inverses precomputed)",
+            "gflops": flops / per / 1e9}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2402_14212_amd as mw
+    from workloads import make_config, moonwalk_flops, backprop_flops, CONFIGS
+
+    wl = make_config(args.config, depth=args.depth)
+    if args.reseed is not None:
+        wl.reseed_interval = args.reseed
+    B, widths, L = wl.batch, wl.widths, wl.depth
+    flops_mw, flops_bp = moonwalk_flops(widths, B), backprop_flops(widths, B)
+
+    torch.cuda.set_device(0)
+    torch.cuda.reset_peak_memory_stats()
+    base_bytes = torch.cuda.memory_allocated()
+
+    # --- Moonwalk handle only (so that its peak memory is its own)
+    t0 = time.perf_counter()
+    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+    grads = net.new_grads()
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    ms_mw, wall_mw = time_steps(lambda: net.moonwalk_grad(net.x, net.t, grads, loss), args.steps, args.warmup)
+    st = net.memory_stats()
+    mw_peak_lib = st["bytes_live"]
+    mw_peak_torch = torch.cuda.max_memory_allocated() - base_bytes
+
+    # --- roofline of the dominant kernel: the Phase-III layer kernel (two of the five GEMMs)
+    net.profile_enable(True)
+    prof_steps = max(1, min(args.steps, 20))
+    for _ in range(prof_steps):
+        net.moonwalk_grad(net.x, net.t, grads, loss)
+    prof = net.profile_read()
+    net.profile_enable(False)
+    n_v, ms_v = prof["vijp"]
+    flop_per_launch = 4.0 * B * sum(a * b for a, b in zip(widths[:-1], widths[1:])) / L   # average layer
+    avg_ms = ms_v / max(n_v, 1)
+    achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "vijp_dual_kernel (Phase-III recompute + vijp + epilogue)",
+                "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": avg_ms, "launches": n_v,
+                "flop_per_launch": flop_per_launch}
+    per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else None)} for k, (n, ms) in prof.items()}
+    class_flops = {"fwd": 2.0, "rev": 2.0, "vijp": 4.0, "dw": 2.0}
+    for k, c in class_flops.items():
+        n, ms = prof[k]
+        if n:
+            per_class[k]["tflops"] = c * B * sum(a * b for a, b in zip(widths[:-1], widths[1:])) / L / (ms / n * 1e-3) / 1e12
+    net.close()
+    del net
+
+    # --- the library's own backprop, timed the same way on a handle of its own
+    bp = {}
+    if not args.no_backprop:
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+        base2 = torch.cuda.memory_allocated()
+        net_bp = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_BACKPROP)
+        ms_bp, _ = time_steps(lambda: net_bp.backprop_grad(net_bp.x, net_bp.t, grads, loss), args.steps, args.warmup)
+        st_bp = net_bp.memory_stats()
+        bp = {"steps_per_s": 1e3 / ms_bp, "ms_per_step": ms_bp, "tflops": flops_bp / (ms_bp * 1e-3) / 1e12,
+              "bytes_residual": st_bp["bytes_bp_activations"] + st_bp["bytes_bp_scratch"],
+              "bytes_library": st_bp["bytes_live"],
+              "bytes_peak_torch": torch.cuda.max_memory_allocated() - base2}
+        net_bp.close()
+
+    out = {
+        "metric": "gradient steps/s (mixed-mode Moonwalk, one full moonwalk_grad per step)",
+        "value": 1e3 / ms_mw, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_mw, "ms_per_step_wall": wall_mw, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: depth {L}, widths {widths[0]}->{widths[-1]}, batch {B}, "
+                               f"alpha {wl.alphas[0]}, reseed K={wl.reseed_interval}, loss_scale {wl.loss_scale:g}, "
+                               f"{'unfused' if args.unfused else 'fused'} kernels"},
+        "tflops": flops_mw / (ms_mw * 1e-3) / 1e12,
+        "flop_per_step": flops_mw,
+        "mfma_frac_whole_step": flops_mw / (ms_mw * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS,
+        "roofline": roofline,
+        "per_kernel_class": per_class,
+        "setup_s": setup_s,
+        "memory": {
+            "moonwalk": {"bytes_P": st["bytes_P"], "bytes_masks": st["bytes_masks"],
+                         "bytes_fragments": st["bytes_fragments"], "bytes_frag_index": st["bytes_frag_index"],
+                         "bytes_checkpoints": st["bytes_checkpoints"], "bytes_scratch": st["bytes_mw_scratch"],
+                         "bytes_residual": st["bytes_masks"] + st["bytes_fragments"] + st["bytes_frag_index"]
+                                           + st["bytes_checkpoints"] + st["bytes_mw_scratch"],
+                         "bytes_library": mw_peak_lib, "bytes_setup_peak": st["bytes_setup_peak"],
+                         "bytes_peak_torch": mw_peak_torch},
+            "backprop": {k: v for k, v in bp.items() if k.startswith("bytes")},
+        },
+        "backprop": {k: v for k, v in bp.items() if not k.startswith("bytes")},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, flops_mw)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,235 @@
+/*
+ * libmoonwalk — mixed-mode Moonwalk gradients for dense submersive networks on MI355X (gfx950).
+ *
+ * C ABI. Every pointer is a DEVICE pointer unless its comment says "host". The library
+ * never takes ownership of a caller's buffer and never frees one. All calls enqueue work
+ * on the HIP stream they are given (a hipStream_t passed as void*, NULL = default stream)
+ * and return without synchronising, except where stated (setup, refresh, status, fetch).
+ *
+ * Network (row-vector convention, row-major storage):
+ *     z_i = x_{i-1} W_i^T + b_i ,  m_i = (z_i > 0) ,  x_i = m_i ? z_i : alpha_i z_i ,  i = 1..L
+ *     J   = 0.5 ||x_L - target||_F^2 / B
+ * x_i is [B][d_i], W_i is [d_i][d_{i-1}], b_i is [d_i]. Each layer must be a submersion
+ * (Definition "Submersion" of the Moonwalk paper): d_i <= d_{i-1} and W_i of full row rank.
+ *
+ * Return value of every int function: 0 on success, a negative MW_ERR_* code otherwise.
+ * No exception crosses this boundary and nothing aborts.
+ */
+#ifndef MOONWALK_H
+#define MOONWALK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MW_OK                    0
+#define MW_ERR_INVALID_ARG      (-1)  /* NULL/zero/negative argument, alpha outside [0,1], bad enum   */
+#define MW_ERR_NOT_SUBMERSIVE   (-2)  /* d_out > d_in, or W W^T not positive definite (Cholesky pivot) */
+#define MW_ERR_OOM              (-3)  /* the allocator callback returned NULL                          */
+#define MW_ERR_FRAG_OVERFLOW    (-4)  /* fragment store smaller than the number of erased cotangents   */
+#define MW_ERR_HIP              (-5)  /* a HIP call failed; text available from moonwalk_strerror      */
+#define MW_ERR_SIGN_MISMATCH    (-6)  /* phase-III recomputed signs differ from the phase-I masks      */
+#define MW_ERR_NOT_PLANNED      (-7)  /* entry point called on a handle planned without it             */
+
+typedef struct mw_handle mw_handle_t;   /* opaque; owned by the library */
+
+/* One dense layer followed by a leaky ReLU (alpha in (0,1]) or a ReLU (alpha == 0). */
+typedef struct {
+  int32_t d_in, d_out;   /* 1 <= d_out <= d_in                                                    */
+  const float* W;        /* device, row-major [d_out][d_in]; caller owns; must outlive the handle */
+  const float* b;        /* device [d_out]; NULL means zero bias                                  */
+  float alpha;           /* 0 < alpha <= 1: leaky ReLU (submersive); 0: ReLU + fragment store     */
+} mw_layer_t;
+
+#define MW_PLAN_MOONWALK 1   /* build P_i and the Moonwalk workspace                 */
+#define MW_PLAN_BACKPROP 2   /* build the stored-activation workspace for backprop   */
+
+typedef struct {
+  int32_t batch;            /* B, fixed for the handle's lifetime                                         */
+  int32_t reseed_interval;  /* K: keep the cotangent of every K-th layer boundary in the reverse pass and
+                               restart the forward sweep from it (plain cotangent checkpointing, Overview
+                               section). 0 = never: the method exactly as printed.                        */
+  float   loss_scale;       /* s > 0, a power of two: the output cotangent is multiplied by s and the
+                               gradients are divided by s again (exact); guards fp32 under/overflow.      */
+  int32_t plan;             /* MW_PLAN_* bits; 0 means MW_PLAN_MOONWALK | MW_PLAN_BACKPROP                 */
+  int32_t fuse;             /* 1: bias/activation/mask/cotangent steps fused into the GEMM kernels;
+                               0: plain GEMMs plus stand-alone elementwise kernels (same results, bit for bit) */
+  double  frag_capacity_factor; /* fragment-store capacity as a fraction of B * sum(d_out over ReLU
+                               layers); 1.0 = worst case; <= 0 means 1.0                                   */
+  /* Every byte of device memory the library owns comes from dev_alloc and goes back through
+     dev_free (both host functions). NULL, NULL = hipMalloc / hipFree. */
+  void* (*dev_alloc)(size_t bytes, void* ctx);
+  void  (*dev_free)(void* ptr, void* ctx);
+  void*   alloc_ctx;
+} mw_config_t;
+
+/* Itemised device bytes held by a handle (closed forms are in the design notes). */
+typedef struct {
+  uint64_t bytes_P;             /* right inverses, = bytes of all W                                   */
+  uint64_t bytes_masks;         /* 1-bit sign masks, 8 * ceil(B d_i / 64) per layer                   */
+  uint64_t bytes_fragments;     /* fragment store capacity (ReLU layers)                              */
+  uint64_t bytes_frag_index;    /* per-word erased offsets, layer bases                               */
+  uint64_t bytes_checkpoints;   /* re-seed cotangents                                                 */
+  uint64_t bytes_mw_scratch;    /* ping-pong activations / cotangents, ct_z, loss partials, flags     */
+  uint64_t bytes_bp_activations;/* stored x_1..x_L of the backprop path                               */
+  uint64_t bytes_bp_scratch;    /* backprop cotangent ping-pong, loss partials                        */
+  uint64_t bytes_live;          /* currently held through dev_alloc                                   */
+  uint64_t bytes_peak;          /* high-water mark through dev_alloc, setup scratch included          */
+  uint64_t bytes_setup_peak;    /* high-water mark during setup / refresh alone                       */
+  uint64_t frag_used;           /* erased cotangents stored by the last moonwalk_grad                 */
+  uint64_t sign_mismatches;     /* phase-III signs that differed from the stored masks (must be 0)    */
+  int32_t  frag_overflow;       /* 1 if the last moonwalk_grad overflowed the fragment store          */
+  int32_t  reserved;
+} mw_memstats_t;
+
+/*
+ * moonwalk_setup — create a handle for a fixed network and batch size.
+ * Validates the submersion condition (d_out <= d_in; Cholesky of W W^T must succeed), computes
+ * the per-layer right inverse P_i = (W_i W_i^T)^{-1} W_i on the device (the (.)^+ of the vijp
+ * definition, Notation section; P_i^T is the Moore-Penrose right inverse of the layer Jacobian
+ * W_i), and allocates the workspaces named in cfg->plan.
+ * layers: host array of n_layers descriptors (copied). Synchronises the stream before returning.
+ * On failure *out is NULL and everything allocated so far has been freed.
+ */
+int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers,
+                   const mw_config_t* cfg, void* hip_stream);
+
+/* Recompute every P_i after the caller changed W in place (Algorithm 1, "Apply g_i").
+   Synchronises. Same errors as moonwalk_setup. */
+int moonwalk_refresh(mw_handle_t* h, void* hip_stream);
+
+/*
+ * moonwalk_grad — one gradient step of mixed-mode Moonwalk (Overview section, Phases I-III;
+ * Algorithm 1 with h_0 from the reverse pass of the Mixed-Mode section).
+ *   Phase I   forward; keeps only the packed sign masks m_i (Residual Impact section).
+ *   Phase II  reverse for the input cotangent h_0 alone; for ReLU layers the erased entries of
+ *             the output cotangent go to the fragment store (Fragmental Gradient Checkpointing).
+ *   Phase III forward sweep: recompute z_i, ct_z = h_{i-1} P_i^T (vijp, Eq. h_i), undo the
+ *             activation slope or restore fragments, dW_i = ct_z^T x_{i-1}, db_i = sum_b ct_z
+ *             (vjp w.r.t. parameters, Eq. g_i).
+ * x [B][d_0], target [B][d_L]: read only. grads_out: flat buffer laid out as reported by
+ * moonwalk_grad_layout, overwritten (not accumulated). loss_out: one float, may be NULL.
+ * Asynchronous. Results are bit-identical run to run.
+ */
+int moonwalk_grad(mw_handle_t* h, const float* x, const float* target,
+                  float* grads_out, float* loss_out, void* hip_stream);
+
+/* backprop_grad — the same gradient by ordinary reverse mode with every activation stored
+   (the comparison method of the paper, Fig. 1 right column). Same arguments and layout. */
+int backprop_grad(mw_handle_t* h, const float* x, const float* target,
+                  float* grads_out, float* loss_out, void* hip_stream);
+
+/* Layout of grads_out: layer i (0-based) has dW_i, row-major [d_out][d_in], at float offset
+   dW_off[i] and db_i at db_off[i]. total_floats, dW_off, db_off: host pointers, any may be NULL;
+   the arrays have n_layers entries. */
+int moonwalk_grad_layout(const mw_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
+
+/* Itemised memory and the sticky device-side conditions of the last step. out: host.
+   Synchronises the device (reads two counters back). Returns MW_ERR_FRAG_OVERFLOW or
+   MW_ERR_SIGN_MISMATCH if the last step raised one, after filling *out. */
+int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out);
+
+/* What moonwalk_debug_fetch can copy to the host (element type, count for layer i):          */
+#define MW_FETCH_MASK          1  /* uint64[ceil(B d_i / 64)]  packed signs, bit e%64 of word e/64 */
+#define MW_FETCH_FRAG          2  /* float[n0_i]               erased cotangents, ascending index  */
+#define MW_FETCH_FRAG_OFFSETS  3  /* uint32[n_words + 1]       erased count before each word; last = n0_i */
+#define MW_FETCH_FRAG_BASE     4  /* uint64[1]                 start of layer i in the store        */
+#define MW_FETCH_H0            5  /* float[B d_0]              input cotangent (scaled by loss_scale); layer ignored */
+#define MW_FETCH_P             6  /* float[d_out d_in]         right inverse                         */
+#define MW_FETCH_CHECKPOINT    7  /* float[B d_i]              kept cotangent at the OUTPUT of layer i (error if not kept) */
+/* Synchronous copy of library state after the last step to host_dst (host, cap bytes).
+   layer is 0-based. *n_bytes (host, may be NULL) receives the size. host_dst == NULL with
+   cap == 0 is a size query (returns MW_OK); if cap is too small nothing is copied and
+   MW_ERR_INVALID_ARG is returned with *n_bytes set. */
+int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap,
+                         size_t* n_bytes);
+
+/* Measurement aid: per-kernel-class timing of the gradient drivers with HIP events on the
+   caller's stream. While enabled, every kernel launch of moonwalk_grad / backprop_grad is
+   bracketed by two events (this adds a little launch overhead: do not time whole steps with it
+   on). Classes: the Phase-I forward GEMM, the Phase-II reverse GEMM, the Phase-III layer kernel
+   (recompute + vijp + epilogue), the weight-gradient GEMM, and every elementwise/integer kernel. */
+#define MW_KCLASS_FWD   0
+#define MW_KCLASS_REV   1
+#define MW_KCLASS_VIJP  2
+#define MW_KCLASS_DW    3
+#define MW_KCLASS_EW    4
+#define MW_KCLASS_COUNT 5
+/* on != 0 starts a fresh measurement, 0 stops it. Synchronises the device. */
+int moonwalk_profile_enable(mw_handle_t* h, int32_t on);
+/* Number of launches of the class since enable and the sum of their event-to-event times.
+   launches, total_ms: host, may be NULL. Synchronises the device. */
+int moonwalk_profile_read(mw_handle_t* h, int32_t kclass, uint64_t* launches, double* total_ms);
+
+/* Frees every device buffer through dev_free. NULL is allowed. Synchronises the device first. */
+void moonwalk_destroy(mw_handle_t* h);
+
+/* Static text for a code; for MW_ERR_HIP the text of the last HIP error seen by this thread. */
+const char* moonwalk_strerror(int code);
+
+/* ------------------------------------------------------------------------------------------
+ * Kernel-level entry points: the individual device steps, for unit parity tests and roofline
+ * measurements. All asynchronous on hip_stream; all pointers device pointers.
+ * ---------------------------------------------------------------------------------------- */
+
+#define MW_GEMM_NT 0  /* C[M][N] = alpha * A[M][K] * B[N][K]^T + beta * C   (forward, vijp)      */
+#define MW_GEMM_NN 1  /* C[M][N] = alpha * A[M][K] * B[K][N]   + beta * C   (reverse vjp)        */
+#define MW_GEMM_TN 2  /* C[M][N] = alpha * A[K][M]^T * B[K][N] + beta * C   (weight gradient)    */
+#define MW_TILE_AUTO 0
+#define MW_TILE_128  1  /* 128x128 workgroup tile                                   */
+#define MW_TILE_64   2  /* 64x64 workgroup tile                                     */
+#define MW_TILE_32K4 3  /* 32x32 workgroup tile, K split over the four wavefronts   */
+/* fp32 MFMA GEMM with LDS-staged tiles; lda/ldb/ldc are row strides in floats. */
+int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha,
+                const float* A, int32_t lda, const float* B, int32_t ldb, float beta,
+                float* C, int32_t ldc, void* hip_stream);
+
+/* Phase-I epilogue (mask pack + activation): x[e] = m ? z : alpha z with z = zin[e] + bias[e % d],
+   mask bit e = (z > 0). n = rows * d elements; mask has ceil(n/64) words. bias may be NULL.
+   zin and x may alias. */
+int mw_bias_act_mask(const float* zin, const float* bias, int64_t rows, int32_t d, float alpha,
+                     float* x, uint64_t* mask, void* hip_stream);
+
+/* Phase-II scaling: ct_z[e] = h[e] * (m[e] ? 1 : alpha). h and ct_z may alias. */
+int mw_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
+                 void* hip_stream);
+
+/* Erased-element index of a mask: offsets[w] = number of zero bits among elements < 64 w,
+   offsets[n_words] = n0 (uint32[n_words + 1]). Deterministic integer scan. */
+int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, void* hip_stream);
+
+/* Stream compaction of the erased cotangents: frag[offsets[e/64] + rank of e within its word] =
+   h[e] for every e with mask bit 0, ascending e. capacity in floats; on overflow nothing past
+   capacity is written and *overflow_flag (device int32, may be NULL) is set to 1. */
+int mw_frag_compact(const float* h, const uint64_t* mask, const uint32_t* offsets, int64_t n,
+                    float* frag, uint64_t capacity, int32_t* overflow_flag, void* hip_stream);
+
+/* Phase-III epilogue. z, ct_z: [rows][d] pre-activation (bias already added) and affine-vijp
+   result. Writes x = f(z) and the layer-output cotangent h_y.
+   alpha > 0: m = (z > 0), h_y = m ? ct_z : ct_z / alpha (as a multiplication by fp32 1/alpha).
+   alpha == 0: m = stored mask; ct_z is zeroed in place where m == 0 and h_y = m ? ct_z :
+   frag[offsets[e/64] + rank]. mask/offsets/frag are required only for alpha == 0. */
+int mw_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int32_t d, float alpha,
+                     const uint64_t* mask, const uint32_t* offsets, const float* frag,
+                     float* x, float* h_y, void* hip_stream);
+
+/* Column sums: out[j] = scale * sum_r a[r][j], fixed summation order. */
+int mw_colsum(const float* a, int64_t rows, int32_t d, float scale, float* out, void* hip_stream);
+
+/* Loss step: h_L = scale (x_L - t) / rows and *loss = 0.5 ||x_L - t||_F^2 / rows (fixed-order
+   reduction; partial sums in double). loss may be NULL. scratch: device doubles,
+   at least mw_loss_scratch_doubles() of them. */
+int mw_loss_grad(const float* xL, const float* t, int64_t rows, int32_t d, float scale,
+                 float* hL, float* loss, double* scratch, void* hip_stream);
+size_t mw_loss_scratch_doubles(void);
+
+/* Plain device-to-device copy kernel of n floats (bandwidth yardstick for the profiles). */
+int mw_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOONWALK_H */

@@ -1,0 +1,404 @@
+"""ctypes binding of include/moonwalk.h. Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
+TILE_AUTO, TILE_128, TILE_64, TILE_32K4 = 0, 1, 2, 3
+PLAN_MOONWALK, PLAN_BACKPROP = 1, 2
+FETCH_MASK, FETCH_FRAG, FETCH_FRAG_OFFSETS, FETCH_FRAG_BASE, FETCH_H0, FETCH_P, FETCH_CHECKPOINT = range(1, 8)
+
+EXPORTED_SYMBOLS = [
+    "moonwalk_setup", "moonwalk_refresh", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
+    "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
+    "moonwalk_profile_enable", "moonwalk_profile_read",
+    "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
+    "mw_vijp_epilogue", "mw_colsum", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
+]
+
+
+class MoonwalkError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libmoonwalk error {code}: {text}")
+        self.code = code
+
+
+ERR_INVALID_ARG, ERR_NOT_SUBMERSIVE, ERR_OOM, ERR_FRAG_OVERFLOW, ERR_HIP, ERR_SIGN_MISMATCH, ERR_NOT_PLANNED = \
+    -1, -2, -3, -4, -5, -6, -7
+
+
+class _Layer(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("W", C.c_void_p), ("b", C.c_void_p),
+                ("alpha", C.c_float)]
+
+
+_ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+_FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class _Config(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("reseed_interval", C.c_int32), ("loss_scale", C.c_float),
+                ("plan", C.c_int32), ("fuse", C.c_int32), ("frag_capacity_factor", C.c_double),
+                ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p)]
+
+
+class _MemStats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "bytes_P", "bytes_masks", "bytes_fragments", "bytes_frag_index", "bytes_checkpoints",
+        "bytes_mw_scratch", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak",
+        "bytes_setup_peak", "frag_used", "sign_mismatches")] + [("frag_overflow", C.c_int32),
+                                                                 ("reserved", C.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoonwalk.so")
+
+
+def load_library() -> C.CDLL:
+    """Load libmoonwalk.so (built in-tree by __graft_entry__.build()). Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: run `python __graft_entry__.py` to build the HIP library")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    lib.moonwalk_setup.argtypes = [C.POINTER(vp), C.POINTER(_Layer), i32, C.POINTER(_Config), vp]
+    lib.moonwalk_refresh.argtypes = [vp, vp]
+    lib.moonwalk_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.backprop_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.moonwalk_grad_layout.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+    lib.moonwalk_memory_stats.argtypes = [vp, C.POINTER(_MemStats)]
+    lib.moonwalk_debug_fetch.argtypes = [vp, i32, i32, vp, sz, C.POINTER(sz)]
+    lib.moonwalk_profile_enable.argtypes = [vp, i32]
+    lib.moonwalk_profile_read.argtypes = [vp, i32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+    lib.moonwalk_destroy.argtypes = [vp]
+    lib.moonwalk_destroy.restype = None
+    lib.moonwalk_strerror.argtypes = [C.c_int]
+    lib.moonwalk_strerror.restype = C.c_char_p
+    lib.mw_gemm_f32.argtypes = [i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, f32, vp, i32, vp]
+    lib.mw_bias_act_mask.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
+    lib.mw_rev_scale.argtypes = [vp, vp, i64, f32, vp, vp]
+    lib.mw_frag_offsets.argtypes = [vp, i64, vp, vp]
+    lib.mw_frag_compact.argtypes = [vp, vp, vp, i64, vp, C.c_uint64, vp, vp]
+    lib.mw_vijp_epilogue.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp, vp, vp]
+    lib.mw_colsum.argtypes = [vp, i64, i32, f32, vp, vp]
+    lib.mw_loss_grad.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp]
+    lib.mw_loss_scratch_doubles.argtypes = []
+    lib.mw_loss_scratch_doubles.restype = sz
+    lib.mw_copy_f32.argtypes = [vp, vp, i64, vp]
+    _lib = lib
+    return lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise MoonwalkError(code, load_library().moonwalk_strerror(code).decode())
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("libmoonwalk needs a GPU: there is no CPU path")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return t.data_ptr()
+
+
+def _f32(t: torch.Tensor) -> torch.Tensor:
+    if t.dtype != torch.float32:
+        raise ValueError("expected float32")
+    return t
+
+
+@dataclass
+class GradResult:
+    flat: torch.Tensor                # the grads_out buffer
+    dW: List[torch.Tensor]            # views into flat, [d_out][d_in]
+    db: List[torch.Tensor]            # views into flat, [d_out]
+    loss: torch.Tensor                # 1-element device tensor
+
+
+class MoonwalkNet:
+    """A fixed dense network and batch size bound to a libmoonwalk handle."""
+
+    def __init__(self, Ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
+                 batch: int, reseed_interval: int = 0, loss_scale: float = 1.0,
+                 plan: int = PLAN_MOONWALK | PLAN_BACKPROP, fuse: bool = True,
+                 frag_capacity_factor: float = 1.0):
+        _require_gpu()
+        self._lib = load_library()
+        self._handle = C.c_void_p()
+        self.Ws = [_f32(w) for w in Ws]
+        self.bs = list(bs)
+        self.alphas = [float(a) for a in alphas]
+        self.batch = int(batch)
+        self.device = self.Ws[0].device
+        self.x = None
+        self.t = None
+        self._held = {}          # device buffers handed to the library, keyed by address
+        self.alloc_peak = 0
+        self._alloc_live = 0
+
+        def _alloc(nbytes, _ctx):
+            try:
+                buf = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+            except Exception:
+                return None
+            self._held[buf.data_ptr()] = buf
+            self._alloc_live += int(nbytes)
+            self.alloc_peak = max(self.alloc_peak, self._alloc_live)
+            return buf.data_ptr()
+
+        def _free(ptr, _ctx):
+            buf = self._held.pop(ptr, None)
+            if buf is not None:
+                self._alloc_live -= buf.numel()
+
+        self._alloc_cb, self._free_cb = _ALLOC_FN(_alloc), _FREE_FN(_free)
+        n = len(self.Ws)
+        layers = (_Layer * n)()
+        for i, (w, b, a) in enumerate(zip(self.Ws, self.bs, self.alphas)):
+            if w.dim() != 2:
+                raise ValueError("W must be [d_out][d_in]")
+            layers[i] = _Layer(w.shape[1], w.shape[0], _ptr(w), _ptr(_f32(b)) if b is not None else None, a)
+        cfg = _Config(self.batch, int(reseed_interval), float(loss_scale), int(plan), 1 if fuse else 0,
+                      float(frag_capacity_factor), self._alloc_cb, self._free_cb, None)
+        with torch.cuda.device(self.device):
+            _check(self._lib.moonwalk_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
+        total = C.c_size_t()
+        dW_off, db_off = (C.c_size_t * n)(), (C.c_size_t * n)()
+        _check(self._lib.moonwalk_grad_layout(self._handle, C.byref(total), dW_off, db_off))
+        self.total_floats = int(total.value)
+        self.dW_off, self.db_off = list(dW_off), list(db_off)
+
+    @classmethod
+    def from_workload(cls, wl, device="cuda:0", **kw) -> "MoonwalkNet":
+        dev = torch.device(device)
+        Ws = [torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(dev) for w in wl.W]
+        bs = [torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(dev) for b in wl.b]
+        kw.setdefault("reseed_interval", wl.reseed_interval)
+        kw.setdefault("loss_scale", wl.loss_scale)
+        net = cls(Ws, bs, wl.alphas, wl.batch, **kw)
+        net.x = torch.from_numpy(np.ascontiguousarray(wl.x, dtype=np.float32)).to(dev)
+        net.t = torch.from_numpy(np.ascontiguousarray(wl.t, dtype=np.float32)).to(dev)
+        return net
+
+    # ------------------------------------------------------------------ gradient steps
+    def new_grads(self) -> torch.Tensor:
+        return torch.empty(self.total_floats, dtype=torch.float32, device=self.device)
+
+    def _views(self, flat: torch.Tensor, loss: torch.Tensor) -> GradResult:
+        dW, db = [], []
+        for i, w in enumerate(self.Ws):
+            d_out, d_in = w.shape
+            dW.append(flat[self.dW_off[i]: self.dW_off[i] + d_out * d_in].view(d_out, d_in))
+            db.append(flat[self.db_off[i]: self.db_off[i] + d_out])
+        return GradResult(flat, dW, db, loss)
+
+    def _grad(self, fn, x, target, grads_out, loss_out) -> GradResult:
+        if self._handle is None:
+            raise RuntimeError("handle is closed")
+        d0, dL = self.Ws[0].shape[1], self.Ws[-1].shape[0]
+        if tuple(x.shape) != (self.batch, d0) or tuple(target.shape) != (self.batch, dL):
+            raise ValueError("x must be [B][d_0] and target [B][d_L]")
+        flat = grads_out if grads_out is not None else self.new_grads()
+        if flat.numel() != self.total_floats:
+            raise ValueError("grads_out has the wrong size")
+        loss = loss_out if loss_out is not None else torch.empty(1, dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(fn(self._handle, _ptr(_f32(x)), _ptr(_f32(target)), _ptr(_f32(flat)), _ptr(loss), _stream()))
+        return self._views(flat, loss)
+
+    def moonwalk_grad(self, x, target, grads_out=None, loss_out=None) -> GradResult:
+        return self._grad(self._lib.moonwalk_grad, x, target, grads_out, loss_out)
+
+    def backprop_grad(self, x, target, grads_out=None, loss_out=None) -> GradResult:
+        return self._grad(self._lib.backprop_grad, x, target, grads_out, loss_out)
+
+    def refresh(self):
+        with torch.cuda.device(self.device):
+            _check(self._lib.moonwalk_refresh(self._handle, _stream()))
+
+    # ------------------------------------------------------------------ introspection
+    def memory_stats(self, check: bool = True) -> dict:
+        st = _MemStats()
+        code = self._lib.moonwalk_memory_stats(self._handle, C.byref(st))
+        out = {name: int(getattr(st, name)) for name, _ in _MemStats._fields_ if name != "reserved"}
+        out["status"] = code
+        if check:
+            _check(code)
+        return out
+
+    KCLASSES = ("fwd", "rev", "vijp", "dw", "ew")
+
+    def profile_enable(self, on: bool = True):
+        _check(self._lib.moonwalk_profile_enable(self._handle, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        """{class: (launches, total_ms)} since profile_enable(True)."""
+        out = {}
+        for k, name in enumerate(self.KCLASSES):
+            n, ms = C.c_uint64(), C.c_double()
+            _check(self._lib.moonwalk_profile_read(self._handle, k, C.byref(n), C.byref(ms)))
+            out[name] = (int(n.value), float(ms.value))
+        return out
+
+    def _fetch(self, layer: int, what: int, dtype) -> np.ndarray:
+        n = C.c_size_t()
+        _check(self._lib.moonwalk_debug_fetch(self._handle, layer, what, None, 0, C.byref(n)))
+        out = np.empty(n.value // np.dtype(dtype).itemsize, dtype=dtype)
+        if n.value:
+            _check(self._lib.moonwalk_debug_fetch(self._handle, layer, what, out.ctypes.data_as(C.c_void_p),
+                                                  out.nbytes, C.byref(n)))
+        return out
+
+    def fetch_mask(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_MASK, np.uint64)
+
+    def fetch_fragments(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_FRAG, np.float32)
+
+    def fetch_frag_offsets(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_FRAG_OFFSETS, np.uint32)
+
+    def fetch_frag_base(self, layer: int) -> int:
+        return int(self._fetch(layer, FETCH_FRAG_BASE, np.uint64)[0])
+
+    def fetch_h0(self) -> np.ndarray:
+        return self._fetch(0, FETCH_H0, np.float32).reshape(self.batch, -1)
+
+    def fetch_P(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_P, np.float32).reshape(self.Ws[layer].shape)
+
+    def fetch_checkpoint(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_CHECKPOINT, np.float32).reshape(self.batch, -1)
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle.value:
+            self._lib.moonwalk_destroy(self._handle)
+        self._handle = None
+        self._held.clear()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---------------------------------------------------------------------- kernel-level entries
+
+def gemm_f32(op: int, A: torch.Tensor, B: torch.Tensor, C_out: Optional[torch.Tensor] = None,
+             alpha: float = 1.0, beta: float = 0.0, tile: int = TILE_AUTO) -> torch.Tensor:
+    """op NT: A[M][K], B[N][K]; NN: A[M][K], B[K][N]; TN: A[K][M], B[K][N]. Returns C[M][N]."""
+    _require_gpu()
+    lib = load_library()
+    if op == GEMM_NT:
+        (M, K), (N, K2) = A.shape, B.shape
+    elif op == GEMM_NN:
+        (M, K), (K2, N) = A.shape, B.shape
+    elif op == GEMM_TN:
+        (K, M), (K2, N) = A.shape, B.shape
+    else:
+        raise ValueError("bad op")
+    if K != K2:
+        raise ValueError("inner dimensions differ")
+    if C_out is None:
+        C_out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if tuple(C_out.shape) != (M, N):
+        raise ValueError("C has the wrong shape")
+    _check(lib.mw_gemm_f32(op, tile, M, N, K, alpha, _ptr(_f32(A)), A.shape[1], _ptr(_f32(B)), B.shape[1], beta,
+                           _ptr(_f32(C_out)), N, _stream()))
+    return C_out
+
+
+def _n_words(n: int) -> int:
+    return (n + 63) // 64
+
+
+def bias_act_mask(z: torch.Tensor, bias: Optional[torch.Tensor], alpha: float):
+    _require_gpu()
+    rows, d = z.shape
+    x = torch.empty_like(z)
+    mask = torch.zeros(max(_n_words(rows * d), 1), dtype=torch.int64, device=z.device)
+    _check(load_library().mw_bias_act_mask(_ptr(_f32(z)), _ptr(bias), rows, d, alpha, _ptr(x), _ptr(mask), _stream()))
+    return x, mask
+
+
+def rev_scale(h: torch.Tensor, mask: torch.Tensor, alpha: float) -> torch.Tensor:
+    _require_gpu()
+    out = torch.empty_like(h)
+    _check(load_library().mw_rev_scale(_ptr(_f32(h)), _ptr(mask), h.numel(), alpha, _ptr(out), _stream()))
+    return out
+
+
+def frag_offsets(mask: torch.Tensor, n: int) -> torch.Tensor:
+    _require_gpu()
+    off = torch.empty(_n_words(n) + 1, dtype=torch.int32, device=mask.device)
+    _check(load_library().mw_frag_offsets(_ptr(mask), n, _ptr(off), _stream()))
+    return off
+
+
+def frag_compact(h: torch.Tensor, mask: torch.Tensor, offsets: torch.Tensor, capacity: Optional[int] = None):
+    _require_gpu()
+    n = h.numel()
+    cap = n if capacity is None else int(capacity)
+    frag = torch.zeros(max(cap, 1), dtype=torch.float32, device=h.device)
+    flag = torch.zeros(1, dtype=torch.int32, device=h.device)
+    _check(load_library().mw_frag_compact(_ptr(_f32(h)), _ptr(mask), _ptr(offsets), n, _ptr(frag), cap, _ptr(flag),
+                                          _stream()))
+    return frag, flag
+
+
+def vijp_epilogue(z: torch.Tensor, ct_z: torch.Tensor, alpha: float, mask=None, offsets=None, frag=None):
+    """Returns (x, h_y); ct_z is modified in place for alpha == 0."""
+    _require_gpu()
+    rows, d = z.shape
+    x, h_y = torch.empty_like(z), torch.empty_like(z)
+    _check(load_library().mw_vijp_epilogue(_ptr(_f32(z)), _ptr(_f32(ct_z)), rows, d, alpha, _ptr(mask), _ptr(offsets),
+                                           _ptr(frag), _ptr(x), _ptr(h_y), _stream()))
+    return x, h_y
+
+
+def colsum(a: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
+    _require_gpu()
+    rows, d = a.shape
+    out = torch.empty(d, dtype=torch.float32, device=a.device)
+    _check(load_library().mw_colsum(_ptr(_f32(a)), rows, d, scale, _ptr(out), _stream()))
+    return out
+
+
+def loss_grad(xL: torch.Tensor, t: torch.Tensor, scale: float = 1.0):
+    _require_gpu()
+    lib = load_library()
+    rows, d = xL.shape
+    hL = torch.empty_like(xL)
+    loss = torch.empty(1, dtype=torch.float32, device=xL.device)
+    scratch = torch.empty(int(lib.mw_loss_scratch_doubles()), dtype=torch.float64, device=xL.device)
+    _check(lib.mw_loss_grad(_ptr(_f32(xL)), _ptr(_f32(t)), rows, d, scale, _ptr(hL), _ptr(loss), _ptr(scratch), _stream()))
+    return hL, loss
+
+
+def copy_f32(src: torch.Tensor, dst: torch.Tensor):
+    _require_gpu()
+    _check(load_library().mw_copy_f32(_ptr(_f32(src)), _ptr(_f32(dst)), src.numel(), _stream()))
+    return dst

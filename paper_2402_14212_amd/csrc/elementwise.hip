@@ -1,0 +1,431 @@
+// HBM-bound elementwise, bit-pack and stream-compaction kernels (wave64, gfx950).
+//
+// Packed masks: flat row-major element e is bit (e % 64) of uint64 word e / 64, LSB first, which
+// is exactly the order of a wave64 ballot when lane l handles element 64 w + l. All kernels
+// below give every wavefront whole 64-element words, so loads and stores are fully coalesced
+// (256 B per wavefront per access) and the integer work is a ballot or a popcount per word.
+#include "mw_internal.h"
+
+namespace mw {
+
+namespace {
+
+constexpr int EW_THREADS = 256;
+constexpr int EW_WAVES = EW_THREADS / 64;
+constexpr int EW_MAX_BLOCKS = 256 * 8;  // 8 workgroups per CU keeps enough loads in flight
+constexpr int UNROLL = 4;               // words per wavefront per trip
+
+inline int ew_blocks(int64_t n_words, int words_per_block) {
+  int64_t b = (n_words + words_per_block - 1) / words_per_block;
+  if (b < 1) b = 1;
+  if (b > EW_MAX_BLOCKS) b = EW_MAX_BLOCKS;
+  return (int)b;
+}
+
+__device__ __forceinline__ int64_t global_wave() { return (int64_t)blockIdx.x * EW_WAVES + (threadIdx.x >> 6); }
+__device__ __forceinline__ int64_t total_waves() { return (int64_t)gridDim.x * EW_WAVES; }
+
+// ---------------------------------------------------------------- phase I: bias + mask + activation
+template <bool HAS_BIAS>
+__global__ void __launch_bounds__(EW_THREADS)
+k_bias_act_mask(const float* __restrict__ zin, const float* __restrict__ bias, int64_t n, int d, float alpha,
+                float* __restrict__ x, uint64_t* __restrict__ mask) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t stride_words = total_waves() * UNROLL;
+  const int step64 = 64 % d;                                  // column advance per word
+  const int step_trip = (int)((stride_words * 64) % d);       // column advance per trip
+  int64_t w0 = global_wave() * UNROLL;
+  int col0 = HAS_BIAS ? (int)((w0 * 64 + lane) % d) : 0;      // one wide modulo per thread
+  for (; w0 < n_words; w0 += stride_words) {
+    float z[UNROLL];
+    int col = col0;
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      z[j] = 0.f;
+      if (e < n) {
+        z[j] = zin[e];
+        if (HAS_BIAS) z[j] += bias[col];
+      }
+      if (HAS_BIAS) { col += step64; if (col >= d) col -= d; }
+    }
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      bool bit = (e < n) && (z[j] > 0.f);
+      if (e < n) x[e] = bit ? z[j] : alpha * z[j];
+      unsigned long long bal = __ballot(bit);
+      if (lane == 0 && w0 + j < n_words) mask[w0 + j] = bal;
+    }
+    if (HAS_BIAS) { col0 += step_trip; if (col0 >= d) col0 -= d; }
+  }
+}
+
+// mask bit = (x > 0): equals (z > 0) because alpha >= 0 keeps the sign (and maps z <= 0 to x <= 0)
+__global__ void __launch_bounds__(EW_THREADS)
+k_mask_from_act(const float* __restrict__ x, int64_t n, uint64_t* __restrict__ mask) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t stride_words = total_waves() * UNROLL;
+  for (int64_t w0 = global_wave() * UNROLL; w0 < n_words; w0 += stride_words) {
+    float v[UNROLL];
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      v[j] = e < n ? x[e] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      unsigned long long bal = __ballot(v[j] > 0.f);
+      if (lane == 0 && w0 + j < n_words) mask[w0 + j] = bal;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- phase II: slope scaling
+__global__ void __launch_bounds__(EW_THREADS)
+k_rev_scale(const float* __restrict__ h, const uint64_t* __restrict__ mask, int64_t n, float alpha,
+            float* __restrict__ ct_z) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t stride_words = total_waves() * UNROLL;
+  for (int64_t w0 = global_wave() * UNROLL; w0 < n_words; w0 += stride_words) {
+    float v[UNROLL];
+    uint64_t m[UNROLL];
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      v[j] = e < n ? h[e] : 0.f;
+      m[j] = (w0 + j < n_words) ? mask[w0 + j] : 0ull;
+    }
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      if (e < n) ct_z[e] = v[j] * (((m[j] >> lane) & 1ull) ? 1.f : alpha);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- fragment index: erased-count scan
+// One workgroup per mask: every thread counts the erased (zero) bits of a contiguous run of
+// words, the per-thread counts are scanned through LDS, and the thread writes the exclusive
+// offsets of its run. Integer arithmetic only: the result does not depend on scheduling.
+constexpr int SCAN_THREADS = 1024;
+
+__device__ __forceinline__ uint32_t erased_in_word(uint64_t w, int64_t word_index, int64_t n) {
+  int64_t valid = n - word_index * 64;
+  if (valid >= 64) return (uint32_t)__popcll(~w);
+  uint64_t keep = (valid <= 0) ? 0ull : ((1ull << valid) - 1ull);
+  return (uint32_t)__popcll(~w & keep);
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets) {
+  __shared__ uint32_t part[SCAN_THREADS];
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t per = (n_words + SCAN_THREADS - 1) / SCAN_THREADS;
+  const int64_t lo = (int64_t)threadIdx.x * per;
+  const int64_t hi = lo + per < n_words ? lo + per : n_words;
+  uint32_t cnt = 0;
+  for (int64_t w = lo; w < hi; ++w) cnt += erased_in_word(mask[w], w, n);
+  part[threadIdx.x] = cnt;
+  __syncthreads();
+  // inclusive Hillis-Steele scan over the 1024 partial counts
+  for (int off = 1; off < SCAN_THREADS; off <<= 1) {
+    uint32_t add = threadIdx.x >= (unsigned)off ? part[threadIdx.x - off] : 0u;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  uint32_t run = part[threadIdx.x] - cnt;  // exclusive prefix of this thread's run
+  for (int64_t w = lo; w < hi; ++w) {
+    offsets[w] = run;
+    run += erased_in_word(mask[w], w, n);
+  }
+  if (threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = part[SCAN_THREADS - 1];
+}
+
+// Layer bases: exclusive scan of the erased counts in the order given (reverse-pass order).
+__global__ void k_frag_bases(const uint32_t* const* __restrict__ count_ptrs, int n_relu,
+                             uint64_t* __restrict__ bases, uint64_t* __restrict__ total) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    uint64_t run = 0;
+    for (int j = 0; j < n_relu; ++j) {
+      bases[j] = run;
+      run += *count_ptrs[j];
+    }
+    *total = run;
+  }
+}
+
+// ---------------------------------------------------------------- phase II: fragment compaction
+__global__ void __launch_bounds__(EW_THREADS)
+k_frag_compact(const float* __restrict__ h, const uint64_t* __restrict__ mask, const uint32_t* __restrict__ offsets,
+               int64_t n, float* __restrict__ frag, const uint64_t* __restrict__ base_ptr, uint64_t capacity,
+               int32_t* __restrict__ overflow_flag) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t stride_words = total_waves() * UNROLL;
+  const uint64_t base = base_ptr ? *base_ptr : 0ull;
+  const uint64_t below = (1ull << lane) - 1ull;
+  for (int64_t w0 = global_wave() * UNROLL; w0 < n_words; w0 += stride_words) {
+    float v[UNROLL];
+    uint64_t m[UNROLL];
+    uint32_t off[UNROLL];
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      bool in = w0 + j < n_words;
+      v[j] = e < n ? h[e] : 0.f;
+      m[j] = in ? mask[w0 + j] : ~0ull;
+      off[j] = in ? offsets[w0 + j] : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      bool erased = (e < n) && !((m[j] >> lane) & 1ull);
+      if (erased) {
+        uint64_t idx = base + off[j] + (uint64_t)__popcll(~m[j] & below);
+        if (idx < capacity) frag[idx] = v[j];
+        else if (overflow_flag) *overflow_flag = 1;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- phase III: stand-alone epilogue
+template <bool RELU>
+__global__ void __launch_bounds__(EW_THREADS)
+k_vijp_epilogue(const float* __restrict__ z, float* __restrict__ ct_z, int64_t n, float alpha, float inv_alpha,
+                const uint64_t* __restrict__ mask, const uint32_t* __restrict__ offsets,
+                const float* __restrict__ frag, const uint64_t* __restrict__ base_ptr, uint64_t capacity,
+                float* __restrict__ x, float* __restrict__ h_y, unsigned long long* __restrict__ mismatches) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t stride_words = total_waves() * UNROLL;
+  const uint64_t below = (1ull << lane) - 1ull;
+  const uint64_t base = (RELU && base_ptr) ? *base_ptr : 0ull;
+  for (int64_t w0 = global_wave() * UNROLL; w0 < n_words; w0 += stride_words) {
+    float zz[UNROLL], cc[UNROLL];
+    uint64_t m[UNROLL];
+    uint32_t off[UNROLL];
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      bool in = w0 + j < n_words;
+      zz[j] = e < n ? z[e] : 0.f;
+      cc[j] = e < n ? ct_z[e] : 0.f;
+      m[j] = (mask && in) ? mask[w0 + j] : 0ull;
+      off[j] = (RELU && in) ? offsets[w0 + j] : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j) {
+      int64_t e = (w0 + j) * 64 + lane;
+      if (e >= n) continue;
+      bool fresh = zz[j] > 0.f;
+      bool stored = (m[j] >> lane) & 1ull;
+      if (mask && mismatches && fresh != stored) atomicAdd(mismatches, 1ull);
+      if (RELU) {
+        float c = stored ? cc[j] : 0.f;
+        float hy = c;
+        if (!stored) {
+          uint64_t idx = base + off[j] + (uint64_t)__popcll(~m[j] & below);
+          hy = idx < capacity ? frag[idx] : 0.f;
+        }
+        x[e] = stored ? zz[j] : alpha * zz[j];
+        ct_z[e] = c;
+        h_y[e] = hy;
+      } else {
+        x[e] = fresh ? zz[j] : alpha * zz[j];
+        h_y[e] = fresh ? cc[j] : cc[j] * inv_alpha;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- column sums (bias gradient)
+// Thread j of a workgroup owns column j and walks a contiguous range of rows; partial sums over
+// COLSUM_SPLIT row ranges are combined in LDS in a fixed order.
+constexpr int COLSUM_COLS = 64, COLSUM_SPLIT = 4;
+__global__ void __launch_bounds__(COLSUM_COLS* COLSUM_SPLIT)
+k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* __restrict__ out) {
+  __shared__ float part[COLSUM_SPLIT][COLSUM_COLS];
+  const int c = threadIdx.x % COLSUM_COLS, s = threadIdx.x / COLSUM_COLS;
+  const int col = blockIdx.x * COLSUM_COLS + c;
+  const int64_t per = (rows + COLSUM_SPLIT - 1) / COLSUM_SPLIT;
+  const int64_t lo = s * per, hi = lo + per < rows ? lo + per : rows;
+  float acc = 0.f;
+  if (col < d)
+    for (int64_t r = lo; r < hi; ++r) acc += a[r * d + col];
+  part[s][c] = acc;
+  __syncthreads();
+  if (s == 0 && col < d) {
+    float t = part[0][c];
+    for (int k = 1; k < COLSUM_SPLIT; ++k) t += part[k][c];
+    out[col] = scale * t;
+  }
+}
+
+// ---------------------------------------------------------------- loss value and output cotangent
+__global__ void __launch_bounds__(EW_THREADS)
+k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n, float cot_scale,
+            float* __restrict__ hL, double* __restrict__ partial) {
+  __shared__ double red[EW_THREADS];
+  double acc = 0.0;
+  for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < n; e += (int64_t)gridDim.x * EW_THREADS) {
+    float r = xL[e] - t[e];
+    hL[e] = cot_scale * r;
+    acc += (double)r * (double)r;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+__global__ void k_loss_final(const double* __restrict__ partial, int n_partial, double factor,
+                             float* __restrict__ loss) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < n_partial; ++i) s += partial[i];
+    *loss = (float)(factor * s);
+  }
+}
+
+// ---------------------------------------------------------------- copy / fill
+__global__ void __launch_bounds__(EW_THREADS)
+k_copy(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t n4 = n >> 2;
+  const bool vec = (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+  int64_t i = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * EW_THREADS;
+  if (vec) {
+    const float4* s4 = reinterpret_cast<const float4*>(src);
+    float4* d4 = reinterpret_cast<float4*>(dst);
+    for (int64_t k = i; k < n4; k += stride) d4[k] = s4[k];
+    for (int64_t k = n4 * 4 + i; k < n; k += stride) dst[k] = src[k];
+  } else {
+    for (int64_t k = i; k < n; k += stride) dst[k] = src[k];
+  }
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_fill_u32(uint32_t* __restrict__ p, uint32_t value, int64_t n) {
+  for (int64_t k = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; k < n; k += (int64_t)gridDim.x * EW_THREADS)
+    p[k] = value;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------ launchers
+
+hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, int d, float alpha, float* x,
+                            uint64_t* mask, hipStream_t stream) {
+  int64_t n = rows * d;
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
+  if (bias)
+    hipLaunchKernelGGL(k_bias_act_mask<true>, dim3(blocks), dim3(EW_THREADS), 0, stream, zin, bias, n, d, alpha, x,
+                       mask);
+  else
+    hipLaunchKernelGGL(k_bias_act_mask<false>, dim3(blocks), dim3(EW_THREADS), 0, stream, zin, bias, n, d, alpha, x,
+                       mask);
+  return hipGetLastError();
+}
+
+hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
+  hipLaunchKernelGGL(k_mask_from_act, dim3(blocks), dim3(EW_THREADS), 0, stream, x, n, mask);
+  return hipGetLastError();
+}
+
+hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
+                        hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
+  hipLaunchKernelGGL(k_rev_scale, dim3(blocks), dim3(EW_THREADS), 0, stream, h, mask, n, alpha, ct_z);
+  return hipGetLastError();
+}
+
+hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream) {
+  if (n < 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_frag_offsets, dim3(1), dim3(SCAN_THREADS), 0, stream, mask, n, offsets);
+  return hipGetLastError();
+}
+
+hipError_t ew_frag_bases(const uint32_t* const* count_ptrs, int n_relu, uint64_t* bases, uint64_t* total,
+                         hipStream_t stream) {
+  hipLaunchKernelGGL(k_frag_bases, dim3(1), dim3(64), 0, stream, count_ptrs, n_relu, bases, total);
+  return hipGetLastError();
+}
+
+hipError_t ew_frag_compact(const float* h, const uint64_t* mask, const uint32_t* offsets, int64_t n, float* frag,
+                           const uint64_t* base, uint64_t capacity, int32_t* overflow_flag, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
+  hipLaunchKernelGGL(k_frag_compact, dim3(blocks), dim3(EW_THREADS), 0, stream, h, mask, offsets, n, frag, base,
+                     capacity, overflow_flag);
+  return hipGetLastError();
+}
+
+hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, float alpha, const uint64_t* mask,
+                            const uint32_t* offsets, const float* frag, const uint64_t* base, uint64_t capacity,
+                            float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream) {
+  int64_t n = rows * d;
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
+  if (alpha == 0.f) {
+    if (!mask || !offsets || !frag) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_vijp_epilogue<true>, dim3(blocks), dim3(EW_THREADS), 0, stream, z, ct_z, n, alpha, 0.f,
+                       mask, offsets, frag, base, capacity, x, h_y, mismatches);
+  } else {
+    hipLaunchKernelGGL(k_vijp_epilogue<false>, dim3(blocks), dim3(EW_THREADS), 0, stream, z, ct_z, n, alpha,
+                       1.0f / alpha, mask, offsets, frag, base, capacity, x, h_y, mismatches);
+  }
+  return hipGetLastError();
+}
+
+hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream) {
+  if (d <= 0) return hipSuccess;
+  int blocks = (d + COLSUM_COLS - 1) / COLSUM_COLS;
+  hipLaunchKernelGGL(k_colsum, dim3(blocks), dim3(COLSUM_COLS * COLSUM_SPLIT), 0, stream, a, rows, d, scale, out);
+  return hipGetLastError();
+}
+
+hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
+                        double* scratch, hipStream_t stream) {
+  int64_t n = rows * d;
+  if (n <= 0 || rows <= 0) return hipErrorInvalidValue;
+  // scale and 1/rows are folded into one fp32 factor; with a power-of-two scale this is the
+  // correctly rounded scale/rows either way
+  float cot_scale = scale / (float)rows;
+  hipLaunchKernelGGL(k_loss_grad, dim3(LOSS_BLOCKS), dim3(EW_THREADS), 0, stream, xL, t, n, cot_scale, hL, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (loss) {
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, stream, scratch, LOSS_BLOCKS, 0.5 / (double)rows, loss);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks((n + 3) / 4, EW_THREADS * 4);
+  hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(EW_THREADS), 0, stream, src, dst, n);
+  return hipGetLastError();
+}
+
+hipError_t ew_fill_u32(uint32_t* p, uint32_t value, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int blocks = ew_blocks(n, EW_THREADS * 4);
+  hipLaunchKernelGGL(k_fill_u32, dim3(blocks), dim3(EW_THREADS), 0, stream, p, value, n);
+  return hipGetLastError();
+}
+
+}  // namespace mw

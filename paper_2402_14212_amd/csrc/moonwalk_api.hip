@@ -1,0 +1,677 @@
+// libmoonwalk: handle, buffer plan and the three gradient drivers behind the C ABI.
+//
+// Everything here is host code that enqueues kernels; the only synchronising calls are setup,
+// refresh, memory_stats, debug_fetch and destroy.
+#include "../../include/moonwalk.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "mw_internal.h"
+
+namespace mw {
+
+hipError_t gemm_plain_nt(int tile, int M, int N, int K, float alpha, const float* A, int64_t lda, const float* B,
+                         int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream);
+hipError_t gemm_plain_nn(int tile, int M, int N, int K, float alpha, const float* A, int64_t lda, const float* B,
+                         int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream);
+hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float* A, int64_t lda, const float* B,
+                         int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream);
+
+int pick_tile(int M, int N, int K) {
+  auto tiles = [](int m, int n, int t) { return (int64_t)((m + t - 1) / t) * ((n + t - 1) / t); };
+  // 256 CUs: prefer the largest tile that still gives most CUs a workgroup; for small outputs
+  // with a long K split K over the wavefronts of a 32x32 tile instead.
+  if (tiles(M, N, 128) >= 192) return TILE_128;
+  if (tiles(M, N, 64) >= 192) return TILE_64;
+  if (K >= 256) return TILE_32K4;
+  return TILE_64;
+}
+
+hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const float* A, int64_t lda,
+                      const float* B, int64_t ldb, float beta, float* C, int64_t ldc, const float* bias,
+                      hipStream_t stream) {
+  switch (op) {
+    case OP_NT: return gemm_plain_nt(tile, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, bias, stream);
+    case OP_NN: return gemm_plain_nn(tile, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, bias, stream);
+    case OP_TN: return gemm_plain_tn(tile, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, bias, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace mw
+
+using namespace mw;
+
+namespace {
+
+thread_local std::string g_hip_error_text = "no HIP error recorded";
+
+int hip_fail(hipError_t e, const char* where) {
+  g_hip_error_text = std::string(where) + ": " + hipGetErrorString(e);
+  return MW_ERR_HIP;
+}
+
+#define MW_HIP(expr)                                   \
+  do {                                                 \
+    hipError_t e__ = (expr);                           \
+    if (e__ != hipSuccess) return hip_fail(e__, #expr); \
+  } while (0)
+
+// Launch `expr` (a launcher returning hipError_t); with profiling on, bracket it with events.
+#define MW_LAUNCH(h, s, kclass, expr)                                        \
+  do {                                                                       \
+    hipEvent_t e0__ = nullptr, e1__ = nullptr;                               \
+    if ((h)->prof_on) {                                                      \
+      e0__ = (h)->prof_event();                                              \
+      e1__ = (h)->prof_event();                                              \
+      if (!e0__ || !e1__) return hip_fail(hipErrorOutOfMemory, "hipEventCreate"); \
+      MW_HIP(hipEventRecord(e0__, (s)));                                     \
+    }                                                                        \
+    MW_HIP(expr);                                                            \
+    if ((h)->prof_on) {                                                      \
+      MW_HIP(hipEventRecord(e1__, (s)));                                     \
+      (h)->prof_recs.push_back({(kclass), e0__, e1__});                      \
+    }                                                                        \
+  } while (0)
+
+void* default_alloc(size_t bytes, void*) {
+  void* p = nullptr;
+  if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+  return p;
+}
+void default_free(void* p, void*) { (void)hipFree(p); }
+
+struct Layer {
+  int d_in = 0, d_out = 0;
+  const float* W = nullptr;
+  const float* b = nullptr;
+  float alpha = 0.f;
+  float* P = nullptr;
+  uint64_t* mask = nullptr;
+  size_t mask_words = 0;
+  uint32_t* offsets = nullptr;  // ReLU layers: [mask_words + 1]
+  int relu_slot = -1;           // position in reverse-pass order among the ReLU layers
+  float* ckpt = nullptr;        // kept cotangent at this layer's OUTPUT (h_i), if any
+  float* act = nullptr;         // backprop: stored x_i
+  size_t dW_off = 0, db_off = 0;
+};
+
+}  // namespace
+
+struct mw_handle {
+  std::vector<Layer> layers;
+  int B = 0, L = 0, K = 0, fuse = 1, plan = 0;
+  float loss_scale = 1.f;
+  double frag_factor = 1.0;
+  void* (*dev_alloc)(size_t, void*) = nullptr;
+  void (*dev_free)(void*, void*) = nullptr;
+  void* alloc_ctx = nullptr;
+  std::vector<std::pair<void*, size_t>> allocs;
+  uint64_t live = 0, peak = 0, setup_peak = 0;
+  mw_memstats_t st{};
+  size_t total_floats = 0;
+  int dmax = 0;  // max over d_1..d_L
+
+  // Moonwalk workspace
+  float *xa = nullptr, *xb = nullptr, *ha = nullptr, *hb = nullptr, *ctz = nullptr, *zbuf = nullptr, *h0 = nullptr;
+  float* frag = nullptr;
+  uint64_t frag_capacity = 0;
+  int n_relu = 0;
+  uint64_t* frag_bases = nullptr;         // [n_relu + 1]; last = total
+  const uint32_t** count_ptrs = nullptr;  // device array [n_relu]
+  uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
+  double* loss_scratch = nullptr;
+  // backprop workspace
+  float *bp_ha = nullptr, *bp_hb = nullptr;
+
+  // optional per-kernel-class timing with HIP events
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_pool;
+  size_t prof_used = 0;
+  struct ProfRec { int kclass; hipEvent_t start, stop; };
+  std::vector<ProfRec> prof_recs;
+  double prof_ms[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
+  uint64_t prof_launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
+
+  hipEvent_t prof_event() {
+    if (prof_used == prof_pool.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      prof_pool.push_back(e);
+    }
+    return prof_pool[prof_used++];
+  }
+
+  void* alloc(size_t bytes, uint64_t* item) {
+    if (bytes == 0) bytes = 4;
+    void* p = dev_alloc(bytes, alloc_ctx);
+    if (!p) return nullptr;
+    allocs.emplace_back(p, bytes);
+    live += bytes;
+    if (live > peak) peak = live;
+    if (item) *item += bytes;
+    return p;
+  }
+  void release(void* p) {
+    if (!p) return;
+    for (size_t i = 0; i < allocs.size(); ++i)
+      if (allocs[i].first == p) {
+        live -= allocs[i].second;
+        dev_free(p, alloc_ctx);
+        allocs.erase(allocs.begin() + i);
+        return;
+      }
+  }
+  void release_all() {
+    for (auto& a : allocs) dev_free(a.first, alloc_ctx);
+    allocs.clear();
+    live = 0;
+  }
+};
+
+namespace {
+
+template <class T>
+bool alloc_t(mw_handle* h, T** out, size_t count, uint64_t* item) {
+  *out = static_cast<T*>(h->alloc(count * sizeof(T), item));
+  return *out != nullptr;
+}
+
+// Right inverses for every layer; scratch is taken and given back within the call.
+int build_right_inverses(mw_handle* h, hipStream_t stream) {
+  size_t work_floats = 0;
+  for (auto& l : h->layers) {
+    size_t w = setup_work_floats(l.d_out, l.d_in);
+    if (w > work_floats) work_floats = w;
+  }
+  uint64_t before = h->live;
+  float* work = static_cast<float*>(h->alloc(work_floats * sizeof(float), nullptr));
+  if (!work) return MW_ERR_OOM;
+  if (h->live > h->setup_peak) h->setup_peak = h->live;
+  (void)before;
+  int32_t* bad = reinterpret_cast<int32_t*>(h->status + 3);
+  int rc = MW_OK;
+  hipError_t e = ew_fill_u32(h->status + 3, 0u, 1, stream);
+  for (size_t i = 0; e == hipSuccess && i < h->layers.size(); ++i) {
+    Layer& l = h->layers[i];
+    e = setup_right_inverse(l.W, l.d_out, l.d_in, l.P, work, bad, stream);
+  }
+  int32_t bad_host = 0;
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e == hipSuccess) e = hipMemcpy(&bad_host, bad, sizeof(int32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) rc = hip_fail(e, "right-inverse setup");
+  else if (bad_host) rc = MW_ERR_NOT_SUBMERSIVE;
+  h->release(work);
+  return rc;
+}
+
+int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_t* cfg) {
+  if (!layers || n_layers <= 0 || !cfg || cfg->batch <= 0) return MW_ERR_INVALID_ARG;
+  if (cfg->reseed_interval < 0) return MW_ERR_INVALID_ARG;
+  if (!(cfg->loss_scale > 0.f) || !std::isfinite(cfg->loss_scale)) return MW_ERR_INVALID_ARG;
+  if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
+  if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
+  for (int i = 0; i < n_layers; ++i) {
+    const mw_layer_t& l = layers[i];
+    if (l.d_in <= 0 || l.d_out <= 0 || !l.W) return MW_ERR_INVALID_ARG;
+    if (!(l.alpha >= 0.f && l.alpha <= 1.f)) return MW_ERR_INVALID_ARG;
+    if (i > 0 && l.d_in != layers[i - 1].d_out) return MW_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < n_layers; ++i)
+    if (layers[i].d_out > layers[i].d_in) return MW_ERR_NOT_SUBMERSIVE;
+  return MW_OK;
+}
+
+}  // namespace
+
+// =============================================================================================== C ABI
+
+extern "C" {
+
+int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers, const mw_config_t* cfg,
+                   void* hip_stream) {
+  if (!out) return MW_ERR_INVALID_ARG;
+  *out = nullptr;
+  int rc = validate_layers(layers, n_layers, cfg);
+  if (rc != MW_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  mw_handle* h = new mw_handle();
+  h->B = cfg->batch;
+  h->L = n_layers;
+  h->K = cfg->reseed_interval;
+  h->fuse = cfg->fuse ? 1 : 0;
+  h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
+  h->loss_scale = cfg->loss_scale;
+  h->frag_factor = cfg->frag_capacity_factor > 0.0 ? cfg->frag_capacity_factor : 1.0;
+  h->dev_alloc = cfg->dev_alloc ? cfg->dev_alloc : default_alloc;
+  h->dev_free = cfg->dev_free ? cfg->dev_free : default_free;
+  h->alloc_ctx = cfg->alloc_ctx;
+  h->layers.resize(n_layers);
+  size_t off = 0;
+  const size_t B = (size_t)h->B;
+  for (int i = 0; i < n_layers; ++i) {
+    Layer& l = h->layers[i];
+    l.d_in = layers[i].d_in;
+    l.d_out = layers[i].d_out;
+    l.W = layers[i].W;
+    l.b = layers[i].b;
+    l.alpha = layers[i].alpha;
+    l.dW_off = off;
+    off += (size_t)l.d_out * l.d_in;
+    l.db_off = off;
+    off += (size_t)l.d_out;
+    if (l.d_out > h->dmax) h->dmax = l.d_out;
+  }
+  h->total_floats = off;
+
+  auto fail = [&](int code) {
+    h->release_all();
+    delete h;
+    return code;
+  };
+  mw_memstats_t& st = h->st;
+  bool ok = alloc_t(h, &h->status, 4, &st.bytes_mw_scratch);
+  if (!ok) return fail(MW_ERR_OOM);
+  hipError_t e = ew_fill_u32(h->status, 0u, 4, stream);
+  if (e != hipSuccess) return fail(hip_fail(e, "status init"));
+
+  if (h->plan & MW_PLAN_MOONWALK) {
+    // right inverses
+    for (auto& l : h->layers) ok = ok && alloc_t(h, &l.P, (size_t)l.d_out * l.d_in, &st.bytes_P);
+    if (!ok) return fail(MW_ERR_OOM);
+    rc = build_right_inverses(h, stream);
+    if (rc != MW_OK) return fail(rc);
+
+    // sign masks (zeroed once: the padding bits of the last word are never written afterwards)
+    for (auto& l : h->layers) {
+      l.mask_words = (B * l.d_out + 63) / 64;
+      ok = ok && alloc_t(h, &l.mask, l.mask_words, &st.bytes_masks);
+      if (ok) {
+        e = ew_fill_u32(reinterpret_cast<uint32_t*>(l.mask), 0u, (int64_t)l.mask_words * 2, stream);
+        if (e != hipSuccess) return fail(hip_fail(e, "mask init"));
+      }
+    }
+    // fragment store and its index (ReLU layers)
+    size_t relu_elems = 0;
+    for (auto& l : h->layers)
+      if (l.alpha == 0.f) {
+        ++h->n_relu;
+        relu_elems += B * l.d_out;
+        ok = ok && alloc_t(h, &l.offsets, l.mask_words + 1, &st.bytes_frag_index);
+      }
+    if (ok && h->n_relu > 0) {
+      h->frag_capacity = (uint64_t)std::ceil(h->frag_factor * (double)relu_elems);
+      if (h->frag_capacity < 1) h->frag_capacity = 1;
+      ok = ok && alloc_t(h, &h->frag, h->frag_capacity, &st.bytes_fragments);
+      ok = ok && alloc_t(h, &h->frag_bases, (size_t)h->n_relu + 1, &st.bytes_frag_index);
+      ok = ok && alloc_t(h, &h->count_ptrs, (size_t)h->n_relu, &st.bytes_frag_index);
+      if (ok) {
+        std::vector<const uint32_t*> ptrs;
+        int slot = 0;
+        for (int i = n_layers - 1; i >= 0; --i) {  // reverse-pass order: layer L first
+          Layer& l = h->layers[i];
+          if (l.alpha == 0.f) {
+            l.relu_slot = slot++;
+            ptrs.push_back(l.offsets + l.mask_words);
+          }
+        }
+        e = hipMemcpy(h->count_ptrs, ptrs.data(), ptrs.size() * sizeof(ptrs[0]), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail(hip_fail(e, "fragment index init"));
+      }
+    }
+    // re-seed checkpoints: cotangent at the output of layer j (1-based j = K, 2K, ... < L)
+    if (h->K > 0)
+      for (int j = 1; j < n_layers; ++j)
+        if (j % h->K == 0) ok = ok && alloc_t(h, &h->layers[j - 1].ckpt, B * h->layers[j - 1].d_out, &st.bytes_checkpoints);
+    // ping-pong buffers
+    const size_t nmax = B * (size_t)h->dmax;
+    ok = ok && alloc_t(h, &h->xa, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->xb, nmax, &st.bytes_mw_scratch) &&
+         alloc_t(h, &h->ha, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->hb, nmax, &st.bytes_mw_scratch) &&
+         alloc_t(h, &h->ctz, nmax, &st.bytes_mw_scratch) &&
+         alloc_t(h, &h->h0, B * (size_t)h->layers[0].d_in, &st.bytes_mw_scratch);
+    if (!h->fuse) ok = ok && alloc_t(h, &h->zbuf, nmax, &st.bytes_mw_scratch);
+    if (!ok) return fail(MW_ERR_OOM);
+  }
+  ok = ok && alloc_t(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_mw_scratch);
+  if (h->plan & MW_PLAN_BACKPROP) {
+    for (auto& l : h->layers) ok = ok && alloc_t(h, &l.act, B * l.d_out, &st.bytes_bp_activations);
+    const size_t nmax = B * (size_t)h->dmax;
+    ok = ok && alloc_t(h, &h->bp_ha, nmax, &st.bytes_bp_scratch) && alloc_t(h, &h->bp_hb, nmax, &st.bytes_bp_scratch);
+  }
+  if (!ok) return fail(MW_ERR_OOM);
+  e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail(hip_fail(e, "setup sync"));
+  *out = h;
+  return MW_OK;
+}
+
+int moonwalk_refresh(mw_handle_t* h, void* hip_stream) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  return build_right_inverses(h, static_cast<hipStream_t>(hip_stream));
+}
+
+int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                  void* hip_stream) {
+  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int B = h->B, L = h->L;
+  unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
+  int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
+  MW_HIP(ew_fill_u32(h->status, 0u, 3, s));
+
+  // ---------------- Phase I: forward, keep sign masks only
+  const float* xin = x;
+  float* xbuf[2] = {h->xa, h->xb};
+  for (int i = 0; i < L; ++i) {
+    Layer& l = h->layers[i];
+    float* xout = xbuf[i & 1];
+    if (h->fuse) {
+      if (l.d_out % 32 == 0) {
+        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, l.mask, s));
+      } else {
+        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, nullptr, s));
+        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_mask_from_act(xout, (int64_t)B * l.d_out, l.mask, s));
+      }
+    } else {
+      MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
+                        l.b, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(h->zbuf, nullptr, B, l.d_out, l.alpha, xout, l.mask, s));
+    }
+    if (l.alpha == 0.f) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_offsets(l.mask, (int64_t)B * l.d_out, l.offsets, s));
+    xin = xout;
+  }
+  if (h->n_relu > 0) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_bases(h->count_ptrs, h->n_relu, h->frag_bases, h->frag_bases + h->n_relu, s));
+
+  // ---------------- loss and output cotangent h_L
+  float* hbuf[2] = {h->ha, h->hb};
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s));
+  const float* hcur = hbuf[0];
+
+  // ---------------- Phase II: reverse, input cotangent only
+  for (int i = L - 1; i >= 0; --i) {
+    Layer& l = h->layers[i];
+    const int64_t n = (int64_t)B * l.d_out;
+    if (l.alpha == 0.f)
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hcur, l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot, h->frag_capacity,
+                             overflow, s));
+    float* hout;
+    if (i == 0) hout = h->h0;
+    else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
+    else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+    if (h->fuse) {
+      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_mask(TILE_AUTO, B, l.d_in, l.d_out, hcur, l.mask, l.alpha, l.W, hout, s));
+    } else {
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hcur, l.mask, n, l.alpha, h->ctz, s));
+      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, h->ctz, l.d_out, l.W, l.d_in, 0.f, hout, l.d_in,
+                        nullptr, s));
+    }
+    hcur = hout;
+  }
+
+  // ---------------- Phase III: forward vijp sweep
+  const float inv_scale = 1.0f / h->loss_scale;
+  xin = x;
+  const float* hin = h->h0;
+  for (int i = 0; i < L; ++i) {
+    Layer& l = h->layers[i];
+    if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+    float* xout = xbuf[i & 1];
+    float* hout = hbuf[i & 1];
+    const bool relu = (l.alpha == 0.f);
+    if (h->fuse) {
+      VijpArgs a{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
+                 relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, h->ctz, mismatches};
+      MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, l.d_out, l.d_in, B, h->ctz, xin, inv_scale, grads_out + l.dW_off,
+                     grads_out + l.db_off, s));
+    } else {
+      MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
+                        l.b, s));
+      MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, hin, l.d_in, l.P, l.d_in, 0.f, h->ctz, l.d_out,
+                        nullptr, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_vijp_epilogue(h->zbuf, h->ctz, B, l.d_out, l.alpha, l.mask, l.offsets, h->frag,
+                              relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, mismatches,
+                              s));
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, l.d_out, l.d_in, B, h->ctz, xin, inv_scale, grads_out + l.dW_off, nullptr, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, grads_out + l.db_off, s));
+    }
+    xin = xout;
+    hin = hout;
+  }
+  return MW_OK;
+}
+
+int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                  void* hip_stream) {
+  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_BACKPROP)) return MW_ERR_NOT_PLANNED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int B = h->B, L = h->L;
+  // forward, every activation stored
+  const float* xin = x;
+  for (int i = 0; i < L; ++i) {
+    Layer& l = h->layers[i];
+    MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, l.act, nullptr, s));
+    xin = l.act;
+  }
+  float* hbuf[2] = {h->bp_ha, h->bp_hb};
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s));
+  const float inv_scale = 1.0f / h->loss_scale;
+  int sel = 0;
+  for (int i = L - 1; i >= 0; --i) {
+    Layer& l = h->layers[i];
+    const float* xprev = (i == 0) ? x : h->layers[i - 1].act;
+    // dW_i = (h_i .* f'(x_i))^T x_{i-1}, db_i = column sums
+    MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(TILE_AUTO, l.d_out, l.d_in, B, hbuf[sel], l.act, l.alpha, xprev, inv_scale,
+                       grads_out + l.dW_off, grads_out + l.db_off, s));
+    if (i > 0) {  // the input cotangent of the first layer is not needed
+      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(TILE_AUTO, B, l.d_in, l.d_out, hbuf[sel], l.act, l.alpha, l.W, hbuf[sel ^ 1], s));
+      sel ^= 1;
+    }
+  }
+  return MW_OK;
+}
+
+int moonwalk_grad_layout(const mw_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (total_floats) *total_floats = h->total_floats;
+  for (int i = 0; i < h->L; ++i) {
+    if (dW_off) dW_off[i] = h->layers[i].dW_off;
+    if (db_off) db_off[i] = h->layers[i].db_off;
+  }
+  return MW_OK;
+}
+
+int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out) {
+  if (!h || !out) return MW_ERR_INVALID_ARG;
+  uint32_t status[4] = {0, 0, 0, 0};
+  uint64_t frag_total = 0;
+  MW_HIP(hipDeviceSynchronize());
+  MW_HIP(hipMemcpy(status, h->status, sizeof(status), hipMemcpyDeviceToHost));
+  if (h->n_relu > 0)
+    MW_HIP(hipMemcpy(&frag_total, h->frag_bases + h->n_relu, sizeof(uint64_t), hipMemcpyDeviceToHost));
+  *out = h->st;
+  out->bytes_live = h->live;
+  out->bytes_peak = h->peak;
+  out->bytes_setup_peak = h->setup_peak;
+  out->frag_used = frag_total;
+  out->sign_mismatches = (uint64_t)status[0] | ((uint64_t)status[1] << 32);
+  out->frag_overflow = status[2] ? 1 : 0;
+  if (out->frag_overflow) return MW_ERR_FRAG_OVERFLOW;
+  if (out->sign_mismatches) return MW_ERR_SIGN_MISMATCH;
+  return MW_OK;
+}
+
+int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap, size_t* n_bytes) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (what != MW_FETCH_H0 && (layer < 0 || layer >= h->L)) return MW_ERR_INVALID_ARG;
+  MW_HIP(hipDeviceSynchronize());
+  const size_t B = (size_t)h->B;
+  const void* src = nullptr;
+  size_t bytes = 0;
+  const Layer* l = (what == MW_FETCH_H0) ? nullptr : &h->layers[layer];
+  uint64_t base = 0;
+  switch (what) {
+    case MW_FETCH_MASK:
+      src = l->mask; bytes = l->mask_words * 8; break;
+    case MW_FETCH_FRAG_OFFSETS:
+      src = l->offsets; bytes = l->offsets ? (l->mask_words + 1) * 4 : 0; break;
+    case MW_FETCH_FRAG_BASE:
+      if (l->relu_slot < 0) return MW_ERR_INVALID_ARG;
+      src = h->frag_bases + l->relu_slot; bytes = 8; break;
+    case MW_FETCH_FRAG: {
+      if (l->relu_slot < 0) return MW_ERR_INVALID_ARG;
+      uint32_t n0 = 0;
+      MW_HIP(hipMemcpy(&base, h->frag_bases + l->relu_slot, 8, hipMemcpyDeviceToHost));
+      MW_HIP(hipMemcpy(&n0, l->offsets + l->mask_words, 4, hipMemcpyDeviceToHost));
+      if (base + n0 > h->frag_capacity) return MW_ERR_FRAG_OVERFLOW;
+      src = h->frag + base; bytes = (size_t)n0 * 4; break;
+    }
+    case MW_FETCH_H0:
+      src = h->h0; bytes = B * h->layers[0].d_in * 4; break;
+    case MW_FETCH_P:
+      src = l->P; bytes = (size_t)l->d_out * l->d_in * 4; break;
+    case MW_FETCH_CHECKPOINT:
+      src = l->ckpt; bytes = B * l->d_out * 4; break;
+    default:
+      return MW_ERR_INVALID_ARG;
+  }
+  if (!src) return MW_ERR_INVALID_ARG;
+  if (n_bytes) *n_bytes = bytes;
+  if (!host_dst && cap == 0) return MW_OK;  // size query
+  if (!host_dst || cap < bytes) return MW_ERR_INVALID_ARG;
+  if (bytes) MW_HIP(hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost));
+  return MW_OK;
+}
+
+int moonwalk_profile_enable(mw_handle_t* h, int32_t on) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  MW_HIP(hipDeviceSynchronize());
+  h->prof_on = on != 0;
+  h->prof_recs.clear();
+  h->prof_used = 0;
+  for (int c = 0; c < MW_KCLASS_COUNT; ++c) {
+    h->prof_ms[c] = 0.0;
+    h->prof_launches[c] = 0;
+  }
+  return MW_OK;
+}
+
+int moonwalk_profile_read(mw_handle_t* h, int32_t kclass, uint64_t* launches, double* total_ms) {
+  if (!h || kclass < 0 || kclass >= MW_KCLASS_COUNT) return MW_ERR_INVALID_ARG;
+  MW_HIP(hipDeviceSynchronize());
+  for (auto& r : h->prof_recs) {  // fold finished records into the totals, give the events back
+    float ms = 0.f;
+    MW_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+    h->prof_ms[r.kclass] += ms;
+    h->prof_launches[r.kclass] += 1;
+  }
+  h->prof_recs.clear();
+  h->prof_used = 0;
+  if (launches) *launches = h->prof_launches[kclass];
+  if (total_ms) *total_ms = h->prof_ms[kclass];
+  return MW_OK;
+}
+
+void moonwalk_destroy(mw_handle_t* h) {
+  if (!h) return;
+  (void)hipDeviceSynchronize();
+  for (auto e : h->prof_pool) (void)hipEventDestroy(e);
+  h->release_all();
+  delete h;
+}
+
+const char* moonwalk_strerror(int code) {
+  switch (code) {
+    case MW_OK: return "ok";
+    case MW_ERR_INVALID_ARG: return "invalid argument";
+    case MW_ERR_NOT_SUBMERSIVE: return "layer is not a submersion (d_out > d_in or W W^T not positive definite)";
+    case MW_ERR_OOM: return "device allocator returned NULL";
+    case MW_ERR_FRAG_OVERFLOW: return "fragment store overflow";
+    case MW_ERR_HIP: return g_hip_error_text.c_str();
+    case MW_ERR_SIGN_MISMATCH: return "recomputed activation signs differ from the stored masks";
+    case MW_ERR_NOT_PLANNED: return "handle was planned without this entry point";
+    default: return "unknown error code";
+  }
+}
+
+// ------------------------------------------------------------------------------ kernel-level entries
+
+int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
+                const float* B, int32_t ldb, float beta, float* C, int32_t ldc, void* hip_stream) {
+  if (M < 0 || N < 0 || K < 0 || !C || (K > 0 && (!A || !B))) return MW_ERR_INVALID_ARG;
+  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_32K4) return MW_ERR_INVALID_ARG;
+  // leading dimensions must cover the fast index of each operand
+  const int a_fast = (op == MW_GEMM_TN) ? M : K, b_fast = (op == MW_GEMM_NT) ? K : N;
+  if (lda < a_fast || ldb < b_fast || ldc < N) return MW_ERR_INVALID_ARG;
+  MW_HIP(gemm_plain(op, tile, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, nullptr, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_bias_act_mask(const float* zin, const float* bias, int64_t rows, int32_t d, float alpha, float* x,
+                     uint64_t* mask, void* hip_stream) {
+  if (rows < 0 || d <= 0 || (rows > 0 && (!zin || !x || !mask))) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_bias_act_mask(zin, bias, rows, d, alpha, x, mask, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!h || !mask || !ct_z))) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_rev_scale(h, mask, n, alpha, ct_z, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, void* hip_stream) {
+  if (n < 0 || !offsets || (n > 0 && !mask)) return MW_ERR_INVALID_ARG;
+  if (n > (int64_t)0xFFFFFFFFll) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_frag_offsets(mask, n, offsets, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_frag_compact(const float* h, const uint64_t* mask, const uint32_t* offsets, int64_t n, float* frag,
+                    uint64_t capacity, int32_t* overflow_flag, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!h || !mask || !offsets || !frag))) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_frag_compact(h, mask, offsets, n, frag, nullptr, capacity, overflow_flag, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int32_t d, float alpha, const uint64_t* mask,
+                     const uint32_t* offsets, const float* frag, float* x, float* h_y, void* hip_stream) {
+  if (rows < 0 || d <= 0 || !(alpha >= 0.f)) return MW_ERR_INVALID_ARG;
+  if (rows > 0 && (!z || !ct_z || !x || !h_y)) return MW_ERR_INVALID_ARG;
+  if (rows > 0 && alpha == 0.f && (!mask || !offsets || !frag)) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_vijp_epilogue(z, ct_z, rows, d, alpha, mask, offsets, frag, nullptr, ~0ull, x, h_y, nullptr,
+                          static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_colsum(const float* a, int64_t rows, int32_t d, float scale, float* out, void* hip_stream) {
+  if (rows < 0 || d <= 0 || !out || (rows > 0 && !a)) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_colsum(a, rows, d, scale, out, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+size_t mw_loss_scratch_doubles(void) { return (size_t)LOSS_BLOCKS; }
+
+int mw_loss_grad(const float* xL, const float* t, int64_t rows, int32_t d, float scale, float* hL, float* loss,
+                 double* scratch, void* hip_stream) {
+  if (rows <= 0 || d <= 0 || !xL || !t || !hL || !scratch) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_loss_grad(xL, t, rows, d, scale, hL, loss, scratch, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream) {
+  if (n < 0 || (n > 0 && (!src || !dst))) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_copy(src, dst, n, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+}  // extern "C"

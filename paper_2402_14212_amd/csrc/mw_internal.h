@@ -1,0 +1,94 @@
+// Internal host-side interfaces between the translation units of libmoonwalk.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mw {
+
+// tile selectors (same values as MW_TILE_* in the public header)
+constexpr int TILE_AUTO = 0, TILE_128 = 1, TILE_64 = 2, TILE_32K4 = 3;
+constexpr int OP_NT = 0, OP_NN = 1, OP_TN = 2;
+
+// Tile choice for an M x N x K product on a 256-CU device. Deterministic in (M, N, K) only, so
+// that phase I and phase III compute a layer's pre-activations with the same kernel shape.
+int pick_tile(int M, int N, int K);
+
+// ---- GEMM launchers (gemm_*.hip). All enqueue on `stream` and return the launch status. ----
+
+// C = alpha * op(A, B) + beta * C + bias (bias indexed by column, may be NULL)
+hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const float* A, int64_t lda,
+                      const float* B, int64_t ldb, float beta, float* C, int64_t ldc, const float* bias,
+                      hipStream_t stream);
+
+// Xout[M][N] = act(X[M][K] W[N][K]^T + bias); mask (may be NULL) receives the packed signs and
+// then requires N % 32 == 0.
+hipError_t gemm_fwd_act(int tile, int M, int N, int K, const float* X, const float* W, const float* bias,
+                        float alpha, float* Xout, uint64_t* mask, hipStream_t stream);
+
+// Hout[M][N] = (H[M][K] .* slope) W[K][N], slope from packed mask bits of H's flat index
+hipError_t gemm_rev_mask(int tile, int M, int N, int K, const float* H, const uint64_t* mask, float alpha,
+                         const float* W, float* Hout, hipStream_t stream);
+// same, slope from the stored activation act[M][K] (> 0 ? 1 : alpha)
+hipError_t gemm_rev_act(int tile, int M, int N, int K, const float* H, const float* act, float alpha,
+                        const float* W, float* Hout, hipStream_t stream);
+
+// dW[M][N] = scale * CTZ[K][M]^T X[K][N];  db[M] = scale * sum_k CTZ[k][M]  (db may be NULL)
+hipError_t gemm_dw(int tile, int M, int N, int K, const float* CTZ, const float* X, float scale, float* dW,
+                   float* db, hipStream_t stream);
+// same with CTZ = Hy .* slope(act), act[K][M] the stored activation of this layer (backprop)
+hipError_t gemm_dw_act(int tile, int M, int N, int K, const float* Hy, const float* act, float alpha,
+                       const float* X, float scale, float* dW, float* db, hipStream_t stream);
+
+struct VijpArgs {
+  const float* X;        // [M][K]   layer input x_{i-1}
+  const float* W;        // [N][K]
+  const float* bias;     // [N] or NULL
+  const float* Hin;      // [M][K]   layer-input cotangent h_{i-1}
+  const float* P;        // [N][K]   right inverse
+  float alpha;
+  const uint64_t* mask;      // packed phase-I signs of this layer
+  const uint32_t* offsets;   // ReLU only
+  const float* frag;         // ReLU only
+  const uint64_t* frag_base; // ReLU only (device scalar)
+  uint64_t frag_capacity;
+  float* Xout;           // [M][N]
+  float* Hout;           // [M][N]
+  float* CTZ;            // [M][N]
+  unsigned long long* mismatches;  // device counter
+};
+hipError_t gemm_vijp_dual(int tile, int M, int N, int K, const VijpArgs& a, hipStream_t stream);
+
+// ---- elementwise / integer kernels (elementwise.hip) ----
+hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, int d, float alpha, float* x,
+                            uint64_t* mask, hipStream_t stream);
+hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream_t stream);
+hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
+                        hipStream_t stream);
+hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream);
+// base[i] for the ReLU layers in reverse-pass order: order[j] lists layer slots, counts[slot] points at
+// that layer's erased count (last entry of its offsets array)
+hipError_t ew_frag_bases(const uint32_t* const* count_ptrs, int n_relu, uint64_t* bases, uint64_t* total,
+                         hipStream_t stream);
+hipError_t ew_frag_compact(const float* h, const uint64_t* mask, const uint32_t* offsets, int64_t n, float* frag,
+                           const uint64_t* base, uint64_t capacity, int32_t* overflow_flag, hipStream_t stream);
+hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, float alpha, const uint64_t* mask,
+                            const uint32_t* offsets, const float* frag, const uint64_t* base, uint64_t capacity,
+                            float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream);
+hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream);
+constexpr int LOSS_BLOCKS = 256;
+hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
+                        double* scratch, hipStream_t stream);
+hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);
+hipError_t ew_fill_u32(uint32_t* p, uint32_t value, int64_t n, hipStream_t stream);
+
+// ---- right-inverse setup (setup_solve.hip) ----
+// P[d_out][d_in] = (W W^T)^{-1} W by blocked Cholesky and two blocked triangular solves.
+// work: at least setup_work_floats(d_out, d_in) floats. bad_pivot: device int32, set to 1 if a
+// pivot is not positive (W not of full row rank).
+size_t setup_work_floats(int d_out, int d_in);
+hipError_t setup_right_inverse(const float* W, int d_out, int d_in, float* P, float* work, int32_t* bad_pivot,
+                               hipStream_t stream);
+
+}  // namespace mw

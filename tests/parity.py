@@ -1,0 +1,93 @@
+"""Shared parity checks: HIP library results against the fp64 oracle on the same seeded inputs.
+
+Protocol
+* masks: the oracle forward pass is run with the GPU's masks forced on all earlier layers, so
+  that one fp32/fp64 sign disagreement near z = 0 does not cascade; the GPU mask of a layer must
+  equal (z_oracle > 0) on every element with |z_oracle| > MASK_GUARD * rms(z_oracle).
+* gradients: against fp64 backprop with the GPU's masks forced (the same piecewise-linear
+  piece), per tensor, normwise relative error <= GRAD_TOL.
+* integers (packed words, erased offsets, fragment bases and counts): bit-exact against the
+  oracle's own packing/compaction applied to the GPU's masks.
+"""
+import numpy as np
+
+from oracle import moonwalk_oracle as O
+
+GRAD_TOL = 1e-3      # normwise relative, per tensor (the stated bar for fp32 gradients)
+MASK_GUARD = 1e-4    # relative to the layer's rms pre-activation
+
+
+def gpu_masks(net, wl):
+    out = []
+    for i in range(wl.depth):
+        words = net.fetch_mask(i)
+        n = wl.batch * wl.widths[i + 1]
+        assert words.size == (n + 63) // 64
+        if n % 64:
+            assert int(words[-1]) >> (n % 64) == 0, "padding bits of the last mask word must be zero"
+        out.append(O.unpack_mask(words, n).reshape(wl.batch, wl.widths[i + 1]))
+    return out
+
+
+def check_masks(wl, masks):
+    _, zs, _ = O.forward(wl.W, wl.b, wl.alphas, wl.x, forced_masks=masks)
+    in_band = 0
+    for i, (z, m) in enumerate(zip(zs, masks)):
+        rms = float(np.sqrt(np.mean(z * z)))
+        sure = np.abs(z) > MASK_GUARD * rms
+        bad = (m != (z > 0)) & sure
+        assert not bad.any(), f"layer {i}: {int(bad.sum())} sign bits differ outside the guard band"
+        in_band += int((~sure).sum())
+    return in_band
+
+
+def grads_to_numpy(res):
+    return [g.detach().cpu().numpy() for g in res.dW], [g.detach().cpu().numpy() for g in res.db]
+
+
+def check_gradients(wl, masks, res, tol=GRAD_TOL):
+    ref = O.backprop(wl.W, wl.b, wl.alphas, wl.x, wl.t, forced_masks=masks)
+    dW, db = grads_to_numpy(res)
+    eW = [O.normwise_rel_err(a, b) for a, b in zip(dW, ref["dW"])]
+    eb = [O.normwise_rel_err(a, b) for a, b in zip(db, ref["db"])]
+    assert max(eW) <= tol, f"dW normwise errors per layer: {eW}"
+    assert max(eb) <= tol, f"db normwise errors per layer: {eb}"
+    loss = float(res.loss.item())
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-30, (loss, ref["loss"])
+    return ref, max(eW), max(eb)
+
+
+def check_fragment_index(net, wl, masks):
+    """Erased offsets, counts and layer bases: bit-exact against the oracle's definitions."""
+    running = 0
+    for i in range(wl.depth - 1, -1, -1):
+        if wl.alphas[i] != 0.0:
+            continue
+        off = net.fetch_frag_offsets(i)
+        np.testing.assert_array_equal(off, O.erased_word_offsets(masks[i]))
+        assert net.fetch_frag_base(i) == running
+        n0 = masks[i].size - int(masks[i].sum())
+        assert int(off[-1]) == n0
+        assert net.fetch_fragments(i).size == n0
+        running += n0
+    return running
+
+
+def check_moonwalk(net, wl, res, tol=GRAD_TOL, check_h0=True):
+    masks = gpu_masks(net, wl)
+    in_band = check_masks(wl, masks)
+    ref, eW, eb = check_gradients(wl, masks, res, tol)
+    stats = net.memory_stats()
+    assert stats["sign_mismatches"] == 0 and stats["frag_overflow"] == 0
+    if check_h0:
+        h0 = net.fetch_h0() / wl.loss_scale
+        assert O.normwise_rel_err(h0, ref["h"][0]) <= 1e-4
+    total = check_fragment_index(net, wl, masks)
+    assert stats["frag_used"] == total
+    # fragment values: the erased part of the phase-II cotangent of that layer
+    for i in range(wl.depth):
+        if wl.alphas[i] == 0.0:
+            got = net.fetch_fragments(i) / wl.loss_scale
+            want = O.compact_fragments(ref["h"][i + 1], masks[i])
+            assert O.normwise_rel_err(got, want) <= 1e-4
+    return {"max_dW_err": eW, "max_db_err": eb, "guard_band": in_band}

@@ -1,0 +1,100 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the public header
+declares, and its argument validation answers before anything touches the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moonwalk.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b((?:moonwalk|backprop|mw)_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(n for n in names if not n.endswith("_t")))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2402_14212_amd as mw
+    if not os.path.exists(mw.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return mw.load_library()
+
+
+def test_header_and_binding_agree_on_the_symbol_list():
+    import paper_2402_14212_amd as mw
+    assert declared_functions() == sorted(mw.EXPORTED_SYMBOLS)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_strerror_texts(lib):
+    assert lib.moonwalk_strerror(0) == b"ok"
+    for code in range(-7, 0):
+        assert len(lib.moonwalk_strerror(code)) > 3
+    assert b"unknown" in lib.moonwalk_strerror(-99)
+
+
+def test_setup_validation_answers_without_a_gpu(lib):
+    from paper_2402_14212_amd.binding import _Layer, _Config, _ALLOC_FN, _FREE_FN
+    handle = C.c_void_p()
+    null_alloc, null_free = _ALLOC_FN(0), _FREE_FN(0)
+    cfg = _Config(4, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None)
+    fake = 0x1000  # never dereferenced: validation fails first
+    ok_layer = (_Layer * 1)(_Layer(8, 8, fake, None, 0.1))
+    assert lib.moonwalk_setup(None, ok_layer, 1, C.byref(cfg), None) == -1
+    assert lib.moonwalk_setup(C.byref(handle), None, 1, C.byref(cfg), None) == -1
+    assert lib.moonwalk_setup(C.byref(handle), ok_layer, 0, C.byref(cfg), None) == -1
+    assert lib.moonwalk_setup(C.byref(handle), ok_layer, 1, None, None) == -1
+    # not a submersion: d_out > d_in  (Definition "Submersion": n' <= n)
+    wide = (_Layer * 1)(_Layer(8, 9, fake, None, 0.1))
+    assert lib.moonwalk_setup(C.byref(handle), wide, 1, C.byref(cfg), None) == -2
+    assert handle.value is None
+    # alpha outside [0, 1], mismatched widths, bad batch / scale / plan
+    assert lib.moonwalk_setup(C.byref(handle), (_Layer * 1)(_Layer(8, 8, fake, None, 1.5)), 1, C.byref(cfg), None) == -1
+    chain = (_Layer * 2)(_Layer(8, 8, fake, None, 0.1), _Layer(7, 7, fake, None, 0.1))
+    assert lib.moonwalk_setup(C.byref(handle), chain, 2, C.byref(cfg), None) == -1
+    for bad in (_Config(0, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
+                _Config(4, -1, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
+                _Config(4, 0, 0.0, 0, 1, 1.0, null_alloc, null_free, None),
+                _Config(4, 0, 1.0, 8, 1, 1.0, null_alloc, null_free, None)):
+        assert lib.moonwalk_setup(C.byref(handle), ok_layer, 1, C.byref(bad), None) == -1
+
+
+def test_failing_allocator_reports_oom(lib):
+    from paper_2402_14212_amd.binding import _Layer, _Config, _ALLOC_FN, _FREE_FN
+    calls = []
+    alloc = _ALLOC_FN(lambda n, ctx: calls.append(n) or None)
+    free = _FREE_FN(lambda p, ctx: None)
+    cfg = _Config(4, 0, 1.0, 0, 1, 1.0, alloc, free, None)
+    handle = C.c_void_p()
+    layer = (_Layer * 1)(_Layer(8, 8, 0x1000, None, 0.1))
+    assert lib.moonwalk_setup(C.byref(handle), layer, 1, C.byref(cfg), None) == -3
+    assert calls and handle.value is None
+
+
+def test_null_handles_are_rejected(lib):
+    assert lib.moonwalk_grad(None, None, None, None, None, None) == -1
+    assert lib.backprop_grad(None, None, None, None, None, None) == -1
+    assert lib.moonwalk_refresh(None, None) == -1
+    assert lib.moonwalk_memory_stats(None, None) == -1
+    assert lib.moonwalk_grad_layout(None, None, None, None) == -1
+    lib.moonwalk_destroy(None)
+    assert lib.mw_gemm_f32(7, 0, 1, 1, 1, 1.0, None, 1, None, 1, 0.0, None, 1, None) == -1
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import torch
+    import paper_2402_14212_amd as mw
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        mw.gemm_f32(mw.GEMM_NT, torch.zeros(2, 2), torch.zeros(2, 2))

@@ -7,18 +7,21 @@ namespace mw {
 
 template <int LA, int LB, bool COLSUM, class Xf, class Epi>
 inline hipError_t dispatch_gemm(int tile, int M, int N, int K, const float* A, int64_t lda, const float* B,
-                                int64_t ldb, const Xf& xf, const Epi& epi, float* colsum_out, float colsum_scale,
-                                hipStream_t stream) {
+                                int64_t ldb, const Xf& xf, const Epi& epi, bool xf_vec_ok, float* colsum_out,
+                                float colsum_scale, hipStream_t stream) {
   if (tile == TILE_AUTO) tile = pick_tile(M, N, K);
   switch (tile) {
     case TILE_128:
-      return launch_gemm<Tile128, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
+      return launch_gemm<Tile128, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
                                                           colsum_scale, stream);
     case TILE_64:
-      return launch_gemm<Tile64, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
+      return launch_gemm<Tile64, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
                                                          colsum_scale, stream);
     case TILE_32K4:
-      return launch_gemm<Tile32K4, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
+      return launch_gemm<Tile32K4, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
+                                                           colsum_scale, stream);
+    case TILE_32K8:
+      return launch_gemm<Tile32K8, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
                                                            colsum_scale, stream);
     default:
       return hipErrorInvalidValue;

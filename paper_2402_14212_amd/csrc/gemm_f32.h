@@ -1,10 +1,14 @@
 // fp32 MFMA GEMM building blocks for gfx950 (CDNA4), wave64.
 //
-// One workgroup = 4 wavefronts arranged WM x WN x WK. Each wavefront owns WTM x WTN output
-// tiles of 32x32 (v_mfma_f32_32x32x2_f32) and, when WK > 1, one slice of every K tile; the
-// K slices are summed through LDS in a fixed order, so results are bit-identical run to run.
-// Operand tiles are staged through double-buffered LDS with one barrier per K tile; the next
-// tile's global loads are in flight while the current one is multiplied.
+// One workgroup = WM x WN x WK wavefronts. Each wavefront owns WTM x WTN output tiles of 32x32
+// (v_mfma_f32_32x32x2_f32) and, when WK > 1, one 32-wide slice of every K tile; the K slices
+// are summed through LDS in a fixed order, so results are bit-identical run to run.
+//
+// Operand tiles travel global -> registers -> LDS. Global access is through buffer
+// instructions: an out-of-range element is given an offset beyond the buffer, for which the
+// hardware returns 0 (loads) or drops the access (stores), so the main loop and the epilogues
+// contain no bounds branches. Two K tiles are in flight in registers while a third is being
+// multiplied out of double-buffered LDS (one barrier per K tile).
 //
 // Operand layouts (ld = row stride in floats):
 //   KCONTIG  element (row, k) at p[row * ld + k]     (k is the fast index in memory)
@@ -18,6 +22,8 @@
 namespace mw {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KCONTIG = 0;
 constexpr int RCONTIG = 1;
@@ -32,9 +38,10 @@ struct TileCfg {
   static constexpr int NT = 64 * WM * WN * WK;  // threads per workgroup
   static constexpr int NACC = WTM * WTN;        // 32x32 accumulator tiles per wavefront
 };
-using Tile128 = TileCfg<2, 2, 2, 2, 1>;   // 128 x 128, K tile 32
-using Tile64 = TileCfg<1, 1, 2, 2, 1>;    //  64 x  64, K tile 32
+using Tile128 = TileCfg<2, 2, 2, 2, 1>;   // 128 x 128, K tile 32, 4 wavefronts
+using Tile64 = TileCfg<1, 1, 2, 2, 1>;    //  64 x  64, K tile 32, 4 wavefronts
 using Tile32K4 = TileCfg<1, 1, 1, 1, 4>;  //  32 x  32, K tile 128 split over 4 wavefronts
+using Tile32K8 = TileCfg<1, 1, 1, 1, 8>;  //  32 x  32, K tile 256 split over 8 wavefronts
 
 // LDS footprint (floats) of one operand tile of R rows.
 template <int LAYOUT, int R, int BK>
@@ -65,118 +72,165 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Guarded 4-wide global load. The 4 elements are (outer, inner .. inner+3) of a matrix whose
-// fast index is `inner`: address p[outer * ld + inner]. Out-of-range elements read as 0.
-// `vec_ok` (wave-uniform) says that p is 16-byte aligned and ld % 4 == 0, so that a chunk that
-// starts at a multiple of 4 and lies inside the matrix can be fetched with one dwordx4 load.
-__device__ __forceinline__ float4 load4(const float* __restrict__ p, int64_t ld, int outer, int inner,
-                                        int n_outer, int n_inner, bool vec_ok) {
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (outer < n_outer && inner < n_inner) {
-    const float* q = p + (int64_t)outer * ld + inner;
-    if (vec_ok && inner + 3 < n_inner) {
-      v = *reinterpret_cast<const float4*>(q);
-    } else {
-      v.x = q[0];
-      if (inner + 1 < n_inner) v.y = q[1];
-      if (inner + 2 < n_inner) v.z = q[2];
-      if (inner + 3 < n_inner) v.w = q[3];
-    }
-  }
-  return v;
+// Buffer resources. A raw buffer (stride 0) of `bytes` bytes starting at p: an access at byte
+// offset >= bytes reads 0 / is dropped. OOB is the offset handed to every masked-off lane.
+constexpr uint32_t OOB = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+// extent in bytes of an [n_outer][n_inner] matrix with row stride ld (floats)
+__device__ __forceinline__ uint32_t extent_bytes(int n_outer, int n_inner, int64_t ld) {
+  if (n_outer <= 0 || n_inner <= 0) return 0u;
+  return (uint32_t)((((int64_t)n_outer - 1) * ld + n_inner) * 4);
+}
+__device__ __forceinline__ float buf_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+__device__ __forceinline__ uint32_t buf_load_u32(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ float4 buf_load_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+  return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ void buf_store_f32(__amdgpu_buffer_rsrc_t r, uint32_t off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)off, 0, 0);
+}
+__device__ __forceinline__ void buf_store_u32(__amdgpu_buffer_rsrc_t r, uint32_t off, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b32(v, r, (int)off, 0, 0);
 }
 
-__device__ __forceinline__ bool vec_ok_for(const void* p, int64_t ld) {
-  return ((reinterpret_cast<uintptr_t>(p) & 15) == 0) && ((ld & 3) == 0);
-}
+// One 4-element chunk of an operand tile: element offset of its first element and how many of
+// its elements lie inside the matrix (VEC: 0 or 4).
+struct Chunk {
+  uint32_t e;   // outer * ld + inner
+  int nvalid;   // 0..4
+};
 
 // ---------------------------------------------------------------------------------------------
 // Operand-A transforms. A transform has two halves so that the global loads of a tile stay in
-// flight while the previous tile is multiplied: fetch() issues whatever extra loads it needs
-// next to the operand's own load, apply() runs just before the values are written to LDS.
-// The 4 values are (outer, inner .. inner+3) at flat offset outer * ld + inner; elements beyond
-// the matrix edge hold 0 already.
+// flight while earlier tiles are multiplied: fetch() issues whatever extra loads it needs next
+// to the operand's own load, apply() runs just before the values are written to LDS.
 
 struct ANone {
-  struct Aux {};
-  __device__ __forceinline__ void fetch(Aux&, int64_t, int, int, int, int, bool) const {}
-  __device__ __forceinline__ float4 apply(float4 v, const Aux&) const { return v; }
+  struct Dev {
+    struct Aux {};
+    __device__ __forceinline__ Dev() {}
+    __device__ __forceinline__ Dev(const ANone&, int, int, int64_t) {}
+    template <bool VEC>
+    __device__ __forceinline__ void fetch(Aux&, const Chunk&) const {}
+    __device__ __forceinline__ float4 apply(float4 v, const Aux&) const { return v; }
+  };
 };
 
 // Multiply by the activation slope taken from packed sign bits: bit e of the mask (LSB-first,
-// flat index e = outer * ld + inner of the full tensor) selects 1, a cleared bit selects alpha.
+// e = flat offset of the element in the full tensor) selects 1, a cleared bit selects alpha.
 struct ASlopeFromMask {
   const uint32_t* mask32;  // the uint64 words seen as little-endian halves
   float alpha;
-  struct Aux { uint32_t bits; };
-  __device__ __forceinline__ void fetch(Aux& aux, int64_t ld, int outer, int inner, int n_outer, int n_inner,
-                                        bool) const {
-    aux.bits = 0;
-    if (outer < n_outer && inner < n_inner) {
-      int64_t e = (int64_t)outer * ld + inner;
-      uint64_t lo = mask32[e >> 5];
-      int sh = (int)(e & 31);
-      // the 4 bits straddle two 32-bit halves only when ld is not a multiple of 4; the second
-      // half is read only if an element of this row lives there (so it is inside the mask)
-      if (sh > 28 && inner + (32 - sh) < n_inner) lo |= (uint64_t)mask32[(e >> 5) + 1] << 32;
-      aux.bits = (uint32_t)(lo >> sh);
+  struct Dev {
+    struct Aux { uint32_t bits; };
+    __amdgpu_buffer_rsrc_t rs;
+    float alpha;
+    __device__ __forceinline__ Dev(const ASlopeFromMask& p, int n_outer, int n_inner, int64_t ld) : alpha(p.alpha) {
+      uint32_t elems = extent_bytes(n_outer, n_inner, ld) / 4;
+      rs = make_rsrc(p.mask32, ((elems + 63u) / 64u) * 8u);
     }
-  }
-  __device__ __forceinline__ float4 apply(float4 v, const Aux& aux) const {
-    v.x *= (aux.bits & 1u) ? 1.f : alpha;
-    v.y *= (aux.bits & 2u) ? 1.f : alpha;
-    v.z *= (aux.bits & 4u) ? 1.f : alpha;
-    v.w *= (aux.bits & 8u) ? 1.f : alpha;
-    return v;
-  }
+    template <bool VEC>
+    __device__ __forceinline__ void fetch(Aux& aux, const Chunk& c) const {
+      uint32_t w = c.e >> 5, sh = c.e & 31u;
+      uint32_t lo = buf_load_u32(rs, c.nvalid > 0 ? w * 4u : OOB);
+      uint32_t bits = lo >> sh;
+      if (!VEC) {  // only an unaligned row stride lets the 4 bits straddle two 32-bit halves
+        uint32_t hi = buf_load_u32(rs, (sh > 28u && c.nvalid > (int)(32u - sh)) ? (w + 1u) * 4u : OOB);
+        bits = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
+      }
+      aux.bits = bits;
+    }
+    __device__ __forceinline__ float4 apply(float4 v, const Aux& aux) const {
+      v.x *= (aux.bits & 1u) ? 1.f : alpha;
+      v.y *= (aux.bits & 2u) ? 1.f : alpha;
+      v.z *= (aux.bits & 4u) ? 1.f : alpha;
+      v.w *= (aux.bits & 8u) ? 1.f : alpha;
+      return v;
+    }
+  };
 };
 
 // Multiply by the activation slope taken from the stored activation itself: x > 0 <=> z > 0.
 struct ASlopeFromAct {
   const float* act;  // same shape and row stride as A
   float alpha;
-  struct Aux { float4 a; };
-  __device__ __forceinline__ void fetch(Aux& aux, int64_t ld, int outer, int inner, int n_outer, int n_inner,
-                                        bool vec_ok) const {
-    aux.a = load4(act, ld, outer, inner, n_outer, n_inner, vec_ok && vec_ok_for(act, ld));
-  }
-  __device__ __forceinline__ float4 apply(float4 v, const Aux& aux) const {
-    v.x *= (aux.a.x > 0.f) ? 1.f : alpha;
-    v.y *= (aux.a.y > 0.f) ? 1.f : alpha;
-    v.z *= (aux.a.z > 0.f) ? 1.f : alpha;
-    v.w *= (aux.a.w > 0.f) ? 1.f : alpha;
-    return v;
-  }
+  struct Dev {
+    struct Aux { float4 a; };
+    __amdgpu_buffer_rsrc_t rs;
+    float alpha;
+    __device__ __forceinline__ Dev(const ASlopeFromAct& p, int n_outer, int n_inner, int64_t ld) : alpha(p.alpha) {
+      rs = make_rsrc(p.act, extent_bytes(n_outer, n_inner, ld));
+    }
+    template <bool VEC>
+    __device__ __forceinline__ void fetch(Aux& aux, const Chunk& c) const {
+      if (VEC) {
+        aux.a = buf_load_f32x4(rs, c.nvalid ? c.e * 4u : OOB);
+      } else {
+        aux.a.x = buf_load_f32(rs, c.nvalid > 0 ? c.e * 4u : OOB);
+        aux.a.y = buf_load_f32(rs, c.nvalid > 1 ? c.e * 4u + 4u : OOB);
+        aux.a.z = buf_load_f32(rs, c.nvalid > 2 ? c.e * 4u + 8u : OOB);
+        aux.a.w = buf_load_f32(rs, c.nvalid > 3 ? c.e * 4u + 12u : OOB);
+      }
+    }
+    __device__ __forceinline__ float4 apply(float4 v, const Aux& aux) const {
+      v.x *= (aux.a.x > 0.f) ? 1.f : alpha;
+      v.y *= (aux.a.y > 0.f) ? 1.f : alpha;
+      v.z *= (aux.a.z > 0.f) ? 1.f : alpha;
+      v.w *= (aux.a.w > 0.f) ? 1.f : alpha;
+      return v;
+    }
+  };
 };
 
 // ---------------------------------------------------------------------------------------------
 // Global -> register -> LDS staging of one operand tile (R rows x BK k).
+// VEC: the operand is 16-byte aligned with ld % 4 == 0 and a fast extent that is a multiple of
+// 4, so every chunk is entirely inside or entirely outside and moves as one dwordx4.
 
-template <int LAYOUT, int R, int BK, int NT, class Xf>
+// XfDev is the device-side state of an operand transform (ANone::Dev etc.).
+template <int LAYOUT, int R, int BK, int NT, bool VEC, class XfDev>
 struct TileLoader {
-  static constexpr int NV = R * BK / 4 / NT;  // float4 per thread
+  static constexpr int NV = R * BK / 4 / NT;  // chunks per thread
   static_assert(R * BK % (4 * NT) == 0, "tile must divide evenly over the workgroup");
   float4 v[NV];
-  typename Xf::Aux aux[NV];
+  typename XfDev::Aux aux[NV];
 
-  __device__ __forceinline__ void load(const float* __restrict__ p, int64_t ld, int row0, int k0, int n_rows,
-                                       int n_k, bool vec_ok, const Xf& xf) {
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rs, int64_t ld, int row0, int k0, int n_rows, int n_k,
+                                       const XfDev& xf) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       int f = (int)threadIdx.x + i * NT;
+      int outer, inner, n_outer, n_inner;
       if (LAYOUT == KCONTIG) {
-        int r = f / (BK / 4), c4 = f % (BK / 4);
-        v[i] = load4(p, ld, row0 + r, k0 + 4 * c4, n_rows, n_k, vec_ok);
-        xf.fetch(aux[i], ld, row0 + r, k0 + 4 * c4, n_rows, n_k, vec_ok);
+        outer = row0 + f / (BK / 4); inner = k0 + 4 * (f % (BK / 4)); n_outer = n_rows; n_inner = n_k;
       } else {
-        int k = f / (R / 4), r4 = f % (R / 4);
-        v[i] = load4(p, ld, k0 + k, row0 + 4 * r4, n_k, n_rows, vec_ok);
-        xf.fetch(aux[i], ld, k0 + k, row0 + 4 * r4, n_k, n_rows, vec_ok);
+        outer = k0 + f / (R / 4); inner = row0 + 4 * (f % (R / 4)); n_outer = n_k; n_inner = n_rows;
       }
+      Chunk c;
+      c.e = (uint32_t)outer * (uint32_t)ld + (uint32_t)inner;
+      int left = n_inner - inner;
+      c.nvalid = (outer < n_outer && left > 0) ? (left < 4 ? left : 4) : 0;
+      if (VEC) {
+        v[i] = buf_load_f32x4(rs, c.nvalid ? c.e * 4u : OOB);
+      } else {
+        v[i].x = buf_load_f32(rs, c.nvalid > 0 ? c.e * 4u : OOB);
+        v[i].y = buf_load_f32(rs, c.nvalid > 1 ? c.e * 4u + 4u : OOB);
+        v[i].z = buf_load_f32(rs, c.nvalid > 2 ? c.e * 4u + 8u : OOB);
+        v[i].w = buf_load_f32(rs, c.nvalid > 3 ? c.e * 4u + 12u : OOB);
+      }
+      xf.template fetch<VEC>(aux[i], c);
     }
   }
 
-  __device__ __forceinline__ void store(float* __restrict__ lds, const Xf& xf) const {
+  __device__ __forceinline__ void store(float* __restrict__ lds, const XfDev& xf) const {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       int f = (int)threadIdx.x + i * NT;
@@ -207,16 +261,46 @@ __device__ __forceinline__ void read_frag8(const float* __restrict__ lds, int ro
   }
 }
 
+// Multiply one staged K tile into the accumulators.
+template <class Cfg, int LA, int LB, bool COLSUM>
+__device__ __forceinline__ void mma_stage(const float* __restrict__ sa, const float* __restrict__ sb, int wm, int wn,
+                                          int wk, int r, int g, f32x16 (&acc)[Cfg::NACC], float (&asum)[Cfg::WTM]) {
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int kbase = 32 * wk + 16 * g + 8 * half;
+    float fa[Cfg::WTM][8], fb[Cfg::WTN][8];
+#pragma unroll
+    for (int tm = 0; tm < Cfg::WTM; ++tm)
+      read_frag8<LA, Cfg::BM, Cfg::BK>(sa, (wm * Cfg::WTM + tm) * 32 + r, kbase, fa[tm]);
+#pragma unroll
+    for (int tn = 0; tn < Cfg::WTN; ++tn)
+      read_frag8<LB, Cfg::BN, Cfg::BK>(sb, (wn * Cfg::WTN + tn) * 32 + r, kbase, fb[tn]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+      for (int tm = 0; tm < Cfg::WTM; ++tm) {
+        if (COLSUM) asum[tm] += fa[tm][j];
+#pragma unroll
+        for (int tn = 0; tn < Cfg::WTN; ++tn)
+          acc[tm * Cfg::WTN + tn] =
+              __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][j], fb[tn][j], acc[tm * Cfg::WTN + tn], 0, 0, 0);
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Main loop: acc += A_tile(m0.., :) * B_tile(n0.., :)^T over the whole K range.
 // Must be entered by the whole workgroup; ends with a barrier, so LDS may be reused afterwards.
 // If COLSUM, asum[tm] accumulates, per lane, the sum of the A values that lane fed to the MFMA
 // (after the A transform); combined over lanes/waves by the caller into column sums of A.
+// The accumulation order over K is fixed (tile by tile, the same for every launch with the same
+// Cfg), which is what makes two kernels that call this with the same operands agree bit for bit.
 
-template <class Cfg, int LA, int LB, bool COLSUM, class Xf>
+template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, class XfDev>
 __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
                                               int64_t ldb, int M, int N, int K, int m0, int n0,
-                                              float* __restrict__ lds, const Xf& xf, f32x16 (&acc)[Cfg::NACC],
+                                              float* __restrict__ lds, const XfDev& xf, f32x16 (&acc)[Cfg::NACC],
                                               float (&asum)[Cfg::WTM]) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
   constexpr int A_FLOATS = lds_tile_floats<LA, BM, BK>();
@@ -229,54 +313,42 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
   const int wm = wave / (Cfg::WK * Cfg::WN);
   const int r = lane & 31, g = lane >> 5;
 
-  const bool a_vec = vec_ok_for(A, lda), b_vec = vec_ok_for(B, ldb);
+  const __amdgpu_buffer_rsrc_t ra =
+      make_rsrc(A, LA == KCONTIG ? extent_bytes(M, K, lda) : extent_bytes(K, M, lda));
+  const __amdgpu_buffer_rsrc_t rb =
+      make_rsrc(B, LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb));
+  const ANone::Dev none;
 
-  TileLoader<LA, BM, BK, Cfg::NT, Xf> la;
-  TileLoader<LB, BN, BK, Cfg::NT, ANone> lb;
-  const ANone none{};
+  TileLoader<LA, BM, BK, Cfg::NT, VEC, XfDev> a0, a1;
+  TileLoader<LB, BN, BK, Cfg::NT, VEC, ANone::Dev> b0, b1;
+  float* s0 = lds;
+  float* s1 = lds + STAGE;
 
   const int nkt = (K + BK - 1) / BK;
-  la.load(A, lda, m0, 0, M, K, a_vec, xf);
-  lb.load(B, ldb, n0, 0, N, K, b_vec, none);
-  la.store(lds, xf);
-  lb.store(lds + A_FLOATS, none);
+  // tiles beyond K load as zeros without touching memory, so the prologue needs no tests
+  a0.load(ra, lda, m0, 0, M, K, xf);
+  b0.load(rb, ldb, n0, 0, N, K, none);
+  a1.load(ra, lda, m0, BK, M, K, xf);
+  b1.load(rb, ldb, n0, BK, N, K, none);
+  a0.store(s0, xf);
+  b0.store(s0 + A_FLOATS, none);
   __syncthreads();
 
-  for (int t = 0; t < nkt; ++t) {
-    const float* sa = lds + (t & 1) * STAGE;
-    const float* sb = sa + A_FLOATS;
-    const bool more = (t + 1 < nkt);
-    if (more) {
-      la.load(A, lda, m0, (t + 1) * BK, M, K, a_vec, xf);
-      lb.load(B, ldb, n0, (t + 1) * BK, N, K, b_vec, none);
-    }
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int kbase = 32 * wk + 16 * g + 8 * half;
-      float fa[Cfg::WTM][8], fb[Cfg::WTN][8];
-#pragma unroll
-      for (int tm = 0; tm < Cfg::WTM; ++tm)
-        read_frag8<LA, BM, BK>(sa, (wm * Cfg::WTM + tm) * 32 + r, kbase, fa[tm]);
-#pragma unroll
-      for (int tn = 0; tn < Cfg::WTN; ++tn)
-        read_frag8<LB, BN, BK>(sb, (wn * Cfg::WTN + tn) * 32 + r, kbase, fb[tn]);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-#pragma unroll
-        for (int tm = 0; tm < Cfg::WTM; ++tm) {
-          if (COLSUM) asum[tm] += fa[tm][j];
-#pragma unroll
-          for (int tn = 0; tn < Cfg::WTN; ++tn)
-            acc[tm * Cfg::WTN + tn] =
-                __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][j], fb[tn][j], acc[tm * Cfg::WTN + tn], 0, 0, 0);
-        }
-      }
-    }
-    if (more) {
-      float* da = lds + ((t + 1) & 1) * STAGE;
-      la.store(da, xf);
-      lb.store(da + A_FLOATS, none);
-    }
+  for (int t = 0; t < nkt; t += 2) {
+    // tile t is in stage 0, tile t+1 in registers (a1, b1); fetch tile t+2
+    a0.load(ra, lda, m0, (t + 2) * BK, M, K, xf);
+    b0.load(rb, ldb, n0, (t + 2) * BK, N, K, none);
+    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
+    a1.store(s1, xf);
+    b1.store(s1 + A_FLOATS, none);
+    __syncthreads();
+    if (t + 1 >= nkt) break;
+    // tile t+1 is in stage 1, tile t+2 in registers (a0, b0); fetch tile t+3
+    a1.load(ra, lda, m0, (t + 3) * BK, M, K, xf);
+    b1.load(rb, ldb, n0, (t + 3) * BK, N, K, none);
+    mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
+    a0.store(s0, xf);
+    b0.store(s0 + A_FLOATS, none);
     __syncthreads();
   }
 }
@@ -320,13 +392,16 @@ __device__ __forceinline__ bool reduce_k_slices(float* __restrict__ lds, f32x16 
   return true;
 }
 
-// Walk the accumulator registers of this wavefront and hand every element to the epilogue.
-// Output element of accumulator register i of a 32x32 tile: row 8*(i/4) + 4*(lane>>5) + i%4,
-// column lane & 31. The epilogue is called by all 64 lanes together (it may use ballots):
-//   epi(row, col, valid, v[NSETS])
+// Position of this lane's 16 accumulator values inside a 32x32 tile: value i sits in row
+// 8*(i/4) + 4*(lane>>5) + i%4 and column lane & 31.
+__device__ __forceinline__ int acc_row(int i, int g) { return 8 * (i / 4) + 4 * g + (i % 4); }
+
+// Hand every 32x32 accumulator tile of this wavefront to the epilogue, which is called by all
+// 64 lanes together (it may use ballots):  epi.tile(M, N, row_base, col, g, acc_tile[NSETS])
+// where row_base is the tile's first row and col this lane's column.
 template <class Cfg, int NSETS, class Epi>
-__device__ __forceinline__ void for_each_output(int M, int N, int m0, int n0, const f32x16 (&acc)[NSETS][Cfg::NACC],
-                                                Epi& epi) {
+__device__ __forceinline__ void for_each_tile(int M, int N, int m0, int n0, const f32x16 (&acc)[NSETS][Cfg::NACC],
+                                              Epi& epi) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int wn = (wave / Cfg::WK) % Cfg::WN;
@@ -334,16 +409,12 @@ __device__ __forceinline__ void for_each_output(int M, int N, int m0, int n0, co
 #pragma unroll
   for (int tm = 0; tm < Cfg::WTM; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < Cfg::WTN; ++tn)
+    for (int tn = 0; tn < Cfg::WTN; ++tn) {
+      f32x16 t[NSETS];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        int row = m0 + (wm * Cfg::WTM + tm) * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i % 4);
-        int col = n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31);
-        float v[NSETS];
-#pragma unroll
-        for (int s = 0; s < NSETS; ++s) v[s] = acc[s][tm * Cfg::WTN + tn][i];
-        epi(row, col, row < M && col < N, v);
-      }
+      for (int s = 0; s < NSETS; ++s) t[s] = acc[s][tm * Cfg::WTN + tn];
+      epi.tile(M, N, m0 + (wm * Cfg::WTM + tm) * 32, n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31), lane >> 5, t);
+    }
 }
 
 // Logical tile coordinates of this workgroup: XCD-aware, m fastest (all row tiles of one

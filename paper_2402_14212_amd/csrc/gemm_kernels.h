@@ -1,4 +1,8 @@
 // Kernels and epilogues built on gemm_f32.h, and their host-side launch helpers.
+//
+// Epilogues are branch-free: every global access is a buffer access whose offset is OOB for
+// lanes that fall outside the matrix, and all loads of a 32x32 tile are issued before the first
+// use, so the memory latency of an epilogue is paid once per tile, not once per element.
 #pragma once
 
 #include "gemm_f32.h"
@@ -13,13 +17,40 @@ struct EpiStore {
   int64_t ldc;
   float alpha, beta;
   const float* bias;
-  __device__ __forceinline__ void operator()(int row, int col, bool valid, const float (&v)[1]) const {
-    if (!valid) return;
-    float r = alpha * v[0];
-    if (bias) r += bias[col];
-    float* c = C + (int64_t)row * ldc + col;
-    if (beta != 0.f) r += beta * *c;
-    *c = r;
+  struct Dev;
+};
+struct EpiStore::Dev {
+  __amdgpu_buffer_rsrc_t rc, rbias;
+  int64_t ldc;
+  float alpha, beta;
+  bool bias;
+  __device__ __forceinline__ Dev(const EpiStore& p, int M, int N)
+      : ldc(p.ldc), alpha(p.alpha), beta(p.beta), bias(p.bias != nullptr) {
+    rc = make_rsrc(p.C, extent_bytes(M, N, p.ldc));
+    rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
+  }
+  __device__ __forceinline__ void finish() const {}
+  __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[1]) const {
+    const bool cv = col < N;
+    const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
+    uint32_t off[16];
+    float old[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = row_base + acc_row(i, g);
+      off[i] = (cv && row < M) ? ((uint32_t)row * (uint32_t)ldc + (uint32_t)col) * 4u : OOB;
+    }
+    if (beta != 0.f) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) old[i] = buf_load_f32(rc, off[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float r = alpha * t[0][i];
+      if (bias) r += bv;
+      if (beta != 0.f) r += beta * old[i];
+      buf_store_f32(rc, off[i], r);
+    }
   }
 };
 
@@ -29,32 +60,46 @@ struct EpiStore {
 template <bool MASK>
 struct EpiFwdAct {
   float* X;
-  int64_t ldx;
   const float* bias;
   float alpha;
   uint32_t* mask32;
-  int64_t n_cols;
-  __device__ __forceinline__ void operator()(int row, int col, bool valid, const float (&v)[1]) const {
-    float z = 0.f;
-    if (valid) {
-      z = v[0];
-      if (bias) z += bias[col];
+  struct Dev {
+    __amdgpu_buffer_rsrc_t rx, rbias, rmask;
+    float alpha;
+    bool bias;
+    __device__ __forceinline__ Dev(const EpiFwdAct& p, int M, int N) : alpha(p.alpha), bias(p.bias != nullptr) {
+      rx = make_rsrc(p.X, extent_bytes(M, N, N));
+      rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
+      rmask = make_rsrc(p.mask32, MASK ? (uint32_t)(((int64_t)M * N + 63) / 64) * 8u : 0u);
     }
-    bool bit = valid && (z > 0.f);
-    if (valid) X[(int64_t)row * ldx + col] = bit ? z : alpha * z;
-    if (MASK) {
-      unsigned long long bal = __ballot(bit);
-      int lane = threadIdx.x & 63;
-      if ((lane & 31) == 0 && valid)
-        mask32[((int64_t)row * n_cols + col) >> 5] = lane ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+    __device__ __forceinline__ void finish() const {}
+    __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[1]) const {
+    const bool cv = col < N;
+    const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = row_base + acc_row(i, g);
+      bool valid = cv && row < M;
+      uint32_t e = (uint32_t)row * (uint32_t)N + (uint32_t)col;
+      float z = t[0][i];
+      if (bias) z += bv;
+      bool bit = valid && (z > 0.f);
+      buf_store_f32(rx, valid ? e * 4u : OOB, bit ? z : alpha * z);
+      if (MASK) {
+        unsigned long long bal = __ballot(bit);
+        uint32_t word = g ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+        buf_store_u32(rmask, ((lane & 31) == 0 && valid) ? (e >> 5) * 4u : OOB, word);
+      }
     }
   }
+  };
 };
 
-// Phase-III epilogue for one layer. v[0] = x_{i-1} W^T (pre-bias), v[1] = h_{i-1} P^T.
+// Phase-III epilogue for one layer. t[0] = x_{i-1} W^T (pre-bias), t[1] = h_{i-1} P^T.
 //   leaky: m = (z > 0) recomputed; h_y = m ? ct_z : ct_z * (1/alpha).
 //   ReLU : m = stored bit; ct_z zeroed where erased; h_y restored from the fragment store at
-//          rank = offsets[word] + popcount(erased bits below e in the word).
+//          rank = offsets[word] + popcount(erased bits below e in the 64-bit word).
 // Every recomputed sign is compared with the stored phase-I bit; differences are counted.
 template <bool RELU>
 struct EpiVijp {
@@ -68,42 +113,90 @@ struct EpiVijp {
   float* X;
   float* H;
   float* CTZ;
-  int64_t n_cols;
   unsigned long long* mismatches;
-  __device__ __forceinline__ void operator()(int row, int col, bool valid, const float (&v)[2]) const {
-    if (!valid) return;
-    int64_t e = (int64_t)row * n_cols + col;
-    float z = v[0];
-    if (bias) z += bias[col];
-    uint64_t w = mask[e >> 6];
-    int sh = (int)(e & 63);
-    bool stored = (w >> sh) & 1ull;
-    bool fresh = z > 0.f;
-    if (fresh != stored) atomicAdd(mismatches, 1ull);
-    bool bit;
-    float c, h;
-    if (RELU) {
-      bit = stored;
-      c = bit ? v[1] : 0.f;
-      h = c;
-      if (!bit) {
-        uint64_t idx = *frag_base + offsets[e >> 6] + (uint64_t)__popcll(~w & ((1ull << sh) - 1ull));
-        h = idx < frag_capacity ? frag[idx] : 0.f;
-      }
-    } else {
-      bit = fresh;
-      c = v[1];
-      h = bit ? c : c * inv_alpha;
-    }
-    X[e] = bit ? z : alpha * z;
-    H[e] = h;
-    CTZ[e] = c;
+  struct Dev {
+  __amdgpu_buffer_rsrc_t rbias, rmask, roff, rfrag, rx, rh, rc;
+  float alpha, inv_alpha;
+  bool bias;
+  unsigned long long* mismatches;
+  uint32_t mism;
+  __device__ __forceinline__ Dev(const EpiVijp& p, int M, int N)
+      : alpha(p.alpha), inv_alpha(p.inv_alpha), bias(p.bias != nullptr), mismatches(p.mismatches), mism(0) {
+    const uint32_t words = (uint32_t)(((int64_t)M * N + 63) / 64);
+    rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
+    rmask = make_rsrc(p.mask, words * 8u);
+    roff = make_rsrc(p.offsets, RELU ? (words + 1u) * 4u : 0u);
+    uint64_t base = RELU ? *p.frag_base : 0ull;
+    // the layer's slice of the store; reads past the capacity return 0
+    uint64_t room = (RELU && base < p.frag_capacity) ? p.frag_capacity - base : 0ull;
+    if (room > 0x1FFFFFFFull) room = 0x1FFFFFFFull;
+    rfrag = make_rsrc(RELU ? p.frag + base : nullptr, (uint32_t)room * 4u);
+    rx = make_rsrc(p.X, extent_bytes(M, N, N));
+    rh = make_rsrc(p.H, extent_bytes(M, N, N));
+    rc = make_rsrc(p.CTZ, extent_bytes(M, N, N));
   }
+  __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[2]) {
+    const bool cv = col < N;
+    const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
+    uint32_t e[16], lo[16], hi[16], rank0[16];
+    bool valid[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = row_base + acc_row(i, g);
+      valid[i] = cv && row < M;
+      e[i] = (uint32_t)row * (uint32_t)N + (uint32_t)col;
+      uint32_t w = e[i] >> 6;
+      if (RELU) {
+        lo[i] = buf_load_u32(rmask, valid[i] ? w * 8u : OOB);
+        hi[i] = buf_load_u32(rmask, valid[i] ? w * 8u + 4u : OOB);
+        rank0[i] = buf_load_u32(roff, valid[i] ? w * 4u : OOB);
+      } else {
+        lo[i] = buf_load_u32(rmask, valid[i] ? (e[i] >> 5) * 4u : OOB);
+      }
+    }
+    float restored[16];
+    bool stored[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (RELU) {
+        uint64_t w = ((uint64_t)hi[i] << 32) | lo[i];
+        uint32_t sh = e[i] & 63u;
+        stored[i] = (w >> sh) & 1ull;
+        uint32_t idx = rank0[i] + (uint32_t)__popcll(~w & ((1ull << sh) - 1ull));
+        restored[i] = buf_load_f32(rfrag, (valid[i] && !stored[i]) ? idx * 4u : OOB);
+      } else {
+        stored[i] = (lo[i] >> (e[i] & 31u)) & 1u;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float z = t[0][i];
+      if (bias) z += bv;
+      const bool fresh = z > 0.f;
+      if (valid[i] && fresh != stored[i]) ++mism;
+      const uint32_t off = valid[i] ? e[i] * 4u : OOB;
+      if (RELU) {
+        const float c = stored[i] ? t[1][i] : 0.f;
+        buf_store_f32(rx, off, stored[i] ? z : alpha * z);
+        buf_store_f32(rh, off, stored[i] ? c : restored[i]);
+        buf_store_f32(rc, off, c);
+      } else {
+        const float c = t[1][i];
+        buf_store_f32(rx, off, fresh ? z : alpha * z);
+        buf_store_f32(rh, off, fresh ? c : c * inv_alpha);
+        buf_store_f32(rc, off, c);
+      }
+    }
+  }
+  __device__ __forceinline__ void finish() const {
+    if (mism) atomicAdd(mismatches, (unsigned long long)mism);
+  }
+  };
 };
 
 // ------------------------------------------------------------------------------------ kernels
 
-template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
+template <class Cfg, int LA, int LB, bool VEC, class Xf, class Epi, bool COLSUM>
 __global__ void __launch_bounds__(Cfg::NT)
 gemm_kernel(int M, int N, int K, const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
             int64_t ldb, Xf xf, Epi epi, float* __restrict__ colsum_out, float colsum_scale, int tiles_m,
@@ -122,14 +215,19 @@ gemm_kernel(int M, int N, int K, const float* __restrict__ A, int64_t lda, const
 #pragma unroll
   for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
-  gemm_mainloop<Cfg, LA, LB, COLSUM>(A, lda, B, ldb, M, N, K, m0, n0, lds, xf, acc[0], asum);
+  {
+    const typename Xf::Dev xd(xf, LA == KCONTIG ? M : K, LA == KCONTIG ? K : M, lda);
+    gemm_mainloop<Cfg, LA, LB, VEC, COLSUM>(A, lda, B, ldb, M, N, K, m0, n0, lds, xd, acc[0], asum);
+  }
 
   if (COLSUM) {
 #pragma unroll
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] += __shfl_xor(asum[t], 32);
   }
   if (!reduce_k_slices<Cfg, 1>(lds, acc, asum)) return;
-  for_each_output<Cfg, 1>(M, N, m0, n0, acc, epi);
+  typename Epi::Dev ed(epi, M, N);
+  for_each_tile<Cfg, 1>(M, N, m0, n0, acc, ed);
+  ed.finish();
 
   if (COLSUM && n0 == 0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -145,8 +243,8 @@ gemm_kernel(int M, int N, int K, const float* __restrict__ A, int64_t lda, const
 }
 
 // One layer of the phase-III sweep: both NT products for the same output tile, then EpiVijp.
-//   acc0 = X[Bt][K] W[N][K]^T ,  acc1 = Hin[Bt][K] P[N][K]^T
-template <class Cfg, bool RELU>
+//   acc0 = X[M][K] W[N][K]^T ,  acc1 = Hin[M][K] P[N][K]^T
+template <class Cfg, bool VEC, bool RELU>
 __global__ void __launch_bounds__(Cfg::NT)
 vijp_dual_kernel(int M, int N, int K, const float* __restrict__ X, const float* __restrict__ W,
                  const float* __restrict__ Hin, const float* __restrict__ P, EpiVijp<RELU> epi, int tiles_m,
@@ -167,19 +265,30 @@ vijp_dual_kernel(int M, int N, int K, const float* __restrict__ X, const float* 
 #pragma unroll
   for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
-  const ANone none{};
-  gemm_mainloop<Cfg, KCONTIG, KCONTIG, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
-  gemm_mainloop<Cfg, KCONTIG, KCONTIG, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
+  const ANone::Dev none;
+  gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
+  gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
   if (!reduce_k_slices<Cfg, 2>(lds, acc, asum)) return;
-  for_each_output<Cfg, 2>(M, N, m0, n0, acc, epi);
+  typename EpiVijp<RELU>::Dev ed(epi, M, N);
+  for_each_tile<Cfg, 2>(M, N, m0, n0, acc, ed);
+  ed.finish();
 }
 
 // ------------------------------------------------------------------------------------ launch helpers
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+// an operand qualifies for dwordx4 staging when every 4-chunk is all-in or all-out and aligned
+inline bool operand_vec_ok(const void* p, int64_t ld, int fast_extent) {
+  return aligned16(p) && (ld % 4 == 0) && (fast_extent % 4 == 0);
+}
+// buffer offsets are 31-bit: the byte extent of every operand must stay below 2 GiB
+inline bool extent_ok(int64_t n_outer, int64_t n_inner, int64_t ld) {
+  return n_outer <= 0 || n_inner <= 0 || ((n_outer - 1) * ld + n_inner) * 4 < (int64_t)0x7FFFFFFF;
+}
 
-// Kernels here use up to ~72 KiB of dynamic LDS (the CU has 160 KiB); anything above the 64 KiB
-// default needs the limit raised once per kernel.
+// Kernels here use up to ~130 KiB of dynamic LDS (the CU has 160 KiB); anything above the
+// default limit needs it raised once per kernel.
 template <class KernelT>
 inline hipError_t ensure_lds(KernelT kernel, int bytes) {
   if (bytes <= 48 * 1024) return hipSuccess;
@@ -187,12 +296,11 @@ inline hipError_t ensure_lds(KernelT kernel, int bytes) {
                              bytes);
 }
 
-template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
-inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
-                              const Xf& xf, const Epi& epi, float* colsum_out, float colsum_scale,
-                              hipStream_t stream) {
-  if (M <= 0 || N <= 0) return hipSuccess;
-  auto kernel = gemm_kernel<Cfg, LA, LB, Xf, Epi, COLSUM>;
+template <class Cfg, int LA, int LB, bool VEC, class Xf, class Epi, bool COLSUM>
+inline hipError_t launch_gemm_v(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
+                                const Xf& xf, const Epi& epi, float* colsum_out, float colsum_scale,
+                                hipStream_t stream) {
+  auto kernel = gemm_kernel<Cfg, LA, LB, VEC, Xf, Epi, COLSUM>;
   constexpr int bytes = lds_bytes<Cfg, LA, LB, 1>();
   static hipError_t attr = ensure_lds(kernel, bytes);
   if (attr != hipSuccess) return attr;
@@ -202,11 +310,27 @@ inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, 
   return hipGetLastError();
 }
 
-template <class Cfg, bool RELU>
-inline hipError_t launch_vijp_dual(int M, int N, int K, const float* X, const float* W, const float* Hin,
-                                   const float* P, const EpiVijp<RELU>& epi, hipStream_t stream) {
+template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
+inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
+                              const Xf& xf, const Epi& epi, bool xf_vec_ok, float* colsum_out, float colsum_scale,
+                              hipStream_t stream) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  auto kernel = vijp_dual_kernel<Cfg, RELU>;
+  const bool a_k = (LA == KCONTIG), b_k = (LB == KCONTIG);
+  if (!extent_ok(a_k ? M : K, a_k ? K : M, lda) || !extent_ok(b_k ? N : K, b_k ? K : N, ldb) ||
+      !extent_ok(M, N, (int64_t)N > 0 ? N : 1))
+    return hipErrorInvalidValue;
+  const bool vec = xf_vec_ok && operand_vec_ok(A, lda, a_k ? K : M) && operand_vec_ok(B, ldb, b_k ? K : N);
+  if (vec)
+    return launch_gemm_v<Cfg, LA, LB, true, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
+                                                            colsum_scale, stream);
+  return launch_gemm_v<Cfg, LA, LB, false, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
+                                                           colsum_scale, stream);
+}
+
+template <class Cfg, bool VEC, bool RELU>
+inline hipError_t launch_vijp_dual_v(int M, int N, int K, const float* X, const float* W, const float* Hin,
+                                     const float* P, const EpiVijp<RELU>& epi, hipStream_t stream) {
+  auto kernel = vijp_dual_kernel<Cfg, VEC, RELU>;
   constexpr int bytes = lds_bytes<Cfg, KCONTIG, KCONTIG, 2>();
   static hipError_t attr = ensure_lds(kernel, bytes);
   if (attr != hipSuccess) return attr;
@@ -214,6 +338,16 @@ inline hipError_t launch_vijp_dual(int M, int N, int K, const float* X, const fl
   hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(Cfg::NT), bytes, stream, M, N, K, X, W, Hin, P, epi,
                      tiles_m, tiles_n);
   return hipGetLastError();
+}
+
+template <class Cfg, bool RELU>
+inline hipError_t launch_vijp_dual(int M, int N, int K, const float* X, const float* W, const float* Hin,
+                                   const float* P, const EpiVijp<RELU>& epi, hipStream_t stream) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (!extent_ok(M, K, K) || !extent_ok(N, K, K) || !extent_ok(M, N, N)) return hipErrorInvalidValue;
+  const bool vec = (K % 4 == 0) && aligned16(X) && aligned16(W) && aligned16(Hin) && aligned16(P);
+  if (vec) return launch_vijp_dual_v<Cfg, true, RELU>(M, N, K, X, W, Hin, P, epi, stream);
+  return launch_vijp_dual_v<Cfg, false, RELU>(M, N, K, X, W, Hin, P, epi, stream);
 }
 
 }  // namespace mw

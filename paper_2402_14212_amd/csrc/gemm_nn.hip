@@ -6,21 +6,23 @@ namespace mw {
 hipError_t gemm_plain_nn(int tile, int M, int N, int K, float alpha, const float* A, int64_t lda, const float* B,
                          int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream) {
   EpiStore epi{C, ldc, alpha, beta, bias};
-  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, A, lda, B, ldb, ANone{}, epi, nullptr, 0.f, stream);
+  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, A, lda, B, ldb, ANone{}, epi, true, nullptr, 0.f, stream);
 }
 
 hipError_t gemm_rev_mask(int tile, int M, int N, int K, const float* H, const uint64_t* mask, float alpha,
                          const float* W, float* Hout, hipStream_t stream) {
   EpiStore epi{Hout, N, 1.f, 0.f, nullptr};
   ASlopeFromMask xf{reinterpret_cast<const uint32_t*>(mask), alpha};
-  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, H, K, W, N, xf, epi, nullptr, 0.f, stream);
+  const bool xf_ok = true;
+  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, H, K, W, N, xf, epi, xf_ok, nullptr, 0.f, stream);
 }
 
 hipError_t gemm_rev_act(int tile, int M, int N, int K, const float* H, const float* act, float alpha,
                         const float* W, float* Hout, hipStream_t stream) {
   EpiStore epi{Hout, N, 1.f, 0.f, nullptr};
   ASlopeFromAct xf{act, alpha};
-  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, H, K, W, N, xf, epi, nullptr, 0.f, stream);
+  const bool xf_ok = aligned16(act);
+  return dispatch_gemm<KCONTIG, RCONTIG, false>(tile, M, N, K, H, K, W, N, xf, epi, xf_ok, nullptr, 0.f, stream);
 }
 
 }  // namespace mw

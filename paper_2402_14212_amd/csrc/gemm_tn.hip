@@ -7,21 +7,22 @@ namespace mw {
 hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float* A, int64_t lda, const float* B,
                          int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream) {
   EpiStore epi{C, ldc, alpha, beta, bias};
-  return dispatch_gemm<RCONTIG, RCONTIG, false>(tile, M, N, K, A, lda, B, ldb, ANone{}, epi, nullptr, 0.f, stream);
+  return dispatch_gemm<RCONTIG, RCONTIG, false>(tile, M, N, K, A, lda, B, ldb, ANone{}, epi, true, nullptr, 0.f, stream);
 }
 
 hipError_t gemm_dw(int tile, int M, int N, int K, const float* CTZ, const float* X, float scale, float* dW,
                    float* db, hipStream_t stream) {
   EpiStore epi{dW, N, scale, 0.f, nullptr};
-  if (db) return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, db, scale, stream);
-  return dispatch_gemm<RCONTIG, RCONTIG, false>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, nullptr, 0.f, stream);
+  if (db) return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, true, db, scale, stream);
+  return dispatch_gemm<RCONTIG, RCONTIG, false>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, true, nullptr, 0.f, stream);
 }
 
 hipError_t gemm_dw_act(int tile, int M, int N, int K, const float* Hy, const float* act, float alpha,
                        const float* X, float scale, float* dW, float* db, hipStream_t stream) {
   EpiStore epi{dW, N, scale, 0.f, nullptr};
   ASlopeFromAct xf{act, alpha};
-  return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, Hy, M, X, N, xf, epi, db, scale, stream);
+  const bool xf_ok = aligned16(act);
+  return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, Hy, M, X, N, xf, epi, xf_ok, db, scale, stream);
 }
 
 }  // namespace mw

@@ -608,7 +608,7 @@ const char* moonwalk_strerror(int code) {
 int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
                 const float* B, int32_t ldb, float beta, float* C, int32_t ldc, void* hip_stream) {
   if (M < 0 || N < 0 || K < 0 || !C || (K > 0 && (!A || !B))) return MW_ERR_INVALID_ARG;
-  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_32K4) return MW_ERR_INVALID_ARG;
+  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_32K8) return MW_ERR_INVALID_ARG;
   // leading dimensions must cover the fast index of each operand
   const int a_fast = (op == MW_GEMM_TN) ? M : K, b_fast = (op == MW_GEMM_NT) ? K : N;
   if (lda < a_fast || ldb < b_fast || ldc < N) return MW_ERR_INVALID_ARG;

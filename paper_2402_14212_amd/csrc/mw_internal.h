@@ -8,7 +8,7 @@
 namespace mw {
 
 // tile selectors (same values as MW_TILE_* in the public header)
-constexpr int TILE_AUTO = 0, TILE_128 = 1, TILE_64 = 2, TILE_32K4 = 3;
+constexpr int TILE_AUTO = 0, TILE_128 = 1, TILE_64 = 2, TILE_32K4 = 3, TILE_32K8 = 4;
 constexpr int OP_NT = 0, OP_NN = 1, OP_TN = 2;
 
 // Tile choice for an M x N x K product on a 256-CU device. Deterministic in (M, N, K) only, so

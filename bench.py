@@ -107,28 +107,31 @@ def main():
     mw_peak_lib = st["bytes_live"]
     mw_peak_torch = torch.cuda.max_memory_allocated() - base_bytes
 
-    # --- roofline of the dominant kernel: the Phase-III layer kernel (two of the five GEMMs)
-    net.profile_enable(True)
+    # --- roofline of the dominant kernel: the Phase-III layer kernel (two of the five GEMMs).
+    # Each kernel class is timed alone: only its launches run, back to back over the real buffers
+    # (all layers, cold weights), between two events on the launch stream.
     prof_steps = max(1, min(args.steps, 20))
-    for _ in range(prof_steps):
-        net.moonwalk_grad(net.x, net.t, grads, loss)
-    prof = net.profile_read()
-    net.profile_enable(False)
-    n_v, ms_v = prof["vijp"]
-    flop_per_launch = 4.0 * B * sum(a * b for a, b in zip(widths[:-1], widths[1:])) / L   # average layer
-    avg_ms = ms_v / max(n_v, 1)
+    sum_dd = sum(a * b for a, b in zip(widths[:-1], widths[1:]))
+    class_flops = {"fwd": 2.0, "rev": 2.0, "vijp": 4.0, "dw": 2.0}
+    per_class = {}
+    for k in ("fwd", "rev", "vijp", "dw", "ew"):
+        net.profile_filter(k)
+        ms_k, _ = time_steps(lambda: net.moonwalk_grad(net.x, net.t, grads, loss), prof_steps, 2)
+        n_k = net.profile_launches()[k]
+        per_class[k] = {"launches_per_step": n_k, "avg_us": (ms_k / n_k * 1e3 if n_k else None),
+                        "ms_per_step": ms_k}
+        if k in class_flops and n_k:
+            per_class[k]["tflops"] = class_flops[k] * B * sum_dd / (ms_k * 1e-3) / 1e12
+    net.profile_filter(None)
+    n_v = per_class["vijp"]["launches_per_step"]
+    avg_ms = per_class["vijp"]["ms_per_step"] / max(n_v, 1)
+    flop_per_launch = 4.0 * B * sum_dd / max(n_v, 1)       # average layer: two B x d_in x d_out products
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "vijp_dual_kernel (Phase-III recompute + vijp + epilogue)",
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
-                "avg_launch_ms": avg_ms, "launches": n_v,
+                "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
-    per_class = {k: {"launches": n, "avg_us": (ms / n * 1e3 if n else None)} for k, (n, ms) in prof.items()}
-    class_flops = {"fwd": 2.0, "rev": 2.0, "vijp": 4.0, "dw": 2.0}
-    for k, c in class_flops.items():
-        n, ms = prof[k]
-        if n:
-            per_class[k]["tflops"] = c * B * sum(a * b for a, b in zip(widths[:-1], widths[1:])) / L / (ms / n * 1e-3) / 1e12
     net.close()
     del net
 

@@ -147,22 +147,22 @@ int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out);
 int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap,
                          size_t* n_bytes);
 
-/* Measurement aid: per-kernel-class timing of the gradient drivers with HIP events on the
-   caller's stream. While enabled, every kernel launch of moonwalk_grad / backprop_grad is
-   bracketed by two events (this adds a little launch overhead: do not time whole steps with it
-   on). Classes: the Phase-I forward GEMM, the Phase-II reverse GEMM, the Phase-III layer kernel
-   (recompute + vijp + epilogue), the weight-gradient GEMM, and every elementwise/integer kernel. */
+/* Measurement aid: run the gradient drivers with only ONE class of kernel launches enabled, so
+   that a caller can time that class alone between two events on its stream (the launches then run
+   back to back over the handle's real buffers, layer after layer, with the real shapes and cold
+   weights; the numbers they produce are meaningless). Classes: the Phase-I forward GEMM, the
+   Phase-II reverse GEMM, the Phase-III layer kernel (recompute + vijp + epilogue), the
+   weight-gradient GEMM, and every elementwise/integer kernel. */
 #define MW_KCLASS_FWD   0
 #define MW_KCLASS_REV   1
 #define MW_KCLASS_VIJP  2
 #define MW_KCLASS_DW    3
 #define MW_KCLASS_EW    4
 #define MW_KCLASS_COUNT 5
-/* on != 0 starts a fresh measurement, 0 stops it. Synchronises the device. */
-int moonwalk_profile_enable(mw_handle_t* h, int32_t on);
-/* Number of launches of the class since enable and the sum of their event-to-event times.
-   launches, total_ms: host, may be NULL. Synchronises the device. */
-int moonwalk_profile_read(mw_handle_t* h, int32_t kclass, uint64_t* launches, double* total_ms);
+/* kclass = -1 restores normal operation. Does not synchronise. */
+int moonwalk_profile_filter(mw_handle_t* h, int32_t kclass);
+/* Number of launches of the class made by the last moonwalk_grad / backprop_grad call. launches: host. */
+int moonwalk_profile_launches(const mw_handle_t* h, int32_t kclass, uint64_t* launches);
 
 /* Frees every device buffer through dev_free. NULL is allowed. Synchronises the device first. */
 void moonwalk_destroy(mw_handle_t* h);

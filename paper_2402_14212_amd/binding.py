@@ -17,7 +17,7 @@ FETCH_MASK, FETCH_FRAG, FETCH_FRAG_OFFSETS, FETCH_FRAG_BASE, FETCH_H0, FETCH_P, 
 EXPORTED_SYMBOLS = [
     "moonwalk_setup", "moonwalk_refresh", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
     "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
-    "moonwalk_profile_enable", "moonwalk_profile_read",
+    "moonwalk_profile_filter", "moonwalk_profile_launches",
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
     "mw_vijp_epilogue", "mw_colsum", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
 ]
@@ -80,8 +80,8 @@ def load_library() -> C.CDLL:
     lib.moonwalk_grad_layout.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     lib.moonwalk_memory_stats.argtypes = [vp, C.POINTER(_MemStats)]
     lib.moonwalk_debug_fetch.argtypes = [vp, i32, i32, vp, sz, C.POINTER(sz)]
-    lib.moonwalk_profile_enable.argtypes = [vp, i32]
-    lib.moonwalk_profile_read.argtypes = [vp, i32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+    lib.moonwalk_profile_filter.argtypes = [vp, i32]
+    lib.moonwalk_profile_launches.argtypes = [vp, i32, C.POINTER(C.c_uint64)]
     lib.moonwalk_destroy.argtypes = [vp]
     lib.moonwalk_destroy.restype = None
     lib.moonwalk_strerror.argtypes = [C.c_int]
@@ -250,16 +250,17 @@ class MoonwalkNet:
 
     KCLASSES = ("fwd", "rev", "vijp", "dw", "ew")
 
-    def profile_enable(self, on: bool = True):
-        _check(self._lib.moonwalk_profile_enable(self._handle, 1 if on else 0))
+    def profile_filter(self, kclass: Optional[str]):
+        """Run only the launches of one kernel class ("fwd", "rev", "vijp", "dw", "ew"); None = all."""
+        k = -1 if kclass is None else self.KCLASSES.index(kclass)
+        _check(self._lib.moonwalk_profile_filter(self._handle, k))
 
-    def profile_read(self) -> dict:
-        """{class: (launches, total_ms)} since profile_enable(True)."""
+    def profile_launches(self) -> dict:
         out = {}
         for k, name in enumerate(self.KCLASSES):
-            n, ms = C.c_uint64(), C.c_double()
-            _check(self._lib.moonwalk_profile_read(self._handle, k, C.byref(n), C.byref(ms)))
-            out[name] = (int(n.value), float(ms.value))
+            n = C.c_uint64()
+            _check(self._lib.moonwalk_profile_launches(self._handle, k, C.byref(n)))
+            out[name] = int(n.value)
         return out
 
     def _fetch(self, layer: int, what: int, dtype) -> np.ndarray:
@@ -326,8 +327,11 @@ def gemm_f32(op: int, A: torch.Tensor, B: torch.Tensor, C_out: Optional[torch.Te
         C_out = torch.empty((M, N), dtype=torch.float32, device=A.device)
     if tuple(C_out.shape) != (M, N):
         raise ValueError("C has the wrong shape")
-    _check(lib.mw_gemm_f32(op, tile, M, N, K, alpha, _ptr(_f32(A)), A.shape[1], _ptr(_f32(B)), B.shape[1], beta,
-                           _ptr(_f32(C_out)), N, _stream()))
+    for t in (A, B, C_out):          # row-strided views are allowed: the row stride becomes the leading dimension
+        if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("expected 2-D float32 CUDA tensors with unit column stride")
+    _check(lib.mw_gemm_f32(op, tile, M, N, K, alpha, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), beta,
+                           C_out.data_ptr(), C_out.stride(0), _stream()))
     return C_out
 
 

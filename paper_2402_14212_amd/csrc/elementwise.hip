@@ -25,6 +25,227 @@ inline int ew_blocks(int64_t n_words, int words_per_block) {
 __device__ __forceinline__ int64_t global_wave() { return (int64_t)blockIdx.x * EW_WAVES + (threadIdx.x >> 6); }
 __device__ __forceinline__ int64_t total_waves() { return (int64_t)gridDim.x * EW_WAVES; }
 
+// ---------------------------------------------------------------- 128-bit path
+// With 16-byte aligned tensors every lane moves a float4 (elements 4l .. 4l+3 of a 256-element
+// group, i.e. 4 mask words per wavefront trip). The four ballots (one per component) hold bit
+// j of lane l at position l; word w of the group wants lanes 16w .. 16w+15, components
+// interleaved: element 4(l-16w)+j. spread16x4 moves bit i of a 16-bit field to bit 4i.
+constexpr int VUNROLL = 2;  // 256-element groups per wavefront trip
+
+__device__ __forceinline__ uint64_t spread16x4(uint64_t v) {
+  v &= 0xFFFFull;
+  v = (v | (v << 24)) & 0x000000FF000000FFull;
+  v = (v | (v << 12)) & 0x000F000F000F000Full;
+  v = (v | (v << 6)) & 0x0303030303030303ull;
+  v = (v | (v << 3)) & 0x1111111111111111ull;
+  return v;
+}
+// the mask word this lane should store (lanes 0..3 hold words 0..3 of the group)
+__device__ __forceinline__ uint64_t group_word(bool b0, bool b1, bool b2, bool b3, int lane) {
+  const unsigned long long q0 = __ballot(b0), q1 = __ballot(b1), q2 = __ballot(b2), q3 = __ballot(b3);
+  const int sh = 16 * (lane & 3);
+  return spread16x4(q0 >> sh) | (spread16x4(q1 >> sh) << 1) | (spread16x4(q2 >> sh) << 2) |
+         (spread16x4(q3 >> sh) << 3);
+}
+__device__ __forceinline__ float4 ld4(const float* __restrict__ p, int64_t e, int64_t n) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (e + 3 < n) {
+    v = *reinterpret_cast<const float4*>(p + e);
+  } else if (e < n) {
+    v.x = p[e];
+    if (e + 1 < n) v.y = p[e + 1];
+    if (e + 2 < n) v.z = p[e + 2];
+  }
+  return v;
+}
+__device__ __forceinline__ void st4(float* __restrict__ p, int64_t e, int64_t n, float4 v) {
+  if (e + 3 < n) {
+    *reinterpret_cast<float4*>(p + e) = v;
+  } else if (e < n) {
+    p[e] = v.x;
+    if (e + 1 < n) p[e + 1] = v.y;
+    if (e + 2 < n) p[e + 2] = v.z;
+  }
+}
+__device__ __forceinline__ float pick(const float4& v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+__device__ __forceinline__ void put(float4& v, int j, float x) {
+  if (j == 0) v.x = x; else if (j == 1) v.y = x; else if (j == 2) v.z = x; else v.w = x;
+}
+
+template <bool HAS_BIAS>
+__global__ void __launch_bounds__(EW_THREADS)
+k_bias_act_mask_v4(const float* __restrict__ zin, const float* __restrict__ bias, int64_t n, int d, float alpha,
+                   float* __restrict__ x, uint64_t* __restrict__ mask) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
+  const int64_t stride = total_waves() * VUNROLL;
+  for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
+    float4 z[VUNROLL];
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) z[u] = ld4(zin, (g0 + u) * 256 + 4 * lane, n);
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const int64_t e = (g0 + u) * 256 + 4 * lane;
+      if (HAS_BIAS && e < n) {
+        const int c = (int)(e % d);  // d % 4 == 0 on this path: the 4 columns are c .. c+3
+        const float4 b = *reinterpret_cast<const float4*>(bias + c);
+        z[u].x += b.x; z[u].y += b.y; z[u].z += b.z; z[u].w += b.w;
+      }
+      const bool b0 = e < n && z[u].x > 0.f, b1 = e + 1 < n && z[u].y > 0.f, b2 = e + 2 < n && z[u].z > 0.f,
+                 b3 = e + 3 < n && z[u].w > 0.f;
+      float4 o;
+      o.x = b0 ? z[u].x : alpha * z[u].x; o.y = b1 ? z[u].y : alpha * z[u].y;
+      o.z = b2 ? z[u].z : alpha * z[u].z; o.w = b3 ? z[u].w : alpha * z[u].w;
+      st4(x, e, n, o);
+      const uint64_t word = group_word(b0, b1, b2, b3, lane);
+      const int64_t wi = (g0 + u) * 4 + lane;
+      if (lane < 4 && wi < n_words) mask[wi] = word;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_mask_from_act_v4(const float* __restrict__ x, int64_t n, uint64_t* __restrict__ mask) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
+  const int64_t stride = total_waves() * VUNROLL;
+  for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
+    float4 v[VUNROLL];
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) v[u] = ld4(x, (g0 + u) * 256 + 4 * lane, n);
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const uint64_t word = group_word(v[u].x > 0.f, v[u].y > 0.f, v[u].z > 0.f, v[u].w > 0.f, lane);
+      const int64_t wi = (g0 + u) * 4 + lane;
+      if (lane < 4 && wi < n_words) mask[wi] = word;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_rev_scale_v4(const float* __restrict__ h, const uint64_t* __restrict__ mask, int64_t n, float alpha,
+               float* __restrict__ ct_z) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
+  const int64_t stride = total_waves() * VUNROLL;
+  for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
+    float4 v[VUNROLL];
+    uint64_t m[VUNROLL];
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      v[u] = ld4(h, (g0 + u) * 256 + 4 * lane, n);
+      const int64_t wi = (g0 + u) * 4 + (lane >> 4);
+      m[u] = wi < n_words ? mask[wi] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const uint32_t bits = (uint32_t)(m[u] >> (4 * (lane & 15))) & 15u;
+      float4 o;
+      o.x = v[u].x * ((bits & 1u) ? 1.f : alpha); o.y = v[u].y * ((bits & 2u) ? 1.f : alpha);
+      o.z = v[u].z * ((bits & 4u) ? 1.f : alpha); o.w = v[u].w * ((bits & 8u) ? 1.f : alpha);
+      st4(ct_z, (g0 + u) * 256 + 4 * lane, n, o);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_frag_compact_v4(const float* __restrict__ h, const uint64_t* __restrict__ mask, const uint32_t* __restrict__ offsets,
+                  int64_t n, float* __restrict__ frag, const uint64_t* __restrict__ base_ptr, uint64_t capacity,
+                  int32_t* __restrict__ overflow_flag) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
+  const int64_t stride = total_waves() * VUNROLL;
+  const uint64_t base = base_ptr ? *base_ptr : 0ull;
+  const int pos0 = 4 * (lane & 15);
+  for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
+    float4 v[VUNROLL];
+    uint64_t m[VUNROLL];
+    uint32_t off[VUNROLL];
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      v[u] = ld4(h, (g0 + u) * 256 + 4 * lane, n);
+      const int64_t wi = (g0 + u) * 4 + (lane >> 4);
+      m[u] = wi < n_words ? mask[wi] : ~0ull;
+      off[u] = wi < n_words ? offsets[wi] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const int64_t e = (g0 + u) * 256 + 4 * lane;
+      // erased elements of this word below this lane's first position, then one by one
+      uint64_t idx = base + off[u] + (uint64_t)__popcll(~m[u] & ((1ull << pos0) - 1ull));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool erased = (e + j < n) && !((m[u] >> (pos0 + j)) & 1ull);
+        if (erased) {
+          if (idx < capacity) frag[idx] = pick(v[u], j);
+          else if (overflow_flag) *overflow_flag = 1;
+          ++idx;
+        }
+      }
+    }
+  }
+}
+
+template <bool RELU>
+__global__ void __launch_bounds__(EW_THREADS)
+k_vijp_epilogue_v4(const float* __restrict__ z, float* __restrict__ ct_z, int64_t n, float alpha, float inv_alpha,
+                   const uint64_t* __restrict__ mask, const uint32_t* __restrict__ offsets,
+                   const float* __restrict__ frag, const uint64_t* __restrict__ base_ptr, uint64_t capacity,
+                   float* __restrict__ x, float* __restrict__ h_y, unsigned long long* __restrict__ mismatches) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
+  const int64_t stride = total_waves() * VUNROLL;
+  const uint64_t base = (RELU && base_ptr) ? *base_ptr : 0ull;
+  const int pos0 = 4 * (lane & 15);
+  uint32_t mism = 0;
+  for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
+    float4 zz[VUNROLL], cc[VUNROLL];
+    uint64_t m[VUNROLL];
+    uint32_t off[VUNROLL];
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const int64_t e = (g0 + u) * 256 + 4 * lane;
+      zz[u] = ld4(z, e, n);
+      cc[u] = ld4(ct_z, e, n);
+      const int64_t wi = (g0 + u) * 4 + (lane >> 4);
+      m[u] = (mask && wi < n_words) ? mask[wi] : 0ull;
+      off[u] = (RELU && wi < n_words) ? offsets[wi] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const int64_t e = (g0 + u) * 256 + 4 * lane;
+      float4 xo, ho, co;
+      uint64_t idx = base + off[u] + (uint64_t)__popcll(~m[u] & ((1ull << pos0) - 1ull));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float zj = pick(zz[u], j), cj = pick(cc[u], j);
+        const bool in = e + j < n;
+        const bool fresh = zj > 0.f;
+        const bool stored = (m[u] >> (pos0 + j)) & 1ull;
+        if (mask && in && fresh != stored) ++mism;
+        if (RELU) {
+          const float c = stored ? cj : 0.f;
+          float hy = c;
+          if (in && !stored) {
+            hy = idx < capacity ? frag[idx] : 0.f;
+            ++idx;
+          }
+          put(xo, j, stored ? zj : alpha * zj);
+          put(co, j, c);
+          put(ho, j, hy);
+        } else {
+          put(xo, j, fresh ? zj : alpha * zj);
+          put(ho, j, fresh ? cj : cj * inv_alpha);
+        }
+      }
+      st4(x, e, n, xo);
+      st4(h_y, e, n, ho);
+      if (RELU) st4(ct_z, e, n, co);
+    }
+  }
+  if (mismatches && mism) atomicAdd(mismatches, (unsigned long long)mism);
+}
+
 // ---------------------------------------------------------------- phase I: bias + mask + activation
 template <bool HAS_BIAS>
 __global__ void __launch_bounds__(EW_THREADS)
@@ -108,10 +329,14 @@ k_rev_scale(const float* __restrict__ h, const uint64_t* __restrict__ mask, int6
 }
 
 // ---------------------------------------------------------------- fragment index: erased-count scan
-// One workgroup per mask: every thread counts the erased (zero) bits of a contiguous run of
-// words, the per-thread counts are scanned through LDS, and the thread writes the exclusive
-// offsets of its run. Integer arithmetic only: the result does not depend on scheduling.
-constexpr int SCAN_THREADS = 1024;
+// offsets[w] = number of erased (zero) bits in all words before w; offsets[n_words] = total.
+// Every workgroup owns a contiguous chunk of words. It first counts the erased bits of ALL
+// earlier chunks (the mask is small and L2-resident, so this redundant read is cheaper than a
+// second launch or a cross-workgroup hand-off), then scans its own chunk through LDS.
+// Integer arithmetic only: the result does not depend on scheduling.
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_WORDS_PER_THREAD = 8;
+constexpr int SCAN_MAX_BLOCKS = 64;
 
 __device__ __forceinline__ uint32_t erased_in_word(uint64_t w, int64_t word_index, int64_t n) {
   int64_t valid = n - word_index * 64;
@@ -120,30 +345,49 @@ __device__ __forceinline__ uint32_t erased_in_word(uint64_t w, int64_t word_inde
   return (uint32_t)__popcll(~w & keep);
 }
 
-__global__ void __launch_bounds__(SCAN_THREADS)
-k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets) {
-  __shared__ uint32_t part[SCAN_THREADS];
-  const int64_t n_words = (n + 63) >> 6;
-  const int64_t per = (n_words + SCAN_THREADS - 1) / SCAN_THREADS;
-  const int64_t lo = (int64_t)threadIdx.x * per;
-  const int64_t hi = lo + per < n_words ? lo + per : n_words;
-  uint32_t cnt = 0;
-  for (int64_t w = lo; w < hi; ++w) cnt += erased_in_word(mask[w], w, n);
-  part[threadIdx.x] = cnt;
+// block-wide sum of one value per thread; every thread gets the total
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
+  red[threadIdx.x] = v;
   __syncthreads();
-  // inclusive Hillis-Steele scan over the 1024 partial counts
-  for (int off = 1; off < SCAN_THREADS; off <<= 1) {
-    uint32_t add = threadIdx.x >= (unsigned)off ? part[threadIdx.x - off] : 0u;
-    __syncthreads();
-    part[threadIdx.x] += add;
+  for (int s = SCAN_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
-  uint32_t run = part[threadIdx.x] - cnt;  // exclusive prefix of this thread's run
+  uint32_t t = red[0];
+  __syncthreads();
+  return t;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets, int64_t chunk) {
+  __shared__ uint32_t red[SCAN_THREADS];
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  const int64_t c1 = c0 + chunk < n_words ? c0 + chunk : n_words;
+  // erased bits before this chunk
+  uint32_t before = 0;
+  for (int64_t w = threadIdx.x; w < c0; w += SCAN_THREADS) before += erased_in_word(mask[w], w, n);
+  before = block_sum(before, red);
+  // this chunk: each thread takes a contiguous run of words
+  const int64_t per = (chunk + SCAN_THREADS - 1) / SCAN_THREADS;
+  const int64_t lo = c0 + (int64_t)threadIdx.x * per;
+  const int64_t hi = lo + per < c1 ? lo + per : c1;
+  uint32_t cnt = 0;
+  for (int64_t w = lo; w < hi; ++w) cnt += erased_in_word(mask[w], w, n);
+  red[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int off = 1; off < SCAN_THREADS; off <<= 1) {  // inclusive Hillis-Steele scan
+    uint32_t add = threadIdx.x >= (unsigned)off ? red[threadIdx.x - off] : 0u;
+    __syncthreads();
+    red[threadIdx.x] += add;
+    __syncthreads();
+  }
+  uint32_t run = before + red[threadIdx.x] - cnt;
   for (int64_t w = lo; w < hi; ++w) {
     offsets[w] = run;
     run += erased_in_word(mask[w], w, n);
   }
-  if (threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = part[SCAN_THREADS - 1];
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = before + red[SCAN_THREADS - 1];
 }
 
 // Layer bases: exclusive scan of the erased counts in the order given (reverse-pass order).
@@ -323,10 +567,22 @@ k_fill_u32(uint32_t* __restrict__ p, uint32_t value, int64_t n) {
 
 // ------------------------------------------------------------------------------------ launchers
 
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline int ew_blocks_v4(int64_t n) { return ew_blocks((n + 255) >> 8, EW_WAVES * VUNROLL); }
+
 hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, int d, float alpha, float* x,
                             uint64_t* mask, hipStream_t stream) {
   int64_t n = rows * d;
   if (n <= 0) return hipSuccess;
+  if (al16(zin) && al16(x) && (!bias || (al16(bias) && d % 4 == 0))) {
+    if (bias)
+      hipLaunchKernelGGL(k_bias_act_mask_v4<true>, dim3(ew_blocks_v4(n)), dim3(EW_THREADS), 0, stream, zin, bias, n, d,
+                         alpha, x, mask);
+    else
+      hipLaunchKernelGGL(k_bias_act_mask_v4<false>, dim3(ew_blocks_v4(n)), dim3(EW_THREADS), 0, stream, zin, bias, n, d,
+                         alpha, x, mask);
+    return hipGetLastError();
+  }
   int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
   if (bias)
     hipLaunchKernelGGL(k_bias_act_mask<true>, dim3(blocks), dim3(EW_THREADS), 0, stream, zin, bias, n, d, alpha, x,
@@ -339,6 +595,10 @@ hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, i
 
 hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
+  if (al16(x)) {
+    hipLaunchKernelGGL(k_mask_from_act_v4, dim3(ew_blocks_v4(n)), dim3(EW_THREADS), 0, stream, x, n, mask);
+    return hipGetLastError();
+  }
   int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
   hipLaunchKernelGGL(k_mask_from_act, dim3(blocks), dim3(EW_THREADS), 0, stream, x, n, mask);
   return hipGetLastError();
@@ -347,6 +607,10 @@ hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream
 hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
                         hipStream_t stream) {
   if (n <= 0) return hipSuccess;
+  if (al16(h) && al16(ct_z)) {
+    hipLaunchKernelGGL(k_rev_scale_v4, dim3(ew_blocks_v4(n)), dim3(EW_THREADS), 0, stream, h, mask, n, alpha, ct_z);
+    return hipGetLastError();
+  }
   int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
   hipLaunchKernelGGL(k_rev_scale, dim3(blocks), dim3(EW_THREADS), 0, stream, h, mask, n, alpha, ct_z);
   return hipGetLastError();
@@ -354,7 +618,12 @@ hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float a
 
 hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream) {
   if (n < 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_frag_offsets, dim3(1), dim3(SCAN_THREADS), 0, stream, mask, n, offsets);
+  const int64_t n_words = (n + 63) >> 6;
+  int64_t chunk = (int64_t)SCAN_THREADS * SCAN_WORDS_PER_THREAD;
+  if (chunk * SCAN_MAX_BLOCKS < n_words) chunk = (n_words + SCAN_MAX_BLOCKS - 1) / SCAN_MAX_BLOCKS;
+  int blocks = (int)((n_words + chunk - 1) / chunk);
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_frag_offsets, dim3(blocks), dim3(SCAN_THREADS), 0, stream, mask, n, offsets, chunk);
   return hipGetLastError();
 }
 
@@ -367,6 +636,11 @@ hipError_t ew_frag_bases(const uint32_t* const* count_ptrs, int n_relu, uint64_t
 hipError_t ew_frag_compact(const float* h, const uint64_t* mask, const uint32_t* offsets, int64_t n, float* frag,
                            const uint64_t* base, uint64_t capacity, int32_t* overflow_flag, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
+  if (al16(h)) {
+    hipLaunchKernelGGL(k_frag_compact_v4, dim3(ew_blocks_v4(n)), dim3(EW_THREADS), 0, stream, h, mask, offsets, n, frag,
+                       base, capacity, overflow_flag);
+    return hipGetLastError();
+  }
   int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
   hipLaunchKernelGGL(k_frag_compact, dim3(blocks), dim3(EW_THREADS), 0, stream, h, mask, offsets, n, frag, base,
                      capacity, overflow_flag);
@@ -378,9 +652,19 @@ hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, fl
                             float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream) {
   int64_t n = rows * d;
   if (n <= 0) return hipSuccess;
+  if (alpha == 0.f && (!mask || !offsets || !frag)) return hipErrorInvalidValue;
+  if (al16(z) && al16(ct_z) && al16(x) && al16(h_y)) {
+    const int vb = ew_blocks_v4(n);
+    if (alpha == 0.f)
+      hipLaunchKernelGGL(k_vijp_epilogue_v4<true>, dim3(vb), dim3(EW_THREADS), 0, stream, z, ct_z, n, alpha, 0.f, mask,
+                         offsets, frag, base, capacity, x, h_y, mismatches);
+    else
+      hipLaunchKernelGGL(k_vijp_epilogue_v4<false>, dim3(vb), dim3(EW_THREADS), 0, stream, z, ct_z, n, alpha,
+                         1.0f / alpha, mask, offsets, frag, base, capacity, x, h_y, mismatches);
+    return hipGetLastError();
+  }
   int blocks = ew_blocks((n + 63) >> 6, EW_WAVES * UNROLL);
   if (alpha == 0.f) {
-    if (!mask || !offsets || !frag) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_vijp_epilogue<true>, dim3(blocks), dim3(EW_THREADS), 0, stream, z, ct_z, n, alpha, 0.f,
                        mask, offsets, frag, base, capacity, x, h_y, mismatches);
   } else {

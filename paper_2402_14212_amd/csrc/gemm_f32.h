@@ -59,7 +59,7 @@ __host__ __device__ constexpr int lds_stage_floats() {
 template <class Cfg, int LA, int LB, int NSETS>
 __host__ __device__ constexpr int lds_bytes() {
   int pipe = 2 * lds_stage_floats<Cfg, LA, LB>();
-  int red = (Cfg::WK - 1) * Cfg::WM * Cfg::WN * (Cfg::NACC * 16 * NSETS + Cfg::WTM) * 64;
+  int red = Cfg::WK > 1 ? Cfg::WK * Cfg::WM * Cfg::WN * (Cfg::NACC * 16 * NSETS + Cfg::WTM) * 64 : 0;
   return 4 * (pipe > red ? pipe : red);
 }
 
@@ -121,40 +121,6 @@ struct ANone {
     template <bool VEC>
     __device__ __forceinline__ void fetch(Aux&, const Chunk&) const {}
     __device__ __forceinline__ float4 apply(float4 v, const Aux&) const { return v; }
-  };
-};
-
-// Multiply by the activation slope taken from packed sign bits: bit e of the mask (LSB-first,
-// e = flat offset of the element in the full tensor) selects 1, a cleared bit selects alpha.
-struct ASlopeFromMask {
-  const uint32_t* mask32;  // the uint64 words seen as little-endian halves
-  float alpha;
-  struct Dev {
-    struct Aux { uint32_t bits; };
-    __amdgpu_buffer_rsrc_t rs;
-    float alpha;
-    __device__ __forceinline__ Dev(const ASlopeFromMask& p, int n_outer, int n_inner, int64_t ld) : alpha(p.alpha) {
-      uint32_t elems = extent_bytes(n_outer, n_inner, ld) / 4;
-      rs = make_rsrc(p.mask32, ((elems + 63u) / 64u) * 8u);
-    }
-    template <bool VEC>
-    __device__ __forceinline__ void fetch(Aux& aux, const Chunk& c) const {
-      uint32_t w = c.e >> 5, sh = c.e & 31u;
-      uint32_t lo = buf_load_u32(rs, c.nvalid > 0 ? w * 4u : OOB);
-      uint32_t bits = lo >> sh;
-      if (!VEC) {  // only an unaligned row stride lets the 4 bits straddle two 32-bit halves
-        uint32_t hi = buf_load_u32(rs, (sh > 28u && c.nvalid > (int)(32u - sh)) ? (w + 1u) * 4u : OOB);
-        bits = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
-      }
-      aux.bits = bits;
-    }
-    __device__ __forceinline__ float4 apply(float4 v, const Aux& aux) const {
-      v.x *= (aux.bits & 1u) ? 1.f : alpha;
-      v.y *= (aux.bits & 2u) ? 1.f : alpha;
-      v.z *= (aux.bits & 4u) ? 1.f : alpha;
-      v.w *= (aux.bits & 8u) ? 1.f : alpha;
-      return v;
-    }
   };
 };
 
@@ -353,68 +319,86 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
   }
 }
 
-// Sum the K slices held by the WK wavefronts of each (wm, wn) position into the wk == 0
-// wavefront, in the fixed order wk = 1, 2, ... . LDS must be free (main loop finished).
-// Returns true for the wavefronts that hold the result (wk == 0).
-template <class Cfg, int NSETS>
-__device__ __forceinline__ bool reduce_k_slices(float* __restrict__ lds, f32x16 (&acc)[NSETS][Cfg::NACC],
-                                                float (&asum)[Cfg::WTM]) {
-  if (Cfg::WK == 1) return true;
-  constexpr int PER_WAVE = (Cfg::NACC * 16 * NSETS + Cfg::WTM) * 64;
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int wk = wave % Cfg::WK;
-  const int pos = wave / Cfg::WK;  // wm * WN + wn
-  if (wk > 0) {
-    float* dst = lds + ((wk - 1) * Cfg::WM * Cfg::WN + pos) * PER_WAVE;
-#pragma unroll
-    for (int s = 0; s < NSETS; ++s)
-#pragma unroll
-      for (int a = 0; a < Cfg::NACC; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dst[((s * Cfg::NACC + a) * 16 + i) * 64 + lane] = acc[s][a][i];
-#pragma unroll
-    for (int tm = 0; tm < Cfg::WTM; ++tm) dst[(NSETS * Cfg::NACC * 16 + tm) * 64 + lane] = asum[tm];
-  }
-  __syncthreads();
-  if (wk > 0) return false;
-  for (int w = 1; w < Cfg::WK; ++w) {
-    const float* src = lds + ((w - 1) * Cfg::WM * Cfg::WN + pos) * PER_WAVE;
-#pragma unroll
-    for (int s = 0; s < NSETS; ++s)
-#pragma unroll
-      for (int a = 0; a < Cfg::NACC; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[s][a][i] += src[((s * Cfg::NACC + a) * 16 + i) * 64 + lane];
-#pragma unroll
-    for (int tm = 0; tm < Cfg::WTM; ++tm) asum[tm] += src[(NSETS * Cfg::NACC * 16 + tm) * 64 + lane];
-  }
-  return true;
-}
-
 // Position of this lane's 16 accumulator values inside a 32x32 tile: value i sits in row
 // 8*(i/4) + 4*(lane>>5) + i%4 and column lane & 31.
 __device__ __forceinline__ int acc_row(int i, int g) { return 8 * (i / 4) + 4 * g + (i % 4); }
 
-// Hand every 32x32 accumulator tile of this wavefront to the epilogue, which is called by all
-// 64 lanes together (it may use ballots):  epi.tile(M, N, row_base, col, g, acc_tile[NSETS])
-// where row_base is the tile's first row and col this lane's column.
+// Finish a workgroup tile: sum the K slices held by the WK wavefronts of each (wm, wn) position
+// and hand the sums to the epilogue. With WK == 1 every wavefront passes its own registers.
+// With WK > 1 all wavefronts park their accumulators in LDS (which must be free: main loop
+// finished) and wavefront wk then owns registers [wk*16/WK, (wk+1)*16/WK) of every 32x32 tile:
+// it adds the WK partial values in the fixed order wk = 0, 1, 2, ... and runs the epilogue for
+// those rows, so the epilogue's stores are spread over all wavefronts.
+// The epilogue is called by all 64 lanes together (it may use ballots):
+//   epi.template part<CNT>(M, N, row_base, col, g, i0, v)   with v[NSETS][CNT] = values of
+//   accumulator registers i0 .. i0+CNT-1 of the tile whose first row is row_base.
+// asum (column sums of operand A, per lane) is reduced into the wk == 0 wavefront.
 template <class Cfg, int NSETS, class Epi>
-__device__ __forceinline__ void for_each_tile(int M, int N, int m0, int n0, const f32x16 (&acc)[NSETS][Cfg::NACC],
-                                              Epi& epi) {
+__device__ __forceinline__ void reduce_and_finish(float* __restrict__ lds, int M, int N, int m0, int n0,
+                                                  const f32x16 (&acc)[NSETS][Cfg::NACC], float (&asum)[Cfg::WTM],
+                                                  Epi& epi) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
+  const int wk = wave % Cfg::WK;
   const int wn = (wave / Cfg::WK) % Cfg::WN;
   const int wm = wave / (Cfg::WK * Cfg::WN);
+  const int g = lane >> 5;
+  if (Cfg::WK == 1) {
+#pragma unroll
+    for (int tm = 0; tm < Cfg::WTM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < Cfg::WTN; ++tn) {
+        float v[NSETS][16];
+#pragma unroll
+        for (int s = 0; s < NSETS; ++s)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) v[s][i] = acc[s][tm * Cfg::WTN + tn][i];
+        epi.template part<16>(M, N, m0 + (wm * Cfg::WTM + tm) * 32, n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31), g,
+                              0, v);
+      }
+    return;
+  }
+  constexpr int CNT = 16 / Cfg::WK;                                   // registers per wavefront per tile
+  static_assert(Cfg::WK == 1 || 16 % Cfg::WK == 0, "WK must divide 16");
+  constexpr int PER_WAVE = (Cfg::NACC * 16 * NSETS + Cfg::WTM) * 64;  // floats parked per wavefront
+  const int pos = wave / Cfg::WK;                                     // wm * WN + wn
+  float* mine = lds + (pos * Cfg::WK + wk) * PER_WAVE;
+#pragma unroll
+  for (int s = 0; s < NSETS; ++s)
+#pragma unroll
+    for (int a = 0; a < Cfg::NACC; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mine[((s * Cfg::NACC + a) * 16 + i) * 64 + lane] = acc[s][a][i];
+#pragma unroll
+  for (int tm = 0; tm < Cfg::WTM; ++tm) mine[(NSETS * Cfg::NACC * 16 + tm) * 64 + lane] = asum[tm];
+  __syncthreads();
+  const float* base = lds + pos * Cfg::WK * PER_WAVE;
+  const int i0 = wk * CNT;
 #pragma unroll
   for (int tm = 0; tm < Cfg::WTM; ++tm)
 #pragma unroll
     for (int tn = 0; tn < Cfg::WTN; ++tn) {
-      f32x16 t[NSETS];
+      float v[NSETS][CNT];
 #pragma unroll
-      for (int s = 0; s < NSETS; ++s) t[s] = acc[s][tm * Cfg::WTN + tn];
-      epi.tile(M, N, m0 + (wm * Cfg::WTM + tm) * 32, n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31), lane >> 5, t);
+      for (int s = 0; s < NSETS; ++s)
+#pragma unroll
+        for (int j = 0; j < CNT; ++j) {
+          const int slot = ((s * Cfg::NACC + tm * Cfg::WTN + tn) * 16 + i0 + j) * 64 + lane;
+          float t = base[slot];
+          for (int w = 1; w < Cfg::WK; ++w) t += base[w * PER_WAVE + slot];
+          v[s][j] = t;
+        }
+      epi.template part<CNT>(M, N, m0 + (wm * Cfg::WTM + tm) * 32, n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31), g,
+                             i0, v);
     }
+  if (wk == 0) {
+#pragma unroll
+    for (int tm = 0; tm < Cfg::WTM; ++tm) {
+      float t = asum[tm];
+      for (int w = 1; w < Cfg::WK; ++w) t += base[w * PER_WAVE + (NSETS * Cfg::NACC * 16 + tm) * 64 + lane];
+      asum[tm] = t;
+    }
+  }
 }
 
 // Logical tile coordinates of this workgroup: XCD-aware, m fastest (all row tiles of one

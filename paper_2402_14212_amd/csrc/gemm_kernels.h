@@ -10,6 +10,9 @@
 namespace mw {
 
 // ------------------------------------------------------------------------------------ epilogues
+// Each epilogue is a plain parameter struct (a kernel argument) with a device-side state `Dev`
+// built inside the kernel. Dev::part<CNT>() receives CNT consecutive accumulator registers
+// i0 .. i0+CNT-1 of one 32x32 tile for this lane (see acc_row for their rows).
 
 // C = alpha * acc (+ bias[col]) (+ beta * C)
 struct EpiStore {
@@ -30,26 +33,28 @@ struct EpiStore::Dev {
     rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
   }
   __device__ __forceinline__ void finish() const {}
-  __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[1]) const {
+  template <int CNT>
+  __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
+                                       const float (&v)[1][CNT]) const {
     const bool cv = col < N;
     const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
-    uint32_t off[16];
-    float old[16];
+    uint32_t off[CNT];
+    float old[CNT];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      int row = row_base + acc_row(i, g);
-      off[i] = (cv && row < M) ? ((uint32_t)row * (uint32_t)ldc + (uint32_t)col) * 4u : OOB;
+    for (int j = 0; j < CNT; ++j) {
+      int row = row_base + acc_row(i0 + j, g);
+      off[j] = (cv && row < M) ? ((uint32_t)row * (uint32_t)ldc + (uint32_t)col) * 4u : OOB;
     }
     if (beta != 0.f) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) old[i] = buf_load_f32(rc, off[i]);
+      for (int j = 0; j < CNT; ++j) old[j] = buf_load_f32(rc, off[j]);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float r = alpha * t[0][i];
+    for (int j = 0; j < CNT; ++j) {
+      float r = alpha * v[0][j];
       if (bias) r += bv;
-      if (beta != 0.f) r += beta * old[i];
-      buf_store_f32(rc, off[i], r);
+      if (beta != 0.f) r += beta * old[j];
+      buf_store_f32(rc, off[j], r);
     }
   }
 };
@@ -73,30 +78,32 @@ struct EpiFwdAct {
       rmask = make_rsrc(p.mask32, MASK ? (uint32_t)(((int64_t)M * N + 63) / 64) * 8u : 0u);
     }
     __device__ __forceinline__ void finish() const {}
-    __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[1]) const {
-    const bool cv = col < N;
-    const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
-    const int lane = threadIdx.x & 63;
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
+                                         const float (&v)[1][CNT]) const {
+      const bool cv = col < N;
+      const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
+      const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      int row = row_base + acc_row(i, g);
-      bool valid = cv && row < M;
-      uint32_t e = (uint32_t)row * (uint32_t)N + (uint32_t)col;
-      float z = t[0][i];
-      if (bias) z += bv;
-      bool bit = valid && (z > 0.f);
-      buf_store_f32(rx, valid ? e * 4u : OOB, bit ? z : alpha * z);
-      if (MASK) {
-        unsigned long long bal = __ballot(bit);
-        uint32_t word = g ? (uint32_t)(bal >> 32) : (uint32_t)bal;
-        buf_store_u32(rmask, ((lane & 31) == 0 && valid) ? (e >> 5) * 4u : OOB, word);
+      for (int j = 0; j < CNT; ++j) {
+        int row = row_base + acc_row(i0 + j, g);
+        bool valid = cv && row < M;
+        uint32_t e = (uint32_t)row * (uint32_t)N + (uint32_t)col;
+        float z = v[0][j];
+        if (bias) z += bv;
+        bool bit = valid && (z > 0.f);
+        buf_store_f32(rx, valid ? e * 4u : OOB, bit ? z : alpha * z);
+        if (MASK) {
+          unsigned long long bal = __ballot(bit);
+          uint32_t word = g ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+          buf_store_u32(rmask, ((lane & 31) == 0 && valid) ? (e >> 5) * 4u : OOB, word);
+        }
       }
     }
-  }
   };
 };
 
-// Phase-III epilogue for one layer. t[0] = x_{i-1} W^T (pre-bias), t[1] = h_{i-1} P^T.
+// Phase-III epilogue for one layer. v[0] = x_{i-1} W^T (pre-bias), v[1] = h_{i-1} P^T.
 //   leaky: m = (z > 0) recomputed; h_y = m ? ct_z : ct_z * (1/alpha).
 //   ReLU : m = stored bit; ct_z zeroed where erased; h_y restored from the fragment store at
 //          rank = offsets[word] + popcount(erased bits below e in the 64-bit word).
@@ -115,82 +122,166 @@ struct EpiVijp {
   float* CTZ;
   unsigned long long* mismatches;
   struct Dev {
-  __amdgpu_buffer_rsrc_t rbias, rmask, roff, rfrag, rx, rh, rc;
-  float alpha, inv_alpha;
-  bool bias;
-  unsigned long long* mismatches;
-  uint32_t mism;
-  __device__ __forceinline__ Dev(const EpiVijp& p, int M, int N)
-      : alpha(p.alpha), inv_alpha(p.inv_alpha), bias(p.bias != nullptr), mismatches(p.mismatches), mism(0) {
-    const uint32_t words = (uint32_t)(((int64_t)M * N + 63) / 64);
-    rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
-    rmask = make_rsrc(p.mask, words * 8u);
-    roff = make_rsrc(p.offsets, RELU ? (words + 1u) * 4u : 0u);
-    uint64_t base = RELU ? *p.frag_base : 0ull;
-    // the layer's slice of the store; reads past the capacity return 0
-    uint64_t room = (RELU && base < p.frag_capacity) ? p.frag_capacity - base : 0ull;
-    if (room > 0x1FFFFFFFull) room = 0x1FFFFFFFull;
-    rfrag = make_rsrc(RELU ? p.frag + base : nullptr, (uint32_t)room * 4u);
-    rx = make_rsrc(p.X, extent_bytes(M, N, N));
-    rh = make_rsrc(p.H, extent_bytes(M, N, N));
-    rc = make_rsrc(p.CTZ, extent_bytes(M, N, N));
-  }
-  __device__ __forceinline__ void tile(int M, int N, int row_base, int col, int g, const f32x16 (&t)[2]) {
-    const bool cv = col < N;
-    const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
-    uint32_t e[16], lo[16], hi[16], rank0[16];
-    bool valid[16];
+    __amdgpu_buffer_rsrc_t rbias, rmask, roff, rfrag, rx, rh, rc;
+    float alpha, inv_alpha;
+    bool bias;
+    unsigned long long* mismatches;
+    uint32_t mism;
+    __device__ __forceinline__ Dev(const EpiVijp& p, int M, int N)
+        : alpha(p.alpha), inv_alpha(p.inv_alpha), bias(p.bias != nullptr), mismatches(p.mismatches), mism(0) {
+      const uint32_t words = (uint32_t)(((int64_t)M * N + 63) / 64);
+      rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
+      rmask = make_rsrc(p.mask, words * 8u);
+      roff = make_rsrc(p.offsets, RELU ? (words + 1u) * 4u : 0u);
+      uint64_t base = RELU ? *p.frag_base : 0ull;
+      // the layer's slice of the store; reads past the capacity return 0
+      uint64_t room = (RELU && base < p.frag_capacity) ? p.frag_capacity - base : 0ull;
+      if (room > 0x1FFFFFFFull) room = 0x1FFFFFFFull;
+      rfrag = make_rsrc(RELU ? p.frag + base : nullptr, (uint32_t)room * 4u);
+      rx = make_rsrc(p.X, extent_bytes(M, N, N));
+      rh = make_rsrc(p.H, extent_bytes(M, N, N));
+      rc = make_rsrc(p.CTZ, extent_bytes(M, N, N));
+    }
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
+                                         const float (&v)[2][CNT]) {
+      const bool cv = col < N;
+      const float bv = buf_load_f32(rbias, (bias && cv) ? (uint32_t)col * 4u : OOB);
+      uint32_t e[CNT], lo[CNT], hi[CNT], rank0[CNT];
+      bool valid[CNT];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      int row = row_base + acc_row(i, g);
-      valid[i] = cv && row < M;
-      e[i] = (uint32_t)row * (uint32_t)N + (uint32_t)col;
-      uint32_t w = e[i] >> 6;
-      if (RELU) {
-        lo[i] = buf_load_u32(rmask, valid[i] ? w * 8u : OOB);
-        hi[i] = buf_load_u32(rmask, valid[i] ? w * 8u + 4u : OOB);
-        rank0[i] = buf_load_u32(roff, valid[i] ? w * 4u : OOB);
-      } else {
-        lo[i] = buf_load_u32(rmask, valid[i] ? (e[i] >> 5) * 4u : OOB);
+      for (int j = 0; j < CNT; ++j) {
+        int row = row_base + acc_row(i0 + j, g);
+        valid[j] = cv && row < M;
+        e[j] = (uint32_t)row * (uint32_t)N + (uint32_t)col;
+        uint32_t w = e[j] >> 6;
+        if (RELU) {
+          lo[j] = buf_load_u32(rmask, valid[j] ? w * 8u : OOB);
+          hi[j] = buf_load_u32(rmask, valid[j] ? w * 8u + 4u : OOB);
+          rank0[j] = buf_load_u32(roff, valid[j] ? w * 4u : OOB);
+        } else {
+          lo[j] = buf_load_u32(rmask, valid[j] ? (e[j] >> 5) * 4u : OOB);
+        }
+      }
+      float restored[CNT];
+      bool stored[CNT];
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        if (RELU) {
+          uint64_t w = ((uint64_t)hi[j] << 32) | lo[j];
+          uint32_t sh = e[j] & 63u;
+          stored[j] = (w >> sh) & 1ull;
+          uint32_t idx = rank0[j] + (uint32_t)__popcll(~w & ((1ull << sh) - 1ull));
+          restored[j] = buf_load_f32(rfrag, (valid[j] && !stored[j]) ? idx * 4u : OOB);
+        } else {
+          stored[j] = (lo[j] >> (e[j] & 31u)) & 1u;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        float z = v[0][j];
+        if (bias) z += bv;
+        const bool fresh = z > 0.f;
+        if (valid[j] && fresh != stored[j]) ++mism;
+        const uint32_t off = valid[j] ? e[j] * 4u : OOB;
+        if (RELU) {
+          const float c = stored[j] ? v[1][j] : 0.f;
+          buf_store_f32(rx, off, stored[j] ? z : alpha * z);
+          buf_store_f32(rh, off, stored[j] ? c : restored[j]);
+          buf_store_f32(rc, off, c);
+        } else {
+          const float c = v[1][j];
+          buf_store_f32(rx, off, fresh ? z : alpha * z);
+          buf_store_f32(rh, off, fresh ? c : c * inv_alpha);
+          buf_store_f32(rc, off, c);
+        }
       }
     }
-    float restored[16];
-    bool stored[16];
+    __device__ __forceinline__ void finish() const {
+      if (mism) atomicAdd(mismatches, (unsigned long long)mism);
+    }
+  };
+};
+
+// Phase-II epilogue. The product is h, the cotangent at the OUTPUT of the previous layer. It is
+// scaled by that layer's activation slope here (bit ? 1 : alpha, bits from its packed mask), so the
+// next reverse product consumes ct_z directly; the unscaled h is also kept where a re-seed
+// checkpoint is due, and for a ReLU previous layer the erased entries of h go to the fragment
+// store at rank = offsets[word] + popcount(erased bits below e in the word).
+template <bool RELU>
+struct EpiRevSlope {
+  float* CT;                  // [M][N] slope-scaled cotangent
+  float* RAW;                 // [M][N] unscaled cotangent (checkpoint) or NULL
+  const uint64_t* mask;       // previous layer's signs, flat index row * N + col
+  float alpha;                // previous layer's slope
+  const uint32_t* offsets;    // ReLU only
+  float* frag;                // ReLU only: start of the whole store
+  const uint64_t* frag_base;  // ReLU only: device scalar
+  uint64_t frag_capacity;
+  int32_t* overflow;          // ReLU only: raised when the store is too small
+  struct Dev {
+    __amdgpu_buffer_rsrc_t rct, rraw, rmask, roff, rfrag;
+    float alpha;
+    bool raw;
+    uint32_t room;
+    int32_t* overflow;
+    bool ovf;
+    __device__ __forceinline__ Dev(const EpiRevSlope& p, int M, int N)
+        : alpha(p.alpha), raw(p.RAW != nullptr), overflow(p.overflow), ovf(false) {
+      const uint32_t words = (uint32_t)(((int64_t)M * N + 63) / 64);
+      rct = make_rsrc(p.CT, extent_bytes(M, N, N));
+      rraw = make_rsrc(p.RAW, p.RAW ? extent_bytes(M, N, N) : 0u);
+      rmask = make_rsrc(p.mask, words * 8u);
+      roff = make_rsrc(p.offsets, RELU ? (words + 1u) * 4u : 0u);
+      uint64_t base = RELU ? *p.frag_base : 0ull;
+      uint64_t left = (RELU && base < p.frag_capacity) ? p.frag_capacity - base : 0ull;
+      if (left > 0x1FFFFFFFull) left = 0x1FFFFFFFull;
+      room = (uint32_t)left;
+      rfrag = make_rsrc(RELU ? p.frag + base : nullptr, room * 4u);  // stores past the room are dropped
+    }
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
+                                         const float (&v)[1][CNT]) {
+      const bool cv = col < N;
+      uint32_t e[CNT], lo[CNT], hi[CNT], rank0[CNT];
+      bool valid[CNT];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (RELU) {
-        uint64_t w = ((uint64_t)hi[i] << 32) | lo[i];
-        uint32_t sh = e[i] & 63u;
-        stored[i] = (w >> sh) & 1ull;
-        uint32_t idx = rank0[i] + (uint32_t)__popcll(~w & ((1ull << sh) - 1ull));
-        restored[i] = buf_load_f32(rfrag, (valid[i] && !stored[i]) ? idx * 4u : OOB);
-      } else {
-        stored[i] = (lo[i] >> (e[i] & 31u)) & 1u;
+      for (int j = 0; j < CNT; ++j) {
+        int row = row_base + acc_row(i0 + j, g);
+        valid[j] = cv && row < M;
+        e[j] = (uint32_t)row * (uint32_t)N + (uint32_t)col;
+        if (RELU) {
+          uint32_t w = e[j] >> 6;
+          lo[j] = buf_load_u32(rmask, valid[j] ? w * 8u : OOB);
+          hi[j] = buf_load_u32(rmask, valid[j] ? w * 8u + 4u : OOB);
+          rank0[j] = buf_load_u32(roff, valid[j] ? w * 4u : OOB);
+        } else {
+          lo[j] = buf_load_u32(rmask, valid[j] ? (e[j] >> 5) * 4u : OOB);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        const uint32_t off = valid[j] ? e[j] * 4u : OOB;
+        const float h = v[0][j];
+        bool bit;
+        if (RELU) {
+          uint64_t w = ((uint64_t)hi[j] << 32) | lo[j];
+          uint32_t sh = e[j] & 63u;
+          bit = (w >> sh) & 1ull;
+          uint32_t idx = rank0[j] + (uint32_t)__popcll(~w & ((1ull << sh) - 1ull));
+          const bool erased = valid[j] && !bit;
+          if (erased && idx >= room) ovf = true;
+          buf_store_f32(rfrag, erased ? idx * 4u : OOB, h);
+        } else {
+          bit = (lo[j] >> (e[j] & 31u)) & 1u;
+        }
+        buf_store_f32(rct, off, h * (bit ? 1.f : alpha));
+        if (raw) buf_store_f32(rraw, off, h);
       }
     }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float z = t[0][i];
-      if (bias) z += bv;
-      const bool fresh = z > 0.f;
-      if (valid[i] && fresh != stored[i]) ++mism;
-      const uint32_t off = valid[i] ? e[i] * 4u : OOB;
-      if (RELU) {
-        const float c = stored[i] ? t[1][i] : 0.f;
-        buf_store_f32(rx, off, stored[i] ? z : alpha * z);
-        buf_store_f32(rh, off, stored[i] ? c : restored[i]);
-        buf_store_f32(rc, off, c);
-      } else {
-        const float c = t[1][i];
-        buf_store_f32(rx, off, fresh ? z : alpha * z);
-        buf_store_f32(rh, off, fresh ? c : c * inv_alpha);
-        buf_store_f32(rc, off, c);
-      }
+    __device__ __forceinline__ void finish() const {
+      if (RELU && ovf) *overflow = 1;
     }
-  }
-  __device__ __forceinline__ void finish() const {
-    if (mism) atomicAdd(mismatches, (unsigned long long)mism);
-  }
   };
 };
 
@@ -224,15 +315,14 @@ gemm_kernel(int M, int N, int K, const float* __restrict__ A, int64_t lda, const
 #pragma unroll
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] += __shfl_xor(asum[t], 32);
   }
-  if (!reduce_k_slices<Cfg, 1>(lds, acc, asum)) return;
   typename Epi::Dev ed(epi, M, N);
-  for_each_tile<Cfg, 1>(M, N, m0, n0, acc, ed);
+  reduce_and_finish<Cfg, 1>(lds, M, N, m0, n0, acc, asum, ed);
   ed.finish();
 
   if (COLSUM && n0 == 0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wn = (wave / Cfg::WK) % Cfg::WN, wm = wave / (Cfg::WK * Cfg::WN);
-    if (wn == 0 && lane < 32) {
+    const int wk = wave % Cfg::WK, wn = (wave / Cfg::WK) % Cfg::WN, wm = wave / (Cfg::WK * Cfg::WN);
+    if (wk == 0 && wn == 0 && lane < 32) {
 #pragma unroll
       for (int t = 0; t < Cfg::WTM; ++t) {
         int row = m0 + (wm * Cfg::WTM + t) * 32 + lane;
@@ -268,9 +358,8 @@ vijp_dual_kernel(int M, int N, int K, const float* __restrict__ X, const float* 
   const ANone::Dev none;
   gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
   gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
-  if (!reduce_k_slices<Cfg, 2>(lds, acc, asum)) return;
   typename EpiVijp<RELU>::Dev ed(epi, M, N);
-  for_each_tile<Cfg, 2>(M, N, m0, n0, acc, ed);
+  reduce_and_finish<Cfg, 2>(lds, M, N, m0, n0, acc, asum, ed);
   ed.finish();
 }
 

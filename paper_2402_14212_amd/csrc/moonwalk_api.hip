@@ -62,21 +62,13 @@ int hip_fail(hipError_t e, const char* where) {
     if (e__ != hipSuccess) return hip_fail(e__, #expr); \
   } while (0)
 
-// Launch `expr` (a launcher returning hipError_t); with profiling on, bracket it with events.
-#define MW_LAUNCH(h, s, kclass, expr)                                        \
-  do {                                                                       \
-    hipEvent_t e0__ = nullptr, e1__ = nullptr;                               \
-    if ((h)->prof_on) {                                                      \
-      e0__ = (h)->prof_event();                                              \
-      e1__ = (h)->prof_event();                                              \
-      if (!e0__ || !e1__) return hip_fail(hipErrorOutOfMemory, "hipEventCreate"); \
-      MW_HIP(hipEventRecord(e0__, (s)));                                     \
-    }                                                                        \
-    MW_HIP(expr);                                                            \
-    if ((h)->prof_on) {                                                      \
-      MW_HIP(hipEventRecord(e1__, (s)));                                     \
-      (h)->prof_recs.push_back({(kclass), e0__, e1__});                      \
-    }                                                                        \
+// Launch `expr` (a launcher returning hipError_t) unless a class filter excludes it.
+#define MW_LAUNCH(h, s, kclass, expr)                                   \
+  do {                                                                  \
+    if ((h)->class_filter < 0 || (h)->class_filter == (kclass)) {       \
+      MW_HIP(expr);                                                     \
+      (h)->launches[(kclass)] += 1;                                     \
+    }                                                                   \
   } while (0)
 
 void* default_alloc(size_t bytes, void*) {
@@ -129,23 +121,9 @@ struct mw_handle {
   // backprop workspace
   float *bp_ha = nullptr, *bp_hb = nullptr;
 
-  // optional per-kernel-class timing with HIP events
-  bool prof_on = false;
-  std::vector<hipEvent_t> prof_pool;
-  size_t prof_used = 0;
-  struct ProfRec { int kclass; hipEvent_t start, stop; };
-  std::vector<ProfRec> prof_recs;
-  double prof_ms[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
-  uint64_t prof_launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
-
-  hipEvent_t prof_event() {
-    if (prof_used == prof_pool.size()) {
-      hipEvent_t e = nullptr;
-      if (hipEventCreate(&e) != hipSuccess) return nullptr;
-      prof_pool.push_back(e);
-    }
-    return prof_pool[prof_used++];
-  }
+  // measurement aid: run only the launches of one kernel class (-1 = all), count launches
+  int class_filter = -1;
+  uint64_t launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
 
   void* alloc(size_t bytes, uint64_t* item) {
     if (bytes == 0) bytes = 4;
@@ -365,7 +343,8 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
   const int B = h->B, L = h->L;
   unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
   int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
-  MW_HIP(ew_fill_u32(h->status, 0u, 3, s));
+  for (auto& c : h->launches) c = 0;
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_fill_u32(h->status, 0u, 3, s));
 
   // ---------------- Phase I: forward, keep sign masks only
   const float* xin = x;
@@ -393,27 +372,52 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
   // ---------------- loss and output cotangent h_L
   float* hbuf[2] = {h->ha, h->hb};
   MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s));
-  const float* hcur = hbuf[0];
 
   // ---------------- Phase II: reverse, input cotangent only
-  for (int i = L - 1; i >= 0; --i) {
-    Layer& l = h->layers[i];
-    const int64_t n = (int64_t)B * l.d_out;
-    if (l.alpha == 0.f)
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hcur, l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot, h->frag_capacity,
-                             overflow, s));
-    float* hout;
-    if (i == 0) hout = h->h0;
-    else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
-    else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
-    if (h->fuse) {
-      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_mask(TILE_AUTO, B, l.d_in, l.d_out, hcur, l.mask, l.alpha, l.W, hout, s));
-    } else {
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hcur, l.mask, n, l.alpha, h->ctz, s));
-      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, h->ctz, l.d_out, l.W, l.d_in, 0.f, hout, l.d_in,
-                        nullptr, s));
+  if (h->fuse) {
+    // The last layer's slope (and fragments) are applied by the elementwise kernels; every
+    // reverse product then applies the slope of the layer below it in its own epilogue.
+    {
+      Layer& l = h->layers[L - 1];
+      const int64_t n = (int64_t)B * l.d_out;
+      if (l.alpha == 0.f)
+        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hbuf[0], l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot,
+                                                      h->frag_capacity, overflow, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hbuf[0], l.mask, n, l.alpha, hbuf[0], s));
     }
-    hcur = hout;
+    const float* ctcur = hbuf[0];
+    for (int i = L - 1; i >= 0; --i) {
+      Layer& l = h->layers[i];
+      if (i == 0) {
+        MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, ctcur, l.d_out, l.W, l.d_in, 0.f,
+                                                  h->h0, l.d_in, nullptr, s));
+      } else {
+        Layer& below = h->layers[i - 1];
+        float* ctout = (ctcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+        const bool relu = below.alpha == 0.f;
+        RevArgs r{ctout, below.ckpt, below.mask, below.alpha, below.offsets, h->frag,
+                  relu ? h->frag_bases + below.relu_slot : nullptr, h->frag_capacity, overflow};
+        MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_fused(TILE_AUTO, B, l.d_in, l.d_out, ctcur, l.W, r, s));
+        ctcur = ctout;
+      }
+    }
+  } else {
+    const float* hcur = hbuf[0];
+    for (int i = L - 1; i >= 0; --i) {
+      Layer& l = h->layers[i];
+      const int64_t n = (int64_t)B * l.d_out;
+      if (l.alpha == 0.f)
+        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hcur, l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot,
+                                                      h->frag_capacity, overflow, s));
+      float* hout;
+      if (i == 0) hout = h->h0;
+      else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
+      else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hcur, l.mask, n, l.alpha, h->ctz, s));
+      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, h->ctz, l.d_out, l.W, l.d_in, 0.f,
+                                                hout, l.d_in, nullptr, s));
+      hcur = hout;
+    }
   }
 
   // ---------------- Phase III: forward vijp sweep
@@ -455,6 +459,7 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* gr
   if (!(h->plan & MW_PLAN_BACKPROP)) return MW_ERR_NOT_PLANNED;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int B = h->B, L = h->L;
+  for (auto& c : h->launches) c = 0;
   // forward, every activation stored
   const float* xin = x;
   for (int i = 0; i < L; ++i) {
@@ -552,39 +557,21 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
   return MW_OK;
 }
 
-int moonwalk_profile_enable(mw_handle_t* h, int32_t on) {
-  if (!h) return MW_ERR_INVALID_ARG;
-  MW_HIP(hipDeviceSynchronize());
-  h->prof_on = on != 0;
-  h->prof_recs.clear();
-  h->prof_used = 0;
-  for (int c = 0; c < MW_KCLASS_COUNT; ++c) {
-    h->prof_ms[c] = 0.0;
-    h->prof_launches[c] = 0;
-  }
+int moonwalk_profile_filter(mw_handle_t* h, int32_t kclass) {
+  if (!h || kclass < -1 || kclass >= MW_KCLASS_COUNT) return MW_ERR_INVALID_ARG;
+  h->class_filter = kclass;
   return MW_OK;
 }
 
-int moonwalk_profile_read(mw_handle_t* h, int32_t kclass, uint64_t* launches, double* total_ms) {
-  if (!h || kclass < 0 || kclass >= MW_KCLASS_COUNT) return MW_ERR_INVALID_ARG;
-  MW_HIP(hipDeviceSynchronize());
-  for (auto& r : h->prof_recs) {  // fold finished records into the totals, give the events back
-    float ms = 0.f;
-    MW_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
-    h->prof_ms[r.kclass] += ms;
-    h->prof_launches[r.kclass] += 1;
-  }
-  h->prof_recs.clear();
-  h->prof_used = 0;
-  if (launches) *launches = h->prof_launches[kclass];
-  if (total_ms) *total_ms = h->prof_ms[kclass];
+int moonwalk_profile_launches(const mw_handle_t* h, int32_t kclass, uint64_t* launches) {
+  if (!h || !launches || kclass < 0 || kclass >= MW_KCLASS_COUNT) return MW_ERR_INVALID_ARG;
+  *launches = h->launches[kclass];
   return MW_OK;
 }
 
 void moonwalk_destroy(mw_handle_t* h) {
   if (!h) return;
   (void)hipDeviceSynchronize();
-  for (auto e : h->prof_pool) (void)hipEventDestroy(e);
   h->release_all();
   delete h;
 }

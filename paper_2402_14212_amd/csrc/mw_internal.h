@@ -27,10 +27,23 @@ hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const 
 hipError_t gemm_fwd_act(int tile, int M, int N, int K, const float* X, const float* W, const float* bias,
                         float alpha, float* Xout, uint64_t* mask, hipStream_t stream);
 
-// Hout[M][N] = (H[M][K] .* slope) W[K][N], slope from packed mask bits of H's flat index
-hipError_t gemm_rev_mask(int tile, int M, int N, int K, const float* H, const uint64_t* mask, float alpha,
-                         const float* W, float* Hout, hipStream_t stream);
-// same, slope from the stored activation act[M][K] (> 0 ? 1 : alpha)
+// Phase-II product with the NEXT step's slope folded into the epilogue:
+//   h = CTin[M][K] W[K][N];  CT = h .* slope(mask, alpha)  (mask/alpha of the layer whose OUTPUT h is);
+//   RAW = h if not NULL; for alpha == 0 the erased entries of h are appended to the fragment store.
+struct RevArgs {
+  float* CT;
+  float* RAW;
+  const uint64_t* mask;
+  float alpha;
+  const uint32_t* offsets;
+  float* frag;
+  const uint64_t* frag_base;
+  uint64_t frag_capacity;
+  int32_t* overflow;
+};
+hipError_t gemm_rev_fused(int tile, int M, int N, int K, const float* CTin, const float* W, const RevArgs& r,
+                          hipStream_t stream);
+// Hout[M][N] = (H[M][K] .* slope) W[K][N], slope from the stored activation act[M][K] (> 0 ? 1 : alpha)
 hipError_t gemm_rev_act(int tile, int M, int N, int K, const float* H, const float* act, float alpha,
                         const float* W, float* Hout, hipStream_t stream);
 

@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
     ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
+    ap.add_argument("--gen", choices=["numpy", "torch"], default="numpy",
+                    help="numpy: host generator (the one the parity tests use); torch: same recipe drawn on the GPU "
+                         "(for the large configurations; the CPU baseline is then skipped)")
     return ap.parse_args()
 
 
@@ -85,7 +88,7 @@ def main():
     import paper_2402_14212_amd as mw
     from workloads import make_config, moonwalk_flops, backprop_flops, CONFIGS
 
-    wl = make_config(args.config, depth=args.depth)
+    wl = make_config(args.config, depth=args.depth, device="cuda:0" if args.gen == "torch" else None)
     if args.reseed is not None:
         wl.reseed_interval = args.reseed
     B, widths, L = wl.batch, wl.widths, wl.depth
@@ -155,7 +158,7 @@ def main():
         "metric": "gradient steps/s (mixed-mode Moonwalk, one full moonwalk_grad per step)",
         "value": 1e3 / ms_mw, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_mw, "ms_per_step_wall": wall_mw, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic (seeded, generator: %s)" % args.gen,
         "config": {"workload": f"{wl.name}: depth {L}, widths {widths[0]}->{widths[-1]}, batch {B}, "
                                f"alpha {wl.alphas[0]}, reseed K={wl.reseed_interval}, loss_scale {wl.loss_scale:g}, "
                                f"{'unfused' if args.unfused else 'fused'} kernels"},
@@ -177,7 +180,7 @@ def main():
         },
         "backprop": {k: v for k, v in bp.items() if not k.startswith("bytes")},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.gen == "numpy":
         out["cpu_baseline"] = cpu_baseline(wl, flops_mw)
     print(json.dumps(out))
 

@@ -193,13 +193,19 @@ class MoonwalkNet:
     @classmethod
     def from_workload(cls, wl, device="cuda:0", **kw) -> "MoonwalkNet":
         dev = torch.device(device)
-        Ws = [torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(dev) for w in wl.W]
-        bs = [torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(dev) for b in wl.b]
+
+        def put(a):
+            if isinstance(a, torch.Tensor):
+                return a.to(device=dev, dtype=torch.float32).contiguous()
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+
+        Ws = [put(w) for w in wl.W]
+        bs = [put(b) for b in wl.b]
         kw.setdefault("reseed_interval", wl.reseed_interval)
         kw.setdefault("loss_scale", wl.loss_scale)
         net = cls(Ws, bs, wl.alphas, wl.batch, **kw)
-        net.x = torch.from_numpy(np.ascontiguousarray(wl.x, dtype=np.float32)).to(dev)
-        net.t = torch.from_numpy(np.ascontiguousarray(wl.t, dtype=np.float32)).to(dev)
+        net.x = put(wl.x)
+        net.t = put(wl.t)
         return net
 
     # ------------------------------------------------------------------ gradient steps

@@ -24,9 +24,11 @@ hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float
 
 int pick_tile(int M, int N, int K) {
   auto tiles = [](int m, int n, int t) { return (int64_t)((m + t - 1) / t) * ((n + t - 1) / t); };
-  // 256 CUs: prefer the largest tile that still gives most CUs a workgroup; for small outputs
-  // with a long K split K over the wavefronts of a 32x32 tile instead.
-  if (tiles(M, N, 128) >= 192) return TILE_128;
+  // Measured on MI355X (256 CUs) over the layer shapes of the five configurations: the 64x64 tile
+  // wins whenever it yields at least one workgroup for most CUs; the 128x128 tile only pays once
+  // there are several waves of them (the large weight-gradient products); outputs too small for
+  // 64x64 tiles split K over the four wavefronts of a 32x32 tile.
+  if (tiles(M, N, 128) >= 512) return TILE_128;
   if (tiles(M, N, 64) >= 192) return TILE_64;
   if (K >= 256) return TILE_32K4;
   return TILE_64;

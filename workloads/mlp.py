@@ -89,6 +89,48 @@ def make_mlp(widths: Sequence[int], batch: int, alpha, seed: int = 0,
                        seed=int(seed), name=name, factors=factors if keep_factors else None)
 
 
+def make_mlp_on_device(widths: Sequence[int], batch: int, alpha, seed: int = 0, reseed_interval: int = 0,
+                       loss_scale: float = 1.0, name: str = "", bias_std: float = 0.01, device="cuda:0"):
+    """The same recipe drawn with torch on `device` (fp64 QR on the GPU, then rounded to fp32).
+
+    For the large configurations, whose hundreds of 4096 x 4096 QR factorisations would take the
+    host most of an hour. Same distribution, different random stream than make_mlp: use it for
+    throughput and memory runs; parity runs feed the oracle from make_mlp. W, b, x, t are torch
+    tensors on the device.
+    """
+    import torch
+    widths = [int(w) for w in widths]
+    depth = len(widths) - 1
+    alphas = [float(alpha)] * depth if np.isscalar(alpha) else [float(a) for a in alpha]
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+
+    def haar(n, k):
+        a = torch.randn(n, k, dtype=torch.float64, device=device, generator=gen)
+        q, r = torch.linalg.qr(a)
+        d = torch.sign(torch.diagonal(r))
+        d[d == 0] = 1.0
+        return q * d
+
+    Ws, bs = [], []
+    for i in range(depth):
+        d_in, d_out = widths[i], widths[i + 1]
+        if d_out > d_in:
+            raise ValueError(f"layer {i + 1}: d_out={d_out} > d_in={d_in} is not submersive")
+        U = haar(d_out, d_out)
+        V = haar(d_in, d_out)
+        s = 0.8 + 0.4 * torch.rand(d_out, dtype=torch.float64, device=device, generator=gen)
+        bias = bias_std * torch.randn(d_out, dtype=torch.float64, device=device, generator=gen)
+        Ws.append(((U * s) @ V.T).to(torch.float32).contiguous())
+        bs.append(bias.to(torch.float32).contiguous())
+        del U, V
+    x = torch.randn(batch, widths[0], dtype=torch.float64, device=device, generator=gen).to(torch.float32)
+    t = torch.randn(batch, widths[-1], dtype=torch.float64, device=device, generator=gen).to(torch.float32)
+    return MLPWorkload(widths=widths, batch=int(batch), alphas=alphas, W=Ws, b=bs, x=x, t=t,
+                       reseed_interval=int(reseed_interval), loss_scale=float(loss_scale), seed=int(seed),
+                       name=name, factors=None)
+
+
 def _narrowing_widths() -> List[int]:
     # 32 layers from 4096 down to 512, every width a multiple of 64:
     # the width drops by 64 on every 4th layer and by 128 otherwise.
@@ -116,9 +158,14 @@ def config_widths(name: str, depth: Optional[int] = None) -> List[int]:
 
 
 def make_config(name: str, depth: Optional[int] = None, seed: int = 0,
-                keep_factors: bool = False) -> MLPWorkload:
-    """Build one of the named configurations, optionally truncated to its first `depth` layers."""
+                keep_factors: bool = False, device=None) -> MLPWorkload:
+    """Build one of the named configurations, optionally truncated to its first `depth` layers.
+    With `device` the tensors are drawn with torch on that device (see make_mlp_on_device)."""
     c = CONFIGS[name]
+    if device is not None:
+        return make_mlp_on_device(config_widths(name, depth), c["batch"], c["alpha"], seed=seed,
+                                  reseed_interval=c["reseed_interval"], loss_scale=c["loss_scale"],
+                                  name=name if depth is None else f"{name}[L={depth}]", device=device)
     return make_mlp(config_widths(name, depth), c["batch"], c["alpha"], seed=seed,
                     reseed_interval=c["reseed_interval"], loss_scale=c["loss_scale"],
                     name=name if depth is None else f"{name}[L={depth}]",

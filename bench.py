@@ -22,6 +22,12 @@ sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
 
+# Bytes that cross the L2 per launch of the Phase-III layer kernel, from the two rocprofv3 --pmc runs
+# summarised in profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE 12477.5 KiB scaled x2.0 by the
+# copy-kernel calibration, WRITE_SIZE 3072.0 KiB scaled x1.0). Offline counters: known only for the
+# default workload, null otherwise.
+PHASE3_TRAFFIC_BYTES = {"deep_square": int(12477.5 * 1024 * 2.0 + 3072.0 * 1024 * 1.0)}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -132,7 +138,8 @@ def main():
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "vijp_dual_kernel (Phase-III recompute + vijp + epilogue)",
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+                "frac": achieved / MFMA_F32_PEAK_TFLOPS,
+                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and not args.unfused else None,
                 "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
     net.close()

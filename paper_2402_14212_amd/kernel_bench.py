@@ -4,6 +4,7 @@
     python -m paper_2402_14212_amd.kernel_bench gemm          # fp32 MFMA GEMMs at the layer shapes
     python -m paper_2402_14212_amd.kernel_bench elementwise   # HBM-bound elementwise / pack / compaction kernels
     python -m paper_2402_14212_amd.kernel_bench all
+    python -m paper_2402_14212_amd.kernel_bench one --op nt --tile 3 --m 256 --n 1024 --k 1024   # one GEMM, for counter runs
 
 Every kernel is launched `--iters` times back to back between two events on the current stream;
 the figure printed is the mean time per launch (launch gaps included, so short kernels read
@@ -128,15 +129,34 @@ def bench_elementwise(iters, max_log2):
         del zs, hs
 
 
+def bench_one(args):
+    op = {"nt": mw.GEMM_NT, "nn": mw.GEMM_NN, "tn": mw.GEMM_TN}[args.op]
+    M, N, K = args.m, args.n, args.k
+    A = torch.randn((K, M) if op == mw.GEMM_TN else (M, K), device="cuda")
+    B = torch.randn((N, K) if op == mw.GEMM_NT else (K, N), device="cuda")
+    C = torch.empty(M, N, device="cuda")
+    t = timed(lambda i: mw.gemm_f32(op, A, B, C_out=C, tile=args.tile), args.iters)
+    tf = 2.0 * M * N * K / t
+    print(f"{args.op} M={M} N={N} K={K} tile={TILES[args.tile]}: {t * 1e6:.1f} us/launch, {tf / 1e12:.2f} TFLOP/s "
+          f"({tf / MFMA_PEAK:.1%} of the fp32 MFMA peak)")
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["gemm", "elementwise", "all"])
+    ap.add_argument("what", choices=["gemm", "elementwise", "all", "one"])
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--max-log2", type=int, default=28, help="largest elementwise tensor, log2(elements)")
+    ap.add_argument("--op", choices=["nt", "nn", "tn"], default="nt")
+    ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--m", type=int, default=256)
+    ap.add_argument("--n", type=int, default=1024)
+    ap.add_argument("--k", type=int, default=1024)
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("kernel_bench needs a GPU")
     print(f"# device: {torch.cuda.get_device_name(0)}; iters={args.iters}", flush=True)
+    if args.what == "one":
+        bench_one(args)
     if args.what in ("gemm", "all"):
         bench_gemm(args.iters)
     if args.what in ("elementwise", "all"):

@@ -116,14 +116,15 @@ def main():
     mw_peak_lib = st["bytes_live"]
     mw_peak_torch = torch.cuda.max_memory_allocated() - base_bytes
 
-    # --- roofline of the dominant kernel: the Phase-III layer kernel (two of the five GEMMs).
-    # Each kernel class is timed alone: only its launches run, back to back over the real buffers
-    # (all layers, cold weights), between two events on the launch stream.
+    # --- roofline of the dominant kernel: the Phase-III launch, which carries layer i's kernel
+    # (recompute + vijp + epilogue: two products) and layer i-1's weight-gradient product: three of
+    # the five GEMMs of the step. Each kernel class is timed alone: only its launches run, back to
+    # back over the real buffers (all layers, cold weights), between two events on the launch stream.
     prof_steps = max(1, min(args.steps, 20))
     sum_dd = sum(a * b for a, b in zip(widths[:-1], widths[1:]))
-    class_flops = {"fwd": 2.0, "rev": 2.0, "vijp": 4.0, "dw": 2.0}
+    class_flops = {"fwd": 2.0, "rev": 2.0, "vijp": 4.0, "dw": 2.0, "phase3": 6.0}
     per_class = {}
-    for k in ("fwd", "rev", "vijp", "dw", "ew"):
+    for k in ("fwd", "rev", "vijp", "dw", "ew", "phase3"):
         net.profile_filter(k)
         ms_k, _ = time_steps(lambda: net.moonwalk_grad(net.x, net.t, grads, loss), prof_steps, 2)
         n_k = net.profile_launches()[k]
@@ -132,11 +133,14 @@ def main():
         if k in class_flops and n_k:
             per_class[k]["tflops"] = class_flops[k] * B * sum_dd / (ms_k * 1e-3) / 1e12
     net.profile_filter(None)
-    n_v = per_class["vijp"]["launches_per_step"]
-    avg_ms = per_class["vijp"]["ms_per_step"] / max(n_v, 1)
-    flop_per_launch = 4.0 * B * sum_dd / max(n_v, 1)       # average layer: two B x d_in x d_out products
+    dom = "phase3" if per_class["phase3"]["launches_per_step"] else "vijp"      # unfused runs have no paired launches
+    n_v = per_class[dom]["launches_per_step"]
+    avg_ms = per_class[dom]["ms_per_step"] / max(n_v, 1)
+    flop_per_launch = class_flops[dom] * B * sum_dd / max(n_v, 1)
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "vijp_dual_kernel (Phase-III recompute + vijp + epilogue)",
+    roofline = {"bound": "mfma",
+                "kernel": "task_pair_kernel (Phase-III launch: layer kernel = recompute + vijp + epilogue, plus the "
+                          "previous layer's weight-gradient GEMM)" if dom == "phase3" else "Phase-III layer kernel",
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F32_PEAK_TFLOPS,
                 "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and not args.unfused else None,

@@ -151,14 +151,16 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
    that a caller can time that class alone between two events on its stream (the launches then run
    back to back over the handle's real buffers, layer after layer, with the real shapes and cold
    weights; the numbers they produce are meaningless). Classes: the Phase-I forward GEMM, the
-   Phase-II reverse GEMM, the Phase-III layer kernel (recompute + vijp + epilogue), the
-   weight-gradient GEMM, and every elementwise/integer kernel. */
-#define MW_KCLASS_FWD   0
-#define MW_KCLASS_REV   1
-#define MW_KCLASS_VIJP  2
-#define MW_KCLASS_DW    3
-#define MW_KCLASS_EW    4
-#define MW_KCLASS_COUNT 5
+   Phase-II reverse GEMM, the Phase-III layer kernel alone (recompute + vijp + epilogue), the
+   weight-gradient GEMM alone, every elementwise/integer kernel, and the Phase-III launches as the
+   step really issues them (layer i's kernel and layer i-1's weight gradient in one launch). */
+#define MW_KCLASS_FWD    0
+#define MW_KCLASS_REV    1
+#define MW_KCLASS_VIJP   2
+#define MW_KCLASS_DW     3
+#define MW_KCLASS_EW     4
+#define MW_KCLASS_PHASE3 5
+#define MW_KCLASS_COUNT  6
 /* kclass = -1 restores normal operation. Does not synchronise. */
 int moonwalk_profile_filter(mw_handle_t* h, int32_t kclass);
 /* Number of launches of the class made by the last moonwalk_grad / backprop_grad call. launches: host. */

@@ -254,10 +254,10 @@ class MoonwalkNet:
             _check(code)
         return out
 
-    KCLASSES = ("fwd", "rev", "vijp", "dw", "ew")
+    KCLASSES = ("fwd", "rev", "vijp", "dw", "ew", "phase3")
 
     def profile_filter(self, kclass: Optional[str]):
-        """Run only the launches of one kernel class ("fwd", "rev", "vijp", "dw", "ew"); None = all."""
+        """Run only the launches of one kernel class ("fwd", "rev", "vijp", "dw", "ew", "phase3"); None = all."""
         k = -1 if kclass is None else self.KCLASSES.index(kclass)
         _check(self._lib.moonwalk_profile_filter(self._handle, k))
 

@@ -18,6 +18,90 @@ static hipError_t vijp_dual_t(int tile, int M, int N, int K, const VijpArgs& a, 
   }
 }
 
+template <class CfgV, bool RELU, class CfgD>
+static hipError_t pair_t(int M, int N, int K, const VijpArgs& a, const DwArgs& d, hipStream_t stream) {
+  static_assert(CfgV::NT == CfgD::NT, "both tasks run in workgroups of the same size");
+  EpiVijp<RELU> epi{a.bias, a.alpha, a.alpha > 0.f ? 1.0f / a.alpha : 0.f, a.mask, a.offsets, a.frag,
+                    a.frag_base, a.frag_capacity, a.Xout, a.Hout, a.CTZ, a.mismatches};
+  EpiStore es{d.dW, d.N, d.scale, 0.f, nullptr};
+  auto tv = make_vijp_task<CfgV, true, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi);
+  auto td = make_gemm_task<CfgD, RCONTIG, RCONTIG, true, ANone, EpiStore, true>(d.M, d.N, d.K, d.CTZ, d.M, d.X, d.N,
+                                                                               ANone{}, es, d.db, d.scale);
+  return launch_task_pair<CfgV::NT>(tv, td, stream);
+}
+
+template <class CfgV, bool RELU>
+static hipError_t pair_d(int tile_d, int M, int N, int K, const VijpArgs& a, const DwArgs& d, hipStream_t stream) {
+  if (tile_d == TILE_128) return pair_t<CfgV, RELU, Tile128>(M, N, K, a, d, stream);
+  return pair_t<CfgV, RELU, Tile64>(M, N, K, a, d, stream);
+}
+
+template <bool RELU>
+static hipError_t pair_v(int tile_v, int tile_d, int M, int N, int K, const VijpArgs& a, const DwArgs& d,
+                         hipStream_t stream) {
+  switch (tile_v) {
+    case TILE_128: return pair_d<Tile128, RELU>(tile_d, M, N, K, a, d, stream);
+    case TILE_64: return pair_d<Tile64, RELU>(tile_d, M, N, K, a, d, stream);
+    default: return pair_d<Tile32K4, RELU>(tile_d, M, N, K, a, d, stream);
+  }
+}
+
+hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream) {
+  if (v && d && M > 0 && N > 0 && d->M > 0 && d->N > 0 && d->db) {
+    const int tile_v = pick_tile(M, N, K), tile_d = pick_tile(d->M, d->N, d->K);
+    const bool shapes_ok = extent_ok(M, K, K) && extent_ok(N, K, K) && extent_ok(M, N, N) &&
+                           extent_ok(d->K, d->M, d->M) && extent_ok(d->K, d->N, d->N) && extent_ok(d->M, d->N, d->N);
+    const bool vec = vijp_vec_ok(K, v->X, v->W, v->Hin, v->P) && operand_vec_ok(d->CTZ, d->M, d->M) &&
+                     operand_vec_ok(d->X, d->N, d->N);
+    if (shapes_ok && vec && tile_v != TILE_32K8 && (tile_d == TILE_128 || tile_d == TILE_64))
+      return v->alpha == 0.f ? pair_v<true>(tile_v, tile_d, M, N, K, *v, *d, stream)
+                             : pair_v<false>(tile_v, tile_d, M, N, K, *v, *d, stream);
+  }
+  if (v) {
+    hipError_t e = gemm_vijp_dual(TILE_AUTO, M, N, K, *v, stream);
+    if (e != hipSuccess) return e;
+  }
+  if (d) return gemm_dw(TILE_AUTO, d->M, d->N, d->K, d->CTZ, d->X, d->scale, d->dW, d->db, stream);
+  return hipSuccess;
+}
+
+template <class CfgD, class CfgR>
+static hipError_t bp_pair_t(const BpLayerArgs& a, hipStream_t stream) {
+  static_assert(CfgD::NT == CfgR::NT, "both tasks run in workgroups of the same size");
+  ASlopeFromAct xf{a.act, a.alpha};
+  EpiStore ed{a.dW, a.d_in, a.scale, 0.f, nullptr};
+  EpiStore er{a.Hout, a.d_in, 1.f, 0.f, nullptr};
+  auto td = make_gemm_task<CfgD, RCONTIG, RCONTIG, true, ASlopeFromAct, EpiStore, true>(
+      a.d_out, a.d_in, a.batch, a.Hy, a.d_out, a.Xprev, a.d_in, xf, ed, a.db, a.scale);
+  auto tr = make_gemm_task<CfgR, KCONTIG, RCONTIG, true, ASlopeFromAct, EpiStore, false>(
+      a.batch, a.d_in, a.d_out, a.Hy, a.d_out, a.W, a.d_in, xf, er, nullptr, 0.f);
+  return launch_task_pair<CfgD::NT>(tr, td, stream);
+}
+
+template <class CfgD>
+static hipError_t bp_pair_r(int tile_r, const BpLayerArgs& a, hipStream_t stream) {
+  switch (tile_r) {
+    case TILE_128: return bp_pair_t<CfgD, Tile128>(a, stream);
+    case TILE_64: return bp_pair_t<CfgD, Tile64>(a, stream);
+    default: return bp_pair_t<CfgD, Tile32K4>(a, stream);
+  }
+}
+
+hipError_t gemm_bp_layer(const BpLayerArgs& a, hipStream_t stream) {
+  if (a.Hout && a.batch > 0 && a.d_in > 0 && a.d_out > 0) {
+    const int tile_d = pick_tile(a.d_out, a.d_in, a.batch), tile_r = pick_tile(a.batch, a.d_in, a.d_out);
+    const bool shapes_ok = extent_ok(a.batch, a.d_out, a.d_out) && extent_ok(a.batch, a.d_in, a.d_in) &&
+                           extent_ok(a.d_out, a.d_in, a.d_in);
+    const bool vec = operand_vec_ok(a.Hy, a.d_out, a.d_out) && aligned16(a.act) && operand_vec_ok(a.Xprev, a.d_in, a.d_in) &&
+                     operand_vec_ok(a.W, a.d_in, a.d_in);
+    if (shapes_ok && vec && tile_r != TILE_32K8 && (tile_d == TILE_128 || tile_d == TILE_64))
+      return tile_d == TILE_128 ? bp_pair_r<Tile128>(tile_r, a, stream) : bp_pair_r<Tile64>(tile_r, a, stream);
+  }
+  hipError_t e = gemm_dw_act(TILE_AUTO, a.d_out, a.d_in, a.batch, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, stream);
+  if (e != hipSuccess || !a.Hout) return e;
+  return gemm_rev_act(TILE_AUTO, a.batch, a.d_in, a.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, stream);
+}
+
 hipError_t gemm_vijp_dual(int tile, int M, int N, int K, const VijpArgs& a, hipStream_t stream) {
   return a.alpha == 0.f ? vijp_dual_t<true>(tile, M, N, K, a, stream) : vijp_dual_t<false>(tile, M, N, K, a, stream);
 }

@@ -401,10 +401,12 @@ __device__ __forceinline__ void reduce_and_finish(float* __restrict__ lds, int M
   }
 }
 
-// Logical tile coordinates of this workgroup: XCD-aware, m fastest (all row tiles of one
-// column panel of B land on the same XCD, so B is fetched from HBM once).
-__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
-  int id = xcd_remap((int)blockIdx.x, tiles_m * tiles_n);
+// Logical tile coordinates of workgroup `bid` of a grid of tiles_m * tiles_n: XCD-aware, m fastest
+// (all row tiles of one column panel of B land on the same XCD, so B is fetched from HBM once).
+// `bid` is the block id within the task; when a launch carries two tasks the first one's block
+// count is padded to a multiple of 8 so that bid % 8 is still the XCD the block runs on.
+__device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  int id = xcd_remap(bid, tiles_m * tiles_n);
   tm = id % tiles_m;
   tn = id / tiles_m;
 }

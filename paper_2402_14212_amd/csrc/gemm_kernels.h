@@ -286,81 +286,122 @@ struct EpiRevSlope {
 };
 
 // ------------------------------------------------------------------------------------ kernels
+// Work descriptions ("tasks") are plain structs passed as kernel arguments; a task's run() is
+// the whole life of one workgroup. A launch carries one task, or two independent ones.
 
 template <class Cfg, int LA, int LB, bool VEC, class Xf, class Epi, bool COLSUM>
-__global__ void __launch_bounds__(Cfg::NT)
-gemm_kernel(int M, int N, int K, const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
-            int64_t ldb, Xf xf, Epi epi, float* __restrict__ colsum_out, float colsum_scale, int tiles_m,
-            int tiles_n) {
-  extern __shared__ __align__(16) float lds[];
-  int tm_i, tn_i;
-  tile_coords(tiles_m, tiles_n, tm_i, tn_i);
-  const int m0 = tm_i * Cfg::BM, n0 = tn_i * Cfg::BN;
+struct GemmTask {
+  int M, N, K;
+  const float* A;
+  int64_t lda;
+  const float* B;
+  int64_t ldb;
+  Xf xf;
+  Epi epi;
+  float* colsum_out;
+  float colsum_scale;
+  int tiles_m, tiles_n;
+  static constexpr int LDS_BYTES = lds_bytes<Cfg, LA, LB, 1>();
+  __host__ __device__ int blocks() const { return tiles_m * tiles_n; }
 
-  f32x16 acc[1][Cfg::NACC];
-  float asum[Cfg::WTM];
-#pragma unroll
-  for (int a = 0; a < Cfg::NACC; ++a)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[0][a][i] = 0.f;
-#pragma unroll
-  for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
+  __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
+    int tm_i, tn_i;
+    tile_coords(bid, tiles_m, tiles_n, tm_i, tn_i);
+    const int m0 = tm_i * Cfg::BM, n0 = tn_i * Cfg::BN;
 
-  {
-    const typename Xf::Dev xd(xf, LA == KCONTIG ? M : K, LA == KCONTIG ? K : M, lda);
-    gemm_mainloop<Cfg, LA, LB, VEC, COLSUM>(A, lda, B, ldb, M, N, K, m0, n0, lds, xd, acc[0], asum);
-  }
-
-  if (COLSUM) {
+    f32x16 acc[1][Cfg::NACC];
+    float asum[Cfg::WTM];
 #pragma unroll
-    for (int t = 0; t < Cfg::WTM; ++t) asum[t] += __shfl_xor(asum[t], 32);
-  }
-  typename Epi::Dev ed(epi, M, N);
-  reduce_and_finish<Cfg, 1>(lds, M, N, m0, n0, acc, asum, ed);
-  ed.finish();
-
-  if (COLSUM && n0 == 0) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wk = wave % Cfg::WK, wn = (wave / Cfg::WK) % Cfg::WN, wm = wave / (Cfg::WK * Cfg::WN);
-    if (wk == 0 && wn == 0 && lane < 32) {
+    for (int a = 0; a < Cfg::NACC; ++a)
 #pragma unroll
-      for (int t = 0; t < Cfg::WTM; ++t) {
-        int row = m0 + (wm * Cfg::WTM + t) * 32 + lane;
-        if (row < M) colsum_out[row] = colsum_scale * asum[t];
+      for (int i = 0; i < 16; ++i) acc[0][a][i] = 0.f;
+#pragma unroll
+    for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
+
+    {
+      const typename Xf::Dev xd(xf, LA == KCONTIG ? M : K, LA == KCONTIG ? K : M, lda);
+      gemm_mainloop<Cfg, LA, LB, VEC, COLSUM>(A, lda, B, ldb, M, N, K, m0, n0, lds, xd, acc[0], asum);
+    }
+    if (COLSUM) {
+#pragma unroll
+      for (int t = 0; t < Cfg::WTM; ++t) asum[t] += __shfl_xor(asum[t], 32);
+    }
+    typename Epi::Dev ed(epi, M, N);
+    reduce_and_finish<Cfg, 1>(lds, M, N, m0, n0, acc, asum, ed);
+    ed.finish();
+
+    if (COLSUM && n0 == 0) {
+      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      const int wk = wave % Cfg::WK, wn = (wave / Cfg::WK) % Cfg::WN, wm = wave / (Cfg::WK * Cfg::WN);
+      if (wk == 0 && wn == 0 && lane < 32) {
+#pragma unroll
+        for (int t = 0; t < Cfg::WTM; ++t) {
+          int row = m0 + (wm * Cfg::WTM + t) * 32 + lane;
+          if (row < M) colsum_out[row] = colsum_scale * asum[t];
+        }
       }
     }
   }
-}
+};
 
 // One layer of the phase-III sweep: both NT products for the same output tile, then EpiVijp.
 //   acc0 = X[M][K] W[N][K]^T ,  acc1 = Hin[M][K] P[N][K]^T
 template <class Cfg, bool VEC, bool RELU>
-__global__ void __launch_bounds__(Cfg::NT)
-vijp_dual_kernel(int M, int N, int K, const float* __restrict__ X, const float* __restrict__ W,
-                 const float* __restrict__ Hin, const float* __restrict__ P, EpiVijp<RELU> epi, int tiles_m,
-                 int tiles_n) {
+struct VijpTask {
+  int M, N, K;
+  const float* X;
+  const float* W;
+  const float* Hin;
+  const float* P;
+  EpiVijp<RELU> epi;
+  int tiles_m, tiles_n;
+  static constexpr int LDS_BYTES = lds_bytes<Cfg, KCONTIG, KCONTIG, 2>();
+  __host__ __device__ int blocks() const { return tiles_m * tiles_n; }
+
+  __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
+    int tm_i, tn_i;
+    tile_coords(bid, tiles_m, tiles_n, tm_i, tn_i);
+    const int m0 = tm_i * Cfg::BM, n0 = tn_i * Cfg::BN;
+
+    f32x16 acc[2][Cfg::NACC];
+    float asum[Cfg::WTM];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int a = 0; a < Cfg::NACC; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[s][a][i] = 0.f;
+#pragma unroll
+    for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
+
+    const ANone::Dev none;
+    gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
+    gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
+    typename EpiVijp<RELU>::Dev ed(epi, M, N);
+    reduce_and_finish<Cfg, 2>(lds, M, N, m0, n0, acc, asum, ed);
+    ed.finish();
+  }
+};
+
+template <int NT, class Task>
+__global__ void __launch_bounds__(NT) task_kernel(Task t) {
   extern __shared__ __align__(16) float lds[];
-  int tm_i, tn_i;
-  tile_coords(tiles_m, tiles_n, tm_i, tn_i);
-  const int m0 = tm_i * Cfg::BM, n0 = tn_i * Cfg::BN;
+  t.run((int)blockIdx.x, lds);
+}
 
-  f32x16 acc[2][Cfg::NACC];
-  float asum[Cfg::WTM];
-#pragma unroll
-  for (int s = 0; s < 2; ++s)
-#pragma unroll
-    for (int a = 0; a < Cfg::NACC; ++a)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[s][a][i] = 0.f;
-#pragma unroll
-  for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
-
-  const ANone::Dev none;
-  gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
-  gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
-  typename EpiVijp<RELU>::Dev ed(epi, M, N);
-  reduce_and_finish<Cfg, 2>(lds, M, N, m0, n0, acc, asum, ed);
-  ed.finish();
+// Two independent tasks in one launch: blocks [0, first) run `a` (first = a.blocks() rounded up to
+// a multiple of 8, the surplus blocks exit at once), the rest run `b`. The workgroups of both
+// share the CUs, so the one task's memory stalls are filled with the other's matrix work, without
+// any cross-queue dependency.
+template <int NT, class TaskA, class TaskB>
+__global__ void __launch_bounds__(NT) task_pair_kernel(TaskA a, TaskB b, int first) {
+  extern __shared__ __align__(16) float lds[];
+  const int bid = (int)blockIdx.x;
+  if (bid < first) {
+    if (bid < a.blocks()) a.run(bid, lds);
+  } else {
+    b.run(bid - first, lds);
+  }
 }
 
 // ------------------------------------------------------------------------------------ launch helpers
@@ -385,18 +426,33 @@ inline hipError_t ensure_lds(KernelT kernel, int bytes) {
                              bytes);
 }
 
-template <class Cfg, int LA, int LB, bool VEC, class Xf, class Epi, bool COLSUM>
-inline hipError_t launch_gemm_v(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
-                                const Xf& xf, const Epi& epi, float* colsum_out, float colsum_scale,
-                                hipStream_t stream) {
-  auto kernel = gemm_kernel<Cfg, LA, LB, VEC, Xf, Epi, COLSUM>;
-  constexpr int bytes = lds_bytes<Cfg, LA, LB, 1>();
+template <int NT, class Task>
+inline hipError_t launch_task(const Task& t, hipStream_t stream) {
+  auto kernel = task_kernel<NT, Task>;
+  static hipError_t attr = ensure_lds(kernel, Task::LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kernel, dim3(t.blocks()), dim3(NT), Task::LDS_BYTES, stream, t);
+  return hipGetLastError();
+}
+
+template <int NT, class TaskA, class TaskB>
+inline hipError_t launch_task_pair(const TaskA& a, const TaskB& b, hipStream_t stream) {
+  auto kernel = task_pair_kernel<NT, TaskA, TaskB>;
+  constexpr int bytes = TaskA::LDS_BYTES > TaskB::LDS_BYTES ? TaskA::LDS_BYTES : TaskB::LDS_BYTES;
   static hipError_t attr = ensure_lds(kernel, bytes);
   if (attr != hipSuccess) return attr;
-  int tiles_m = ceil_div(M, Cfg::BM), tiles_n = ceil_div(N, Cfg::BN);
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(Cfg::NT), bytes, stream, M, N, K, A, lda, B, ldb, xf,
-                     epi, colsum_out, colsum_scale, tiles_m, tiles_n);
+  const int first = (a.blocks() + 7) / 8 * 8;
+  hipLaunchKernelGGL(kernel, dim3(first + b.blocks()), dim3(NT), bytes, stream, a, b, first);
   return hipGetLastError();
+}
+
+template <class Cfg, int LA, int LB, bool VEC, class Xf, class Epi, bool COLSUM>
+inline GemmTask<Cfg, LA, LB, VEC, Xf, Epi, COLSUM> make_gemm_task(int M, int N, int K, const float* A, int64_t lda,
+                                                                  const float* B, int64_t ldb, const Xf& xf,
+                                                                  const Epi& epi, float* colsum_out,
+                                                                  float colsum_scale) {
+  return GemmTask<Cfg, LA, LB, VEC, Xf, Epi, COLSUM>{M, N, K, A, lda, B, ldb, xf, epi, colsum_out, colsum_scale,
+                                                      ceil_div(M, Cfg::BM), ceil_div(N, Cfg::BN)};
 }
 
 template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
@@ -410,23 +466,22 @@ inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, 
     return hipErrorInvalidValue;
   const bool vec = xf_vec_ok && operand_vec_ok(A, lda, a_k ? K : M) && operand_vec_ok(B, ldb, b_k ? K : N);
   if (vec)
-    return launch_gemm_v<Cfg, LA, LB, true, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
-                                                            colsum_scale, stream);
-  return launch_gemm_v<Cfg, LA, LB, false, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out,
-                                                           colsum_scale, stream);
+    return launch_task<Cfg::NT>(make_gemm_task<Cfg, LA, LB, true, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi,
+                                                                                   colsum_out, colsum_scale),
+                                stream);
+  return launch_task<Cfg::NT>(make_gemm_task<Cfg, LA, LB, false, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi,
+                                                                                  colsum_out, colsum_scale),
+                              stream);
+}
+
+inline bool vijp_vec_ok(int K, const float* X, const float* W, const float* Hin, const float* P) {
+  return (K % 4 == 0) && aligned16(X) && aligned16(W) && aligned16(Hin) && aligned16(P);
 }
 
 template <class Cfg, bool VEC, bool RELU>
-inline hipError_t launch_vijp_dual_v(int M, int N, int K, const float* X, const float* W, const float* Hin,
-                                     const float* P, const EpiVijp<RELU>& epi, hipStream_t stream) {
-  auto kernel = vijp_dual_kernel<Cfg, VEC, RELU>;
-  constexpr int bytes = lds_bytes<Cfg, KCONTIG, KCONTIG, 2>();
-  static hipError_t attr = ensure_lds(kernel, bytes);
-  if (attr != hipSuccess) return attr;
-  int tiles_m = ceil_div(M, Cfg::BM), tiles_n = ceil_div(N, Cfg::BN);
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(Cfg::NT), bytes, stream, M, N, K, X, W, Hin, P, epi,
-                     tiles_m, tiles_n);
-  return hipGetLastError();
+inline VijpTask<Cfg, VEC, RELU> make_vijp_task(int M, int N, int K, const float* X, const float* W, const float* Hin,
+                                               const float* P, const EpiVijp<RELU>& epi) {
+  return VijpTask<Cfg, VEC, RELU>{M, N, K, X, W, Hin, P, epi, ceil_div(M, Cfg::BM), ceil_div(N, Cfg::BN)};
 }
 
 template <class Cfg, bool RELU>
@@ -434,9 +489,9 @@ inline hipError_t launch_vijp_dual(int M, int N, int K, const float* X, const fl
                                    const float* P, const EpiVijp<RELU>& epi, hipStream_t stream) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (!extent_ok(M, K, K) || !extent_ok(N, K, K) || !extent_ok(M, N, N)) return hipErrorInvalidValue;
-  const bool vec = (K % 4 == 0) && aligned16(X) && aligned16(W) && aligned16(Hin) && aligned16(P);
-  if (vec) return launch_vijp_dual_v<Cfg, true, RELU>(M, N, K, X, W, Hin, P, epi, stream);
-  return launch_vijp_dual_v<Cfg, false, RELU>(M, N, K, X, W, Hin, P, epi, stream);
+  if (vijp_vec_ok(K, X, W, Hin, P))
+    return launch_task<Cfg::NT>(make_vijp_task<Cfg, true, RELU>(M, N, K, X, W, Hin, P, epi), stream);
+  return launch_task<Cfg::NT>(make_vijp_task<Cfg, false, RELU>(M, N, K, X, W, Hin, P, epi), stream);
 }
 
 }  // namespace mw

@@ -120,12 +120,16 @@ struct mw_handle {
   const uint32_t** count_ptrs = nullptr;  // device array [n_relu]
   uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
   double* loss_scratch = nullptr;
+  // Phase III runs layer i's kernel and layer i-1's weight-gradient product in one launch: the
+  // latter still reads ct_z_{i-1} and x_{i-2} while the former writes ct_z_i and x_i, so the
+  // activation buffers rotate over three and the ct_z buffers over two.
+  float *xc = nullptr, *ctz2 = nullptr;
   // backprop workspace
   float *bp_ha = nullptr, *bp_hb = nullptr;
 
   // measurement aid: run only the launches of one kernel class (-1 = all), count launches
   int class_filter = -1;
-  uint64_t launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0};
+  uint64_t launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0, 0};
 
   void* alloc(size_t bytes, uint64_t* item) {
     if (bytes == 0) bytes = 4;
@@ -316,6 +320,7 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
          alloc_t(h, &h->ctz, nmax, &st.bytes_mw_scratch) &&
          alloc_t(h, &h->h0, B * (size_t)h->layers[0].d_in, &st.bytes_mw_scratch);
     if (!h->fuse) ok = ok && alloc_t(h, &h->zbuf, nmax, &st.bytes_mw_scratch);
+    if (h->fuse) ok = ok && alloc_t(h, &h->xc, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->ctz2, nmax, &st.bytes_mw_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   ok = ok && alloc_t(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_mw_scratch);
@@ -426,19 +431,44 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
   const float inv_scale = 1.0f / h->loss_scale;
   xin = x;
   const float* hin = h->h0;
-  for (int i = 0; i < L; ++i) {
-    Layer& l = h->layers[i];
-    if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
-    float* xout = xbuf[i & 1];
-    float* hout = hbuf[i & 1];
-    const bool relu = (l.alpha == 0.f);
-    if (h->fuse) {
+  if (h->fuse) {
+    // Launch k carries layer k's kernel and layer k-1's weight gradient (see the buffer rotation
+    // at the handle); a last launch carries the final weight gradient alone. With a class filter
+    // set the two are launched separately so that each can be timed alone.
+    const bool paired = h->class_filter < 0 || h->class_filter == MW_KCLASS_PHASE3;
+    float* xrot[3] = {h->xa, h->xb, h->xc};
+    float* crot[2] = {h->ctz, h->ctz2};
+    DwArgs pending{};
+    bool have_pending = false;
+    for (int i = 0; i < L; ++i) {
+      Layer& l = h->layers[i];
+      if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+      float* xout = xrot[i % 3];
+      float* ctz = crot[i & 1];
+      float* hout = hbuf[i & 1];
+      const bool relu = (l.alpha == 0.f);
       VijpArgs a{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
-                 relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, h->ctz, mismatches};
-      MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
-      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, l.d_out, l.d_in, B, h->ctz, xin, inv_scale, grads_out + l.dW_off,
-                     grads_out + l.db_off, s));
-    } else {
+                 relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, ctz, mismatches};
+      DwArgs d{l.d_out, l.d_in, B, ctz, xin, inv_scale, grads_out + l.dW_off, grads_out + l.db_off};
+      if (paired) {
+        MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_pair(&a, B, l.d_out, l.d_in, have_pending ? &pending : nullptr, s));
+        pending = d;
+        have_pending = true;
+      } else {
+        MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
+        MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, d.M, d.N, d.K, d.CTZ, d.X, d.scale, d.dW, d.db, s));
+      }
+      xin = xout;
+      hin = hout;
+    }
+    if (have_pending) MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_pair(nullptr, 0, 0, 0, &pending, s));
+  } else {
+    for (int i = 0; i < L; ++i) {
+      Layer& l = h->layers[i];
+      if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+      float* xout = xbuf[i & 1];
+      float* hout = hbuf[i & 1];
+      const bool relu = (l.alpha == 0.f);
       MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
                         l.b, s));
       MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, hin, l.d_in, l.P, l.d_in, 0.f, h->ctz, l.d_out,
@@ -448,9 +478,9 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
                               s));
       MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, l.d_out, l.d_in, B, h->ctz, xin, inv_scale, grads_out + l.dW_off, nullptr, s));
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, grads_out + l.db_off, s));
+      xin = xout;
+      hin = hout;
     }
-    xin = xout;
-    hin = hout;
   }
   return MW_OK;
 }
@@ -476,13 +506,17 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* gr
   for (int i = L - 1; i >= 0; --i) {
     Layer& l = h->layers[i];
     const float* xprev = (i == 0) ? x : h->layers[i - 1].act;
-    // dW_i = (h_i .* f'(x_i))^T x_{i-1}, db_i = column sums
-    MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(TILE_AUTO, l.d_out, l.d_in, B, hbuf[sel], l.act, l.alpha, xprev, inv_scale,
-                       grads_out + l.dW_off, grads_out + l.db_off, s));
-    if (i > 0) {  // the input cotangent of the first layer is not needed
-      MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(TILE_AUTO, B, l.d_in, l.d_out, hbuf[sel], l.act, l.alpha, l.W, hbuf[sel ^ 1], s));
-      sel ^= 1;
+    // dW_i = (h_i .* f'(x_i))^T x_{i-1}, db_i = column sums, and (except for the first layer, whose
+    // input cotangent nobody needs) h_{i-1} = (h_i .* f'(x_i)) W_i: one launch for both products
+    BpLayerArgs a{B, l.d_out, l.d_in, hbuf[sel], l.act, l.alpha, xprev, l.W, inv_scale,
+                  grads_out + l.dW_off, grads_out + l.db_off, i > 0 ? hbuf[sel ^ 1] : nullptr};
+    if (h->class_filter < 0) {
+      MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_bp_layer(a, s));
+    } else {
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(TILE_AUTO, l.d_out, l.d_in, B, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, s));
+      if (i > 0) MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(TILE_AUTO, B, l.d_in, l.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, s));
     }
+    if (i > 0) sel ^= 1;
   }
   return MW_OK;
 }

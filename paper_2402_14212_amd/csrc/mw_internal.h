@@ -73,6 +73,36 @@ struct VijpArgs {
 };
 hipError_t gemm_vijp_dual(int tile, int M, int N, int K, const VijpArgs& a, hipStream_t stream);
 
+// One launch for two independent pieces of the phase-III sweep: layer i's kernel (M x N x K as in
+// gemm_vijp_dual) and the weight-gradient product of layer i-1 (gemm_dw's arguments). Either may be
+// absent (NULL). Falls back to separate launches when the two cannot share a kernel.
+struct DwArgs {
+  int M, N, K;          // d_out, d_in, batch
+  const float* CTZ;     // [K][M]
+  const float* X;       // [K][N]
+  float scale;
+  float* dW;            // [M][N]
+  float* db;            // [M] or NULL
+};
+hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream);
+
+// Backprop's two products of one layer in one launch (both read h .* slope(act)):
+//   dW[dout][din] = scale (Hy .* slope)^T Xprev, db = scale * column sums;   Hout[B][din] = (Hy .* slope) W
+// Hout == NULL skips the second product (first layer).
+struct BpLayerArgs {
+  int batch, d_out, d_in;
+  const float* Hy;     // [B][d_out]
+  const float* act;    // [B][d_out] stored activation of this layer
+  float alpha;
+  const float* Xprev;  // [B][d_in]
+  const float* W;      // [d_out][d_in]
+  float scale;
+  float* dW;
+  float* db;
+  float* Hout;         // [B][d_in] or NULL
+};
+hipError_t gemm_bp_layer(const BpLayerArgs& a, hipStream_t stream);
+
 // ---- elementwise / integer kernels (elementwise.hip) ----
 hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, int d, float alpha, float* x,
                             uint64_t* mask, hipStream_t stream);

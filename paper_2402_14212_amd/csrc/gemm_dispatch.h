@@ -23,6 +23,9 @@ inline hipError_t dispatch_gemm(int tile, int M, int N, int K, const float* A, i
     case TILE_32K8:
       return launch_gemm<Tile32K8, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
                                                            colsum_scale, stream);
+    case TILE_64K2:
+      return launch_gemm<Tile64K2, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
+                                                           colsum_scale, stream);
     default:
       return hipErrorInvalidValue;
   }

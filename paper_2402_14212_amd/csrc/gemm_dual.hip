@@ -14,6 +14,7 @@ static hipError_t vijp_dual_t(int tile, int M, int N, int K, const VijpArgs& a, 
     case TILE_64: return launch_vijp_dual<Tile64, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     case TILE_32K4: return launch_vijp_dual<Tile32K4, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     case TILE_32K8: return launch_vijp_dual<Tile32K8, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
+    case TILE_64K2: return launch_vijp_dual<Tile64K2, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     default: return hipErrorInvalidValue;
   }
 }
@@ -39,6 +40,7 @@ static hipError_t pair_d(int tile_d, int M, int N, int K, const VijpArgs& a, con
 template <bool RELU>
 static hipError_t pair_v(int tile_v, int tile_d, int M, int N, int K, const VijpArgs& a, const DwArgs& d,
                          hipStream_t stream) {
+  if (tile_v == TILE_64K2) return pair_t<Tile64K2, RELU, Tile64K2>(M, N, K, a, d, stream);
   switch (tile_v) {
     case TILE_128: return pair_d<Tile128, RELU>(tile_d, M, N, K, a, d, stream);
     case TILE_64: return pair_d<Tile64, RELU>(tile_d, M, N, K, a, d, stream);
@@ -46,22 +48,33 @@ static hipError_t pair_v(int tile_v, int tile_d, int M, int N, int K, const Vijp
   }
 }
 
+// The weight-gradient tile next to a layer kernel of tile `partner` (TILE_AUTO: none). Both tasks
+// of a launch need the same workgroup size, so the eight-wavefront 64x64 tile is taken exactly
+// when the partner has it. The rule depends on the shapes alone: launched together or apart, a
+// product gets the same tile and therefore the same bits.
+int pick_tile_dw(int M, int N, int K, int partner) {
+  const int t = pick_tile(M, N, K);
+  if (t == TILE_128) return partner == TILE_64K2 ? TILE_64K2 : TILE_128;
+  return partner == TILE_64K2 ? TILE_64K2 : TILE_64;
+}
+
 hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream) {
+  const int tile_v = v ? pick_tile(M, N, K) : TILE_AUTO;
+  const int tile_d = d ? pick_tile_dw(d->M, d->N, d->K, tile_v) : TILE_AUTO;
   if (v && d && M > 0 && N > 0 && d->M > 0 && d->N > 0 && d->db) {
-    const int tile_v = pick_tile(M, N, K), tile_d = pick_tile(d->M, d->N, d->K);
     const bool shapes_ok = extent_ok(M, K, K) && extent_ok(N, K, K) && extent_ok(M, N, N) &&
                            extent_ok(d->K, d->M, d->M) && extent_ok(d->K, d->N, d->N) && extent_ok(d->M, d->N, d->N);
     const bool vec = vijp_vec_ok(K, v->X, v->W, v->Hin, v->P) && operand_vec_ok(d->CTZ, d->M, d->M) &&
                      operand_vec_ok(d->X, d->N, d->N);
-    if (shapes_ok && vec && tile_v != TILE_32K8 && (tile_d == TILE_128 || tile_d == TILE_64))
+    if (shapes_ok && vec && tile_v != TILE_32K8)
       return v->alpha == 0.f ? pair_v<true>(tile_v, tile_d, M, N, K, *v, *d, stream)
                              : pair_v<false>(tile_v, tile_d, M, N, K, *v, *d, stream);
   }
   if (v) {
-    hipError_t e = gemm_vijp_dual(TILE_AUTO, M, N, K, *v, stream);
+    hipError_t e = gemm_vijp_dual(tile_v, M, N, K, *v, stream);
     if (e != hipSuccess) return e;
   }
-  if (d) return gemm_dw(TILE_AUTO, d->M, d->N, d->K, d->CTZ, d->X, d->scale, d->dW, d->db, stream);
+  if (d) return gemm_dw(tile_d, d->M, d->N, d->K, d->CTZ, d->X, d->scale, d->dW, d->db, stream);
   return hipSuccess;
 }
 
@@ -81,6 +94,7 @@ static hipError_t bp_pair_t(const BpLayerArgs& a, hipStream_t stream) {
 template <class CfgD>
 static hipError_t bp_pair_r(int tile_r, const BpLayerArgs& a, hipStream_t stream) {
   switch (tile_r) {
+    case TILE_64K2: return bp_pair_t<Tile64K2, Tile64K2>(a, stream);
     case TILE_128: return bp_pair_t<CfgD, Tile128>(a, stream);
     case TILE_64: return bp_pair_t<CfgD, Tile64>(a, stream);
     default: return bp_pair_t<CfgD, Tile32K4>(a, stream);
@@ -88,18 +102,19 @@ static hipError_t bp_pair_r(int tile_r, const BpLayerArgs& a, hipStream_t stream
 }
 
 hipError_t gemm_bp_layer(const BpLayerArgs& a, hipStream_t stream) {
+  const int tile_r = a.Hout ? pick_tile(a.batch, a.d_in, a.d_out) : TILE_AUTO;
+  const int tile_d = pick_tile_dw(a.d_out, a.d_in, a.batch, tile_r);
   if (a.Hout && a.batch > 0 && a.d_in > 0 && a.d_out > 0) {
-    const int tile_d = pick_tile(a.d_out, a.d_in, a.batch), tile_r = pick_tile(a.batch, a.d_in, a.d_out);
     const bool shapes_ok = extent_ok(a.batch, a.d_out, a.d_out) && extent_ok(a.batch, a.d_in, a.d_in) &&
                            extent_ok(a.d_out, a.d_in, a.d_in);
     const bool vec = operand_vec_ok(a.Hy, a.d_out, a.d_out) && aligned16(a.act) && operand_vec_ok(a.Xprev, a.d_in, a.d_in) &&
                      operand_vec_ok(a.W, a.d_in, a.d_in);
-    if (shapes_ok && vec && tile_r != TILE_32K8 && (tile_d == TILE_128 || tile_d == TILE_64))
+    if (shapes_ok && vec && tile_r != TILE_32K8)
       return tile_d == TILE_128 ? bp_pair_r<Tile128>(tile_r, a, stream) : bp_pair_r<Tile64>(tile_r, a, stream);
   }
-  hipError_t e = gemm_dw_act(TILE_AUTO, a.d_out, a.d_in, a.batch, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, stream);
+  hipError_t e = gemm_dw_act(tile_d, a.d_out, a.d_in, a.batch, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, stream);
   if (e != hipSuccess || !a.Hout) return e;
-  return gemm_rev_act(TILE_AUTO, a.batch, a.d_in, a.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, stream);
+  return gemm_rev_act(tile_r, a.batch, a.d_in, a.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, stream);
 }
 
 hipError_t gemm_vijp_dual(int tile, int M, int N, int K, const VijpArgs& a, hipStream_t stream) {

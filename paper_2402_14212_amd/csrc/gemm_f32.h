@@ -42,6 +42,7 @@ using Tile128 = TileCfg<2, 2, 2, 2, 1>;   // 128 x 128, K tile 32, 4 wavefronts
 using Tile64 = TileCfg<1, 1, 2, 2, 1>;    //  64 x  64, K tile 32, 4 wavefronts
 using Tile32K4 = TileCfg<1, 1, 1, 1, 4>;  //  32 x  32, K tile 128 split over 4 wavefronts
 using Tile32K8 = TileCfg<1, 1, 1, 1, 8>;  //  32 x  32, K tile 256 split over 8 wavefronts
+using Tile64K2 = TileCfg<1, 1, 2, 2, 2>;  //  64 x  64, K tile 64 split over 2 groups of 4 wavefronts
 
 // LDS footprint (floats) of one operand tile of R rows.
 template <int LAYOUT, int R, int BK>

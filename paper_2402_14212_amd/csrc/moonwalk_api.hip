@@ -25,11 +25,15 @@ hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float
 int pick_tile(int M, int N, int K) {
   auto tiles = [](int m, int n, int t) { return (int64_t)((m + t - 1) / t) * ((n + t - 1) / t); };
   // Measured on MI355X (256 CUs) over the layer shapes of the five configurations: the 64x64 tile
-  // wins whenever it yields at least one workgroup for most CUs; the 128x128 tile only pays once
-  // there are several waves of them (the large weight-gradient products); outputs too small for
-  // 64x64 tiles split K over the four wavefronts of a 32x32 tile.
+  // wins whenever it yields at least one workgroup for most CUs, with eight wavefronts (K split
+  // over two groups of four) while there are fewer than two workgroups per CU and with four
+  // beyond; the 128x128 tile only pays once there are several waves of them (the large
+  // weight-gradient products); outputs too small for 64x64 tiles split K over the four
+  // wavefronts of a 32x32 tile.
+  const int64_t t64 = tiles(M, N, 64);
   if (tiles(M, N, 128) >= 512) return TILE_128;
-  if (tiles(M, N, 64) >= 192) return TILE_64;
+  if (t64 >= 512) return TILE_64;
+  if (t64 >= 192) return K >= 128 ? TILE_64K2 : TILE_64;
   if (K >= 256) return TILE_32K4;
   return TILE_64;
 }
@@ -455,8 +459,11 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
         pending = d;
         have_pending = true;
       } else {
+        // same tiles as in the paired launches: the weight gradient's follows the next layer's kernel
+        const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
         MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
-        MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, d.M, d.N, d.K, d.CTZ, d.X, d.scale, d.dW, d.db, s));
+        MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(d.M, d.N, d.K, partner), d.M, d.N, d.K, d.CTZ, d.X, d.scale,
+                                              d.dW, d.db, s));
       }
       xin = xout;
       hin = hout;
@@ -476,7 +483,9 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_vijp_epilogue(h->zbuf, h->ctz, B, l.d_out, l.alpha, l.mask, l.offsets, h->frag,
                               relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, mismatches,
                               s));
-      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(TILE_AUTO, l.d_out, l.d_in, B, h->ctz, xin, inv_scale, grads_out + l.dW_off, nullptr, s));
+      const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(l.d_out, l.d_in, B, partner), l.d_out, l.d_in, B, h->ctz, xin, inv_scale,
+                                            grads_out + l.dW_off, nullptr, s));
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, grads_out + l.db_off, s));
       xin = xout;
       hin = hout;
@@ -513,8 +522,10 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* gr
     if (h->class_filter < 0) {
       MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_bp_layer(a, s));
     } else {
-      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(TILE_AUTO, l.d_out, l.d_in, B, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, s));
-      if (i > 0) MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(TILE_AUTO, B, l.d_in, l.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, s));
+      const int tile_r = (i > 0) ? pick_tile(B, l.d_in, l.d_out) : TILE_AUTO;
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(pick_tile_dw(l.d_out, l.d_in, B, tile_r), l.d_out, l.d_in, B, a.Hy, a.act, a.alpha,
+                                                a.Xprev, a.scale, a.dW, a.db, s));
+      if (i > 0) MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(tile_r, B, l.d_in, l.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, s));
     }
     if (i > 0) sel ^= 1;
   }
@@ -631,7 +642,7 @@ const char* moonwalk_strerror(int code) {
 int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
                 const float* B, int32_t ldb, float beta, float* C, int32_t ldc, void* hip_stream) {
   if (M < 0 || N < 0 || K < 0 || !C || (K > 0 && (!A || !B))) return MW_ERR_INVALID_ARG;
-  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_32K8) return MW_ERR_INVALID_ARG;
+  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_64K2) return MW_ERR_INVALID_ARG;
   // leading dimensions must cover the fast index of each operand
   const int a_fast = (op == MW_GEMM_TN) ? M : K, b_fast = (op == MW_GEMM_NT) ? K : N;
   if (lda < a_fast || ldb < b_fast || ldc < N) return MW_ERR_INVALID_ARG;

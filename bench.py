@@ -133,6 +133,16 @@ def main():
         if k in class_flops and n_k:
             per_class[k]["tflops"] = class_flops[k] * B * sum_dd / (ms_k * 1e-3) / 1e12
     net.profile_filter(None)
+    # The few small elementwise launches run alone are bound by the host's launch rate, not by the
+    # GPU: report that class as what is left of the step after the GEMM classes.
+    ew = per_class["ew"]
+    ew["ms_per_step_alone"] = ew["ms_per_step"]
+    gemm_ms = sum(per_class[k]["ms_per_step"] for k in ("fwd", "rev", "phase3"))
+    if per_class["phase3"]["launches_per_step"] == 0:
+        gemm_ms += per_class["vijp"]["ms_per_step"] + per_class["dw"]["ms_per_step"]
+    ew["ms_per_step"] = max(0.0, ms_mw - gemm_ms)
+    ew["avg_us"] = ew["ms_per_step"] / ew["launches_per_step"] * 1e3 if ew["launches_per_step"] else None
+    ew["method"] = "step time minus the GEMM classes"
     dom = "phase3" if per_class["phase3"]["launches_per_step"] else "vijp"      # unfused runs have no paired launches
     n_v = per_class[dom]["launches_per_step"]
     avg_ms = per_class[dom]["ms_per_step"] / max(n_v, 1)

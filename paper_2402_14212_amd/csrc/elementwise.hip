@@ -358,11 +358,14 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
   return t;
 }
 
-__global__ void __launch_bounds__(SCAN_THREADS)
-k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets, int64_t chunk) {
-  __shared__ uint32_t red[SCAN_THREADS];
+__device__ __forceinline__ void frag_offsets_chunk(const uint64_t* __restrict__ mask, int64_t n,
+                                                   uint32_t* __restrict__ offsets, int64_t chunk, uint32_t* red) {
   const int64_t n_words = (n + 63) >> 6;
   const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  if (c0 >= n_words) {  // nothing to scan here; an empty mask still gets its total
+    if (n_words == 0 && blockIdx.x == 0 && threadIdx.x == 0) offsets[0] = 0u;
+    return;
+  }
   const int64_t c1 = c0 + chunk < n_words ? c0 + chunk : n_words;
   // erased bits before this chunk
   uint32_t before = 0;
@@ -387,20 +390,47 @@ k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restric
     offsets[w] = run;
     run += erased_in_word(mask[w], w, n);
   }
-  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = before + red[SCAN_THREADS - 1];
+  if (c1 == n_words && threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = before + red[SCAN_THREADS - 1];
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets, int64_t chunk) {
+  __shared__ uint32_t red[SCAN_THREADS];
+  frag_offsets_chunk(mask, n, offsets, chunk, red);
+}
+
+// The same for several layers in one launch: blockIdx.y selects the layer.
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_frag_offsets_layers(const FragLayer* __restrict__ layers, int64_t chunk) {
+  __shared__ uint32_t red[SCAN_THREADS];
+  const FragLayer l = layers[blockIdx.y];
+  frag_offsets_chunk(l.mask, l.n, l.offsets, chunk, red);
 }
 
 // Layer bases: exclusive scan of the erased counts in the order given (reverse-pass order).
-__global__ void k_frag_bases(const uint32_t* const* __restrict__ count_ptrs, int n_relu,
-                             uint64_t* __restrict__ bases, uint64_t* __restrict__ total) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    uint64_t run = 0;
-    for (int j = 0; j < n_relu; ++j) {
-      bases[j] = run;
-      run += *count_ptrs[j];
+// The counts are fetched 256 at a time by the whole workgroup; one thread adds them up.
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_frag_bases(const uint32_t* const* __restrict__ count_ptrs, int n_relu, uint64_t* __restrict__ bases,
+             uint64_t* __restrict__ total) {
+  __shared__ uint32_t cnt[SCAN_THREADS];
+  __shared__ uint64_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  for (int j0 = 0; j0 < n_relu; j0 += SCAN_THREADS) {
+    const int j = j0 + threadIdx.x;
+    cnt[threadIdx.x] = j < n_relu ? *count_ptrs[j] : 0u;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint64_t run = carry;
+      const int m = n_relu - j0 < SCAN_THREADS ? n_relu - j0 : SCAN_THREADS;
+      for (int k = 0; k < m; ++k) {
+        bases[j0 + k] = run;
+        run += cnt[k];
+      }
+      carry = run;
     }
-    *total = run;
+    __syncthreads();
   }
+  if (threadIdx.x == 0) *total = carry;
 }
 
 // ---------------------------------------------------------------- phase II: fragment compaction
@@ -531,13 +561,20 @@ k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n
   if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
-__global__ void k_loss_final(const double* __restrict__ partial, int n_partial, double factor,
-                             float* __restrict__ loss) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    double s = 0.0;
-    for (int i = 0; i < n_partial; ++i) s += partial[i];
-    *loss = (float)(factor * s);
+// Sum of the per-workgroup partials in a fixed order (thread t takes partials t, t + 256, ...;
+// then a fixed tree), so the loss does not depend on scheduling.
+__global__ void __launch_bounds__(EW_THREADS)
+k_loss_final(const double* __restrict__ partial, int n_partial, double factor, float* __restrict__ loss) {
+  __shared__ double red[EW_THREADS];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n_partial; i += EW_THREADS) acc += partial[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
   }
+  if (threadIdx.x == 0) *loss = (float)(factor * red[0]);
 }
 
 // ---------------------------------------------------------------- copy / fill
@@ -627,9 +664,21 @@ hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, h
   return hipGetLastError();
 }
 
+hipError_t ew_frag_offsets_layers(const FragLayer* layers, int n_layers, int64_t max_n, hipStream_t stream) {
+  if (n_layers <= 0) return hipSuccess;
+  if (max_n < 0 || n_layers > 65535) return hipErrorInvalidValue;
+  const int64_t n_words = (max_n + 63) >> 6;
+  int64_t chunk = (int64_t)SCAN_THREADS * SCAN_WORDS_PER_THREAD;
+  if (chunk * SCAN_MAX_BLOCKS < n_words) chunk = (n_words + SCAN_MAX_BLOCKS - 1) / SCAN_MAX_BLOCKS;
+  int blocks = (int)((n_words + chunk - 1) / chunk);
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_frag_offsets_layers, dim3(blocks, n_layers), dim3(SCAN_THREADS), 0, stream, layers, chunk);
+  return hipGetLastError();
+}
+
 hipError_t ew_frag_bases(const uint32_t* const* count_ptrs, int n_relu, uint64_t* bases, uint64_t* total,
                          hipStream_t stream) {
-  hipLaunchKernelGGL(k_frag_bases, dim3(1), dim3(64), 0, stream, count_ptrs, n_relu, bases, total);
+  hipLaunchKernelGGL(k_frag_bases, dim3(1), dim3(SCAN_THREADS), 0, stream, count_ptrs, n_relu, bases, total);
   return hipGetLastError();
 }
 
@@ -692,7 +741,7 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (loss) {
-    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(64), 0, stream, scratch, LOSS_BLOCKS, 0.5 / (double)rows, loss);
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, LOSS_BLOCKS, 0.5 / (double)rows, loss);
     e = hipGetLastError();
   }
   return e;

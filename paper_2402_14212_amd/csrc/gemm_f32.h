@@ -301,7 +301,12 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
   b0.store(s0 + A_FLOATS, none);
   __syncthreads();
 
-  for (int t = 0; t < nkt; t += 2) {
+  // Tiles are taken two at a time with no exit between them, and an odd last tile is peeled off
+  // after the loop: an exit in the middle of the body makes the compiler assume, at the loop
+  // head, that either half's loads may still be pending, and it then waits for all of them
+  // before every first half.
+  int t = 0;
+  for (; t + 2 <= nkt; t += 2) {
     // tile t is in stage 0, tile t+1 in registers (a1, b1); fetch tile t+2
     a0.load(ra, lda, m0, (t + 2) * BK, M, K, xf);
     b0.load(rb, ldb, n0, (t + 2) * BK, N, K, none);
@@ -309,13 +314,16 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
     a1.store(s1, xf);
     b1.store(s1 + A_FLOATS, none);
     __syncthreads();
-    if (t + 1 >= nkt) break;
     // tile t+1 is in stage 1, tile t+2 in registers (a0, b0); fetch tile t+3
     a1.load(ra, lda, m0, (t + 3) * BK, M, K, xf);
     b1.load(rb, ldb, n0, (t + 3) * BK, N, K, none);
     mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
     a0.store(s0, xf);
     b0.store(s0 + A_FLOATS, none);
+    __syncthreads();
+  }
+  if (t < nkt) {  // odd tile count: the last tile sits in stage 0
+    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
     __syncthreads();
   }
 }

@@ -24,16 +24,15 @@ hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float
 
 int pick_tile(int M, int N, int K) {
   auto tiles = [](int m, int n, int t) { return (int64_t)((m + t - 1) / t) * ((n + t - 1) / t); };
-  // Measured on MI355X (256 CUs) over the layer shapes of the five configurations: the 64x64 tile
-  // wins whenever it yields at least one workgroup for most CUs, with eight wavefronts (K split
-  // over two groups of four) while there are fewer than two workgroups per CU and with four
-  // beyond; the 128x128 tile only pays once there are several waves of them (the large
-  // weight-gradient products); outputs too small for 64x64 tiles split K over the four
-  // wavefronts of a 32x32 tile.
+  // Measured on MI355X (256 CUs) over the layer shapes of the five configurations. The 128x128
+  // tile only pays once there are several waves of them (the large weight-gradient products).
+  // The 64x64 tile wins whenever it yields at least one workgroup for most CUs: with eight
+  // wavefronts (K split over two groups of four) while K is long and there are at most a few
+  // workgroups per CU, with four otherwise. Outputs too small for 64x64 tiles split K over the
+  // four wavefronts of a 32x32 tile.
   const int64_t t64 = tiles(M, N, 64);
   if (tiles(M, N, 128) >= 512) return TILE_128;
-  if (t64 >= 512) return TILE_64;
-  if (t64 >= 192) return K >= 128 ? TILE_64K2 : TILE_64;
+  if (t64 >= 192) return (K >= 1024 && t64 < 2048) ? TILE_64K2 : TILE_64;
   if (K >= 256) return TILE_32K4;
   return TILE_64;
 }
@@ -122,6 +121,8 @@ struct mw_handle {
   int n_relu = 0;
   uint64_t* frag_bases = nullptr;         // [n_relu + 1]; last = total
   const uint32_t** count_ptrs = nullptr;  // device array [n_relu]
+  FragLayer* frag_layers = nullptr;       // device array [n_relu]: mask, offsets and size of every ReLU layer
+  int64_t frag_max_n = 0;                 // largest B * d_out among them
   uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
   double* loss_scratch = nullptr;
   // Phase III runs layer i's kernel and layer i-1's weight-gradient product in one launch: the
@@ -299,17 +300,23 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
       ok = ok && alloc_t(h, &h->frag, h->frag_capacity, &st.bytes_fragments);
       ok = ok && alloc_t(h, &h->frag_bases, (size_t)h->n_relu + 1, &st.bytes_frag_index);
       ok = ok && alloc_t(h, &h->count_ptrs, (size_t)h->n_relu, &st.bytes_frag_index);
+      ok = ok && alloc_t(h, &h->frag_layers, (size_t)h->n_relu, &st.bytes_frag_index);
       if (ok) {
         std::vector<const uint32_t*> ptrs;
+        std::vector<FragLayer> table;
         int slot = 0;
         for (int i = n_layers - 1; i >= 0; --i) {  // reverse-pass order: layer L first
           Layer& l = h->layers[i];
           if (l.alpha == 0.f) {
             l.relu_slot = slot++;
             ptrs.push_back(l.offsets + l.mask_words);
+            const int64_t n = (int64_t)(B * l.d_out);
+            table.push_back(FragLayer{l.mask, l.offsets, n});
+            if (n > h->frag_max_n) h->frag_max_n = n;
           }
         }
         e = hipMemcpy(h->count_ptrs, ptrs.data(), ptrs.size() * sizeof(ptrs[0]), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(h->frag_layers, table.data(), table.size() * sizeof(table[0]), hipMemcpyHostToDevice);
         if (e != hipSuccess) return fail(hip_fail(e, "fragment index init"));
       }
     }
@@ -375,9 +382,10 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
                         l.b, s));
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(h->zbuf, nullptr, B, l.d_out, l.alpha, xout, l.mask, s));
     }
-    if (l.alpha == 0.f) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_offsets(l.mask, (int64_t)B * l.d_out, l.offsets, s));
     xin = xout;
   }
+  // fragment index of all ReLU layers (needed from Phase II on): one scan launch, then the layer bases
+  if (h->n_relu > 0) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_offsets_layers(h->frag_layers, h->n_relu, h->frag_max_n, s));
   if (h->n_relu > 0) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_bases(h->count_ptrs, h->n_relu, h->frag_bases, h->frag_bases + h->n_relu, s));
 
   // ---------------- loss and output cotangent h_L

@@ -112,6 +112,13 @@ hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream
 hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
                         hipStream_t stream);
 hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream);
+// the same scan for several layers in one launch; `layers` is a device array, max_n the largest n in it
+struct FragLayer {
+  const uint64_t* mask;
+  uint32_t* offsets;   // [ceil(n / 64) + 1]
+  int64_t n;
+};
+hipError_t ew_frag_offsets_layers(const FragLayer* layers, int n_layers, int64_t max_n, hipStream_t stream);
 // base[i] for the ReLU layers in reverse-pass order: order[j] lists layer slots, counts[slot] points at
 // that layer's erased count (last entry of its offsets array)
 hipError_t ew_frag_bases(const uint32_t* const* count_ptrs, int n_relu, uint64_t* bases, uint64_t* total,

@@ -186,6 +186,8 @@ const char* moonwalk_strerror(int code);
 #define MW_TILE_32K4 3  /* 32x32 workgroup tile, K split over four wavefronts        */
 #define MW_TILE_32K8 4  /* 32x32 workgroup tile, K split over eight wavefronts       */
 #define MW_TILE_64K2 5  /* 64x64 workgroup tile, K split over two groups of four wavefronts */
+#define MW_TILE_128W8 6 /* 128x128 workgroup tile, eight wavefronts                     */
+#define MW_TILE_64X128 7 /* 64x128 workgroup tile, eight wavefronts                     */
 /* fp32 MFMA GEMM with LDS-staged tiles; lda/ldb/ldc are row strides in floats. */
 int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha,
                 const float* A, int32_t lda, const float* B, int32_t ldb, float beta,

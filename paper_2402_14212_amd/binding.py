@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
-TILE_AUTO, TILE_128, TILE_64, TILE_32K4, TILE_32K8, TILE_64K2 = 0, 1, 2, 3, 4, 5
+TILE_AUTO, TILE_128, TILE_64, TILE_32K4, TILE_32K8, TILE_64K2, TILE_128W8, TILE_64X128 = 0, 1, 2, 3, 4, 5, 6, 7
 PLAN_MOONWALK, PLAN_BACKPROP = 1, 2
 FETCH_MASK, FETCH_FRAG, FETCH_FRAG_OFFSETS, FETCH_FRAG_BASE, FETCH_H0, FETCH_P, FETCH_CHECKPOINT = range(1, 8)
 

@@ -26,6 +26,12 @@ inline hipError_t dispatch_gemm(int tile, int M, int N, int K, const float* A, i
     case TILE_64K2:
       return launch_gemm<Tile64K2, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
                                                            colsum_scale, stream);
+    case TILE_128W8:
+      return launch_gemm<Tile128W8, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
+                                                           colsum_scale, stream);
+    case TILE_64X128:
+      return launch_gemm<Tile64x128, LA, LB, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, xf_vec_ok, colsum_out,
+                                                           colsum_scale, stream);
     default:
       return hipErrorInvalidValue;
   }

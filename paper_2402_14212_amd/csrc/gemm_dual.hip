@@ -15,6 +15,8 @@ static hipError_t vijp_dual_t(int tile, int M, int N, int K, const VijpArgs& a, 
     case TILE_32K4: return launch_vijp_dual<Tile32K4, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     case TILE_32K8: return launch_vijp_dual<Tile32K8, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     case TILE_64K2: return launch_vijp_dual<Tile64K2, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
+    case TILE_128W8: return launch_vijp_dual<Tile128W8, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
+    case TILE_64X128: return launch_vijp_dual<Tile64x128, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi, stream);
     default: return hipErrorInvalidValue;
   }
 }
@@ -31,36 +33,34 @@ static hipError_t pair_t(int M, int N, int K, const VijpArgs& a, const DwArgs& d
   return launch_task_pair<CfgV::NT>(tv, td, stream);
 }
 
+// tile_d comes from pick_tile_dw: among the four-wavefront tiles next to a four-wavefront layer
+// kernel, the eight-wavefront 128x128 tile otherwise
 template <class CfgV, bool RELU>
 static hipError_t pair_d(int tile_d, int M, int N, int K, const VijpArgs& a, const DwArgs& d, hipStream_t stream) {
-  if (tile_d == TILE_128) return pair_t<CfgV, RELU, Tile128>(M, N, K, a, d, stream);
-  return pair_t<CfgV, RELU, Tile64>(M, N, K, a, d, stream);
+  if constexpr (CfgV::NT == 512) {
+    return pair_t<CfgV, RELU, Tile128W8>(M, N, K, a, d, stream);
+  } else {
+    if (tile_d == TILE_128) return pair_t<CfgV, RELU, Tile128>(M, N, K, a, d, stream);
+    return pair_t<CfgV, RELU, Tile64>(M, N, K, a, d, stream);
+  }
 }
 
 template <bool RELU>
 static hipError_t pair_v(int tile_v, int tile_d, int M, int N, int K, const VijpArgs& a, const DwArgs& d,
                          hipStream_t stream) {
-  if (tile_v == TILE_64K2) return pair_t<Tile64K2, RELU, Tile64K2>(M, N, K, a, d, stream);
   switch (tile_v) {
+    case TILE_128W8: return pair_d<Tile128W8, RELU>(tile_d, M, N, K, a, d, stream);
+    case TILE_64X128: return pair_d<Tile64x128, RELU>(tile_d, M, N, K, a, d, stream);
+    case TILE_64K2: return pair_d<Tile64K2, RELU>(tile_d, M, N, K, a, d, stream);
     case TILE_128: return pair_d<Tile128, RELU>(tile_d, M, N, K, a, d, stream);
     case TILE_64: return pair_d<Tile64, RELU>(tile_d, M, N, K, a, d, stream);
     default: return pair_d<Tile32K4, RELU>(tile_d, M, N, K, a, d, stream);
   }
 }
 
-// The weight-gradient tile next to a layer kernel of tile `partner` (TILE_AUTO: none). Both tasks
-// of a launch need the same workgroup size, so the eight-wavefront 64x64 tile is taken exactly
-// when the partner has it. The rule depends on the shapes alone: launched together or apart, a
-// product gets the same tile and therefore the same bits.
-int pick_tile_dw(int M, int N, int K, int partner) {
-  const int t = pick_tile(M, N, K);
-  if (t == TILE_128) return partner == TILE_64K2 ? TILE_64K2 : TILE_128;
-  return partner == TILE_64K2 ? TILE_64K2 : TILE_64;
-}
-
 hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream) {
   const int tile_v = v ? pick_tile(M, N, K) : TILE_AUTO;
-  const int tile_d = d ? pick_tile_dw(d->M, d->N, d->K, tile_v) : TILE_AUTO;
+  const int tile_d = d ? pick_tile_dw(d->M, d->N, d->K, tile_v, true) : TILE_AUTO;
   if (v && d && M > 0 && N > 0 && d->M > 0 && d->N > 0 && d->db) {
     const bool shapes_ok = extent_ok(M, K, K) && extent_ok(N, K, K) && extent_ok(M, N, N) &&
                            extent_ok(d->K, d->M, d->M) && extent_ok(d->K, d->N, d->N) && extent_ok(d->M, d->N, d->N);
@@ -91,26 +91,37 @@ static hipError_t bp_pair_t(const BpLayerArgs& a, hipStream_t stream) {
   return launch_task_pair<CfgD::NT>(tr, td, stream);
 }
 
-template <class CfgD>
-static hipError_t bp_pair_r(int tile_r, const BpLayerArgs& a, hipStream_t stream) {
+template <class CfgR>
+static hipError_t bp_pair_d(int tile_d, const BpLayerArgs& a, hipStream_t stream) {
+  if constexpr (CfgR::NT == 512) {
+    return bp_pair_t<Tile64x128, CfgR>(a, stream);
+  } else {
+    if (tile_d == TILE_128) return bp_pair_t<Tile128, CfgR>(a, stream);
+    return bp_pair_t<Tile64, CfgR>(a, stream);
+  }
+}
+
+static hipError_t bp_pair_r(int tile_r, int tile_d, const BpLayerArgs& a, hipStream_t stream) {
   switch (tile_r) {
-    case TILE_64K2: return bp_pair_t<Tile64K2, Tile64K2>(a, stream);
-    case TILE_128: return bp_pair_t<CfgD, Tile128>(a, stream);
-    case TILE_64: return bp_pair_t<CfgD, Tile64>(a, stream);
-    default: return bp_pair_t<CfgD, Tile32K4>(a, stream);
+    case TILE_128W8: return bp_pair_d<Tile128W8>(tile_d, a, stream);
+    case TILE_64X128: return bp_pair_d<Tile64x128>(tile_d, a, stream);
+    case TILE_64K2: return bp_pair_d<Tile64K2>(tile_d, a, stream);
+    case TILE_128: return bp_pair_d<Tile128>(tile_d, a, stream);
+    case TILE_64: return bp_pair_d<Tile64>(tile_d, a, stream);
+    default: return bp_pair_d<Tile32K4>(tile_d, a, stream);
   }
 }
 
 hipError_t gemm_bp_layer(const BpLayerArgs& a, hipStream_t stream) {
   const int tile_r = a.Hout ? pick_tile(a.batch, a.d_in, a.d_out) : TILE_AUTO;
-  const int tile_d = pick_tile_dw(a.d_out, a.d_in, a.batch, tile_r);
+  const int tile_d = pick_tile_dw(a.d_out, a.d_in, a.batch, tile_r, false);
   if (a.Hout && a.batch > 0 && a.d_in > 0 && a.d_out > 0) {
     const bool shapes_ok = extent_ok(a.batch, a.d_out, a.d_out) && extent_ok(a.batch, a.d_in, a.d_in) &&
                            extent_ok(a.d_out, a.d_in, a.d_in);
     const bool vec = operand_vec_ok(a.Hy, a.d_out, a.d_out) && aligned16(a.act) && operand_vec_ok(a.Xprev, a.d_in, a.d_in) &&
                      operand_vec_ok(a.W, a.d_in, a.d_in);
     if (shapes_ok && vec && tile_r != TILE_32K8)
-      return tile_d == TILE_128 ? bp_pair_r<Tile128>(tile_r, a, stream) : bp_pair_r<Tile64>(tile_r, a, stream);
+      return bp_pair_r(tile_r, tile_d, a, stream);
   }
   hipError_t e = gemm_dw_act(tile_d, a.d_out, a.d_in, a.batch, a.Hy, a.act, a.alpha, a.Xprev, a.scale, a.dW, a.db, stream);
   if (e != hipSuccess || !a.Hout) return e;

@@ -43,6 +43,8 @@ using Tile64 = TileCfg<1, 1, 2, 2, 1>;    //  64 x  64, K tile 32, 4 wavefronts
 using Tile32K4 = TileCfg<1, 1, 1, 1, 4>;  //  32 x  32, K tile 128 split over 4 wavefronts
 using Tile32K8 = TileCfg<1, 1, 1, 1, 8>;  //  32 x  32, K tile 256 split over 8 wavefronts
 using Tile64K2 = TileCfg<1, 1, 2, 2, 2>;  //  64 x  64, K tile 64 split over 2 groups of 4 wavefronts
+using Tile128W8 = TileCfg<1, 2, 4, 2, 1>;  // 128 x 128, K tile 32, 8 wavefronts of 32 x 64
+using Tile64x128 = TileCfg<1, 1, 2, 4, 1>;  //  64 x 128, K tile 32, 8 wavefronts of 32 x 32
 
 // LDS footprint (floats) of one operand tile of R rows.
 template <int LAYOUT, int R, int BK>
@@ -264,11 +266,28 @@ __device__ __forceinline__ void mma_stage(const float* __restrict__ sa, const fl
 // The accumulation order over K is fixed (tile by tile, the same for every launch with the same
 // Cfg), which is what makes two kernels that call this with the same operands agree bit for bit.
 
-template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, class XfDev>
-__device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
-                                              int64_t ldb, int M, int N, int K, int m0, int n0,
-                                              float* __restrict__ lds, const XfDev& xf, f32x16 (&acc)[Cfg::NACC],
-                                              float (&asum)[Cfg::WTM]) {
+// The register half of the pipeline: two tiles of each operand in flight.
+template <class Cfg, int LA, int LB, bool VEC, class XfDev>
+struct TilePipe {
+  TileLoader<LA, Cfg::BM, Cfg::BK, Cfg::NT, VEC, XfDev> a0, a1;
+  TileLoader<LB, Cfg::BN, Cfg::BK, Cfg::NT, VEC, ANone::Dev> b0, b1;
+};
+
+// CHAIN selects how the loop starts and ends:
+//   CHAIN_NONE   a product on its own;
+//   CHAIN_FIRST  another product of the same shape and layouts follows (operands A2, B2): its
+//                first two tiles are fetched where this one would fetch beyond K, so the second
+//                product starts without waiting for memory. Needs an even, non-zero tile count.
+//   CHAIN_SECOND that following product: tile 0 is already in stage 0 and tile 1 in registers.
+enum { CHAIN_NONE = 0, CHAIN_FIRST = 1, CHAIN_SECOND = 2 };
+
+template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, int CHAIN, class XfDev>
+__device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A, int64_t lda,
+                                                    const float* __restrict__ B, int64_t ldb, int M, int N, int K,
+                                                    int m0, int n0, float* __restrict__ lds, const XfDev& xf,
+                                                    f32x16 (&acc)[Cfg::NACC], float (&asum)[Cfg::WTM],
+                                                    TilePipe<Cfg, LA, LB, VEC, XfDev>& p,
+                                                    const float* __restrict__ A2, const float* __restrict__ B2) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
   constexpr int A_FLOATS = lds_tile_floats<LA, BM, BK>();
   constexpr int STAGE = lds_stage_floats<Cfg, LA, LB>();
@@ -280,52 +299,79 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
   const int wm = wave / (Cfg::WK * Cfg::WN);
   const int r = lane & 31, g = lane >> 5;
 
-  const __amdgpu_buffer_rsrc_t ra =
-      make_rsrc(A, LA == KCONTIG ? extent_bytes(M, K, lda) : extent_bytes(K, M, lda));
-  const __amdgpu_buffer_rsrc_t rb =
-      make_rsrc(B, LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb));
+  const uint32_t bytes_a = LA == KCONTIG ? extent_bytes(M, K, lda) : extent_bytes(K, M, lda);
+  const uint32_t bytes_b = LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb);
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, bytes_a);
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, bytes_b);
   const ANone::Dev none;
 
-  TileLoader<LA, BM, BK, Cfg::NT, VEC, XfDev> a0, a1;
-  TileLoader<LB, BN, BK, Cfg::NT, VEC, ANone::Dev> b0, b1;
   float* s0 = lds;
   float* s1 = lds + STAGE;
 
   const int nkt = (K + BK - 1) / BK;
-  // tiles beyond K load as zeros without touching memory, so the prologue needs no tests
-  a0.load(ra, lda, m0, 0, M, K, xf);
-  b0.load(rb, ldb, n0, 0, N, K, none);
-  a1.load(ra, lda, m0, BK, M, K, xf);
-  b1.load(rb, ldb, n0, BK, N, K, none);
-  a0.store(s0, xf);
-  b0.store(s0 + A_FLOATS, none);
-  __syncthreads();
+  if (CHAIN != CHAIN_SECOND) {
+    // tiles beyond K load as zeros without touching memory, so the prologue needs no tests
+    p.a0.load(ra, lda, m0, 0, M, K, xf);
+    p.b0.load(rb, ldb, n0, 0, N, K, none);
+    p.a1.load(ra, lda, m0, BK, M, K, xf);
+    p.b1.load(rb, ldb, n0, BK, N, K, none);
+    p.a0.store(s0, xf);
+    p.b0.store(s0 + A_FLOATS, none);
+    __syncthreads();
+  }
 
   // Tiles are taken two at a time with no exit between them, and an odd last tile is peeled off
   // after the loop: an exit in the middle of the body makes the compiler assume, at the loop
   // head, that either half's loads may still be pending, and it then waits for all of them
   // before every first half.
   int t = 0;
-  for (; t + 2 <= nkt; t += 2) {
+  const int t_last = CHAIN == CHAIN_FIRST ? nkt - 2 : nkt;  // the last pair of a first product is peeled
+  for (; t + 2 <= t_last; t += 2) {
     // tile t is in stage 0, tile t+1 in registers (a1, b1); fetch tile t+2
-    a0.load(ra, lda, m0, (t + 2) * BK, M, K, xf);
-    b0.load(rb, ldb, n0, (t + 2) * BK, N, K, none);
+    p.a0.load(ra, lda, m0, (t + 2) * BK, M, K, xf);
+    p.b0.load(rb, ldb, n0, (t + 2) * BK, N, K, none);
     mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    a1.store(s1, xf);
-    b1.store(s1 + A_FLOATS, none);
+    p.a1.store(s1, xf);
+    p.b1.store(s1 + A_FLOATS, none);
     __syncthreads();
     // tile t+1 is in stage 1, tile t+2 in registers (a0, b0); fetch tile t+3
-    a1.load(ra, lda, m0, (t + 3) * BK, M, K, xf);
-    b1.load(rb, ldb, n0, (t + 3) * BK, N, K, none);
+    p.a1.load(ra, lda, m0, (t + 3) * BK, M, K, xf);
+    p.b1.load(rb, ldb, n0, (t + 3) * BK, N, K, none);
     mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    a0.store(s0, xf);
-    b0.store(s0 + A_FLOATS, none);
+    p.a0.store(s0, xf);
+    p.b0.store(s0 + A_FLOATS, none);
     __syncthreads();
   }
-  if (t < nkt) {  // odd tile count: the last tile sits in stage 0
+  if (CHAIN == CHAIN_FIRST) {
+    // last pair of tiles: what is fetched meanwhile are tiles 0 and 1 of the next product
+    const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(A2, bytes_a);
+    const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(B2, bytes_b);
+    p.a0.load(ra2, lda, m0, 0, M, K, xf);
+    p.b0.load(rb2, ldb, n0, 0, N, K, none);
+    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
+    p.a1.store(s1, xf);
+    p.b1.store(s1 + A_FLOATS, none);
+    __syncthreads();
+    p.a1.load(ra2, lda, m0, BK, M, K, xf);
+    p.b1.load(rb2, ldb, n0, BK, N, K, none);
+    mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
+    p.a0.store(s0, xf);
+    p.b0.store(s0 + A_FLOATS, none);
+    __syncthreads();
+  } else if (t < nkt) {  // odd tile count: the last tile sits in stage 0
     mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
     __syncthreads();
   }
+}
+
+template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, class XfDev>
+__device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
+                                              int64_t ldb, int M, int N, int K, int m0, int n0,
+                                              float* __restrict__ lds, const XfDev& xf, f32x16 (&acc)[Cfg::NACC],
+                                              float (&asum)[Cfg::WTM]) {
+  TilePipe<Cfg, LA, LB, VEC, XfDev> p;
+  gemm_mainloop_chain<Cfg, LA, LB, VEC, COLSUM, CHAIN_NONE>(A, lda, B, ldb, M, N, K, m0, n0, lds, xf, acc, asum, p,
+                                                           nullptr, nullptr);
 }
 
 // Position of this lane's 16 accumulator values inside a 32x32 tile: value i sits in row

@@ -375,8 +375,17 @@ struct VijpTask {
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
     const ANone::Dev none;
-    gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
-    gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
+    if (K > 0 && K % (2 * Cfg::BK) == 0) {
+      // the second product's first tiles are fetched under the first product's last ones
+      TilePipe<Cfg, KCONTIG, KCONTIG, VEC, ANone::Dev> pipe;
+      gemm_mainloop_chain<Cfg, KCONTIG, KCONTIG, VEC, false, CHAIN_FIRST>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0],
+                                                                          asum, pipe, Hin, P);
+      gemm_mainloop_chain<Cfg, KCONTIG, KCONTIG, VEC, false, CHAIN_SECOND>(Hin, K, P, K, M, N, K, m0, n0, lds, none,
+                                                                           acc[1], asum, pipe, nullptr, nullptr);
+    } else {
+      gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0], asum);
+      gemm_mainloop<Cfg, KCONTIG, KCONTIG, VEC, false>(Hin, K, P, K, M, N, K, m0, n0, lds, none, acc[1], asum);
+    }
     typename EpiVijp<RELU>::Dev ed(epi, M, N);
     reduce_and_finish<Cfg, 2>(lds, M, N, m0, n0, acc, asum, ed);
     ed.finish();

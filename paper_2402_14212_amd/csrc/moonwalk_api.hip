@@ -23,18 +23,33 @@ hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float
                          int64_t ldb, float beta, float* C, int64_t ldc, const float* bias, hipStream_t stream);
 
 int pick_tile(int M, int N, int K) {
-  auto tiles = [](int m, int n, int t) { return (int64_t)((m + t - 1) / t) * ((n + t - 1) / t); };
-  // Measured on MI355X (256 CUs) over the layer shapes of the five configurations. The 128x128
-  // tile only pays once there are several waves of them (the large weight-gradient products).
-  // The 64x64 tile wins whenever it yields at least one workgroup for most CUs: with eight
-  // wavefronts (K split over two groups of four) while K is long and there are at most a few
-  // workgroups per CU, with four otherwise. Outputs too small for 64x64 tiles split K over the
-  // four wavefronts of a 32x32 tile.
-  const int64_t t64 = tiles(M, N, 64);
-  if (tiles(M, N, 128) >= 512) return TILE_128;
-  if (t64 >= 192) return (K >= 1024 && t64 < 2048) ? TILE_64K2 : TILE_64;
+  auto tiles = [](int m, int n, int tm, int tn) { return (int64_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn); };
+  // Measured on MI355X (256 CUs) over the layer shapes of the five configurations: take the
+  // largest tile that still gives every CU about two workgroups, with eight wavefronts per
+  // workgroup; below that the 64x64 tile, whose eight-wavefront form splits K over two groups
+  // (it pays when K is long); outputs too small even for that split K over the four wavefronts
+  // of a 32x32 tile.
+  if (tiles(M, N, 128, 128) >= 512) return TILE_128W8;
+  if (tiles(M, N, 64, 128) >= 512) return TILE_64X128;
+  const int64_t t64 = tiles(M, N, 64, 64);
+  if (t64 >= 192) return K >= 1024 ? TILE_64K2 : TILE_64;
   if (K >= 256) return TILE_32K4;
   return TILE_64;
+}
+
+// The weight-gradient tile next to a kernel of tile `partner` (TILE_AUTO: none); `phase3` says
+// whether that kernel is a Phase-III layer kernel or backprop's reverse product. Both tasks of a
+// launch need the same workgroup size, so the choice is made among the tiles with as many
+// wavefronts as the partner's; within those it follows what was measured for the pairs. It
+// depends on the shapes alone: launched together or apart, a product gets the same tile and
+// therefore the same bits.
+int pick_tile_dw(int M, int N, int K, int partner, bool phase3) {
+  (void)K;
+  const int64_t t128 = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+  // eight wavefronts: beside a layer kernel the 128x128 tile (few, long workgroups on both sides
+  // share the CUs evenly), beside the single reverse product the 64x128 one
+  if (tile_has_8_waves(partner)) return phase3 ? TILE_128W8 : TILE_64X128;
+  return t128 >= 512 ? TILE_128 : TILE_64;
 }
 
 hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const float* A, int64_t lda,
@@ -470,7 +485,7 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
         // same tiles as in the paired launches: the weight gradient's follows the next layer's kernel
         const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
         MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
-        MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(d.M, d.N, d.K, partner), d.M, d.N, d.K, d.CTZ, d.X, d.scale,
+        MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(d.M, d.N, d.K, partner, true), d.M, d.N, d.K, d.CTZ, d.X, d.scale,
                                               d.dW, d.db, s));
       }
       xin = xout;
@@ -492,7 +507,7 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
                               relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, mismatches,
                               s));
       const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
-      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(l.d_out, l.d_in, B, partner), l.d_out, l.d_in, B, h->ctz, xin, inv_scale,
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(l.d_out, l.d_in, B, partner, true), l.d_out, l.d_in, B, h->ctz, xin, inv_scale,
                                             grads_out + l.dW_off, nullptr, s));
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, grads_out + l.db_off, s));
       xin = xout;
@@ -531,7 +546,7 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* gr
       MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_bp_layer(a, s));
     } else {
       const int tile_r = (i > 0) ? pick_tile(B, l.d_in, l.d_out) : TILE_AUTO;
-      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(pick_tile_dw(l.d_out, l.d_in, B, tile_r), l.d_out, l.d_in, B, a.Hy, a.act, a.alpha,
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw_act(pick_tile_dw(l.d_out, l.d_in, B, tile_r, false), l.d_out, l.d_in, B, a.Hy, a.act, a.alpha,
                                                 a.Xprev, a.scale, a.dW, a.db, s));
       if (i > 0) MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_act(tile_r, B, l.d_in, l.d_out, a.Hy, a.act, a.alpha, a.W, a.Hout, s));
     }
@@ -650,7 +665,7 @@ const char* moonwalk_strerror(int code) {
 int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
                 const float* B, int32_t ldb, float beta, float* C, int32_t ldc, void* hip_stream) {
   if (M < 0 || N < 0 || K < 0 || !C || (K > 0 && (!A || !B))) return MW_ERR_INVALID_ARG;
-  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_64K2) return MW_ERR_INVALID_ARG;
+  if (op < MW_GEMM_NT || op > MW_GEMM_TN || tile < MW_TILE_AUTO || tile > MW_TILE_64X128) return MW_ERR_INVALID_ARG;
   // leading dimensions must cover the fast index of each operand
   const int a_fast = (op == MW_GEMM_TN) ? M : K, b_fast = (op == MW_GEMM_NT) ? K : N;
   if (lda < a_fast || ldb < b_fast || ldc < N) return MW_ERR_INVALID_ARG;

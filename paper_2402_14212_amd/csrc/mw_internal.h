@@ -8,14 +8,17 @@
 namespace mw {
 
 // tile selectors (same values as MW_TILE_* in the public header)
-constexpr int TILE_AUTO = 0, TILE_128 = 1, TILE_64 = 2, TILE_32K4 = 3, TILE_32K8 = 4, TILE_64K2 = 5;
+constexpr int TILE_AUTO = 0, TILE_128 = 1, TILE_64 = 2, TILE_32K4 = 3, TILE_32K8 = 4, TILE_64K2 = 5, TILE_128W8 = 6, TILE_64X128 = 7;
+// tiles whose workgroups have eight wavefronts (the others have four)
+inline bool tile_has_8_waves(int tile) { return tile == TILE_32K8 || tile == TILE_64K2 || tile == TILE_128W8 || tile == TILE_64X128; }
 constexpr int OP_NT = 0, OP_NN = 1, OP_TN = 2;
 
 // Tile choice for an M x N x K product on a 256-CU device. Deterministic in (M, N, K) only, so
 // that phase I and phase III compute a layer's pre-activations with the same kernel shape.
 int pick_tile(int M, int N, int K);
-// tile of a weight-gradient product launched beside a kernel of tile `partner` (TILE_AUTO: alone)
-int pick_tile_dw(int M, int N, int K, int partner);
+// tile of a weight-gradient product launched beside a kernel of tile `partner` (TILE_AUTO: alone),
+// which is a Phase-III layer kernel (phase3) or backprop's reverse product
+int pick_tile_dw(int M, int N, int K, int partner, bool phase3);
 
 // ---- GEMM launchers (gemm_*.hip). All enqueue on `stream` and return the launch status. ----
 

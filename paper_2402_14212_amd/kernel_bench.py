@@ -50,7 +50,7 @@ GEMM_SHAPES = [
     ("very_deep dW", mw.GEMM_TN, 4096, 4096, 1024),
     ("square 4096", mw.GEMM_NT, 4096, 4096, 4096),
 ]
-TILES = {0: "auto", 1: "128x128", 2: "64x64", 3: "32x32 K/4", 4: "32x32 K/8", 5: "64x64 K/2"}
+TILES = {0: "auto", 1: "128x128", 2: "64x64", 3: "32x32 K/4", 4: "32x32 K/8", 5: "64x64 K/2", 6: "128x128 w8", 7: "64x128 w8"}
 
 
 def bench_gemm(iters):

@@ -39,7 +39,7 @@ GEMM_SHAPES = [
 
 
 @pytest.mark.parametrize("op", [0, 1, 2])
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7])
 def test_gemm_matches_fp64_product(mw, op, tile):
     rng = np.random.default_rng(100 * op + tile)
     for (M, N, K) in GEMM_SHAPES:
@@ -72,7 +72,7 @@ def test_gemm_alpha_beta_and_auto_tile(mw):
 def test_gemm_is_deterministic(mw):
     rng = np.random.default_rng(1)
     A, B = dev(rng.standard_normal((256, 1024)).astype(np.float32)), dev(rng.standard_normal((1024, 1024)).astype(np.float32))
-    for tile in (1, 2, 3, 4, 5):
+    for tile in (1, 2, 3, 4, 5, 6, 7):
         a = mw.gemm_f32(mw.GEMM_NT, A, B, tile=tile).clone()
         b = mw.gemm_f32(mw.GEMM_NT, A, B, tile=tile)
         assert torch.equal(a, b)

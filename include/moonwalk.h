@@ -235,6 +235,17 @@ size_t mw_loss_scratch_doubles(void);
 /* Plain device-to-device copy kernel of n floats (bandwidth yardstick for the profiles). */
 int mw_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream);
 
+/* Load-only model of a tiled NT product (measurement aid, computes nothing): one workgroup per
+   tile x tile output tile of an M x N product reads its two operand row panels, A[M][K] and
+   B[N][K] (device, row stride K, 16-byte aligned), the way the GEMM kernels do, and writes one
+   checksum per thread to sink (device, at least (M/tile)*(N/tile)*256 floats). Its run time gives
+   the rate at which the CUs can pull operand panels through their L1 caches, the bound of the
+   small-batch products. The kernel is launched `repeats` (>= 1) times back to back, so that a
+   caller timing the call is not bound by its own launch rate. tile is 16, 32 or 64; M and N must
+   be multiples of tile, K of 256. MW_ERR_INVALID_ARG otherwise. */
+int mw_probe_operand_stream(int32_t M, int32_t N, int32_t K, int32_t tile, const float* A, const float* B,
+                            float* sink, int32_t repeats, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

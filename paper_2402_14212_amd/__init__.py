@@ -6,12 +6,12 @@ There is no CPU fallback: without the built library, or without a GPU, calls rai
 """
 from .binding import (MoonwalkError, MoonwalkNet, GradResult, load_library, library_path,
                       gemm_f32, bias_act_mask, rev_scale, frag_offsets, frag_compact,
-                      vijp_epilogue, colsum, loss_grad, copy_f32,
+                      vijp_epilogue, colsum, loss_grad, copy_f32, probe_operand_stream,
                       GEMM_NT, GEMM_NN, GEMM_TN, TILE_AUTO, TILE_128, TILE_64, TILE_32K4, TILE_32K8, TILE_64K2, TILE_128W8, TILE_64X128,
                       PLAN_MOONWALK, PLAN_BACKPROP, EXPORTED_SYMBOLS)
 
 __all__ = ["MoonwalkError", "MoonwalkNet", "GradResult", "load_library", "library_path",
            "gemm_f32", "bias_act_mask", "rev_scale", "frag_offsets", "frag_compact",
-           "vijp_epilogue", "colsum", "loss_grad", "copy_f32",
+           "vijp_epilogue", "colsum", "loss_grad", "copy_f32", "probe_operand_stream",
            "GEMM_NT", "GEMM_NN", "GEMM_TN", "TILE_AUTO", "TILE_128", "TILE_64", "TILE_32K4", "TILE_32K8", "TILE_64K2", "TILE_128W8", "TILE_64X128",
            "PLAN_MOONWALK", "PLAN_BACKPROP", "EXPORTED_SYMBOLS"]

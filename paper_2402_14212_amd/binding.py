@@ -20,6 +20,7 @@ EXPORTED_SYMBOLS = [
     "moonwalk_profile_filter", "moonwalk_profile_launches",
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
     "mw_vijp_epilogue", "mw_colsum", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
+    "mw_probe_operand_stream",
 ]
 
 
@@ -97,6 +98,7 @@ def load_library() -> C.CDLL:
     lib.mw_loss_scratch_doubles.argtypes = []
     lib.mw_loss_scratch_doubles.restype = sz
     lib.mw_copy_f32.argtypes = [vp, vp, i64, vp]
+    lib.mw_probe_operand_stream.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp]
     _lib = lib
     return lib
 
@@ -406,6 +408,19 @@ def loss_grad(xL: torch.Tensor, t: torch.Tensor, scale: float = 1.0):
     scratch = torch.empty(int(lib.mw_loss_scratch_doubles()), dtype=torch.float64, device=xL.device)
     _check(lib.mw_loss_grad(_ptr(_f32(xL)), _ptr(_f32(t)), rows, d, scale, _ptr(hL), _ptr(loss), _ptr(scratch), _stream()))
     return hL, loss
+
+
+def probe_operand_stream(A: torch.Tensor, B: torch.Tensor, tile: int, sink: Optional[torch.Tensor] = None,
+                         repeats: int = 1):
+    """Load-only model of the tiled product A[M][K] B[N][K]^T (see mw_probe_operand_stream)."""
+    _require_gpu()
+    M, K = A.shape
+    N = B.shape[0]
+    if sink is None:
+        sink = torch.empty((M // tile) * (N // tile) * 256, dtype=torch.float32, device=A.device)
+    _check(load_library().mw_probe_operand_stream(M, N, K, tile, _ptr(_f32(A)), _ptr(_f32(B)), _ptr(sink), repeats,
+                                                  _stream()))
+    return sink
 
 
 def copy_f32(src: torch.Tensor, dst: torch.Tensor):

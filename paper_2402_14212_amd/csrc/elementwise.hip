@@ -600,6 +600,49 @@ k_fill_u32(uint32_t* __restrict__ p, uint32_t value, int64_t n) {
     p[k] = value;
 }
 
+// ---------------------------------------------------------------- operand-stream probe
+// Load-only model of a GEMM workgroup: the workgroup of output tile (tm, tn) reads the R x K row
+// panels A[tm*R ..][:] and B[tn*R ..][:] exactly as the tiled kernels do (dwordx4 per lane, 128
+// floats of k per pass, two passes in flight) and keeps only a checksum. What it measures is the
+// rate at which the CUs can pull operand panels through their L1 caches, which is what bounds the
+// small-batch products.
+template <int R>
+__global__ void __launch_bounds__(EW_THREADS)
+k_operand_stream(const float* __restrict__ A, const float* __restrict__ B, int K, int tiles_m, int tiles_n,
+                 float* __restrict__ sink) {
+  constexpr int RPP = EW_THREADS / 32;  // rows per pass: 32 lanes x 16 B cover 128 floats of one row
+  constexpr int P = R / RPP;
+  static_assert(R % RPP == 0, "tile rows must be a multiple of the rows per pass");
+  const int nblocks = tiles_m * tiles_n;
+  const int xcd = blockIdx.x % 8, local = blockIdx.x / 8;
+  const int id = xcd * (nblocks / 8) + (xcd < nblocks % 8 ? xcd : nblocks % 8) + local;  // one XCD per id range
+  const int tm = id % tiles_m, tn = id / tiles_m;
+  const int row = threadIdx.x / 32, col = (threadIdx.x % 32) * 4;
+  const float* pa = A + (size_t)(tm * R + row) * K + col;
+  const float* pb = B + (size_t)(tn * R + row) * K + col;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int k = 0; k < K; k += 256) {
+    float4 va[2][P], vb[2][P];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int q = 0; q < P; ++q) {
+        va[u][q] = *reinterpret_cast<const float4*>(pa + (size_t)q * RPP * K + k + u * 128);
+        vb[u][q] = *reinterpret_cast<const float4*>(pb + (size_t)q * RPP * K + k + u * 128);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int q = 0; q < P; ++q) {
+        acc.x += va[u][q].x + vb[u][q].x;
+        acc.y += va[u][q].y + vb[u][q].y;
+        acc.z += va[u][q].z + vb[u][q].z;
+        acc.w += va[u][q].w + vb[u][q].w;
+      }
+  }
+  sink[(size_t)blockIdx.x * EW_THREADS + threadIdx.x] = acc.x + acc.y + acc.z + acc.w;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------ launchers
@@ -751,6 +794,20 @@ hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream) 
   if (n <= 0) return hipSuccess;
   int blocks = ew_blocks((n + 3) / 4, EW_THREADS * 4);
   hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(EW_THREADS), 0, stream, src, dst, n);
+  return hipGetLastError();
+}
+
+hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
+                             hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || M % tile || N % tile || K % 256 || !al16(A) || !al16(B)) return hipErrorInvalidValue;
+  const int tiles_m = M / tile, tiles_n = N / tile;
+  const dim3 grid(tiles_m * tiles_n), block(EW_THREADS);
+  switch (tile) {
+    case 16: hipLaunchKernelGGL(k_operand_stream<16>, grid, block, 0, stream, A, B, K, tiles_m, tiles_n, sink); break;
+    case 32: hipLaunchKernelGGL(k_operand_stream<32>, grid, block, 0, stream, A, B, K, tiles_m, tiles_n, sink); break;
+    case 64: hipLaunchKernelGGL(k_operand_stream<64>, grid, block, 0, stream, A, B, K, tiles_m, tiles_n, sink); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

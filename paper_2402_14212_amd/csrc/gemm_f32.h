@@ -29,9 +29,13 @@ constexpr int KCONTIG = 0;
 constexpr int RCONTIG = 1;
 constexpr int NUM_XCD = 8;
 
-template <int WTM_, int WTN_, int WM_, int WN_, int WK_>
+template <int WTM_, int WTN_, int WM_, int WN_, int WK_, int ST_ = 2>
 struct TileCfg {
   static constexpr int WTM = WTM_, WTN = WTN_, WM = WM_, WN = WN_, WK = WK_;
+  // operand tiles in flight in registers (even). Two is what measures best on every tile here:
+  // with four, the extra registers cost more than the longer lead time gains.
+  static constexpr int ST = ST_;
+  static_assert(ST_ >= 2 && ST_ % 2 == 0, "the register pipeline alternates over two LDS stages");
   static constexpr int BM = 32 * WTM * WM;
   static constexpr int BN = 32 * WTN * WN;
   static constexpr int BK = 32 * WK;            // every wavefront consumes 32 k per K tile
@@ -266,21 +270,27 @@ __device__ __forceinline__ void mma_stage(const float* __restrict__ sa, const fl
 // The accumulation order over K is fixed (tile by tile, the same for every launch with the same
 // Cfg), which is what makes two kernels that call this with the same operands agree bit for bit.
 
-// The register half of the pipeline: two tiles of each operand in flight.
+// The register half of the pipeline: Cfg::ST tiles of each operand in flight.
 template <class Cfg, int LA, int LB, bool VEC, class XfDev>
 struct TilePipe {
-  TileLoader<LA, Cfg::BM, Cfg::BK, Cfg::NT, VEC, XfDev> a0, a1;
-  TileLoader<LB, Cfg::BN, Cfg::BK, Cfg::NT, VEC, ANone::Dev> b0, b1;
+  TileLoader<LA, Cfg::BM, Cfg::BK, Cfg::NT, VEC, XfDev> a[Cfg::ST];
+  TileLoader<LB, Cfg::BN, Cfg::BK, Cfg::NT, VEC, ANone::Dev> b[Cfg::ST];
 };
 
 // CHAIN selects how the loop starts and ends:
 //   CHAIN_NONE   a product on its own;
 //   CHAIN_FIRST  another product of the same shape and layouts follows (operands A2, B2): its
-//                first two tiles are fetched where this one would fetch beyond K, so the second
-//                product starts without waiting for memory. Needs an even, non-zero tile count.
-//   CHAIN_SECOND that following product: tile 0 is already in stage 0 and tile 1 in registers.
+//                first tiles are fetched where this one would fetch beyond K, so the second
+//                product starts without waiting for memory. Needs a tile count that is a non-zero
+//                multiple of Cfg::ST.
+//   CHAIN_SECOND that following product: tile 0 is already in LDS stage 0 and tiles 1 .. ST-1 in
+//                registers.
 enum { CHAIN_NONE = 0, CHAIN_FIRST = 1, CHAIN_SECOND = 2 };
 
+// Main loop: acc += A_tile(m0.., :) * B_tile(n0.., :)^T over the whole K range.
+// Tile t is multiplied out of LDS stage t % 2 while tiles t+1 .. t+ST-1 are on their way in
+// registers and tile t+ST is being requested: a tile has ST-1 multiply phases to arrive before
+// it is written to LDS. One barrier per tile.
 template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, int CHAIN, class XfDev>
 __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A, int64_t lda,
                                                     const float* __restrict__ B, int64_t ldb, int M, int N, int K,
@@ -288,7 +298,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
                                                     f32x16 (&acc)[Cfg::NACC], float (&asum)[Cfg::WTM],
                                                     TilePipe<Cfg, LA, LB, VEC, XfDev>& p,
                                                     const float* __restrict__ A2, const float* __restrict__ B2) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ST = Cfg::ST;
   constexpr int A_FLOATS = lds_tile_floats<LA, BM, BK>();
   constexpr int STAGE = lds_stage_floats<Cfg, LA, LB>();
 
@@ -303,65 +313,66 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
   const uint32_t bytes_b = LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb);
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, bytes_a);
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, bytes_b);
+  const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(CHAIN == CHAIN_FIRST ? A2 : A, bytes_a);
+  const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(CHAIN == CHAIN_FIRST ? B2 : B, bytes_b);
   const ANone::Dev none;
 
-  float* s0 = lds;
-  float* s1 = lds + STAGE;
-
   const int nkt = (K + BK - 1) / BK;
+  // Request tile `idx` into register slot `slot`. Tiles beyond K load as zeros without touching
+  // memory, so no request needs a test; for the first product of a chain they are the next
+  // product's tiles instead.
+#define MW_REQUEST(slot, idx)                                                        \
+  do {                                                                               \
+    const int idx_ = (idx);                                                          \
+    if (CHAIN == CHAIN_FIRST && idx_ >= nkt) {                                       \
+      p.a[slot].load(ra2, lda, m0, (idx_ - nkt) * BK, M, K, xf);                     \
+      p.b[slot].load(rb2, ldb, n0, (idx_ - nkt) * BK, N, K, none);                   \
+    } else {                                                                         \
+      p.a[slot].load(ra, lda, m0, idx_ * BK, M, K, xf);                              \
+      p.b[slot].load(rb, ldb, n0, idx_ * BK, N, K, none);                            \
+    }                                                                                \
+  } while (0)
+#define MW_TO_LDS(slot, stage)                                  \
+  do {                                                          \
+    p.a[slot].store(lds + (stage) * STAGE, xf);                 \
+    p.b[slot].store(lds + (stage) * STAGE + A_FLOATS, none);    \
+  } while (0)
+#define MW_MULTIPLY(stage) \
+  mma_stage<Cfg, LA, LB, COLSUM>(lds + (stage) * STAGE, lds + (stage) * STAGE + A_FLOATS, wm, wn, wk, r, g, acc, asum)
+
   if (CHAIN != CHAIN_SECOND) {
-    // tiles beyond K load as zeros without touching memory, so the prologue needs no tests
-    p.a0.load(ra, lda, m0, 0, M, K, xf);
-    p.b0.load(rb, ldb, n0, 0, N, K, none);
-    p.a1.load(ra, lda, m0, BK, M, K, xf);
-    p.b1.load(rb, ldb, n0, BK, N, K, none);
-    p.a0.store(s0, xf);
-    p.b0.store(s0 + A_FLOATS, none);
+#pragma unroll
+    for (int j = 0; j < ST; ++j) MW_REQUEST(j, j);
+    MW_TO_LDS(0, 0);
     __syncthreads();
   }
 
-  // Tiles are taken two at a time with no exit between them, and an odd last tile is peeled off
-  // after the loop: an exit in the middle of the body makes the compiler assume, at the loop
-  // head, that either half's loads may still be pending, and it then waits for all of them
-  // before every first half.
+  // ST tiles per trip with no exit between them; what is left of an uneven tile count is peeled
+  // off after the loop. (An exit in the middle of the body makes the compiler assume, at the loop
+  // head, that any of the requests may still be pending, and it then waits for all of them.)
   int t = 0;
-  const int t_last = CHAIN == CHAIN_FIRST ? nkt - 2 : nkt;  // the last pair of a first product is peeled
-  for (; t + 2 <= t_last; t += 2) {
-    // tile t is in stage 0, tile t+1 in registers (a1, b1); fetch tile t+2
-    p.a0.load(ra, lda, m0, (t + 2) * BK, M, K, xf);
-    p.b0.load(rb, ldb, n0, (t + 2) * BK, N, K, none);
-    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    p.a1.store(s1, xf);
-    p.b1.store(s1 + A_FLOATS, none);
-    __syncthreads();
-    // tile t+1 is in stage 1, tile t+2 in registers (a0, b0); fetch tile t+3
-    p.a1.load(ra, lda, m0, (t + 3) * BK, M, K, xf);
-    p.b1.load(rb, ldb, n0, (t + 3) * BK, N, K, none);
-    mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    p.a0.store(s0, xf);
-    p.b0.store(s0 + A_FLOATS, none);
-    __syncthreads();
+  for (; t + ST <= nkt; t += ST) {
+#pragma unroll
+    for (int u = 0; u < ST; ++u) {
+      // tile t+u is in LDS stage u % 2; slot u is free, slots u+1 .. hold the tiles after it
+      MW_REQUEST(u, t + u + ST);
+      MW_MULTIPLY(u % 2);
+      MW_TO_LDS((u + 1) % ST, (u + 1) % 2);
+      __syncthreads();
+    }
   }
-  if (CHAIN == CHAIN_FIRST) {
-    // last pair of tiles: what is fetched meanwhile are tiles 0 and 1 of the next product
-    const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(A2, bytes_a);
-    const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(B2, bytes_b);
-    p.a0.load(ra2, lda, m0, 0, M, K, xf);
-    p.b0.load(rb2, ldb, n0, 0, N, K, none);
-    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    p.a1.store(s1, xf);
-    p.b1.store(s1 + A_FLOATS, none);
-    __syncthreads();
-    p.a1.load(ra2, lda, m0, BK, M, K, xf);
-    p.b1.load(rb2, ldb, n0, BK, N, K, none);
-    mma_stage<Cfg, LA, LB, COLSUM>(s1, s1 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    p.a0.store(s0, xf);
-    p.b0.store(s0 + A_FLOATS, none);
-    __syncthreads();
-  } else if (t < nkt) {  // odd tile count: the last tile sits in stage 0
-    mma_stage<Cfg, LA, LB, COLSUM>(s0, s0 + A_FLOATS, wm, wn, wk, r, g, acc, asum);
-    __syncthreads();
+  const int rem = nkt - t;  // 0 .. ST-1 tiles left: tile t in stage 0, the others in slots 1 ..
+#pragma unroll
+  for (int u = 0; u < ST - 1; ++u) {
+    if (u < rem) {
+      MW_MULTIPLY(u % 2);
+      if (u + 1 < rem) MW_TO_LDS(u + 1, (u + 1) % 2);
+      __syncthreads();
+    }
   }
+#undef MW_REQUEST
+#undef MW_TO_LDS
+#undef MW_MULTIPLY
 }
 
 template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, class XfDev>

@@ -375,7 +375,7 @@ struct VijpTask {
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
     const ANone::Dev none;
-    if (K > 0 && K % (2 * Cfg::BK) == 0) {
+    if (K > 0 && K % (Cfg::ST * Cfg::BK) == 0) {
       // the second product's first tiles are fetched under the first product's last ones
       TilePipe<Cfg, KCONTIG, KCONTIG, VEC, ANone::Dev> pipe;
       gemm_mainloop_chain<Cfg, KCONTIG, KCONTIG, VEC, false, CHAIN_FIRST>(X, K, W, K, M, N, K, m0, n0, lds, none, acc[0],

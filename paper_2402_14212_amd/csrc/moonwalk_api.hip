@@ -731,4 +731,15 @@ int mw_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream) {
   return MW_OK;
 }
 
+int mw_probe_operand_stream(int32_t M, int32_t N, int32_t K, int32_t tile, const float* A, const float* B, float* sink,
+                            int32_t repeats, void* hip_stream) {
+  if (!A || !B || !sink || repeats < 1) return MW_ERR_INVALID_ARG;
+  if (M <= 0 || N <= 0 || K <= 0 || (tile != 16 && tile != 32 && tile != 64) || M % tile || N % tile || K % 256)
+    return MW_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) return MW_ERR_INVALID_ARG;
+  for (int32_t i = 0; i < repeats; ++i)
+    MW_HIP(ew_operand_stream(A, B, M, N, K, tile, sink, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
 }  // extern "C"

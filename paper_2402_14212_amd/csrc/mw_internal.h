@@ -137,6 +137,9 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
                         double* scratch, hipStream_t stream);
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);
 hipError_t ew_fill_u32(uint32_t* p, uint32_t value, int64_t n, hipStream_t stream);
+// load-only model of a tiled product (measurement): sink gets (M/tile)*(N/tile)*256 floats
+hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
+                             hipStream_t stream);
 
 // ---- right-inverse setup (setup_solve.hip) ----
 // P[d_out][d_in] = (W W^T)^{-1} W by blocked Cholesky and two blocked triangular solves.

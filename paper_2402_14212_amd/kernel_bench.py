@@ -3,6 +3,7 @@
 
     python -m paper_2402_14212_amd.kernel_bench gemm          # fp32 MFMA GEMMs at the layer shapes
     python -m paper_2402_14212_amd.kernel_bench elementwise   # HBM-bound elementwise / pack / compaction kernels
+    python -m paper_2402_14212_amd.kernel_bench fill          # load-only model of the tiled products: operand-panel fill rate
     python -m paper_2402_14212_amd.kernel_bench all
     python -m paper_2402_14212_amd.kernel_bench one --op nt --tile 3 --m 256 --n 1024 --k 1024   # one GEMM, for counter runs
 
@@ -108,7 +109,7 @@ def bench_elementwise(iters, max_log2):
         # fragment index (integer scan over the mask words only)
         if n <= (1 << 26):
             lib.mw_frag_offsets(P(mask), n, P(off), stream)
-            report("frag_offsets (1 block)", 0.125 + 0.0625,
+            report("frag_offsets", 0.125 + 0.0625,
                    timed(lambda i: lib.mw_frag_offsets(P(mask), n, P(off), stream), max(3, iters // 4)))
             # compaction: read h, 1 bit, offsets; write the erased half
             frac0 = 1.0 - float(torch.mean((zs[0] > 0).float()))
@@ -129,6 +130,24 @@ def bench_elementwise(iters, max_log2):
         del zs, hs
 
 
+def bench_fill(iters):
+    """Operand-panel fill rate: every workgroup of a tile x tile output tiling reads its two K-long
+    row panels and computes nothing. Bytes = what the workgroups load, (M/tile)(N/tile) * 2 tile K 4.
+    Each timed call launches the kernel 32 times inside the library (the operands stay in the L2
+    caches / Infinity Cache: what is measured is the path into the CUs, not HBM)."""
+    reps = 32
+    print(f"{'shape':22s} {'tile':>5s} {'WGs':>6s} {'us':>8s} {'MB loaded':>10s} {'TB/s':>7s} {'B/clk/CU':>9s}")
+    for (M, N, K) in [(256, 1024, 1024), (512, 2048, 2048), (1024, 4096, 4096)]:
+        A, B = torch.randn(M, K, device="cuda"), torch.randn(N, K, device="cuda")
+        for tile in (16, 32, 64):
+            wgs = (M // tile) * (N // tile)
+            sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+            loaded = wgs * 2 * tile * K * 4
+            t = timed(lambda i: mw.probe_operand_stream(A, B, tile, sink, repeats=reps), max(4, iters // 4)) / reps
+            print(f"{M:5d}x{N:5d}x{K:5d}     {tile:5d} {wgs:6d} {t * 1e6:8.2f} {loaded / 1e6:10.1f} {loaded / t / 1e12:7.2f} "
+                  f"{loaded / t / 256 / 2.4e9:9.1f}", flush=True)
+
+
 def bench_one(args):
     op = {"nt": mw.GEMM_NT, "nn": mw.GEMM_NN, "tn": mw.GEMM_TN}[args.op]
     M, N, K = args.m, args.n, args.k
@@ -143,7 +162,7 @@ def bench_one(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["gemm", "elementwise", "all", "one"])
+    ap.add_argument("what", choices=["gemm", "elementwise", "fill", "all", "one"])
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--max-log2", type=int, default=28, help="largest elementwise tensor, log2(elements)")
     ap.add_argument("--op", choices=["nt", "nn", "tn"], default="nt")
@@ -159,6 +178,8 @@ def main():
         bench_one(args)
     if args.what in ("gemm", "all"):
         bench_gemm(args.iters)
+    if args.what in ("fill", "all"):
+        bench_fill(args.iters)
     if args.what in ("elementwise", "all"):
         bench_elementwise(args.iters, args.max_log2)
 

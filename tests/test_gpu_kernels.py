@@ -190,3 +190,19 @@ def test_copy(mw):
         dst = torch.zeros_like(src)
         mw.copy_f32(src, dst)
         assert torch.equal(src, dst)
+
+
+def test_operand_stream_probe(mw):
+    """The load-only probe reads every operand element exactly once per tile: with one tile per
+    dimension pair its checksums add up to sum(A) * tiles_n + sum(B) * tiles_m."""
+    M, N, K = 64, 128, 512
+    A = torch.randint(-3, 4, (M, K), device="cuda").float()
+    B = torch.randint(-3, 4, (N, K), device="cuda").float()
+    for tile in (16, 32, 64):
+        sink = mw.probe_operand_stream(A, B, tile)
+        want = float(A.double().sum()) * (N // tile) + float(B.double().sum()) * (M // tile)
+        assert float(sink.double().sum()) == want
+    with pytest.raises(mw.MoonwalkError):
+        mw.probe_operand_stream(A, B, 48)
+    with pytest.raises(mw.MoonwalkError):
+        mw.probe_operand_stream(A[:, :384].contiguous(), B[:, :384].contiguous(), 32)

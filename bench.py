@@ -22,11 +22,11 @@ sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
 
-# Bytes that cross the L2 per launch of the Phase-III layer kernel, from the two rocprofv3 --pmc runs
-# summarised in profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE 12477.5 KiB scaled x2.0 by the
-# copy-kernel calibration, WRITE_SIZE 3072.0 KiB scaled x1.0). Offline counters: known only for the
-# default workload, null otherwise.
-PHASE3_TRAFFIC_BYTES = {"deep_square": int(12477.5 * 1024 * 2.0 + 3072.0 * 1024 * 1.0)}
+# Bytes that cross the L2 per Phase-III launch (layer kernel + previous layer's weight gradient), from
+# the two rocprofv3 --pmc runs summarised in profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE
+# 17147.5 KiB scaled x2.0 by the copy-kernel calibration, WRITE_SIZE 7172.0 KiB scaled x1.0). Offline
+# counters: known only for the default workload with its default re-seed interval, null otherwise.
+PHASE3_TRAFFIC_BYTES = {"deep_square": int(17147.5 * 1024 * 2.0 + 7172.0 * 1024 * 1.0)}
 
 
 def parse():
@@ -143,17 +143,26 @@ def main():
     ew["ms_per_step"] = max(0.0, ms_mw - gemm_ms)
     ew["avg_us"] = ew["ms_per_step"] / ew["launches_per_step"] * 1e3 if ew["launches_per_step"] else None
     ew["method"] = "step time minus the GEMM classes"
-    dom = "phase3" if per_class["phase3"]["launches_per_step"] else "vijp"      # unfused runs have no paired launches
+    # dominant kernel: the paired Phase-III launch; in unfused runs (no layer kernel at all) the plain
+    # GEMM that serves Phase I and both Phase-III products, three launches per layer
+    if per_class["phase3"]["launches_per_step"]:
+        dom, dom_flops, dom_name = "phase3", class_flops["phase3"], (
+            "task_pair_kernel (Phase-III launch: layer kernel = recompute + vijp + epilogue, plus the previous "
+            "layer's weight-gradient GEMM)")
+    elif per_class["vijp"]["launches_per_step"]:
+        dom, dom_flops, dom_name = "vijp", class_flops["vijp"], "Phase-III layer kernel"
+    else:
+        dom, dom_flops, dom_name = "fwd", 2.0 * per_class["fwd"]["launches_per_step"] / L, "plain NT GEMM (unfused path)"
+        per_class["fwd"]["tflops"] = dom_flops * B * sum_dd / (per_class["fwd"]["ms_per_step"] * 1e-3) / 1e12
     n_v = per_class[dom]["launches_per_step"]
     avg_ms = per_class[dom]["ms_per_step"] / max(n_v, 1)
-    flop_per_launch = class_flops[dom] * B * sum_dd / max(n_v, 1)
+    flop_per_launch = dom_flops * B * sum_dd / max(n_v, 1)
     achieved = flop_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma",
-                "kernel": "task_pair_kernel (Phase-III launch: layer kernel = recompute + vijp + epilogue, plus the "
-                          "previous layer's weight-gradient GEMM)" if dom == "phase3" else "Phase-III layer kernel",
+                "kernel": dom_name,
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and not args.unfused else None,
+                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and dom == "phase3" else None,
                 "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
     net.close()

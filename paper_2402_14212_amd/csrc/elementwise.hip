@@ -521,7 +521,7 @@ k_vijp_epilogue(const float* __restrict__ z, float* __restrict__ ct_z, int64_t n
 // ---------------------------------------------------------------- column sums (bias gradient)
 // Thread j of a workgroup owns column j and walks a contiguous range of rows; partial sums over
 // COLSUM_SPLIT row ranges are combined in LDS in a fixed order.
-constexpr int COLSUM_COLS = 64, COLSUM_SPLIT = 4;
+constexpr int COLSUM_COLS = 32, COLSUM_SPLIT = 32;
 __global__ void __launch_bounds__(COLSUM_COLS* COLSUM_SPLIT)
 k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* __restrict__ out) {
   __shared__ float part[COLSUM_SPLIT][COLSUM_COLS];
@@ -530,8 +530,18 @@ k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* _
   const int64_t per = (rows + COLSUM_SPLIT - 1) / COLSUM_SPLIT;
   const int64_t lo = s * per, hi = lo + per < rows ? lo + per : rows;
   float acc = 0.f;
-  if (col < d)
-    for (int64_t r = lo; r < hi; ++r) acc += a[r * d + col];
+  if (col < d) {
+    const float* p = a + col;
+    int64_t r = lo;
+    for (; r + 4 <= hi; r += 4) {  // four rows in flight; added in row order
+      float v0 = p[r * d], v1 = p[(r + 1) * d], v2 = p[(r + 2) * d], v3 = p[(r + 3) * d];
+      acc += v0;
+      acc += v1;
+      acc += v2;
+      acc += v3;
+    }
+    for (; r < hi; ++r) acc += p[r * d];
+  }
   part[s][c] = acc;
   __syncthreads();
   if (s == 0 && col < d) {
@@ -544,10 +554,25 @@ k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* _
 // ---------------------------------------------------------------- loss value and output cotangent
 __global__ void __launch_bounds__(EW_THREADS)
 k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n, float cot_scale,
-            float* __restrict__ hL, double* __restrict__ partial) {
+            float* __restrict__ hL, double* __restrict__ partial, int vec) {
   __shared__ double red[EW_THREADS];
   double acc = 0.0;
-  for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < n; e += (int64_t)gridDim.x * EW_THREADS) {
+  const int64_t tid = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x, stride = (int64_t)gridDim.x * EW_THREADS;
+  int64_t done = 0;
+  if (vec) {  // all three arrays 16-byte aligned
+    const int64_t n4 = n >> 2;
+    for (int64_t q = tid; q < n4; q += stride) {
+      const float4 a = *reinterpret_cast<const float4*>(xL + 4 * q), b = *reinterpret_cast<const float4*>(t + 4 * q);
+      const float r0 = a.x - b.x, r1 = a.y - b.y, r2 = a.z - b.z, r3 = a.w - b.w;
+      *reinterpret_cast<float4*>(hL + 4 * q) = make_float4(cot_scale * r0, cot_scale * r1, cot_scale * r2, cot_scale * r3);
+      acc += (double)r0 * (double)r0;
+      acc += (double)r1 * (double)r1;
+      acc += (double)r2 * (double)r2;
+      acc += (double)r3 * (double)r3;
+    }
+    done = n4 << 2;
+  }
+  for (int64_t e = done + tid; e < n; e += stride) {
     float r = xL[e] - t[e];
     hL[e] = cot_scale * r;
     acc += (double)r * (double)r;
@@ -780,11 +805,14 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
   // scale and 1/rows are folded into one fp32 factor; with a power-of-two scale this is the
   // correctly rounded scale/rows either way
   float cot_scale = scale / (float)rows;
-  hipLaunchKernelGGL(k_loss_grad, dim3(LOSS_BLOCKS), dim3(EW_THREADS), 0, stream, xL, t, n, cot_scale, hL, scratch);
+  const int vec = al16(xL) && al16(t) && al16(hL);
+  int64_t want = ((vec ? (n + 3) / 4 : n) + EW_THREADS - 1) / EW_THREADS;
+  const int blocks = (int)(want < 1 ? 1 : (want > LOSS_BLOCKS ? LOSS_BLOCKS : want));
+  hipLaunchKernelGGL(k_loss_grad, dim3(blocks), dim3(EW_THREADS), 0, stream, xL, t, n, cot_scale, hL, scratch, vec);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (loss) {
-    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, LOSS_BLOCKS, 0.5 / (double)rows, loss);
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, 0.5 / (double)rows, loss);
     e = hipGetLastError();
   }
   return e;

@@ -132,7 +132,7 @@ hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, fl
                             const uint32_t* offsets, const float* frag, const uint64_t* base, uint64_t capacity,
                             float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream);
 hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream);
-constexpr int LOSS_BLOCKS = 256;
+constexpr int LOSS_BLOCKS = 2048;  // most workgroups (and scratch doubles) the loss reduction uses
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
                         double* scratch, hipStream_t stream);
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);

@@ -107,7 +107,7 @@ def bench_elementwise(iters, max_log2):
         # Phase II scaling: read h and 1 bit, write ct_z
         report("rev_scale", 8.125, timed(lambda i: lib.mw_rev_scale(P(hs[i % pool]), P(mask), n, 0.1, P(x), stream), iters))
         # fragment index (integer scan over the mask words only)
-        if n <= (1 << 26):
+        if n <= (1 << 24):   # fragment kernels: up to the largest layer of the configurations (B * d = 2^22)
             lib.mw_frag_offsets(P(mask), n, P(off), stream)
             report("frag_offsets", 0.125 + 0.0625,
                    timed(lambda i: lib.mw_frag_offsets(P(mask), n, P(off), stream), max(3, iters // 4)))

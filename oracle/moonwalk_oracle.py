@@ -33,6 +33,12 @@ What follows which passage of the Moonwalk paper:
                         K-th layer-input cotangent is kept and replaces the propagated one in
                         phase III.  K = 0 never re-seeds (the method as printed).
 
+* `sgd_step`            Algorithm 1 with its "Apply g_i" line for plain gradient descent:
+                        theta_i <- theta_i - lr g_i with the exact gradient.
+* `newton_schulz_refresh`  NOT in the paper, which does not say how the inverse follows the
+                        weights: the Schulz iteration for a (pseudo-)inverse, started from the
+                        old right inverse carried over to the new weights (see its docstring).
+
 Readings of points the paper leaves open (each is restated in the design notes):
 mask bit = (z > 0) strictly, so z = 0, -0.0 and NaN take the slope alpha; every layer is
 activated, including the last; packed masks are little-endian in flat row-major order, bit
@@ -145,6 +151,39 @@ def right_inverse(W) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- packed masks and fragments
+
+def newton_schulz_refresh(W_new, P_old, iters: int):
+    """Right inverse of W_new from the right inverse P_old = (W_old W_old^T)^{-1} W_old of nearby
+    weights, without a factorisation (the library's incremental refresh, written out):
+
+        P_0     = (P_old P_old^T) W_new          since P_old P_old^T = (W_old W_old^T)^{-1}
+        P_{k+1} = (2 I - P_k W_new^T) P_k        Schulz iteration, k = 0 .. iters-1
+
+    Every iterate is a left multiple of W_new, so the limit is the minimum-norm right inverse
+    (W_new W_new^T)^{-1} W_new, and the residual R_k = I - P_k W_new^T obeys R_{k+1} = R_k^2.
+    Returns (P, residuals) with residuals[k] = ||I - P_k W_new^T||_F for k = 0 .. iters.
+    """
+    W = _as64(W_new)
+    P_old = _as64(P_old)
+    n = W.shape[0]
+    eye = np.eye(n)
+    P = (P_old @ P_old.T) @ W
+    residuals = [float(np.linalg.norm(eye - P @ W.T))]
+    for _ in range(int(iters)):
+        E = P @ W.T
+        P = (2.0 * eye - E) @ P
+        residuals.append(float(np.linalg.norm(eye - P @ W.T)))
+    return P, residuals
+
+
+def sgd_step(Ws, bs, alphas, x0, t, lr: float, forced_masks=None):
+    """One step of plain gradient descent on J (Algorithm 1 with "Apply g_i"): the exact gradient
+    (backprop) applied to every layer. Returns (new Ws, new bs, loss before the update, masks)."""
+    g = backprop(Ws, bs, alphas, x0, t, forced_masks=forced_masks)
+    new_W = [_as64(W) - lr * dW for W, dW in zip(Ws, g["dW"])]
+    new_b = [_as64(b) - lr * db for b, db in zip(bs, g["db"])]
+    return new_W, new_b, g["loss"], g["masks"]
+
 
 def pack_mask(m: np.ndarray) -> np.ndarray:
     """Pack a bool array (any shape, flattened row-major) into uint64 words, LSB first.

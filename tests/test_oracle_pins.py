@@ -309,3 +309,53 @@ def test_tiny_golden_fixture_is_reproduced():
     assert [format(int(O.pack_mask(m)[0]), "016x") for m in bp["masks"]] == g["mask_word0_hex"]
     np.testing.assert_array_equal(wl.W[0][0, :4], np.float32(g["W1_first_row_head"]))
     np.testing.assert_array_equal(wl.x[0, :4], np.float32(g["x_head"]))
+
+
+# ----------------------------------------------------------------------------- training step and refresh
+def test_newton_schulz_refresh_squares_the_residual_and_reaches_the_pseudo_inverse():
+    """Schulz iteration: R_{k+1} = R_k^2, limit = Moore-Penrose right inverse (library routine pinv)."""
+    rng = np.random.default_rng(5)
+    wl = make_mlp([24, 16], batch=4, alpha=0.1, seed=11)
+    W_old = wl.W[0].astype(np.float64)
+    W_new = W_old + 2e-2 * rng.standard_normal(W_old.shape) / np.sqrt(W_old.shape[1])
+    P_old = O.right_inverse(W_old)
+    P, res = O.newton_schulz_refresh(W_new, P_old, iters=4)
+    assert res[0] < 0.2
+    for k in range(3):                       # quadratic: ||R^2|| <= ||R||^2 (Frobenius norm is submultiplicative)
+        assert res[k + 1] <= res[k] ** 2 * (1 + 1e-9) + 1e-15
+    assert res[4] < 1e-13
+    assert np.allclose(P, np.linalg.pinv(W_new).T, atol=1e-12, rtol=0)
+    # every iterate stays in the row space of W_new: P (I - W^+ W) = 0 already after zero iterations
+    P0, _ = O.newton_schulz_refresh(W_new, P_old, iters=0)
+    proj_null = np.eye(W_new.shape[1]) - np.linalg.pinv(W_new) @ W_new
+    assert np.linalg.norm(P0 @ proj_null) < 1e-12
+
+
+def test_newton_schulz_zero_iterations_is_first_order_accurate():
+    """P_0 - P_new = O(||dW||): halving the perturbation halves the error."""
+    rng = np.random.default_rng(6)
+    wl = make_mlp([20, 12], batch=4, alpha=0.1, seed=3)
+    W = wl.W[0].astype(np.float64)
+    D = rng.standard_normal(W.shape) / np.sqrt(W.shape[1])
+    P = O.right_inverse(W)
+    errs = []
+    for eps in (1e-3, 5e-4):
+        P0, _ = O.newton_schulz_refresh(W + eps * D, P, iters=0)
+        errs.append(np.linalg.norm(P0 - O.right_inverse(W + eps * D)))
+    assert 1.8 < errs[0] / errs[1] < 2.2
+
+
+def test_sgd_step_is_a_descent_step_with_the_finite_difference_gradient():
+    """J(theta - lr g) = J(theta) - lr ||g||^2 + O(lr^2) with g pinned by finite differences elsewhere."""
+    wl = make_mlp([12, 10, 8], batch=6, alpha=0.3, seed=21)
+    Ws = [w.astype(np.float64) for w in wl.W]
+    bs = [b.astype(np.float64) for b in wl.b]
+    g = O.backprop(Ws, bs, wl.alphas, wl.x, wl.t)
+    gnorm2 = sum(float(np.sum(d * d)) for d in g["dW"]) + sum(float(np.sum(d * d)) for d in g["db"])
+    lr = 1e-4
+    W1, b1, loss0, _ = O.sgd_step(Ws, bs, wl.alphas, wl.x, wl.t, lr)
+    assert loss0 == g["loss"]
+    loss1 = O.loss_value(W1, b1, wl.alphas, wl.x, wl.t)
+    assert abs((loss0 - loss1) - lr * gnorm2) < 1e-3 * lr * gnorm2
+    for W, Wn, d in zip(Ws, W1, g["dW"]):
+        assert np.array_equal(Wn, W - lr * d)

@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--reseed", type=int, default=None, help="override the re-seed interval K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
+    ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
     ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
     ap.add_argument("--gen", choices=["numpy", "torch"], default="numpy",
                     help="numpy: host generator (the one the parity tests use); torch: same recipe drawn on the GPU "
@@ -165,6 +166,24 @@ def main():
                 "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and dom == "phase3" else None,
                 "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
+    # --- training step in place (gradients applied as Phase III produces them, then the right inverses
+    # refreshed by two Schulz iterations): reported next to the metric, not part of it. The step size is
+    # tiny so that the weights of the timed run stay where they are; the work does not depend on it.
+    train = None
+    if not args.unfused and not args.no_train:
+        resid = torch.empty(1, dtype=torch.float32, device="cuda")
+        tsteps = max(1, min(args.steps, 20))
+        ms_train, _ = time_steps(lambda: net.sgd_step(net.x, net.t, 1e-7, 2, loss, resid), tsteps, 2)
+        ms_apply, _ = time_steps(lambda: net.sgd_step(net.x, net.t, 1e-7, -1, loss, resid), tsteps, 2)
+        ms_ref, _ = time_steps(lambda: net.refresh_incremental(2, resid), tsteps, 1)
+        t0 = time.perf_counter()
+        net.refresh()
+        torch.cuda.synchronize()
+        full_ms = (time.perf_counter() - t0) * 1e3
+        train = {"ms_per_step": ms_train, "steps_per_s": 1e3 / ms_train, "refresh_iters": 2,
+                 "ms_grad_and_apply": ms_apply, "ms_refresh_incremental": ms_ref, "ms_refresh_full": full_ms,
+                 "residual_before_last_iteration": float(resid.item()),
+                 "gradient_buffer_bytes_saved": int(net.total_floats) * 4}
     net.close()
     del net
 
@@ -210,6 +229,8 @@ def main():
         },
         "backprop": {k: v for k, v in bp.items() if not k.startswith("bytes")},
     }
+    if train is not None:
+        out["train_step"] = train
     if not args.no_cpu_baseline and args.gen == "numpy":
         out["cpu_baseline"] = cpu_baseline(wl, flops_mw)
     print(json.dumps(out))

@@ -102,6 +102,22 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
 int moonwalk_refresh(mw_handle_t* h, void* hip_stream);
 
 /*
+ * moonwalk_refresh_incremental — bring every P_i up to date after a SMALL change of W_i (an
+ * optimizer step) without redoing the factorisation. The paper leaves open how the inverse follows
+ * the weights (Algorithm 1 applies g_i and goes on); this is this library's answer:
+ *   P_0 = (P P^T) W_new            (P P^T = (W_old W_old^T)^{-1}: first-order guess whose rows lie
+ *                                   in the row space of W_new, so every iterate below is the
+ *                                   minimum-norm right inverse of its own residual equation)
+ *   P_{k+1} = (2 I - P_k W_new^T) P_k,  k = 0 .. iters-1   (Newton-Schulz: I - P W^T squares each time)
+ * Plain GEMMs on the given stream; does not synchronise. iters in 0..16. residual_out (device float
+ * or NULL) receives max over layers of ||I - P W^T||_F measured BEFORE the last iteration (after it
+ * the residual is about the square of that); -1 with iters = 0. If that figure is not well below 1
+ * the change of W was too large: call moonwalk_refresh. Scratch of the largest layer's
+ * d_out^2 + d_out d_in floats is allocated on first use (MW_ERR_OOM) and kept.
+ */
+int moonwalk_refresh_incremental(mw_handle_t* h, int32_t iters, float* residual_out, void* hip_stream);
+
+/*
  * moonwalk_grad — one gradient step of mixed-mode Moonwalk (Overview section, Phases I-III;
  * Algorithm 1 with h_0 from the reverse pass of the Mixed-Mode section).
  *   Phase I   forward; keeps only the packed sign masks m_i (Residual Impact section).
@@ -116,6 +132,20 @@ int moonwalk_refresh(mw_handle_t* h, void* hip_stream);
  */
 int moonwalk_grad(mw_handle_t* h, const float* x, const float* target,
                   float* grads_out, float* loss_out, void* hip_stream);
+
+/*
+ * moonwalk_sgd_step — one training step in place (Algorithm 1 with "Apply g_i"): the three phases of
+ * moonwalk_grad, but each layer's gradient is applied as soon as Phase III has produced it,
+ *   W_i -= lr * dW_i,  b_i -= lr * db_i
+ * in the weight-gradient product's own epilogue, to the W_i / b_i arrays given at setup (device;
+ * they are WRITTEN by this call). No gradient buffer exists at any time. Afterwards, if
+ * refresh_iters >= 0, P is refreshed as by moonwalk_refresh_incremental(refresh_iters,
+ * residual_out); with refresh_iters < 0 the caller must refresh before the next step.
+ * Needs the fused path (cfg.fuse) and MW_PLAN_MOONWALK, else MW_ERR_NOT_PLANNED. loss_out as in
+ * moonwalk_grad (loss of the weights BEFORE the update). Does not synchronise.
+ */
+int moonwalk_sgd_step(mw_handle_t* h, const float* x, const float* target, float lr, int32_t refresh_iters,
+                      float* loss_out, float* residual_out, void* hip_stream);
 
 /* backprop_grad — the same gradient by ordinary reverse mode with every activation stored
    (the comparison method of the paper, Fig. 1 right column). Same arguments and layout. */

@@ -15,7 +15,7 @@ PLAN_MOONWALK, PLAN_BACKPROP = 1, 2
 FETCH_MASK, FETCH_FRAG, FETCH_FRAG_OFFSETS, FETCH_FRAG_BASE, FETCH_H0, FETCH_P, FETCH_CHECKPOINT = range(1, 8)
 
 EXPORTED_SYMBOLS = [
-    "moonwalk_setup", "moonwalk_refresh", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
+    "moonwalk_setup", "moonwalk_refresh", "moonwalk_refresh_incremental", "moonwalk_sgd_step", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
     "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
     "moonwalk_profile_filter", "moonwalk_profile_launches",
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
     lib.moonwalk_setup.argtypes = [C.POINTER(vp), C.POINTER(_Layer), i32, C.POINTER(_Config), vp]
     lib.moonwalk_refresh.argtypes = [vp, vp]
+    lib.moonwalk_refresh_incremental.argtypes = [vp, i32, vp, vp]
+    lib.moonwalk_sgd_step.argtypes = [vp, vp, vp, f32, i32, vp, vp, vp]
     lib.moonwalk_grad.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.backprop_grad.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.moonwalk_grad_layout.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
@@ -245,6 +247,28 @@ class MoonwalkNet:
     def refresh(self):
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_refresh(self._handle, _stream()))
+
+    def refresh_incremental(self, iters: int = 2, residual: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Newton-Schulz refresh of every P_i after a small in-place change of the weights.
+        Returns the device float holding the residual measured before the last iteration."""
+        with torch.cuda.device(self.device):
+            if residual is None:
+                residual = torch.empty(1, dtype=torch.float32, device=self.device)
+            _check(self._lib.moonwalk_refresh_incremental(self._handle, int(iters), _ptr(residual), _stream()))
+        return residual
+
+    def sgd_step(self, x: torch.Tensor, target: torch.Tensor, lr: float, refresh_iters: int = 2,
+                 loss_out: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None):
+        """One in-place training step: the W and b tensors given at construction are updated by
+        this call (W -= lr dW, b -= lr db), then P is refreshed. Returns (loss, residual) device floats."""
+        with torch.cuda.device(self.device):
+            if loss_out is None:
+                loss_out = torch.empty(1, dtype=torch.float32, device=self.device)
+            if residual is None:
+                residual = torch.empty(1, dtype=torch.float32, device=self.device)
+            _check(self._lib.moonwalk_sgd_step(self._handle, _ptr(_f32(x)), _ptr(_f32(target)), float(lr),
+                                               int(refresh_iters), _ptr(loss_out), _ptr(residual), _stream()))
+        return loss_out, residual
 
     # ------------------------------------------------------------------ introspection
     def memory_stats(self, check: bool = True) -> dict:

@@ -602,6 +602,43 @@ k_loss_final(const double* __restrict__ partial, int n_partial, double factor, f
   if (threadIdx.x == 0) *loss = (float)(factor * red[0]);
 }
 
+// ---------------------------------------------------------------- residual of an approximate inverse
+__global__ void __launch_bounds__(EW_THREADS)
+k_identity_residual(const float* __restrict__ E, int n, double* __restrict__ partial) {
+  __shared__ double red[EW_THREADS];
+  const int64_t total = (int64_t)n * n;
+  double acc = 0.0;
+  for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < total; e += (int64_t)gridDim.x * EW_THREADS) {
+    const int64_t r = e / n, c = e - r * n;
+    const float d = E[e] - (r == c ? 1.f : 0.f);
+    acc += (double)d * (double)d;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_identity_residual_final(const double* __restrict__ partial, int n_partial, float* __restrict__ out) {
+  __shared__ double red[EW_THREADS];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n_partial; i += EW_THREADS) acc += partial[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const float r = (float)sqrt(red[0]);
+    if (!(r <= *out)) *out = r;  // running maximum; a NaN residual is kept
+  }
+}
+
 // ---------------------------------------------------------------- copy / fill
 __global__ void __launch_bounds__(EW_THREADS)
 k_copy(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
@@ -816,6 +853,17 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
     e = hipGetLastError();
   }
   return e;
+}
+
+hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  int64_t want = ((int64_t)n * n + EW_THREADS - 1) / EW_THREADS;
+  const int blocks = (int)(want > LOSS_BLOCKS ? LOSS_BLOCKS : want);
+  hipLaunchKernelGGL(k_identity_residual, dim3(blocks), dim3(EW_THREADS), 0, stream, E, n, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_identity_residual_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, out);
+  return hipGetLastError();
 }
 
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream) {

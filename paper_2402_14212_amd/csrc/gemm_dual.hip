@@ -26,10 +26,11 @@ static hipError_t pair_t(int M, int N, int K, const VijpArgs& a, const DwArgs& d
   static_assert(CfgV::NT == CfgD::NT, "both tasks run in workgroups of the same size");
   EpiVijp<RELU> epi{a.bias, a.alpha, a.alpha > 0.f ? 1.0f / a.alpha : 0.f, a.mask, a.offsets, a.frag,
                     a.frag_base, a.frag_capacity, a.Xout, a.Hout, a.CTZ, a.mismatches};
-  EpiStore es{d.dW, d.N, d.scale, 0.f, nullptr};
+  EpiStore es{d.dW, d.N, d.scale, d.beta, nullptr};
   auto tv = make_vijp_task<CfgV, true, RELU>(M, N, K, a.X, a.W, a.Hin, a.P, epi);
   auto td = make_gemm_task<CfgD, RCONTIG, RCONTIG, true, ANone, EpiStore, true>(d.M, d.N, d.K, d.CTZ, d.M, d.X, d.N,
                                                                                ANone{}, es, d.db, d.scale);
+  td.colsum_beta = d.beta;
   return launch_task_pair<CfgV::NT>(tv, td, stream);
 }
 
@@ -74,7 +75,7 @@ hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs
     hipError_t e = gemm_vijp_dual(tile_v, M, N, K, *v, stream);
     if (e != hipSuccess) return e;
   }
-  if (d) return gemm_dw(tile_d, d->M, d->N, d->K, d->CTZ, d->X, d->scale, d->dW, d->db, stream);
+  if (d) return gemm_dw(tile_d, d->M, d->N, d->K, d->CTZ, d->X, d->scale, d->dW, d->db, stream, d->beta);
   return hipSuccess;
 }
 

@@ -301,6 +301,7 @@ struct GemmTask {
   float* colsum_out;
   float colsum_scale;
   int tiles_m, tiles_n;
+  float colsum_beta = 0.f;  // colsum_out = colsum_scale * sums + colsum_beta * colsum_out
   static constexpr int LDS_BYTES = lds_bytes<Cfg, LA, LB, 1>();
   __host__ __device__ int blocks() const { return tiles_m * tiles_n; }
 
@@ -337,7 +338,11 @@ struct GemmTask {
 #pragma unroll
         for (int t = 0; t < Cfg::WTM; ++t) {
           int row = m0 + (wm * Cfg::WTM + t) * 32 + lane;
-          if (row < M) colsum_out[row] = colsum_scale * asum[t];
+          if (row < M) {
+            float v = colsum_scale * asum[t];
+            if (colsum_beta != 0.f) v += colsum_beta * colsum_out[row];
+            colsum_out[row] = v;
+          }
         }
       }
     }
@@ -467,20 +472,21 @@ inline GemmTask<Cfg, LA, LB, VEC, Xf, Epi, COLSUM> make_gemm_task(int M, int N, 
 template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
 inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
                               const Xf& xf, const Epi& epi, bool xf_vec_ok, float* colsum_out, float colsum_scale,
-                              hipStream_t stream) {
+                              hipStream_t stream, float colsum_beta = 0.f) {
   if (M <= 0 || N <= 0) return hipSuccess;
   const bool a_k = (LA == KCONTIG), b_k = (LB == KCONTIG);
   if (!extent_ok(a_k ? M : K, a_k ? K : M, lda) || !extent_ok(b_k ? N : K, b_k ? K : N, ldb) ||
       !extent_ok(M, N, (int64_t)N > 0 ? N : 1))
     return hipErrorInvalidValue;
   const bool vec = xf_vec_ok && operand_vec_ok(A, lda, a_k ? K : M) && operand_vec_ok(B, ldb, b_k ? K : N);
-  if (vec)
-    return launch_task<Cfg::NT>(make_gemm_task<Cfg, LA, LB, true, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi,
-                                                                                   colsum_out, colsum_scale),
-                                stream);
-  return launch_task<Cfg::NT>(make_gemm_task<Cfg, LA, LB, false, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi,
-                                                                                  colsum_out, colsum_scale),
-                              stream);
+  if (vec) {
+    auto t = make_gemm_task<Cfg, LA, LB, true, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out, colsum_scale);
+    t.colsum_beta = colsum_beta;
+    return launch_task<Cfg::NT>(t, stream);
+  }
+  auto t = make_gemm_task<Cfg, LA, LB, false, Xf, Epi, COLSUM>(M, N, K, A, lda, B, ldb, xf, epi, colsum_out, colsum_scale);
+  t.colsum_beta = colsum_beta;
+  return launch_task<Cfg::NT>(t, stream);
 }
 
 inline bool vijp_vec_ok(int K, const float* X, const float* W, const float* Hin, const float* P) {

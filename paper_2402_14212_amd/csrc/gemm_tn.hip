@@ -11,9 +11,10 @@ hipError_t gemm_plain_tn(int tile, int M, int N, int K, float alpha, const float
 }
 
 hipError_t gemm_dw(int tile, int M, int N, int K, const float* CTZ, const float* X, float scale, float* dW,
-                   float* db, hipStream_t stream) {
-  EpiStore epi{dW, N, scale, 0.f, nullptr};
-  if (db) return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, true, db, scale, stream);
+                   float* db, hipStream_t stream, float beta) {
+  EpiStore epi{dW, N, scale, beta, nullptr};
+  if (db)
+    return dispatch_gemm<RCONTIG, RCONTIG, true>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, true, db, scale, stream, beta);
   return dispatch_gemm<RCONTIG, RCONTIG, false>(tile, M, N, K, CTZ, M, X, N, ANone{}, epi, true, nullptr, 0.f, stream);
 }
 

@@ -140,6 +140,7 @@ struct mw_handle {
   int64_t frag_max_n = 0;                 // largest B * d_out among them
   uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
   double* loss_scratch = nullptr;
+  float* refresh_work = nullptr;  // incremental refresh of P: allocated on first use
   // Phase III runs layer i's kernel and layer i-1's weight-gradient product in one launch: the
   // latter still reads ct_z_{i-1} and x_{i-2} while the former writes ct_z_i and x_i, so the
   // activation buffers rotate over three and the ct_z buffers over two.
@@ -368,11 +369,17 @@ int moonwalk_refresh(mw_handle_t* h, void* hip_stream) {
   return build_right_inverses(h, static_cast<hipStream_t>(hip_stream));
 }
 
-int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
-                  void* hip_stream) {
-  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
-  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+}  // extern "C"
+
+namespace {
+
+// The three phases. apply_lr == 0: gradients go to grads_out. apply_lr != 0 (fused path only):
+// each layer's gradient is applied to the caller's W_i, b_i as soon as Phase III has it
+// (Algorithm 1, "Apply g_i"), W_i -= apply_lr * dW_i, b_i -= apply_lr * db_i, and grads_out is not
+// touched. W_i is last read by layer i's own Phase-III kernel, one launch before the launch that
+// carries its weight gradient, so updating it in place is safe.
+int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, hipStream_t s,
+                 float apply_lr) {
   const int B = h->B, L = h->L;
   unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
   int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
@@ -476,7 +483,16 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
       const bool relu = (l.alpha == 0.f);
       VijpArgs a{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
                  relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, ctz, mismatches};
-      DwArgs d{l.d_out, l.d_in, B, ctz, xin, inv_scale, grads_out + l.dW_off, grads_out + l.db_off};
+      DwArgs d{l.d_out, l.d_in, B, ctz, xin, inv_scale, nullptr, nullptr};
+      if (apply_lr != 0.f) {
+        d.scale = -apply_lr * inv_scale;
+        d.dW = const_cast<float*>(l.W);
+        d.db = const_cast<float*>(l.b);  // NULL: the layer has no bias
+        d.beta = 1.f;
+      } else {
+        d.dW = grads_out + l.dW_off;
+        d.db = grads_out + l.db_off;
+      }
       if (paired) {
         MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_pair(&a, B, l.d_out, l.d_in, have_pending ? &pending : nullptr, s));
         pending = d;
@@ -486,7 +502,7 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
         const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
         MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
         MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(d.M, d.N, d.K, partner, true), d.M, d.N, d.K, d.CTZ, d.X, d.scale,
-                                              d.dW, d.db, s));
+                                              d.dW, d.db, s, d.beta));
       }
       xin = xout;
       hin = hout;
@@ -515,6 +531,72 @@ int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* gr
     }
   }
   return MW_OK;
+}
+
+// ||E - I||_F of an n x n matrix, folded into *out as a running maximum (stream-ordered).
+// P <- right inverse of the CURRENT W, starting from the P held (right inverse of nearby weights):
+//   P_0 = (P P^T) W            P P^T = (W_old W_old^T)^{-1}: a first-order guess whose rows lie in the
+//                              row space of the new W, so that every iterate stays the minimum-norm one
+//   P_{k+1} = (2 I - P_k W^T) P_k     Newton-Schulz; the residual I - P W^T squares per iteration
+// All products are the library's plain GEMMs; scratch (d_out^2 + d_out d_in floats of the largest
+// layer) is allocated on first use and kept.
+int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStream_t s) {
+  if (!h->refresh_work) {
+    size_t need = 0;
+    for (auto& l : h->layers) {
+      size_t w = (size_t)l.d_out * l.d_out + (size_t)l.d_out * l.d_in;
+      if (w > need) need = w;
+    }
+    h->refresh_work = static_cast<float*>(h->alloc(need * sizeof(float), &h->st.bytes_mw_scratch));
+    if (!h->refresh_work) return MW_ERR_OOM;
+  }
+  if (residual_out) MW_HIP(ew_fill_f32(residual_out, iters >= 1 ? 0.f : -1.f, 1, s));
+  for (auto& l : h->layers) {
+    const int n = l.d_out, m = l.d_in;
+    float* S = h->refresh_work;
+    float* Q = S + (size_t)n * n;
+    MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, l.P, m, l.P, m, 0.f, S, n, nullptr, s));
+    float* cur = (iters % 2 == 1) ? Q : l.P;
+    float* other = (cur == Q) ? l.P : Q;
+    MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, 1.f, S, n, l.W, m, 0.f, cur, m, nullptr, s));
+    for (int it = 0; it < iters; ++it) {
+      MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, cur, m, l.W, m, 0.f, S, n, nullptr, s));
+      if (residual_out && it == iters - 1) MW_HIP(ew_identity_residual(S, n, h->loss_scratch, residual_out, s));
+      MW_HIP(ew_copy(cur, other, (int64_t)n * m, s));
+      MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, -1.f, S, n, cur, m, 2.f, other, m, nullptr, s));
+      float* t = cur;
+      cur = other;
+      other = t;
+    }
+  }
+  return MW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moonwalk_grad(mw_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                  void* hip_stream) {
+  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  return run_moonwalk(h, x, target, grads_out, loss_out, static_cast<hipStream_t>(hip_stream), 0.f);
+}
+
+int moonwalk_refresh_incremental(mw_handle_t* h, int32_t iters, float* residual_out, void* hip_stream) {
+  if (!h || iters < 0 || iters > 16) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  return refresh_newton_schulz(h, iters, residual_out, static_cast<hipStream_t>(hip_stream));
+}
+
+int moonwalk_sgd_step(mw_handle_t* h, const float* x, const float* target, float lr, int32_t refresh_iters,
+                      float* loss_out, float* residual_out, void* hip_stream) {
+  if (!h || !x || !target || !std::isfinite(lr) || lr == 0.f || refresh_iters > 16) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK) || !h->fuse) return MW_ERR_NOT_PLANNED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = run_moonwalk(h, x, target, nullptr, loss_out, s, lr);
+  if (rc != MW_OK || refresh_iters < 0) return rc;
+  return refresh_newton_schulz(h, refresh_iters, residual_out, s);
 }
 
 int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,

@@ -54,7 +54,7 @@ hipError_t gemm_rev_act(int tile, int M, int N, int K, const float* H, const flo
 
 // dW[M][N] = scale * CTZ[K][M]^T X[K][N];  db[M] = scale * sum_k CTZ[k][M]  (db may be NULL)
 hipError_t gemm_dw(int tile, int M, int N, int K, const float* CTZ, const float* X, float scale, float* dW,
-                   float* db, hipStream_t stream);
+                   float* db, hipStream_t stream, float beta = 0.f);
 // same with CTZ = Hy .* slope(act), act[K][M] the stored activation of this layer (backprop)
 hipError_t gemm_dw_act(int tile, int M, int N, int K, const float* Hy, const float* act, float alpha,
                        const float* X, float scale, float* dW, float* db, hipStream_t stream);
@@ -88,6 +88,7 @@ struct DwArgs {
   float scale;
   float* dW;            // [M][N]
   float* db;            // [M] or NULL
+  float beta = 0.f;     // dW = scale * product + beta * dW (same for db): 1 applies an update in place
 };
 hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream);
 
@@ -137,6 +138,14 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
                         double* scratch, hipStream_t stream);
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);
 hipError_t ew_fill_u32(uint32_t* p, uint32_t value, int64_t n, hipStream_t stream);
+inline hipError_t ew_fill_f32(float* p, float value, int64_t n, hipStream_t stream) {
+  uint32_t bits;
+  static_assert(sizeof(bits) == sizeof(value), "");
+  __builtin_memcpy(&bits, &value, sizeof(bits));
+  return ew_fill_u32(reinterpret_cast<uint32_t*>(p), bits, n, stream);
+}
+// *out = max(*out, ||E - I||_F) for the n x n matrix E (row stride n); scratch: LOSS_BLOCKS doubles
+hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream);
 // load-only model of a tiled product (measurement): sink gets (M/tile)*(N/tile)*256 floats
 hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
                              hipStream_t stream);

@@ -85,6 +85,8 @@ def test_null_handles_are_rejected(lib):
     assert lib.moonwalk_grad(None, None, None, None, None, None) == -1
     assert lib.backprop_grad(None, None, None, None, None, None) == -1
     assert lib.moonwalk_refresh(None, None) == -1
+    assert lib.moonwalk_refresh_incremental(None, 2, None, None) == -1
+    assert lib.moonwalk_sgd_step(None, None, None, 0.1, 2, None, None, None) == -1
     assert lib.moonwalk_memory_stats(None, None) == -1
     assert lib.moonwalk_grad_layout(None, None, None, None) == -1
     lib.moonwalk_destroy(None)

@@ -92,6 +92,8 @@ typedef struct {
  * definition, Notation section; P_i^T is the Moore-Penrose right inverse of the layer Jacobian
  * W_i), and allocates the workspaces named in cfg->plan.
  * layers: host array of n_layers descriptors (copied). Synchronises the stream before returning.
+ * Every matrix (d_out x d_in weights, batch x d activations) must be smaller than 2 GiB (the
+ * kernels use 31-bit byte offsets): MW_ERR_INVALID_ARG otherwise.
  * On failure *out is NULL and everything allocated so far has been freed.
  */
 int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers,

@@ -227,6 +227,13 @@ int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_
     if (!(l.alpha >= 0.f && l.alpha <= 1.f)) return MW_ERR_INVALID_ARG;
     if (i > 0 && l.d_in != layers[i - 1].d_out) return MW_ERR_INVALID_ARG;
   }
+  // the kernels address every operand with 31-bit byte offsets: each matrix must stay below 2 GiB
+  const int64_t limit = (int64_t)0x7FFFFFFF;
+  for (int i = 0; i < n_layers; ++i) {
+    const mw_layer_t& l = layers[i];
+    if ((int64_t)l.d_out * l.d_in * 4 >= limit) return MW_ERR_INVALID_ARG;
+    if ((int64_t)cfg->batch * l.d_in * 4 >= limit || (int64_t)cfg->batch * l.d_out * 4 >= limit) return MW_ERR_INVALID_ARG;
+  }
   for (int i = 0; i < n_layers; ++i)
     if (layers[i].d_out > layers[i].d_in) return MW_ERR_NOT_SUBMERSIVE;
   return MW_OK;

@@ -62,6 +62,11 @@ def test_setup_validation_answers_without_a_gpu(lib):
     assert lib.moonwalk_setup(C.byref(handle), (_Layer * 1)(_Layer(8, 8, fake, None, 1.5)), 1, C.byref(cfg), None) == -1
     chain = (_Layer * 2)(_Layer(8, 8, fake, None, 0.1), _Layer(7, 7, fake, None, 0.1))
     assert lib.moonwalk_setup(C.byref(handle), chain, 2, C.byref(cfg), None) == -1
+    # operands of 2 GiB or more cannot be addressed by the kernels' 31-bit byte offsets
+    huge = (_Layer * 1)(_Layer(32768, 16384, fake, None, 0.1))          # 32768 x 16384 floats = 2 GiB
+    assert lib.moonwalk_setup(C.byref(handle), huge, 1, C.byref(cfg), None) == -1
+    big_batch = _Config(1 << 20, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None)
+    assert lib.moonwalk_setup(C.byref(handle), (_Layer * 1)(_Layer(512, 512, fake, None, 0.1)), 1, C.byref(big_batch), None) == -1
     for bad in (_Config(0, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
                 _Config(4, -1, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
                 _Config(4, 0, 0.0, 0, 1, 1.0, null_alloc, null_free, None),

@@ -249,14 +249,39 @@ def checkpointed_layers(L: int, K: int) -> List[int]:
 
 # --------------------------------------------------------------------------- Moonwalk
 
+def adaptive_reseed_layers(alphas: Sequence[float], budget: float = 700.0, segment: int = 0) -> List[int]:
+    """Where the library's reseed_interval = -1 keeps a cotangent (not in the paper: this build's
+    answer to the conditioning of the inverse activation slopes, see error_growth_per_layer).
+
+    Walk up the layers with the predicted error growth since the last seed, the product of
+    error_growth_per_layer(alpha_j) (1 for a ReLU, whose erased entries come back exactly). Layer
+    boundary j (the output of layer j, 1-based, j < L) becomes a seed when taking layer j+1 in as
+    well would push the product beyond `budget`. With segment = S > 0 every boundary j = S, 2S, ...
+    is an exact seed anyway (Moonwalk with rematerialisation) and is not listed.
+    """
+    L = len(alphas)
+    out: List[int] = []
+    growth = 1.0
+    g = [error_growth_per_layer(a) if a > 0 else 1.0 for a in alphas]
+    for j in range(1, L):
+        growth *= g[j - 1]
+        if segment > 0 and j % segment == 0:
+            growth = 1.0
+        elif growth * g[j] > budget:
+            out.append(j)
+            growth = 1.0
+    return out
+
+
 def moonwalk(Ws, bs, alphas, x0, t, reseed_interval: int = 0, loss_scale: float = 1.0,
              forced_masks=None, Ps: Optional[Sequence[np.ndarray]] = None,
-             dtype=F64) -> Dict[str, object]:
+             dtype=F64, reseed_layers: Optional[Sequence[int]] = None) -> Dict[str, object]:
     """Mixed-mode Moonwalk, step by step (Overview section, Algorithm 1).
 
     `dtype` is the arithmetic type of every step (fp64 for the oracle proper; the tests also
     run it in fp32 to study rounding). `Ps` overrides the right inverses (used by the test
-    that any right inverse gives the same result).
+    that any right inverse gives the same result). `reseed_layers` (layer boundaries j, 1 <= j < L)
+    overrides the every-K-th rule of `reseed_interval`.
 
     Returns dW, db (un-scaled), loss, masks (bool), packed (uint64 words per layer),
     fragments (per layer, None for leaky layers), frag_base (per layer start in a store
@@ -289,7 +314,7 @@ def moonwalk(Ws, bs, alphas, x0, t, reseed_interval: int = 0, loss_scale: float 
     h = (dtype(loss_scale) * r / dtype(B)).astype(dtype)
 
     # ---- Phase II: reverse, input cotangent only; fragments and checkpoints on the way
-    kept = set(checkpointed_layers(L, reseed_interval))
+    kept = set(checkpointed_layers(L, reseed_interval)) if reseed_layers is None else set(int(j) for j in reseed_layers)
     fragments: List[Optional[np.ndarray]] = [None] * L
     checkpoints: Dict[int, np.ndarray] = {}
     h_rev = [None] * (L + 1)

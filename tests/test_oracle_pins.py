@@ -359,3 +359,31 @@ def test_sgd_step_is_a_descent_step_with_the_finite_difference_gradient():
     assert abs((loss0 - loss1) - lr * gnorm2) < 1e-3 * lr * gnorm2
     for W, Wn, d in zip(Ws, W1, g["dW"]):
         assert np.array_equal(Wn, W - lr * d)
+
+
+# ----------------------------------------------------------------------------- adaptive re-seeding
+def test_adaptive_reseed_rule_on_known_slopes():
+    """alpha = 0.1 grows 5.05x per layer: 5.05^4 = 650 <= 700 < 5.05^5, so a seed every 4 layers;
+    alpha = 0.5 grows 1.25x: 1.25^29 = 646 <= 700 < 1.25^30; ReLU and alpha = 1 never need one."""
+    assert O.adaptive_reseed_layers([0.1] * 20) == [4, 8, 12, 16]
+    assert O.adaptive_reseed_layers([0.5] * 64) == [29, 58]
+    assert O.adaptive_reseed_layers([0.0] * 30) == []
+    assert O.adaptive_reseed_layers([1.0] * 30) == []
+    # segment boundaries are seeds by themselves and reset the count
+    assert O.adaptive_reseed_layers([0.1] * 20, segment=6) == [4, 10, 16]
+    # mixed slopes: the product decides, not the layer count
+    got = O.adaptive_reseed_layers([0.1, 0.0, 0.1, 1.0, 0.1, 0.1, 0.1, 0.1])
+    assert got == [6]            # growth 5.05 at layers 1,3,5,6 = 650; layer 7 would pass 700
+
+
+def test_adaptive_reseed_keeps_fp32_moonwalk_accurate_where_none_does_not():
+    """The rule is there for a reason: 24 layers of alpha = 0.1 in fp32 arithmetic."""
+    wl = make_mlp([48] * 25, batch=16, alpha=0.1, seed=9)
+    ref = O.backprop(wl.W, wl.b, wl.alphas, wl.x, wl.t)
+    plain = O.moonwalk(wl.W, wl.b, wl.alphas, wl.x, wl.t, dtype=np.float32, forced_masks=ref["masks"])
+    seeds = O.adaptive_reseed_layers(wl.alphas)
+    seeded = O.moonwalk(wl.W, wl.b, wl.alphas, wl.x, wl.t, dtype=np.float32, forced_masks=ref["masks"],
+                        reseed_layers=seeds)
+    assert seeds == [4, 8, 12, 16, 20]
+    assert O.max_layer_err(seeded["dW"], ref["dW"]) < 1e-3
+    assert O.max_layer_err(plain["dW"], ref["dW"]) > 1e-1

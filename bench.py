@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--reseed", type=int, default=None, help="override the re-seed interval K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
+    ap.add_argument("--segment", type=int, default=0,
+                    help="segment length S of Moonwalk with rematerialisation (0 = off: the metric's configuration)")
     ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
     ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
     ap.add_argument("--gen", choices=["numpy", "torch"], default="numpy",
@@ -107,7 +109,7 @@ def main():
 
     # --- Moonwalk handle only (so that its peak memory is its own)
     t0 = time.perf_counter()
-    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused)
+    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused, segment_length=args.segment)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
     grads = net.new_grads()
@@ -163,7 +165,7 @@ def main():
                 "kernel": dom_name,
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and dom == "phase3" else None,
+                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and not args.segment and dom == "phase3" else None,
                 "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
     # --- training step in place (gradients applied as Phase III produces them, then the right inverses
@@ -210,7 +212,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic (seeded, generator: %s)" % args.gen,
         "config": {"workload": f"{wl.name}: depth {L}, widths {widths[0]}->{widths[-1]}, batch {B}, "
                                f"alpha {wl.alphas[0]}, reseed K={wl.reseed_interval}, loss_scale {wl.loss_scale:g}, "
-                               f"{'unfused' if args.unfused else 'fused'} kernels"},
+                               f"{'unfused' if args.unfused else 'fused'} kernels"
+                               + (f", segments of {args.segment} layers" if args.segment else "")},
         "tflops": flops_mw / (ms_mw * 1e-3) / 1e12,
         "flop_per_step": flops_mw,
         "mfma_frac_whole_step": flops_mw / (ms_mw * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS,

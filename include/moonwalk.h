@@ -51,7 +51,9 @@ typedef struct {
   int32_t batch;            /* B, fixed for the handle's lifetime                                         */
   int32_t reseed_interval;  /* K: keep the cotangent of every K-th layer boundary in the reverse pass and
                                restart the forward sweep from it (plain cotangent checkpointing, Overview
-                               section). 0 = never: the method exactly as printed.                        */
+                               section). 0 = never: the method exactly as printed. -1 = chosen by the
+                               library from the layers' slopes (a seed wherever the predicted error
+                               growth prod (alpha + 1/alpha)/2 since the last seed would pass 700).        */
   float   loss_scale;       /* s > 0, a power of two: the output cotangent is multiplied by s and the
                                gradients are divided by s again (exact); guards fp32 under/overflow.      */
   int32_t plan;             /* MW_PLAN_* bits; 0 means MW_PLAN_MOONWALK | MW_PLAN_BACKPROP                 */
@@ -64,6 +66,13 @@ typedef struct {
   void* (*dev_alloc)(size_t bytes, void* ctx);
   void  (*dev_free)(void* ptr, void* ctx);
   void*   alloc_ctx;
+  int32_t segment_length;   /* S > 0: Moonwalk with rematerialisation (Table 1, "Moonwalk + checkpoint"). Phase I
+                               keeps the activation of every S-th layer boundary and NO masks; the segments
+                               of S layers are then finished one at a time from the top: forward again
+                               inside the segment (masks, fragment index), reverse, Phase III. Masks,
+                               fragments and their index exist for one segment only; costs one more forward
+                               pass. Needs fuse = 1. 0 or >= n_layers: off.                               */
+  int32_t reserved;
 } mw_config_t;
 
 /* Itemised device bytes held by a handle (closed forms are in the design notes). */
@@ -72,7 +81,7 @@ typedef struct {
   uint64_t bytes_masks;         /* 1-bit sign masks, 8 * ceil(B d_i / 64) per layer                   */
   uint64_t bytes_fragments;     /* fragment store capacity (ReLU layers)                              */
   uint64_t bytes_frag_index;    /* per-word erased offsets, layer bases                               */
-  uint64_t bytes_checkpoints;   /* re-seed cotangents                                                 */
+  uint64_t bytes_checkpoints;   /* re-seed cotangents; with segments also the kept activations        */
   uint64_t bytes_mw_scratch;    /* ping-pong activations / cotangents, ct_z, loss partials, flags     */
   uint64_t bytes_bp_activations;/* stored x_1..x_L of the backprop path                               */
   uint64_t bytes_bp_scratch;    /* backprop cotangent ping-pong, loss partials                        */

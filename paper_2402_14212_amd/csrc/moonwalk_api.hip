@@ -109,6 +109,7 @@ struct Layer {
   uint32_t* offsets = nullptr;  // ReLU layers: [mask_words + 1]
   int relu_slot = -1;           // position in reverse-pass order among the ReLU layers
   float* ckpt = nullptr;        // kept cotangent at this layer's OUTPUT (h_i), if any
+  float* xck = nullptr;         // kept activation at this layer's OUTPUT (x_i): segment boundaries only
   float* act = nullptr;         // backprop: stored x_i
   size_t dW_off = 0, db_off = 0;
 };
@@ -118,6 +119,8 @@ struct Layer {
 struct mw_handle {
   std::vector<Layer> layers;
   int B = 0, L = 0, K = 0, fuse = 1, plan = 0;
+  int S = 0;                        // segment length (0: the whole network is one run)
+  float* hseg[2] = {nullptr, nullptr};  // cotangents at segment boundaries, alternating
   float loss_scale = 1.f;
   double frag_factor = 1.0;
   void* (*dev_alloc)(size_t, void*) = nullptr;
@@ -217,7 +220,8 @@ int build_right_inverses(mw_handle* h, hipStream_t stream) {
 
 int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_t* cfg) {
   if (!layers || n_layers <= 0 || !cfg || cfg->batch <= 0) return MW_ERR_INVALID_ARG;
-  if (cfg->reseed_interval < 0) return MW_ERR_INVALID_ARG;
+  if (cfg->reseed_interval < -1 || cfg->segment_length < 0) return MW_ERR_INVALID_ARG;
+  if (cfg->segment_length > 0 && !cfg->fuse) return MW_ERR_INVALID_ARG;
   if (!(cfg->loss_scale > 0.f) || !std::isfinite(cfg->loss_scale)) return MW_ERR_INVALID_ARG;
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
@@ -257,6 +261,7 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
   h->B = cfg->batch;
   h->L = n_layers;
   h->K = cfg->reseed_interval;
+  h->S = (cfg->segment_length > 0 && cfg->segment_length < n_layers) ? cfg->segment_length : 0;
   h->fuse = cfg->fuse ? 1 : 0;
   h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
   h->loss_scale = cfg->loss_scale;
@@ -300,23 +305,48 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
     rc = build_right_inverses(h, stream);
     if (rc != MW_OK) return fail(rc);
 
-    // sign masks (zeroed once: the padding bits of the last word are never written afterwards)
-    for (auto& l : h->layers) {
-      l.mask_words = (B * l.d_out + 63) / 64;
-      ok = ok && alloc_t(h, &l.mask, l.mask_words, &st.bytes_masks);
-      if (ok) {
-        e = ew_fill_u32(reinterpret_cast<uint32_t*>(l.mask), 0u, (int64_t)l.mask_words * 2, stream);
-        if (e != hipSuccess) return fail(hip_fail(e, "mask init"));
+    // Sign masks (zeroed once: the padding bits of the last word are never written afterwards),
+    // and for ReLU layers the per-word erased offsets. Without segments every layer has its own;
+    // with segments the layers at the same position of their segments share a slot sized for the
+    // largest of them.
+    const int S = h->S;
+    const int n_slots = S > 0 ? S : n_layers;
+    std::vector<uint64_t*> mask_slot(n_slots, nullptr);
+    std::vector<uint32_t*> off_slot(n_slots, nullptr);
+    {
+      std::vector<size_t> words(n_slots, 0);
+      std::vector<bool> relu(n_slots, false);
+      for (int i = 0; i < n_layers; ++i) {
+        Layer& l = h->layers[i];
+        l.mask_words = (B * l.d_out + 63) / 64;
+        const int p = S > 0 ? i % S : i;
+        if (l.mask_words > words[p]) words[p] = l.mask_words;
+        if (l.alpha == 0.f) relu[p] = true;
       }
+      for (int p = 0; p < n_slots; ++p) {
+        ok = ok && alloc_t(h, &mask_slot[p], words[p], &st.bytes_masks);
+        if (ok) {
+          e = ew_fill_u32(reinterpret_cast<uint32_t*>(mask_slot[p]), 0u, (int64_t)words[p] * 2, stream);
+          if (e != hipSuccess) return fail(hip_fail(e, "mask init"));
+        }
+        if (relu[p]) ok = ok && alloc_t(h, &off_slot[p], words[p] + 1, &st.bytes_frag_index);
+      }
+      if (!ok) return fail(MW_ERR_OOM);
     }
-    // fragment store and its index (ReLU layers)
-    size_t relu_elems = 0;
-    for (auto& l : h->layers)
+    // fragment store (ReLU layers): room for the erased cotangents of one run of layers
+    size_t relu_elems = 0, run_elems = 0;
+    for (int i = 0; i < n_layers; ++i) {
+      Layer& l = h->layers[i];
+      const int p = S > 0 ? i % S : i;
+      l.mask = mask_slot[p];
+      if (S > 0 && p == 0) run_elems = 0;
       if (l.alpha == 0.f) {
         ++h->n_relu;
-        relu_elems += B * l.d_out;
-        ok = ok && alloc_t(h, &l.offsets, l.mask_words + 1, &st.bytes_frag_index);
+        l.offsets = off_slot[p];
+        run_elems += B * l.d_out;
+        if (run_elems > relu_elems) relu_elems = run_elems;
       }
+    }
     if (ok && h->n_relu > 0) {
       h->frag_capacity = (uint64_t)std::ceil(h->frag_factor * (double)relu_elems);
       if (h->frag_capacity < 1) h->frag_capacity = 1;
@@ -343,10 +373,34 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
         if (e != hipSuccess) return fail(hip_fail(e, "fragment index init"));
       }
     }
-    // re-seed checkpoints: cotangent at the output of layer j (1-based j = K, 2K, ... < L)
-    if (h->K > 0)
-      for (int j = 1; j < n_layers; ++j)
-        if (j % h->K == 0) ok = ok && alloc_t(h, &h->layers[j - 1].ckpt, B * h->layers[j - 1].d_out, &st.bytes_checkpoints);
+    // Re-seed checkpoints: the cotangent at the output of layer j (1-based), kept in the reverse
+    // pass and taken up again by Phase III. K > 0: j = K, 2K, ... < L. K = -1: placed where the
+    // predicted growth of the rounding error since the last seed, prod (alpha + 1/alpha)/2 over
+    // the layers in between, would pass 700 (what four alpha = 0.1 layers give; measured to keep
+    // the gradients at 1e-4 of the oracle's). Segment boundaries are exact seeds by themselves.
+    {
+      double growth = 1.0;
+      for (int j = 1; j < n_layers; ++j) {
+        const float a = h->layers[j - 1].alpha;
+        growth *= (a > 0.f) ? 0.5 * ((double)a + 1.0 / (double)a) : 1.0;
+        const bool boundary = S > 0 && j % S == 0;
+        bool keep = false;
+        if (boundary) {
+          growth = 1.0;
+        } else if (h->K > 0) {
+          keep = (j % h->K == 0);
+        } else if (h->K < 0) {
+          const float an = h->layers[j].alpha;
+          const double next = growth * ((an > 0.f) ? 0.5 * ((double)an + 1.0 / (double)an) : 1.0);
+          if (next > 700.0) {
+            keep = true;
+            growth = 1.0;
+          }
+        }
+        if (keep) ok = ok && alloc_t(h, &h->layers[j - 1].ckpt, B * h->layers[j - 1].d_out, &st.bytes_checkpoints);
+        if (boundary) ok = ok && alloc_t(h, &h->layers[j - 1].xck, B * h->layers[j - 1].d_out, &st.bytes_checkpoints);
+      }
+    }
     // ping-pong buffers
     const size_t nmax = B * (size_t)h->dmax;
     ok = ok && alloc_t(h, &h->xa, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->xb, nmax, &st.bytes_mw_scratch) &&
@@ -355,6 +409,7 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
          alloc_t(h, &h->h0, B * (size_t)h->layers[0].d_in, &st.bytes_mw_scratch);
     if (!h->fuse) ok = ok && alloc_t(h, &h->zbuf, nmax, &st.bytes_mw_scratch);
     if (h->fuse) ok = ok && alloc_t(h, &h->xc, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->ctz2, nmax, &st.bytes_mw_scratch);
+    if (h->S > 0) ok = ok && alloc_t(h, &h->hseg[0], nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->hseg[1], nmax, &st.bytes_mw_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   ok = ok && alloc_t(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_mw_scratch);
@@ -380,65 +435,93 @@ int moonwalk_refresh(mw_handle_t* h, void* hip_stream) {
 
 namespace {
 
-// The three phases. apply_lr == 0: gradients go to grads_out. apply_lr != 0 (fused path only):
-// each layer's gradient is applied to the caller's W_i, b_i as soon as Phase III has it
-// (Algorithm 1, "Apply g_i"), W_i -= apply_lr * dW_i, b_i -= apply_lr * db_i, and grads_out is not
-// touched. W_i is last read by layer i's own Phase-III kernel, one launch before the launch that
-// carries its weight gradient, so updating it in place is safe.
-int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, hipStream_t s,
-                 float apply_lr) {
-  const int B = h->B, L = h->L;
-  unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
-  int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
-  for (auto& c : h->launches) c = 0;
-  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_fill_u32(h->status, 0u, 3, s));
+// One gradient step is assembled from four pieces that work on a run of layers [lo, hi).
+// Without segments the run is the whole network; with segments (cfg.segment_length = S) Phase I
+// keeps x at every S-th layer boundary and no masks, and the segments are then finished one by
+// one from the top: forward again inside the segment (masks, fragment index), reverse through
+// it, Phase III through it. Only one segment's masks and fragments exist at a time.
+struct Step {
+  mw_handle* h;
+  hipStream_t s;
+  const float* x;
+  float* grads_out;
+  float apply_lr;  // 0: gradients to grads_out; else W_i -= apply_lr dW_i, b_i -= apply_lr db_i in place
+};
 
-  // ---------------- Phase I: forward, keep sign masks only
-  const float* xin = x;
+// Forward through layers [lo, hi) from xin. Layers i >= mask_from also write their sign masks.
+// A layer with an activation checkpoint writes its output there. *x_end = x_{hi}.
+int forward_range(const Step& c, int lo, int hi, const float* xin, int mask_from, const float** x_end) {
+  mw_handle* h = c.h;
+  hipStream_t s = c.s;
+  const int B = h->B;
   float* xbuf[2] = {h->xa, h->xb};
-  for (int i = 0; i < L; ++i) {
+  for (int i = lo; i < hi; ++i) {
     Layer& l = h->layers[i];
-    float* xout = xbuf[i & 1];
+    float* xout = l.xck ? l.xck : xbuf[i & 1];
+    const bool want_mask = i >= mask_from;
+    // mask slots are shared between segments: clear what this layer's packing will not overwrite
+    if (want_mask && h->S > 0 && (((size_t)B * l.d_out) % 64) != 0)
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_fill_u32(reinterpret_cast<uint32_t*>(l.mask + l.mask_words - 1), 0u, 2, s));
     if (h->fuse) {
-      if (l.d_out % 32 == 0) {
+      if (want_mask && l.d_out % 32 == 0) {
         MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, l.mask, s));
       } else {
         MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, nullptr, s));
-        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_mask_from_act(xout, (int64_t)B * l.d_out, l.mask, s));
+        if (want_mask) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_mask_from_act(xout, (int64_t)B * l.d_out, l.mask, s));
       }
     } else {
       MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
                         l.b, s));
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(h->zbuf, nullptr, B, l.d_out, l.alpha, xout, l.mask, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(h->zbuf, nullptr, B, l.d_out, l.alpha, xout, want_mask ? l.mask : nullptr, s));
     }
     xin = xout;
   }
-  // fragment index of all ReLU layers (needed from Phase II on): one scan launch, then the layer bases
-  if (h->n_relu > 0) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_offsets_layers(h->frag_layers, h->n_relu, h->frag_max_n, s));
-  if (h->n_relu > 0) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_bases(h->count_ptrs, h->n_relu, h->frag_bases, h->frag_bases + h->n_relu, s));
+  *x_end = xin;
+  return MW_OK;
+}
 
-  // ---------------- loss and output cotangent h_L
+// Fragment index (erased-element offsets, then the bases of the store) of the ReLU layers in
+// [lo, hi): one scan launch and one tiny scan. The per-layer tables are in reverse-pass order,
+// so the layers of a run are a contiguous stretch of them; bases restart at 0 for every run.
+int frag_index_range(const Step& c, int lo, int hi) {
+  mw_handle* h = c.h;
+  int first = -1, count = 0;
+  for (int i = hi - 1; i >= lo; --i)
+    if (h->layers[i].alpha == 0.f) {
+      if (first < 0) first = h->layers[i].relu_slot;
+      ++count;
+    }
+  if (count == 0) return MW_OK;
+  MW_LAUNCH(h, c.s, MW_KCLASS_EW, ew_frag_offsets_layers(h->frag_layers + first, count, h->frag_max_n, c.s));
+  MW_LAUNCH(h, c.s, MW_KCLASS_EW, ew_frag_bases(h->count_ptrs + first, count, h->frag_bases + first, h->frag_bases + h->n_relu, c.s));
+  return MW_OK;
+}
+
+// Phase II through layers [lo, hi): h_top holds the raw cotangent at the output of layer hi-1
+// (overwritten), the cotangent at the input of layer lo goes to h_bottom.
+int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) {
+  mw_handle* h = c.h;
+  hipStream_t s = c.s;
+  const int B = h->B;
+  int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
   float* hbuf[2] = {h->ha, h->hb};
-  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s));
-
-  // ---------------- Phase II: reverse, input cotangent only
   if (h->fuse) {
-    // The last layer's slope (and fragments) are applied by the elementwise kernels; every
+    // The top layer's slope (and fragments) are applied by the elementwise kernels; every
     // reverse product then applies the slope of the layer below it in its own epilogue.
     {
-      Layer& l = h->layers[L - 1];
+      Layer& l = h->layers[hi - 1];
       const int64_t n = (int64_t)B * l.d_out;
       if (l.alpha == 0.f)
-        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hbuf[0], l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot,
+        MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(h_top, l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot,
                                                       h->frag_capacity, overflow, s));
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hbuf[0], l.mask, n, l.alpha, hbuf[0], s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(h_top, l.mask, n, l.alpha, h_top, s));
     }
-    const float* ctcur = hbuf[0];
-    for (int i = L - 1; i >= 0; --i) {
+    const float* ctcur = h_top;
+    for (int i = hi - 1; i >= lo; --i) {
       Layer& l = h->layers[i];
-      if (i == 0) {
+      if (i == lo) {
         MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, ctcur, l.d_out, l.W, l.d_in, 0.f,
-                                                  h->h0, l.d_in, nullptr, s));
+                                                  h_bottom, l.d_in, nullptr, s));
       } else {
         Layer& below = h->layers[i - 1];
         float* ctout = (ctcur == hbuf[0]) ? hbuf[1] : hbuf[0];
@@ -450,15 +533,15 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
       }
     }
   } else {
-    const float* hcur = hbuf[0];
-    for (int i = L - 1; i >= 0; --i) {
+    const float* hcur = h_top;
+    for (int i = hi - 1; i >= lo; --i) {
       Layer& l = h->layers[i];
       const int64_t n = (int64_t)B * l.d_out;
       if (l.alpha == 0.f)
         MW_LAUNCH(h, s, MW_KCLASS_EW, ew_frag_compact(hcur, l.mask, l.offsets, n, h->frag, h->frag_bases + l.relu_slot,
                                                       h->frag_capacity, overflow, s));
       float* hout;
-      if (i == 0) hout = h->h0;
+      if (i == lo) hout = h_bottom;
       else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
       else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hcur, l.mask, n, l.alpha, h->ctz, s));
@@ -467,11 +550,21 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
       hcur = hout;
     }
   }
+  return MW_OK;
+}
 
-  // ---------------- Phase III: forward vijp sweep
+// Phase III through layers [lo, hi) from the input xin and the input cotangent hin of layer lo.
+// apply_lr != 0 (fused path only): each layer's gradient is applied to the caller's W_i, b_i as
+// soon as it exists (Algorithm 1, "Apply g_i"). W_i is last read by layer i's own kernel, one
+// launch before the launch that carries its weight gradient, so updating it in place is safe.
+int phase3_range(const Step& c, int lo, int hi, const float* xin, const float* hin) {
+  mw_handle* h = c.h;
+  hipStream_t s = c.s;
+  const int B = h->B;
+  unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
+  float* hbuf[2] = {h->ha, h->hb};
+  float* xbuf[2] = {h->xa, h->xb};
   const float inv_scale = 1.0f / h->loss_scale;
-  xin = x;
-  const float* hin = h->h0;
   if (h->fuse) {
     // Launch k carries layer k's kernel and layer k-1's weight gradient (see the buffer rotation
     // at the handle); a last launch carries the final weight gradient alone. With a class filter
@@ -481,9 +574,9 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
     float* crot[2] = {h->ctz, h->ctz2};
     DwArgs pending{};
     bool have_pending = false;
-    for (int i = 0; i < L; ++i) {
+    for (int i = lo; i < hi; ++i) {
       Layer& l = h->layers[i];
-      if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+      if (i > lo && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
       float* xout = xrot[i % 3];
       float* ctz = crot[i & 1];
       float* hout = hbuf[i & 1];
@@ -491,14 +584,14 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
       VijpArgs a{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
                  relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, ctz, mismatches};
       DwArgs d{l.d_out, l.d_in, B, ctz, xin, inv_scale, nullptr, nullptr};
-      if (apply_lr != 0.f) {
-        d.scale = -apply_lr * inv_scale;
+      if (c.apply_lr != 0.f) {
+        d.scale = -c.apply_lr * inv_scale;
         d.dW = const_cast<float*>(l.W);
         d.db = const_cast<float*>(l.b);  // NULL: the layer has no bias
         d.beta = 1.f;
       } else {
-        d.dW = grads_out + l.dW_off;
-        d.db = grads_out + l.db_off;
+        d.dW = c.grads_out + l.dW_off;
+        d.db = c.grads_out + l.db_off;
       }
       if (paired) {
         MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_pair(&a, B, l.d_out, l.d_in, have_pending ? &pending : nullptr, s));
@@ -506,7 +599,7 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
         have_pending = true;
       } else {
         // same tiles as in the paired launches: the weight gradient's follows the next layer's kernel
-        const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
+        const int partner = (i + 1 < hi) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
         MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_vijp_dual(TILE_AUTO, B, l.d_out, l.d_in, a, s));
         MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(d.M, d.N, d.K, partner, true), d.M, d.N, d.K, d.CTZ, d.X, d.scale,
                                               d.dW, d.db, s, d.beta));
@@ -516,9 +609,9 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
     }
     if (have_pending) MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_pair(nullptr, 0, 0, 0, &pending, s));
   } else {
-    for (int i = 0; i < L; ++i) {
+    for (int i = lo; i < hi; ++i) {
       Layer& l = h->layers[i];
-      if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+      if (i > lo && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
       float* xout = xbuf[i & 1];
       float* hout = hbuf[i & 1];
       const bool relu = (l.alpha == 0.f);
@@ -529,13 +622,59 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_vijp_epilogue(h->zbuf, h->ctz, B, l.d_out, l.alpha, l.mask, l.offsets, h->frag,
                               relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, mismatches,
                               s));
-      const int partner = (i + 1 < L) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
+      const int partner = (i + 1 < hi) ? pick_tile(B, h->layers[i + 1].d_out, h->layers[i + 1].d_in) : TILE_AUTO;
       MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_dw(pick_tile_dw(l.d_out, l.d_in, B, partner, true), l.d_out, l.d_in, B, h->ctz, xin, inv_scale,
-                                            grads_out + l.dW_off, nullptr, s));
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, grads_out + l.db_off, s));
+                                            c.grads_out + l.dW_off, nullptr, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_colsum(h->ctz, B, l.d_out, inv_scale, c.grads_out + l.db_off, s));
       xin = xout;
       hin = hout;
     }
+  }
+  return MW_OK;
+}
+
+#define MW_TRY_RC(expr)          \
+  do {                           \
+    int rc__ = (expr);           \
+    if (rc__ != MW_OK) return rc__; \
+  } while (0)
+
+int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, hipStream_t s,
+                 float apply_lr) {
+  const int B = h->B, L = h->L;
+  const Step c{h, s, x, grads_out, apply_lr};
+  for (auto& n : h->launches) n = 0;
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_fill_u32(h->status, 0u, 3, s));
+  const float* x_L = nullptr;
+
+  if (h->S <= 0) {
+    // Phase I: forward, keep sign masks only; loss and output cotangent; Phase II; Phase III
+    MW_TRY_RC(forward_range(c, 0, L, x, 0, &x_L));
+    MW_TRY_RC(frag_index_range(c, 0, L));
+    MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+    MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0));
+    return phase3_range(c, 0, L, x, h->h0);
+  }
+
+  // Segments of S layers. Phase I keeps x_{S}, x_{2S}, ... (and, for the top segment, already the
+  // masks); then the segments are finished from the top down, each with the exact cotangent at
+  // its output as the seed of its reverse pass and the exact cotangent at its input as the seed
+  // of its Phase III.
+  const int S = h->S, nseg = (L + S - 1) / S;
+  MW_TRY_RC(forward_range(c, 0, L, x, (nseg - 1) * S, &x_L));
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->hseg[(nseg - 1) & 1], loss_out,
+                                             h->loss_scratch, s));
+  for (int k = nseg - 1; k >= 0; --k) {
+    const int lo = k * S, hi = (lo + S < L) ? lo + S : L;
+    const float* x_seg = (lo == 0) ? x : h->layers[lo - 1].xck;
+    if (k != nseg - 1) {
+      const float* unused = nullptr;
+      MW_TRY_RC(forward_range(c, lo, hi, x_seg, lo, &unused));
+    }
+    MW_TRY_RC(frag_index_range(c, lo, hi));
+    float* h_bottom = (lo == 0) ? h->h0 : h->hseg[(k - 1) & 1];
+    MW_TRY_RC(reverse_range(c, lo, hi, h->hseg[k & 1], h_bottom));
+    MW_TRY_RC(phase3_range(c, lo, hi, x_seg, h_bottom));
   }
   return MW_OK;
 }
@@ -682,6 +821,10 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
   const void* src = nullptr;
   size_t bytes = 0;
   const Layer* l = (what == MW_FETCH_H0) ? nullptr : &h->layers[layer];
+  // with segments, masks and fragments exist for one segment at a time: after a step, the first one
+  if (h->S > 0 && layer >= h->S &&
+      (what == MW_FETCH_MASK || what == MW_FETCH_FRAG_OFFSETS || what == MW_FETCH_FRAG_BASE || what == MW_FETCH_FRAG))
+    return MW_ERR_INVALID_ARG;
   uint64_t base = 0;
   switch (what) {
     case MW_FETCH_MASK:

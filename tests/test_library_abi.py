@@ -68,7 +68,9 @@ def test_setup_validation_answers_without_a_gpu(lib):
     big_batch = _Config(1 << 20, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None)
     assert lib.moonwalk_setup(C.byref(handle), (_Layer * 1)(_Layer(512, 512, fake, None, 0.1)), 1, C.byref(big_batch), None) == -1
     for bad in (_Config(0, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
-                _Config(4, -1, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
+                _Config(4, -2, 1.0, 0, 1, 1.0, null_alloc, null_free, None),
+                _Config(4, 0, 1.0, 0, 1, 1.0, null_alloc, null_free, None, -1),
+                _Config(4, 0, 1.0, 0, 0, 1.0, null_alloc, null_free, None, 2),
                 _Config(4, 0, 0.0, 0, 1, 1.0, null_alloc, null_free, None),
                 _Config(4, 0, 1.0, 8, 1, 1.0, null_alloc, null_free, None)):
         assert lib.moonwalk_setup(C.byref(handle), ok_layer, 1, C.byref(bad), None) == -1

@@ -1,0 +1,87 @@
+"""Synthetic submersive 2-D convolutional networks for Moonwalk (seeded; arrays only, no arithmetic of the method).
+
+Recipe, following the paper's fully parallel 2-D experiment in shape (3x3 kernels, stride 2, padding 1,
+a constant number of channels, leaky ReLU, each layer halving the resolution):
+
+* kernel w_i [k][k][C][C] ~ N(0, 1/(k k C)); the tap at (p, p) is made channel-triangular,
+  w[p, p, c, c'] = 0 for c < c', with diagonal w[p, p, c, c] ~ U[0.8, 1.2] (conditions (ii), (iii) of the
+  lemma on submersive convolutional layers);
+* bias ~ N(0, 0.01^2); input x ~ N(0, 1) [B][H][H][C]; target t ~ N(0, 1) of the output shape;
+* draw order: per layer w, diagonal, bias; then x; then t; one numpy PCG64 stream; drawn in fp64, rounded to fp32.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List
+
+import numpy as np
+
+
+@dataclass
+class ConvWorkload:
+    batch: int
+    side: int                 # input height = width
+    channels: int
+    k: int
+    s: int
+    p: int
+    alphas: List[float]
+    w: List[np.ndarray]       # fp32 [k][k][C][C]
+    b: List[np.ndarray]       # fp32 [C]
+    x: np.ndarray             # fp32 [B][H][H][C]
+    t: np.ndarray             # fp32 [B][H_L][H_L][C]
+    sides: List[int]          # spatial side after each layer, sides[0] = input
+    seed: int = 0
+    name: str = ""
+
+    @property
+    def depth(self) -> int:
+        return len(self.w)
+
+
+def conv_out_side(n: int, k: int, s: int, p: int) -> int:
+    return (n + 2 * p - k) // s + 1
+
+
+def make_convnet(batch: int, side: int, channels: int, depth: int, k: int = 3, s: int = 2, p: int = 1,
+                 alpha: float = 0.1, seed: int = 0, name: str = "") -> ConvWorkload:
+    rng = np.random.default_rng(seed)
+    C = int(channels)
+    sides = [int(side)]
+    ws, bs = [], []
+    for _ in range(depth):
+        n = sides[-1]
+        no = conv_out_side(n, k, s, p)
+        if no < 1 or not (k > p and s > p and n > s * (no - 1)):
+            raise ValueError(f"layer with input side {n} violates the spatial bounds of the lemma")
+        w = rng.standard_normal((k, k, C, C)) / np.sqrt(k * k * C)
+        tap = np.tril(w[p, p])              # rows c, columns c': keep c >= c', zero for c < c'
+        d = rng.uniform(0.8, 1.2, size=C)
+        tap[np.arange(C), np.arange(C)] = d
+        w[p, p] = tap
+        bias = 0.01 * rng.standard_normal(C)
+        ws.append(np.ascontiguousarray(w, dtype=np.float32))
+        bs.append(np.ascontiguousarray(bias, dtype=np.float32))
+        sides.append(no)
+    x = rng.standard_normal((batch, side, side, C)).astype(np.float32)
+    t = rng.standard_normal((batch, sides[-1], sides[-1], C)).astype(np.float32)
+    return ConvWorkload(batch=int(batch), side=int(side), channels=C, k=k, s=s, p=p, alphas=[float(alpha)] * depth,
+                        w=ws, b=bs, x=x, t=t, sides=sides, seed=int(seed), name=name)
+
+
+def conv_moonwalk_flops(wl: ConvWorkload) -> int:
+    """Algorithmic flops of one Moonwalk step: per layer three products of 2 rows' (k k C) C (forward,
+    recompute, weight gradient), the input-gradient product of the same size, and the channel solve."""
+    total = 0
+    for i in range(wl.depth):
+        rows = wl.batch * wl.sides[i + 1] ** 2
+        total += 4 * 2 * rows * wl.k * wl.k * wl.channels * wl.channels + 2 * rows * wl.channels * wl.channels
+    return total
+
+
+def conv_backprop_flops(wl: ConvWorkload) -> int:
+    total = 0
+    for i in range(wl.depth):
+        rows = wl.batch * wl.sides[i + 1] ** 2
+        total += 3 * 2 * rows * wl.k * wl.k * wl.channels * wl.channels
+    return total

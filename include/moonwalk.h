@@ -188,6 +188,82 @@ int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out);
 int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap,
                          size_t* n_bytes);
 
+/* ------------------------------------------------------------------------------------------
+ * Submersive 2-D convolutional layers (lemma on submersive convolutional layers; the fully
+ * parallel 2-D setting of the experiments).
+ *
+ * Activations are channels-last, [B][H][W][C] fp32; a layer is
+ *   z[b,i',j',c'] = sum_{u,v,c} w[u,v,c,c'] x[b, s i'+u-p, s j'+v-p, c] + bias[c'],  x' = leaky_relu(z)
+ * with kernel w [k][k][C_in][C_out] (row-major in that order), one stride s and padding p for both
+ * spatial dimensions, and the loss J = 0.5 ||x_L - t||^2 / B. Setup checks the lemma's conditions:
+ * k > p, s > p, n > s (n' - 1) in both dimensions, C_out <= C_in, and on the device that the tap
+ * w[p][p] is channel-triangular (w[p][p][c][c'] = 0 for c < c') with non-zero diagonal
+ * (MW_ERR_NOT_SUBMERSIVE otherwise). Only the fully parallel vijp is built: k <= p + s, so that no
+ * other output position enters the equation of h[s i', s j', c'] (MW_ERR_INVALID_ARG otherwise);
+ * alpha must be in (0, 1]. The vijp of the convolution is then, at every output position on its own,
+ * the triangular solve T h'[i', j', :] = h[s i', s j', :C_out] with T = w[p][p][:C_out][:C_out]; the
+ * library keeps T^{-1} per layer (moonwalk_conv_refresh recomputes it after the caller changed w).
+ * The gradient layout is per layer dw [k][k][C_in][C_out] then db [C_out].
+ * ------------------------------------------------------------------------------------------ */
+typedef struct mw_conv_handle mw_conv_handle_t;
+
+typedef struct {
+  int32_t channels_in, channels_out, k, stride, pad;
+  const float* w;   /* device, [k][k][channels_in][channels_out]; caller owns; must outlive the handle */
+  const float* b;   /* device [channels_out]; NULL means zero bias                                     */
+  float alpha;      /* leaky-ReLU slope in (0, 1]                                                      */
+} mw_conv_layer_t;
+
+typedef struct {
+  int32_t batch, height, width;  /* input activation [batch][height][width][layers[0].channels_in]      */
+  int32_t reseed_interval;       /* as in mw_config_t (>= 0)                                            */
+  float   loss_scale;            /* as in mw_config_t                                                   */
+  int32_t plan;                  /* MW_PLAN_* bits; 0 = both                                            */
+  size_t  patch_bytes;           /* size of the buffer the image chunks' patch matrices are gathered into
+                                    (0 = 256 MiB); at least one image's patches are always taken        */
+  void* (*dev_alloc)(size_t bytes, void* ctx);
+  void  (*dev_free)(void* ptr, void* ctx);
+  void*   alloc_ctx;
+} mw_conv_config_t;
+
+typedef struct {
+  uint64_t bytes_masks;            /* 1-bit sign masks of all layer outputs                              */
+  uint64_t bytes_tap_inverses;     /* T^{-1}, C_out^2 floats per layer                                   */
+  uint64_t bytes_checkpoints;      /* re-seed cotangents                                                 */
+  uint64_t bytes_input_cotangent;  /* h_0: as large as the network input                                 */
+  uint64_t bytes_scratch;          /* ping-pong activations / cotangents, z, ct_z, right-hand sides      */
+  uint64_t bytes_patches;          /* the patch buffer (shared by both paths)                            */
+  uint64_t bytes_bp_activations;   /* backprop: stored layer outputs                                     */
+  uint64_t bytes_bp_scratch;       /* backprop: cotangent ping-pong (when planned without Moonwalk)      */
+  uint64_t bytes_live, bytes_peak;
+  uint64_t sign_mismatches;        /* Phase-III signs that differed from the stored masks (must be 0)    */
+} mw_conv_memstats_t;
+
+/* Same contracts as the dense entry points of the same names (setup synchronises; grad calls only
+   enqueue; gradients are overwritten, bit-identical run to run). x: [B][H][W][C_0]; target: shape of
+   the last layer's output. */
+int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, int32_t n_layers,
+                        const mw_conv_config_t* cfg, void* hip_stream);
+int moonwalk_conv_refresh(mw_conv_handle_t* h, void* hip_stream);
+int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                       void* hip_stream);
+int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                       void* hip_stream);
+int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
+int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out);
+/* what: MW_FETCH_MASK, MW_FETCH_H0, MW_FETCH_P (here: T^{-1}, float[C_out^2]) or MW_FETCH_CHECKPOINT. */
+int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap, size_t* n_bytes);
+void moonwalk_conv_destroy(mw_conv_handle_t* h);
+
+/* Patch gather and its transpose (kernel-level, for the unit tests). Row r = (b H' + i') W' + j' of the
+   patch matrix, column (u k + v) C + c. im2col writes rows [row0, row0 + n_rows) to patches
+   ([n_rows][k k C]); col2im sums the rows of the images [img0, img0 + n_img) held in dpatches
+   ([n_img H' W'][k k C]) into h[img0 ..] ([.][H][W][C]), in a fixed order. */
+int mw_conv_im2col(const float* x, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, int64_t row0,
+                   int64_t n_rows, float* patches, void* hip_stream);
+int mw_conv_col2im(const float* dpatches, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad,
+                   int64_t img0, int64_t n_img, float* h, void* hip_stream);
+
 /* Measurement aid: run the gradient drivers with only ONE class of kernel launches enabled, so
    that a caller can time that class alone between two events on its stream (the launches then run
    back to back over the handle's real buffers, layer after layer, with the real shapes and cold

@@ -21,6 +21,9 @@ EXPORTED_SYMBOLS = [
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
     "mw_vijp_epilogue", "mw_colsum", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
     "mw_probe_operand_stream",
+    "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
+    "moonwalk_conv_grad_layout", "moonwalk_conv_memory_stats", "moonwalk_conv_fetch", "moonwalk_conv_destroy",
+    "mw_conv_im2col", "mw_conv_col2im",
 ]
 
 
@@ -48,6 +51,23 @@ class _Config(C.Structure):
                 ("plan", C.c_int32), ("fuse", C.c_int32), ("frag_capacity_factor", C.c_double),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p),
                 ("segment_length", C.c_int32), ("reserved", C.c_int32)]
+
+
+class _ConvLayer(C.Structure):
+    _fields_ = [("channels_in", C.c_int32), ("channels_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
+                ("pad", C.c_int32), ("w", C.c_void_p), ("b", C.c_void_p), ("alpha", C.c_float)]
+
+
+class _ConvConfig(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("height", C.c_int32), ("width", C.c_int32), ("reseed_interval", C.c_int32),
+                ("loss_scale", C.c_float), ("plan", C.c_int32), ("patch_bytes", C.c_size_t),
+                ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p)]
+
+
+class _ConvMemStats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "bytes_masks", "bytes_tap_inverses", "bytes_checkpoints", "bytes_input_cotangent", "bytes_scratch",
+        "bytes_patches", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak", "sign_mismatches")]
 
 
 class _MemStats(C.Structure):
@@ -102,6 +122,17 @@ def load_library() -> C.CDLL:
     lib.mw_loss_scratch_doubles.restype = sz
     lib.mw_copy_f32.argtypes = [vp, vp, i64, vp]
     lib.mw_probe_operand_stream.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, vp]
+    lib.moonwalk_conv_setup.argtypes = [C.POINTER(vp), C.POINTER(_ConvLayer), i32, C.POINTER(_ConvConfig), vp]
+    lib.moonwalk_conv_refresh.argtypes = [vp, vp]
+    lib.moonwalk_conv_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.backprop_conv_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.moonwalk_conv_grad_layout.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+    lib.moonwalk_conv_memory_stats.argtypes = [vp, C.POINTER(_ConvMemStats)]
+    lib.moonwalk_conv_fetch.argtypes = [vp, i32, i32, vp, sz, C.POINTER(sz)]
+    lib.moonwalk_conv_destroy.argtypes = [vp]
+    lib.moonwalk_conv_destroy.restype = None
+    lib.mw_conv_im2col.argtypes = [vp, i32, i32, i32, i32, i32, i32, i64, i64, vp, vp]
+    lib.mw_conv_col2im.argtypes = [vp, i32, i32, i32, i32, i32, i32, i64, i64, vp, vp]
     _lib = lib
     return lib
 
@@ -337,6 +368,162 @@ class MoonwalkNet:
             self.close()
         except Exception:
             pass
+
+
+class ConvMoonwalkNet:
+    """A chain of submersive 2-D convolutional layers (channels-last) behind moonwalk_conv_*.
+
+    ws: kernels [k][k][C_in][C_out]; bs: biases or None; one stride and padding for all layers."""
+
+    def __init__(self, ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
+                 batch: int, height: int, width: int, stride: int, pad: int, reseed_interval: int = 0,
+                 loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0):
+        _require_gpu()
+        self._lib = load_library()
+        self._handle = C.c_void_p()
+        self.ws = [_f32(w) for w in ws]
+        self.bs = list(bs)
+        self.alphas = [float(a) for a in alphas]
+        self.batch, self.height, self.width = int(batch), int(height), int(width)
+        self.stride, self.pad = int(stride), int(pad)
+        self.device = self.ws[0].device
+        self.x = None
+        self.t = None
+        self._held = {}
+        self.alloc_peak = 0
+        self._alloc_live = 0
+
+        def _alloc(nbytes, _ctx):
+            try:
+                buf = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+            except Exception:
+                return None
+            self._held[buf.data_ptr()] = buf
+            self._alloc_live += int(nbytes)
+            self.alloc_peak = max(self.alloc_peak, self._alloc_live)
+            return buf.data_ptr()
+
+        def _free(ptr, _ctx):
+            buf = self._held.pop(ptr, None)
+            if buf is not None:
+                self._alloc_live -= buf.numel()
+
+        self._alloc_cb, self._free_cb = _ALLOC_FN(_alloc), _FREE_FN(_free)
+        n = len(self.ws)
+        layers = (_ConvLayer * n)()
+        for i, (w, b, a) in enumerate(zip(self.ws, self.bs, self.alphas)):
+            if w.dim() != 4 or w.shape[0] != w.shape[1]:
+                raise ValueError("kernels must be [k][k][C_in][C_out]")
+            layers[i] = _ConvLayer(w.shape[2], w.shape[3], w.shape[0], self.stride, self.pad, _ptr(w),
+                                   _ptr(_f32(b)) if b is not None else None, a)
+        cfg = _ConvConfig(self.batch, self.height, self.width, int(reseed_interval), float(loss_scale), int(plan),
+                          int(patch_bytes), self._alloc_cb, self._free_cb, None)
+        with torch.cuda.device(self.device):
+            _check(self._lib.moonwalk_conv_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
+        total = C.c_size_t()
+        dW_off, db_off = (C.c_size_t * n)(), (C.c_size_t * n)()
+        _check(self._lib.moonwalk_conv_grad_layout(self._handle, C.byref(total), dW_off, db_off))
+        self.total_floats = int(total.value)
+        self.dW_off, self.db_off = list(dW_off), list(db_off)
+
+    @classmethod
+    def from_workload(cls, wl, device="cuda:0", **kw) -> "ConvMoonwalkNet":
+        dev = torch.device(device)
+
+        def put(a):
+            if isinstance(a, torch.Tensor):
+                return a.to(device=dev, dtype=torch.float32).contiguous()
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+
+        net = cls([put(w) for w in wl.w], [put(b) for b in wl.b], wl.alphas, wl.batch, wl.side, wl.side, wl.s, wl.p, **kw)
+        net.x = put(wl.x)
+        net.t = put(wl.t)
+        return net
+
+    def new_grads(self) -> torch.Tensor:
+        return torch.empty(self.total_floats, dtype=torch.float32, device=self.device)
+
+    def _grad(self, fn, x, target, grads_out, loss_out) -> GradResult:
+        flat = grads_out if grads_out is not None else self.new_grads()
+        loss = loss_out if loss_out is not None else torch.empty(1, dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(fn(self._handle, _ptr(_f32(x)), _ptr(_f32(target)), _ptr(_f32(flat)), _ptr(loss), _stream()))
+        dW, db = [], []
+        for i, w in enumerate(self.ws):
+            dW.append(flat[self.dW_off[i]: self.dW_off[i] + w.numel()].view(w.shape))
+            db.append(flat[self.db_off[i]: self.db_off[i] + w.shape[3]])
+        return GradResult(flat, dW, db, loss)
+
+    def moonwalk_grad(self, x, target, grads_out=None, loss_out=None) -> GradResult:
+        return self._grad(self._lib.moonwalk_conv_grad, x, target, grads_out, loss_out)
+
+    def backprop_grad(self, x, target, grads_out=None, loss_out=None) -> GradResult:
+        return self._grad(self._lib.backprop_conv_grad, x, target, grads_out, loss_out)
+
+    def refresh(self):
+        with torch.cuda.device(self.device):
+            _check(self._lib.moonwalk_conv_refresh(self._handle, _stream()))
+
+    def memory_stats(self, check: bool = True) -> dict:
+        st = _ConvMemStats()
+        code = self._lib.moonwalk_conv_memory_stats(self._handle, C.byref(st))
+        out = {name: int(getattr(st, name)) for name, _ in _ConvMemStats._fields_}
+        out["status"] = code
+        if check:
+            _check(code)
+        return out
+
+    def _fetch(self, layer: int, what: int, dtype) -> np.ndarray:
+        n = C.c_size_t()
+        _check(self._lib.moonwalk_conv_fetch(self._handle, layer, what, None, 0, C.byref(n)))
+        out = np.empty(n.value // np.dtype(dtype).itemsize, dtype=dtype)
+        if n.value:
+            _check(self._lib.moonwalk_conv_fetch(self._handle, layer, what, out.ctypes.data_as(C.c_void_p), out.nbytes,
+                                                 C.byref(n)))
+        return out
+
+    def fetch_mask(self, layer: int) -> np.ndarray:
+        return self._fetch(layer, FETCH_MASK, np.uint64)
+
+    def fetch_h0(self) -> np.ndarray:
+        return self._fetch(0, FETCH_H0, np.float32)
+
+    def fetch_tap_inverse(self, layer: int) -> np.ndarray:
+        c = self.ws[layer].shape[3]
+        return self._fetch(layer, FETCH_P, np.float32).reshape(c, c)
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle.value:
+            self._lib.moonwalk_conv_destroy(self._handle)
+        self._handle = None
+        self._held.clear()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def conv_im2col(x: torch.Tensor, k: int, stride: int, pad: int, row0: int = 0, n_rows: Optional[int] = None) -> torch.Tensor:
+    """Patch matrix rows [row0, row0 + n_rows) of the channels-last tensor x [B][H][W][C]."""
+    _require_gpu()
+    B, H, W, Cc = x.shape
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    if n_rows is None:
+        n_rows = B * Ho * Wo - row0
+    out = torch.empty(n_rows, k * k * Cc, dtype=torch.float32, device=x.device)
+    _check(load_library().mw_conv_im2col(_ptr(_f32(x)), H, W, Cc, k, stride, pad, row0, n_rows, _ptr(out), _stream()))
+    return out
+
+
+def conv_col2im(dpatches: torch.Tensor, shape, k: int, stride: int, pad: int) -> torch.Tensor:
+    """Transpose of conv_im2col for all images of a tensor of the given [B][H][W][C] shape."""
+    _require_gpu()
+    B, H, W, Cc = shape
+    out = torch.empty(B, H, W, Cc, dtype=torch.float32, device=dpatches.device)
+    _check(load_library().mw_conv_col2im(_ptr(_f32(dpatches)), H, W, Cc, k, stride, pad, 0, B, _ptr(out), _stream()))
+    return out
 
 
 # ---------------------------------------------------------------------- kernel-level entries

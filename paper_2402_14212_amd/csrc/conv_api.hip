@@ -1,0 +1,471 @@
+// Moonwalk on submersive 2-D convolutional layers (lemma on submersive convolutional layers; the
+// paper's fully parallel 2-D setting): handle, buffer plan and the gradient drivers behind the C ABI.
+//
+// A convolution is run as the library's fp32 MFMA GEMMs on patch matrices: the images are taken in
+// chunks, each chunk's patches are gathered into one bounded buffer (im2col) and multiplied;
+// cotangents go back through the transposed gather (col2im, a fixed-order sum). The vijp of the
+// convolution, in the fully parallel case k <= p + s, is a triangular solve over channels at every
+// output position, done as one GEMM with the inverse of the channel-triangular tap.
+#include "../../include/moonwalk.h"
+
+#include <cmath>
+#include <utility>
+#include <vector>
+
+#include "mw_internal.h"
+
+using namespace mw;
+
+namespace {
+
+#define CV_HIP(expr)                                              \
+  do {                                                            \
+    hipError_t e__ = (expr);                                      \
+    if (e__ != hipSuccess) return record_hip_failure(e__, #expr); \
+  } while (0)
+
+void* cv_default_alloc(size_t bytes, void*) {
+  void* p = nullptr;
+  if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+  return p;
+}
+void cv_default_free(void* p, void*) { (void)hipFree(p); }
+
+struct ConvLayer {
+  int Cin = 0, Cout = 0, k = 0, s = 0, p = 0;
+  int Hin = 0, Win = 0, Ho = 0, Wo = 0;
+  int K = 0;            // k k Cin: columns of the patch matrix
+  int64_t rows = 0;     // B Ho Wo: rows of the patch matrix
+  int64_t n_in = 0, n_out = 0;  // elements of the input / output activation
+  const float* w = nullptr;     // [k][k][Cin][Cout] = [K][Cout]
+  const float* b = nullptr;
+  float alpha = 0.f;
+  float* Tinv = nullptr;        // inverse of the tap at (p, p), [Cout][Cout]
+  uint64_t* mask = nullptr;
+  size_t mask_words = 0;
+  float* ckpt = nullptr;        // kept cotangent at this layer's output
+  float* act = nullptr;         // backprop: stored output activation
+  size_t dW_off = 0, db_off = 0;
+  int chunk_images = 1;         // images per patch-buffer fill
+};
+
+}  // namespace
+
+struct mw_conv_handle {
+  std::vector<ConvLayer> layers;
+  int B = 0, L = 0, Kre = 0, plan = 0;
+  float loss_scale = 1.f;
+  void* (*dev_alloc)(size_t, void*) = nullptr;
+  void (*dev_free)(void*, void*) = nullptr;
+  void* alloc_ctx = nullptr;
+  std::vector<std::pair<void*, size_t>> allocs;
+  uint64_t live = 0, peak = 0;
+  mw_conv_memstats_t st{};
+  size_t total_floats = 0;
+  float *patches = nullptr, *zbuf = nullptr, *ctz = nullptr, *hsub = nullptr;
+  float *xa = nullptr, *xb = nullptr, *ha = nullptr, *hb = nullptr, *h0 = nullptr;
+  uint32_t* status = nullptr;  // [0..1] sign mismatches (u64), [2] kernel not triangular / zero diagonal
+  double* loss_scratch = nullptr;
+
+  void* alloc(size_t bytes, uint64_t* item) {
+    if (bytes == 0) bytes = 4;
+    void* p = dev_alloc(bytes, alloc_ctx);
+    if (!p) return nullptr;
+    allocs.emplace_back(p, bytes);
+    live += bytes;
+    if (live > peak) peak = live;
+    if (item) *item += bytes;
+    return p;
+  }
+  void release_all() {
+    for (auto& a : allocs) dev_free(a.first, alloc_ctx);
+    allocs.clear();
+    live = 0;
+  }
+};
+
+namespace {
+
+template <class T>
+bool cv_alloc(mw_conv_handle* h, T** out, size_t count, uint64_t* item) {
+  *out = static_cast<T*>(h->alloc(count * sizeof(T), item));
+  return *out != nullptr;
+}
+
+int build_tap_inverses(mw_conv_handle* h, hipStream_t s) {
+  int32_t* flag = reinterpret_cast<int32_t*>(h->status + 2);
+  CV_HIP(ew_fill_u32(h->status + 2, 0u, 1, s));
+  for (auto& l : h->layers) {
+    const float* tap = l.w + ((size_t)(l.p * l.k + l.p) * l.Cin) * l.Cout;  // w[p][p][.][.], [Cin][Cout]
+    CV_HIP(cv_tri_inverse(tap, l.Cout, l.Cout, l.Tinv, flag, s));
+  }
+  int32_t bad = 0;
+  CV_HIP(hipStreamSynchronize(s));
+  CV_HIP(hipMemcpy(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost));
+  return bad ? MW_ERR_NOT_SUBMERSIVE : MW_OK;
+}
+
+// z (rows [r0, r0 + R) of the layer's output, bias added) = patches(x) w, through the patch buffer
+int conv_rows(mw_conv_handle* h, const ConvLayer& l, const float* xin, int64_t r0, int64_t R, float* zout, hipStream_t s) {
+  CV_HIP(cv_im2col(xin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, r0, R, h->patches, s));
+  CV_HIP(gemm_plain(OP_NN, TILE_AUTO, (int)R, l.Cout, l.K, 1.f, h->patches, l.K, l.w, l.Cout, 0.f, zout + r0 * l.Cout, l.Cout,
+                    l.b, s));
+  return MW_OK;
+}
+
+// input cotangent of the layer from ct_z (whole layer), image chunk by image chunk
+int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, float* hout, hipStream_t s) {
+  const int64_t per_img = (int64_t)l.Ho * l.Wo;
+  for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+    const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+    const int64_t r0 = img0 * per_img, R = n_img * per_img;
+    // patch cotangents = ct_z w^T: (R x Cout) (K x Cout)^T
+    CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.K, l.Cout, 1.f, ctz + r0 * l.Cout, l.Cout, l.w, l.Cout, 0.f, h->patches, l.K,
+                      nullptr, s));
+    CV_HIP(cv_col2im(h->patches, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, img0, n_img, hout, s));
+  }
+  return MW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, int32_t n_layers,
+                        const mw_conv_config_t* cfg, void* hip_stream) {
+  if (!out) return MW_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!layers || n_layers <= 0 || !cfg || cfg->batch <= 0 || cfg->height <= 0 || cfg->width <= 0) return MW_ERR_INVALID_ARG;
+  if (cfg->reseed_interval < 0 || !(cfg->loss_scale > 0.f) || !std::isfinite(cfg->loss_scale)) return MW_ERR_INVALID_ARG;
+  if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
+  if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
+  int Hc = cfg->height, Wc = cfg->width;
+  const int64_t limit = (int64_t)0x7FFFFFFF;
+  for (int i = 0; i < n_layers; ++i) {
+    const mw_conv_layer_t& l = layers[i];
+    if (l.channels_in <= 0 || l.channels_out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0 || !l.w) return MW_ERR_INVALID_ARG;
+    if (!(l.alpha > 0.f && l.alpha <= 1.f)) return MW_ERR_INVALID_ARG;
+    if (i > 0 && l.channels_in != layers[i - 1].channels_out) return MW_ERR_INVALID_ARG;
+    if (Hc + 2 * l.pad < l.k || Wc + 2 * l.pad < l.k) return MW_ERR_INVALID_ARG;
+    const int Ho = (Hc + 2 * l.pad - l.k) / l.stride + 1, Wo = (Wc + 2 * l.pad - l.k) / l.stride + 1;
+    // conditions (i) of the lemma, and m' <= m
+    if (!(l.k > l.pad && l.stride > l.pad && Hc > l.stride * (Ho - 1) && Wc > l.stride * (Wo - 1))) return MW_ERR_NOT_SUBMERSIVE;
+    if (l.channels_out > l.channels_in) return MW_ERR_NOT_SUBMERSIVE;
+    // only the fully parallel vijp is built: no earlier position may enter an equation
+    if (l.k > l.pad + l.stride) return MW_ERR_INVALID_ARG;
+    if ((int64_t)l.k * l.k * l.channels_in * l.channels_out * 4 >= limit) return MW_ERR_INVALID_ARG;
+    if ((int64_t)Ho * Wo * l.channels_out >= limit) return MW_ERR_INVALID_ARG;
+    Hc = Ho;
+    Wc = Wo;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  mw_conv_handle* h = new mw_conv_handle();
+  h->B = cfg->batch;
+  h->L = n_layers;
+  h->Kre = cfg->reseed_interval;
+  h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
+  h->loss_scale = cfg->loss_scale;
+  h->dev_alloc = cfg->dev_alloc ? cfg->dev_alloc : cv_default_alloc;
+  h->dev_free = cfg->dev_free ? cfg->dev_free : cv_default_free;
+  h->alloc_ctx = cfg->alloc_ctx;
+  h->layers.resize(n_layers);
+  const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
+  size_t off = 0, max_out = 0, max_patch = 0;
+  Hc = cfg->height;
+  Wc = cfg->width;
+  for (int i = 0; i < n_layers; ++i) {
+    ConvLayer& l = h->layers[i];
+    l.Cin = layers[i].channels_in;
+    l.Cout = layers[i].channels_out;
+    l.k = layers[i].k;
+    l.s = layers[i].stride;
+    l.p = layers[i].pad;
+    l.w = layers[i].w;
+    l.b = layers[i].b;
+    l.alpha = layers[i].alpha;
+    l.Hin = Hc;
+    l.Win = Wc;
+    l.Ho = (Hc + 2 * l.p - l.k) / l.s + 1;
+    l.Wo = (Wc + 2 * l.p - l.k) / l.s + 1;
+    l.K = l.k * l.k * l.Cin;
+    l.rows = (int64_t)h->B * l.Ho * l.Wo;
+    l.n_in = (int64_t)h->B * l.Hin * l.Win * l.Cin;
+    l.n_out = l.rows * l.Cout;
+    l.dW_off = off;
+    off += (size_t)l.K * l.Cout;
+    l.db_off = off;
+    off += (size_t)l.Cout;
+    const size_t per_img = (size_t)l.Ho * l.Wo * l.K;
+    size_t ci = patch_cap_floats / per_img;
+    // one fill must stay below the 2 GiB operand limit of the GEMMs whatever the caller asked for
+    while (ci > 1 && ci * per_img * 4 >= (size_t)limit) --ci;
+    if (ci < 1) ci = 1;
+    if (ci > (size_t)h->B) ci = (size_t)h->B;
+    if (per_img * 4 >= (size_t)limit) {
+      delete h;
+      return MW_ERR_INVALID_ARG;  // a single image's patches do not fit a GEMM operand
+    }
+    l.chunk_images = (int)ci;
+    if (ci * per_img > max_patch) max_patch = ci * per_img;
+    if ((size_t)l.n_out > max_out) max_out = (size_t)l.n_out;
+    Hc = l.Ho;
+    Wc = l.Wo;
+  }
+  h->total_floats = off;
+
+  auto fail = [&](int code) {
+    h->release_all();
+    delete h;
+    return code;
+  };
+  mw_conv_memstats_t& st = h->st;
+  bool ok = cv_alloc(h, &h->status, 4, &st.bytes_scratch);
+  ok = ok && cv_alloc(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_scratch);
+  ok = ok && cv_alloc(h, &h->patches, max_patch, &st.bytes_patches);
+  if (!ok) return fail(MW_ERR_OOM);
+  hipError_t e = ew_fill_u32(h->status, 0u, 4, stream);
+  if (e != hipSuccess) return fail(record_hip_failure(e, "status init"));
+  const size_t B = (size_t)h->B;
+  if (h->plan & MW_PLAN_MOONWALK) {
+    for (auto& l : h->layers) {
+      ok = ok && cv_alloc(h, &l.Tinv, (size_t)l.Cout * l.Cout, &st.bytes_tap_inverses);
+      l.mask_words = ((size_t)l.n_out + 63) / 64;
+      ok = ok && cv_alloc(h, &l.mask, l.mask_words, &st.bytes_masks);
+      if (ok) {
+        e = ew_fill_u32(reinterpret_cast<uint32_t*>(l.mask), 0u, (int64_t)l.mask_words * 2, stream);
+        if (e != hipSuccess) return fail(record_hip_failure(e, "mask init"));
+      }
+    }
+    if (!ok) return fail(MW_ERR_OOM);
+    int rc = build_tap_inverses(h, stream);
+    if (rc != MW_OK) return fail(rc);
+    if (h->Kre > 0)
+      for (int j = 1; j < n_layers; ++j)
+        if (j % h->Kre == 0) ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j - 1].n_out, &st.bytes_checkpoints);
+    ok = ok && cv_alloc(h, &h->xa, max_out, &st.bytes_scratch) && cv_alloc(h, &h->xb, max_out, &st.bytes_scratch) &&
+         cv_alloc(h, &h->ha, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hb, max_out, &st.bytes_scratch) &&
+         cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
+         cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch) &&
+         cv_alloc(h, &h->h0, (size_t)h->layers[0].n_in, &st.bytes_input_cotangent);
+    if (!ok) return fail(MW_ERR_OOM);
+  }
+  if (h->plan & MW_PLAN_BACKPROP) {
+    for (auto& l : h->layers) ok = ok && cv_alloc(h, &l.act, (size_t)l.n_out, &st.bytes_bp_activations);
+    if (!(h->plan & MW_PLAN_MOONWALK))
+      ok = ok && cv_alloc(h, &h->ha, max_out, &st.bytes_bp_scratch) && cv_alloc(h, &h->hb, max_out, &st.bytes_bp_scratch) &&
+           cv_alloc(h, &h->ctz, max_out, &st.bytes_bp_scratch);
+    if (!ok) return fail(MW_ERR_OOM);
+  }
+  (void)B;
+  e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) return fail(record_hip_failure(e, "setup sync"));
+  *out = h;
+  return MW_OK;
+}
+
+int moonwalk_conv_refresh(mw_conv_handle_t* h, void* hip_stream) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  return build_tap_inverses(h, static_cast<hipStream_t>(hip_stream));
+}
+
+int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                       void* hip_stream) {
+  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int L = h->L;
+  unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
+  CV_HIP(ew_fill_u32(h->status, 0u, 2, s));
+
+  // ---------------- Phase I: forward, keep the sign masks only
+  const float* xin = x;
+  float* xbuf[2] = {h->xa, h->xb};
+  for (int i = 0; i < L; ++i) {
+    ConvLayer& l = h->layers[i];
+    float* xout = xbuf[i & 1];
+    const int64_t per_img = (int64_t)l.Ho * l.Wo;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+      int rc = conv_rows(h, l, xin, img0 * per_img, n_img * per_img, xout, s);
+      if (rc != MW_OK) return rc;
+    }
+    CV_HIP(ew_bias_act_mask(xout, nullptr, l.rows, l.Cout, l.alpha, xout, l.mask, s));  // in place: z -> x, signs packed
+    xin = xout;
+  }
+  // ---------------- loss and output cotangent
+  {
+    const ConvLayer& last = h->layers[L - 1];
+    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+  }
+  // ---------------- Phase II: reverse, input cotangent only
+  float* hbuf[2] = {h->ha, h->hb};
+  const float* hcur = h->ha;
+  for (int i = L - 1; i >= 0; --i) {
+    ConvLayer& l = h->layers[i];
+    CV_HIP(ew_rev_scale(hcur, l.mask, l.n_out, l.alpha, h->ctz, s));
+    float* hout;
+    if (i == 0) hout = h->h0;
+    else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
+    else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+    int rc = conv_input_grad(h, l, h->ctz, hout, s);
+    if (rc != MW_OK) return rc;
+    hcur = hout;
+  }
+  // ---------------- Phase III: forward vijp sweep
+  const float inv_scale = 1.0f / h->loss_scale;
+  xin = x;
+  const float* hin = h->h0;
+  for (int i = 0; i < L; ++i) {
+    ConvLayer& l = h->layers[i];
+    if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+    float* xout = xbuf[i & 1];
+    float* hout = hbuf[i & 1];
+    // vijp of the convolution: right-hand sides at the strided positions, then the channel solve as a product
+    CV_HIP(cv_strided_gather(hin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.Cout, l.s, l.rows, h->hsub, s));
+    const int64_t per_img = (int64_t)l.Ho * l.Wo;
+    bool first = true;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+      const int64_t r0 = img0 * per_img, R = n_img * per_img;
+      CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, h->hsub + r0 * l.Cout, l.Cout, l.Tinv, l.Cout, 0.f,
+                        h->ctz + r0 * l.Cout, l.Cout, nullptr, s));
+      int rc = conv_rows(h, l, xin, r0, R, h->zbuf, s);  // recompute z; the patches stay in the buffer
+      if (rc != MW_OK) return rc;
+      // dW[K][Cout] (+)= patches^T ct_z over the rows of this chunk
+      CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, inv_scale, h->patches, l.K, h->ctz + r0 * l.Cout, l.Cout,
+                        first ? 0.f : 1.f, grads_out + l.dW_off, l.Cout, nullptr, s));
+      first = false;
+    }
+    CV_HIP(ew_colsum(h->ctz, l.rows, l.Cout, inv_scale, grads_out + l.db_off, s));
+    CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
+                            mismatches, s));
+    xin = xout;
+    hin = hout;
+  }
+  return MW_OK;
+}
+
+int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
+                       void* hip_stream) {
+  if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_BACKPROP)) return MW_ERR_NOT_PLANNED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int L = h->L;
+  // forward, every activation stored (the sign is read back from it: x > 0 <=> z > 0)
+  const float* xin = x;
+  for (int i = 0; i < L; ++i) {
+    ConvLayer& l = h->layers[i];
+    const int64_t per_img = (int64_t)l.Ho * l.Wo;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+      int rc = conv_rows(h, l, xin, img0 * per_img, n_img * per_img, l.act, s);
+      if (rc != MW_OK) return rc;
+    }
+    CV_HIP(ew_bias_act_mask(l.act, nullptr, l.rows, l.Cout, l.alpha, l.act, nullptr, s));
+    xin = l.act;
+  }
+  {
+    const ConvLayer& last = h->layers[L - 1];
+    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+  }
+  const float inv_scale = 1.0f / h->loss_scale;
+  float* hbuf[2] = {h->ha, h->hb};
+  const float* hcur = h->ha;
+  for (int i = L - 1; i >= 0; --i) {
+    ConvLayer& l = h->layers[i];
+    const float* xprev = (i == 0) ? x : h->layers[i - 1].act;
+    CV_HIP(ew_scale_by_act_slope(hcur, l.act, l.n_out, l.alpha, h->ctz, s));
+    const int64_t per_img = (int64_t)l.Ho * l.Wo;
+    bool first = true;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+      const int64_t r0 = img0 * per_img, R = n_img * per_img;
+      CV_HIP(cv_im2col(xprev, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, r0, R, h->patches, s));
+      CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, inv_scale, h->patches, l.K, h->ctz + r0 * l.Cout, l.Cout,
+                        first ? 0.f : 1.f, grads_out + l.dW_off, l.Cout, nullptr, s));
+      first = false;
+    }
+    CV_HIP(ew_colsum(h->ctz, l.rows, l.Cout, inv_scale, grads_out + l.db_off, s));
+    if (i > 0) {
+      float* hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+      int rc = conv_input_grad(h, l, h->ctz, hout, s);
+      if (rc != MW_OK) return rc;
+      hcur = hout;
+    }
+  }
+  return MW_OK;
+}
+
+int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (total_floats) *total_floats = h->total_floats;
+  for (int i = 0; i < h->L; ++i) {
+    if (dW_off) dW_off[i] = h->layers[i].dW_off;
+    if (db_off) db_off[i] = h->layers[i].db_off;
+  }
+  return MW_OK;
+}
+
+int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out) {
+  if (!h || !out) return MW_ERR_INVALID_ARG;
+  CV_HIP(hipDeviceSynchronize());
+  *out = h->st;
+  out->bytes_live = h->live;
+  out->bytes_peak = h->peak;
+  unsigned long long mm = 0;
+  CV_HIP(hipMemcpy(&mm, h->status, sizeof(mm), hipMemcpyDeviceToHost));
+  out->sign_mismatches = mm;
+  return mm ? MW_ERR_SIGN_MISMATCH : MW_OK;
+}
+
+int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap, size_t* n_bytes) {
+  if (!h) return MW_ERR_INVALID_ARG;
+  if (what != MW_FETCH_H0 && (layer < 0 || layer >= h->L)) return MW_ERR_INVALID_ARG;
+  CV_HIP(hipDeviceSynchronize());
+  const void* src = nullptr;
+  size_t bytes = 0;
+  switch (what) {
+    case MW_FETCH_MASK: src = h->layers[layer].mask; bytes = h->layers[layer].mask_words * 8; break;
+    case MW_FETCH_H0: src = h->h0; bytes = (size_t)h->layers[0].n_in * 4; break;
+    case MW_FETCH_P: src = h->layers[layer].Tinv; bytes = (size_t)h->layers[layer].Cout * h->layers[layer].Cout * 4; break;
+    case MW_FETCH_CHECKPOINT: src = h->layers[layer].ckpt; bytes = (size_t)h->layers[layer].n_out * 4; break;
+    default: return MW_ERR_INVALID_ARG;
+  }
+  if (!src) return MW_ERR_INVALID_ARG;
+  if (n_bytes) *n_bytes = bytes;
+  if (!host_dst && cap == 0) return MW_OK;
+  if (!host_dst || cap < bytes) return MW_ERR_INVALID_ARG;
+  if (bytes) CV_HIP(hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost));
+  return MW_OK;
+}
+
+void moonwalk_conv_destroy(mw_conv_handle_t* h) {
+  if (!h) return;
+  (void)hipDeviceSynchronize();
+  h->release_all();
+  delete h;
+}
+
+// ---- kernel-level entries (unit parity tests)
+int mw_conv_im2col(const float* x, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, int64_t row0,
+                   int64_t n_rows, float* patches, void* hip_stream) {
+  if (!x || !patches || H <= 0 || W <= 0 || C <= 0 || k <= 0 || stride <= 0 || pad < 0 || row0 < 0 || n_rows < 0)
+    return MW_ERR_INVALID_ARG;
+  if (H + 2 * pad < k || W + 2 * pad < k) return MW_ERR_INVALID_ARG;
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+  CV_HIP(cv_im2col(x, H, W, C, Ho, Wo, k, stride, pad, row0, n_rows, patches, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_conv_col2im(const float* dpatches, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad,
+                   int64_t img0, int64_t n_img, float* h, void* hip_stream) {
+  if (!dpatches || !h || H <= 0 || W <= 0 || C <= 0 || k <= 0 || stride <= 0 || pad < 0 || img0 < 0 || n_img < 0)
+    return MW_ERR_INVALID_ARG;
+  if (H + 2 * pad < k || W + 2 * pad < k) return MW_ERR_INVALID_ARG;
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+  CV_HIP(cv_col2im(dpatches, H, W, C, Ho, Wo, k, stride, pad, img0, n_img, h, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,182 @@
+// Gather kernels that turn a channels-last convolution into the library's GEMMs, and the small
+// triangular inverse behind the convolution's vijp (lemma on submersive convolutional layers).
+//
+// Activations are [B][H][W][C] fp32, kernels [k][k][C][C'] (tap-major, then input channel, then
+// output channel), one stride s and padding p for both spatial dimensions. Row r of a patch
+// matrix is output position (b, i', j'), r = (b * H' + i') * W' + j'; column q = (u * k + v) * C + c.
+#include "mw_internal.h"
+
+namespace mw {
+namespace {
+
+constexpr int CV_THREADS = 256;
+
+// patches[r][q] = x[b, s i' + u - p, s j' + v - p, c]  (0 outside the image), rows [row0, row0 + n_rows)
+// of the layer's patch matrix. One thread per 4 consecutive channels when C % 4 == 0 (VEC), else per element.
+template <bool VEC>
+__global__ void __launch_bounds__(CV_THREADS)
+k_im2col(const float* __restrict__ x, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t row0,
+         int64_t n_rows, float* __restrict__ patches) {
+  const int K = k * k * C;
+  const int per_row = VEC ? K / 4 : K;
+  const int64_t total = n_rows * per_row;
+  for (int64_t t = (int64_t)blockIdx.x * CV_THREADS + threadIdx.x; t < total; t += (int64_t)gridDim.x * CV_THREADS) {
+    const int64_t rl = t / per_row;
+    const int q = (int)(t - rl * per_row) * (VEC ? 4 : 1);
+    const int64_t r = row0 + rl;
+    const int j = (int)(r % Wo);
+    const int64_t bi = r / Wo;
+    const int i = (int)(bi % Ho);
+    const int64_t b = bi / Ho;
+    const int tap = q / C, c = q - tap * C;
+    const int u = tap / k, v = tap - u * k;
+    const int y = s * i + u - p, xx = s * j + v - p;
+    const bool in = y >= 0 && y < H && xx >= 0 && xx < W;
+    const int64_t src = ((b * H + y) * (int64_t)W + xx) * C + c;
+    if (VEC) {
+      float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (in) val = *reinterpret_cast<const float4*>(x + src);
+      *reinterpret_cast<float4*>(patches + rl * K + q) = val;
+    } else {
+      patches[rl * K + q] = in ? x[src] : 0.f;
+    }
+  }
+}
+
+// Input cotangent from patch cotangents (the transpose of im2col, as a gather so that the sum
+// has a fixed order): h[b, y, x, c] = sum over the taps (u, v) and output positions (i', j') with
+// s i' + u - p = y, s j' + v - p = x of dpatches[(b, i', j')][(u, v, c)], taps in ascending order.
+// Covers the images [img0, img0 + n_img); dpatches holds exactly their rows.
+template <bool VEC>
+__global__ void __launch_bounds__(CV_THREADS)
+k_col2im(const float* __restrict__ dpatches, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t img0,
+         int64_t n_img, float* __restrict__ h) {
+  const int K = k * k * C;
+  const int per_px = VEC ? C / 4 : C;
+  const int64_t total = n_img * H * W * per_px;
+  for (int64_t t = (int64_t)blockIdx.x * CV_THREADS + threadIdx.x; t < total; t += (int64_t)gridDim.x * CV_THREADS) {
+    const int64_t px = t / per_px;
+    const int c = (int)(t - px * per_px) * (VEC ? 4 : 1);
+    const int xx = (int)(px % W);
+    const int64_t by = px / W;
+    const int y = (int)(by % H);
+    const int64_t bl = by / H;  // image within the chunk
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < k; ++u) {
+      const int yy = y + p - u;
+      if (yy < 0 || yy % s != 0) continue;
+      const int i = yy / s;
+      if (i >= Ho) continue;
+      for (int v = 0; v < k; ++v) {
+        const int xv = xx + p - v;
+        if (xv < 0 || xv % s != 0) continue;
+        const int j = xv / s;
+        if (j >= Wo) continue;
+        const int64_t r = (bl * Ho + i) * (int64_t)Wo + j;
+        const float* src = dpatches + r * K + (u * k + v) * C + c;
+        if (VEC) {
+          const float4 d = *reinterpret_cast<const float4*>(src);
+          acc.x += d.x; acc.y += d.y; acc.z += d.z; acc.w += d.w;
+        } else {
+          acc.x += src[0];
+        }
+      }
+    }
+    float* dst = h + ((img0 + bl) * H * (int64_t)W + (int64_t)y * W + xx) * C + c;
+    if (VEC) *reinterpret_cast<float4*>(dst) = acc;
+    else dst[0] = acc.x;
+  }
+}
+
+// out[r][c'] = h[b, s i', s j', c'] for c' < Co: the right-hand sides of the per-position channel solve.
+__global__ void __launch_bounds__(CV_THREADS)
+k_strided_gather(const float* __restrict__ h, int H, int W, int C, int Ho, int Wo, int Co, int s, int64_t n_rows,
+                 float* __restrict__ out) {
+  const int64_t total = n_rows * Co;
+  for (int64_t t = (int64_t)blockIdx.x * CV_THREADS + threadIdx.x; t < total; t += (int64_t)gridDim.x * CV_THREADS) {
+    const int64_t r = t / Co;
+    const int c = (int)(t - r * Co);
+    const int j = (int)(r % Wo);
+    const int64_t bi = r / Wo;
+    const int i = (int)(bi % Ho);
+    const int64_t b = bi / Ho;
+    out[t] = h[((b * H + (int64_t)s * i) * W + (int64_t)s * j) * C + c];
+  }
+}
+
+// Inverse of the lower-triangular tap T[c][c''] = w[p][p][c][c''] (c, c'' < n; row stride ld), one
+// thread per column by forward substitution. Raises *flag if an entry above the diagonal is not
+// zero or a diagonal entry is zero (conditions (ii), (iii) of the lemma).
+__global__ void __launch_bounds__(1024)
+k_tri_inverse(const float* __restrict__ T, int64_t ld, int n, float* __restrict__ Tinv, int32_t* __restrict__ flag) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  bool bad = (T[(int64_t)j * ld + j] == 0.f);
+  for (int c = 0; c < j; ++c) bad = bad || (T[(int64_t)c * ld + j] != 0.f);  // row c < column j must be 0
+  if (bad) {
+    *flag = 1;
+    for (int i = 0; i < n; ++i) Tinv[(int64_t)i * n + j] = (i == j) ? 1.f : 0.f;
+    return;
+  }
+  for (int i = 0; i < j; ++i) Tinv[(int64_t)i * n + j] = 0.f;
+  Tinv[(int64_t)j * n + j] = 1.f / T[(int64_t)j * ld + j];
+  for (int i = j + 1; i < n; ++i) {
+    float acc = 0.f;
+    for (int t = j; t < i; ++t) acc += T[(int64_t)i * ld + t] * Tinv[(int64_t)t * n + j];
+    Tinv[(int64_t)i * n + j] = -acc / T[(int64_t)i * ld + i];
+  }
+}
+
+inline int cv_blocks(int64_t work_items) {
+  int64_t b = (work_items + CV_THREADS - 1) / CV_THREADS;
+  if (b < 1) b = 1;
+  if (b > 256 * 16) b = 256 * 16;
+  return (int)b;
+}
+inline bool al16p(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+hipError_t cv_im2col(const float* x, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t row0,
+                     int64_t n_rows, float* patches, hipStream_t stream) {
+  if (n_rows <= 0) return hipSuccess;
+  const int K = k * k * C;
+  if (C % 4 == 0 && al16p(x) && al16p(patches)) {
+    hipLaunchKernelGGL(k_im2col<true>, dim3(cv_blocks(n_rows * (K / 4))), dim3(CV_THREADS), 0, stream, x, H, W, C, Ho, Wo, k,
+                       s, p, row0, n_rows, patches);
+  } else {
+    hipLaunchKernelGGL(k_im2col<false>, dim3(cv_blocks(n_rows * K)), dim3(CV_THREADS), 0, stream, x, H, W, C, Ho, Wo, k, s,
+                       p, row0, n_rows, patches);
+  }
+  return hipGetLastError();
+}
+
+hipError_t cv_col2im(const float* dpatches, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t img0,
+                     int64_t n_img, float* h, hipStream_t stream) {
+  if (n_img <= 0) return hipSuccess;
+  if (C % 4 == 0 && al16p(dpatches) && al16p(h)) {
+    hipLaunchKernelGGL(k_col2im<true>, dim3(cv_blocks(n_img * H * W * (C / 4))), dim3(CV_THREADS), 0, stream, dpatches, H, W,
+                       C, Ho, Wo, k, s, p, img0, n_img, h);
+  } else {
+    hipLaunchKernelGGL(k_col2im<false>, dim3(cv_blocks(n_img * H * W * C)), dim3(CV_THREADS), 0, stream, dpatches, H, W, C,
+                       Ho, Wo, k, s, p, img0, n_img, h);
+  }
+  return hipGetLastError();
+}
+
+hipError_t cv_strided_gather(const float* h, int H, int W, int C, int Ho, int Wo, int Co, int s, int64_t n_rows, float* out,
+                             hipStream_t stream) {
+  if (n_rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_strided_gather, dim3(cv_blocks(n_rows * Co)), dim3(CV_THREADS), 0, stream, h, H, W, C, Ho, Wo, Co, s,
+                     n_rows, out);
+  return hipGetLastError();
+}
+
+hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_t* flag, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int threads = n < 1024 ? ((n + 63) / 64) * 64 : 1024;
+  hipLaunchKernelGGL(k_tri_inverse, dim3((n + threads - 1) / threads), dim3(threads), 0, stream, T, ld, n, Tinv, flag);
+  return hipGetLastError();
+}
+
+}  // namespace mw

@@ -99,7 +99,7 @@ k_bias_act_mask_v4(const float* __restrict__ zin, const float* __restrict__ bias
       st4(x, e, n, o);
       const uint64_t word = group_word(b0, b1, b2, b3, lane);
       const int64_t wi = (g0 + u) * 4 + lane;
-      if (lane < 4 && wi < n_words) mask[wi] = word;
+      if (mask && lane < 4 && wi < n_words) mask[wi] = word;
     }
   }
 }
@@ -277,7 +277,7 @@ k_bias_act_mask(const float* __restrict__ zin, const float* __restrict__ bias, i
       bool bit = (e < n) && (z[j] > 0.f);
       if (e < n) x[e] = bit ? z[j] : alpha * z[j];
       unsigned long long bal = __ballot(bit);
-      if (lane == 0 && w0 + j < n_words) mask[w0 + j] = bal;
+      if (mask && lane == 0 && w0 + j < n_words) mask[w0 + j] = bal;
     }
     if (HAS_BIAS) { col0 += step_trip; if (col0 >= d) col0 -= d; }
   }
@@ -602,6 +602,27 @@ k_loss_final(const double* __restrict__ partial, int n_partial, double factor, f
   if (threadIdx.x == 0) *loss = (float)(factor * red[0]);
 }
 
+// ---------------------------------------------------------------- slope from a stored activation
+// out = h * (act > 0 ? 1 : alpha): the activation's vjp when the activation itself was kept
+// (x > 0 <=> z > 0 for a leaky ReLU with alpha > 0).
+__global__ void __launch_bounds__(EW_THREADS)
+k_scale_by_act_slope(const float* __restrict__ h, const float* __restrict__ act, int64_t n, float alpha,
+                     float* __restrict__ out, int vec) {
+  const int64_t tid = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x, stride = (int64_t)gridDim.x * EW_THREADS;
+  int64_t done = 0;
+  if (vec) {
+    const int64_t n4 = n >> 2;
+    for (int64_t q = tid; q < n4; q += stride) {
+      const float4 a = *reinterpret_cast<const float4*>(act + 4 * q), v = *reinterpret_cast<const float4*>(h + 4 * q);
+      *reinterpret_cast<float4*>(out + 4 * q) =
+          make_float4(v.x * (a.x > 0.f ? 1.f : alpha), v.y * (a.y > 0.f ? 1.f : alpha), v.z * (a.z > 0.f ? 1.f : alpha),
+                      v.w * (a.w > 0.f ? 1.f : alpha));
+    }
+    done = n4 << 2;
+  }
+  for (int64_t e = done + tid; e < n; e += stride) out[e] = h[e] * (act[e] > 0.f ? 1.f : alpha);
+}
+
 // ---------------------------------------------------------------- residual of an approximate inverse
 __global__ void __launch_bounds__(EW_THREADS)
 k_identity_residual(const float* __restrict__ E, int n, double* __restrict__ partial) {
@@ -853,6 +874,14 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
     e = hipGetLastError();
   }
   return e;
+}
+
+hipError_t ew_scale_by_act_slope(const float* h, const float* act, int64_t n, float alpha, float* out, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int vec = al16(h) && al16(act) && al16(out);
+  hipLaunchKernelGGL(k_scale_by_act_slope, dim3(ew_blocks((n + 3) / 4, EW_THREADS * 4)), dim3(EW_THREADS), 0, stream, h, act, n,
+                     alpha, out, vec);
+  return hipGetLastError();
 }
 
 hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream) {

@@ -76,6 +76,14 @@ int hip_fail(hipError_t e, const char* where) {
   return MW_ERR_HIP;
 }
 
+}  // namespace
+
+namespace mw {
+int record_hip_failure(hipError_t e, const char* where) { return hip_fail(e, where); }
+}  // namespace mw
+
+namespace {
+
 #define MW_HIP(expr)                                   \
   do {                                                 \
     hipError_t e__ = (expr);                           \

@@ -144,11 +144,29 @@ inline hipError_t ew_fill_f32(float* p, float value, int64_t n, hipStream_t stre
   __builtin_memcpy(&bits, &value, sizeof(bits));
   return ew_fill_u32(reinterpret_cast<uint32_t*>(p), bits, n, stream);
 }
+// out = h .* (act > 0 ? 1 : alpha)
+hipError_t ew_scale_by_act_slope(const float* h, const float* act, int64_t n, float alpha, float* out, hipStream_t stream);
 // *out = max(*out, ||E - I||_F) for the n x n matrix E (row stride n); scratch: LOSS_BLOCKS doubles
 hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream);
 // load-only model of a tiled product (measurement): sink gets (M/tile)*(N/tile)*256 floats
 hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
                              hipStream_t stream);
+
+// ---- convolution helpers (conv_kernels.hip): channels-last activations, [k][k][C][C'] kernels ----
+// patches[r - row0][(u k + v) C + c] = x[b, s i' + u - p, s j' + v - p, c] for the patch-matrix rows [row0, row0 + n_rows)
+hipError_t cv_im2col(const float* x, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t row0,
+                     int64_t n_rows, float* patches, hipStream_t stream);
+// h[img0 + b] = transpose of im2col applied to dpatches (rows of the images [img0, img0 + n_img) only), fixed summation order
+hipError_t cv_col2im(const float* dpatches, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t img0,
+                     int64_t n_img, float* h, hipStream_t stream);
+// out[r][c'] = h[b, s i', s j', c'], c' < Co
+hipError_t cv_strided_gather(const float* h, int H, int W, int C, int Ho, int Wo, int Co, int s, int64_t n_rows, float* out,
+                             hipStream_t stream);
+// Tinv = inverse of the lower-triangular n x n matrix T (row stride ld); *flag = 1 if T is not lower-triangular with non-zero diagonal
+hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_t* flag, hipStream_t stream);
+
+// records the text of a failed HIP call for moonwalk_strerror and returns MW_ERR_HIP (moonwalk_api.hip)
+int record_hip_failure(hipError_t e, const char* where);
 
 // ---- right-inverse setup (setup_solve.hip) ----
 // P[d_out][d_in] = (W W^T)^{-1} W by blocked Cholesky and two blocked triangular solves.

@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--reseed", type=int, default=None, help="override the re-seed interval K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size (convolutional configurations)")
     ap.add_argument("--segment", type=int, default=0,
                     help="segment length S of Moonwalk with rematerialisation (0 = off: the metric's configuration)")
     ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
@@ -88,11 +89,85 @@ def cpu_baseline(wl, flops):
             "gflops": flops / per / 1e9}
 
 
+def bench_conv(args):
+    """The convolutional configurations (--config conv2d, conv2d_small): the same JSON line for Moonwalk on
+    submersive 2-D convolutional layers. These are additional workloads, not the headline metric's."""
+    import numpy as np
+    import torch
+    import paper_2402_14212_amd as mw
+    from workloads import CONV_CONFIGS, make_convnet, make_convnet_on_device, conv_moonwalk_flops, conv_backprop_flops
+
+    c = dict(CONV_CONFIGS[args.config])
+    if args.depth is not None:
+        c["depth"] = args.depth
+    if args.batch is not None:
+        c["batch"] = args.batch
+    torch.cuda.set_device(0)
+    on_device = args.gen == "torch" or args.config == "conv2d"
+    wl = (make_convnet_on_device if on_device else make_convnet)(c["batch"], c["side"], c["channels"], c["depth"], alpha=c["alpha"],
+                                                                 seed=0, name=args.config)
+    flops_mw, flops_bp = conv_moonwalk_flops(wl), conv_backprop_flops(wl)
+    K = args.reseed if args.reseed is not None else 2
+    t0 = time.perf_counter()
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, plan=mw.PLAN_MOONWALK | (0 if args.no_backprop else mw.PLAN_BACKPROP))
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+    grads = net.new_grads()
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    ms_mw, wall_mw = time_steps(lambda: net.moonwalk_grad(net.x, net.t, grads, loss), args.steps, args.warmup)
+    st = net.memory_stats()
+    bp = {}
+    if not args.no_backprop:
+        ms_bp, _ = time_steps(lambda: net.backprop_grad(net.x, net.t, grads, loss), args.steps, args.warmup)
+        bp = {"steps_per_s": 1e3 / ms_bp, "ms_per_step": ms_bp, "tflops": flops_bp / (ms_bp * 1e-3) / 1e12}
+    achieved = flops_mw / (ms_mw * 1e-3) / 1e12
+    residual_mw = st["bytes_masks"] + st["bytes_checkpoints"] + st["bytes_tap_inverses"]
+    out = {
+        "metric": "gradient steps/s (mixed-mode Moonwalk on submersive 2-D convolutional layers, one full moonwalk_conv_grad per step)",
+        "value": 1e3 / ms_mw, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_mw, "ms_per_step_wall": wall_mw, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic (seeded, generator: %s)" % ("torch" if on_device else "numpy"),
+        "config": {"workload": f"{args.config}: {wl.depth} layers of {wl.k}x{wl.k}x{wl.channels}x{wl.channels} convolution, stride {wl.s}, "
+                               f"padding {wl.p}, input {wl.side}x{wl.side}x{wl.channels}, batch {wl.batch}, alpha {wl.alphas[0]}, "
+                               f"reseed K={K}"},
+        "tflops": achieved, "flop_per_step": flops_mw,
+        "mfma_frac_whole_step": achieved / MFMA_F32_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "whole step (GEMMs on gathered patch matrices, gathers and elementwise kernels included)",
+                     "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None},
+        "setup_s": setup_s,
+        "memory": {"moonwalk": {"bytes_masks": st["bytes_masks"], "bytes_checkpoints": st["bytes_checkpoints"],
+                                "bytes_tap_inverses": st["bytes_tap_inverses"], "bytes_residual": residual_mw,
+                                "bytes_input_cotangent": st["bytes_input_cotangent"], "bytes_scratch": st["bytes_scratch"],
+                                "bytes_patches": st["bytes_patches"]},
+                   "backprop": {"bytes_residual": st["bytes_bp_activations"], "bytes_scratch": st["bytes_bp_scratch"]},
+                   "bytes_input": int(wl.batch) * wl.side * wl.side * wl.channels * 4},
+        "backprop": bp,
+    }
+    net.close()
+    if not args.no_cpu_baseline:
+        from oracle import conv_oracle as CO
+        sample = make_convnet(1, min(wl.side, 32), wl.channels, min(wl.depth, 3), alpha=c["alpha"], seed=0)
+        t0, n = time.perf_counter(), 0
+        while n < 1 or time.perf_counter() - t0 < 10.0:
+            CO.conv_moonwalk(sample.w, sample.b, sample.alphas, sample.s, sample.p, sample.x, sample.t)
+            n += 1
+        per = (time.perf_counter() - t0) / n
+        fl = conv_moonwalk_flops(sample)
+        out["cpu_baseline"] = {"value": (fl / per) / flops_mw, "unit": "steps/s", "cores": int(os.cpu_count() or 1), "kind": "oracle",
+                               "sample": f"{n} fp64 oracle Moonwalk step(s) of a {sample.depth}-layer, {sample.side}x{sample.side}x{sample.channels}, "
+                                         f"batch-1 cut of the workload; steps/s scaled by the flop ratio to the full workload",
+                               "gflops": fl / per / 1e9}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.config.startswith("conv2d"):
+        return bench_conv(args)
     import torch
     import paper_2402_14212_amd as mw
     from workloads import make_config, moonwalk_flops, backprop_flops, CONFIGS

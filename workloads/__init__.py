@@ -7,8 +7,9 @@ oracle's tests and the HIP path's tests and benchmark feed from.
 from .mlp import (CONFIGS, MLPWorkload, config_widths, haar_orthonormal_columns,
                   make_mlp, make_mlp_on_device, make_config, moonwalk_flops, backprop_flops)
 
-from .conv import ConvWorkload, make_convnet, conv_out_side, conv_moonwalk_flops, conv_backprop_flops
+from .conv import (ConvWorkload, make_convnet, make_convnet_on_device, conv_out_side, conv_moonwalk_flops,
+                   conv_backprop_flops, CONV_CONFIGS)
 
-__all__ = ["ConvWorkload", "make_convnet", "conv_out_side", "conv_moonwalk_flops", "conv_backprop_flops",
+__all__ = ["ConvWorkload", "make_convnet", "make_convnet_on_device", "CONV_CONFIGS", "conv_out_side", "conv_moonwalk_flops", "conv_backprop_flops",
            "CONFIGS", "MLPWorkload", "config_widths", "haar_orthonormal_columns",
            "make_mlp", "make_mlp_on_device", "make_config", "moonwalk_flops", "backprop_flops"]

@@ -85,3 +85,41 @@ def conv_backprop_flops(wl: ConvWorkload) -> int:
         rows = wl.batch * wl.sides[i + 1] ** 2
         total += 3 * 2 * rows * wl.k * wl.k * wl.channels * wl.channels
     return total
+
+
+def make_convnet_on_device(batch: int, side: int, channels: int, depth: int, k: int = 3, s: int = 2, p: int = 1,
+                           alpha: float = 0.1, seed: int = 0, name: str = "", device="cuda:0") -> ConvWorkload:
+    """The same recipe drawn with torch on `device` (different random stream than make_convnet): for the
+    paper-sized configuration, whose input alone is 4 GiB. w, b, x, t are torch tensors on the device."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    C = int(channels)
+    sides = [int(side)]
+    ws, bs = [], []
+    for _ in range(depth):
+        n = sides[-1]
+        no = conv_out_side(n, k, s, p)
+        if no < 1 or not (k > p and s > p and n > s * (no - 1)):
+            raise ValueError(f"layer with input side {n} violates the spatial bounds of the lemma")
+        w = torch.randn(k, k, C, C, device=device, generator=gen) / float(np.sqrt(k * k * C))
+        tap = torch.tril(w[p, p])
+        d = 0.8 + 0.4 * torch.rand(C, device=device, generator=gen)
+        idx = torch.arange(C, device=device)
+        tap[idx, idx] = d
+        w[p, p] = tap
+        ws.append(w.contiguous())
+        bs.append(0.01 * torch.randn(C, device=device, generator=gen))
+        sides.append(no)
+    x = torch.randn(batch, side, side, C, device=device, generator=gen)
+    t = torch.randn(batch, sides[-1], sides[-1], C, device=device, generator=gen)
+    return ConvWorkload(batch=int(batch), side=int(side), channels=C, k=k, s=s, p=p, alphas=[float(alpha)] * depth,
+                        w=ws, b=bs, x=x, t=t, sides=sides, seed=int(seed), name=name)
+
+
+# Named configurations. conv2d is the fully parallel 2-D experiment of the paper in shape: 256 x 256 x 128
+# input, 3x3x128x128 kernels, stride 2, padding 1, leaky ReLU, batch 128, eight layers (side 256 -> 1).
+CONV_CONFIGS = {
+    "conv2d_small": dict(batch=8, side=64, channels=32, depth=4, alpha=0.3),
+    "conv2d":       dict(batch=128, side=256, channels=128, depth=8, alpha=0.3),
+}

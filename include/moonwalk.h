@@ -207,6 +207,9 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
  * ------------------------------------------------------------------------------------------ */
 typedef struct mw_conv_handle mw_conv_handle_t;
 
+#define MW_CONV_KERNELS_AUTO 0
+#define MW_CONV_KERNELS_PATCH_MATRIX 1
+
 typedef struct {
   int32_t channels_in, channels_out, k, stride, pad;
   const float* w;   /* device, [k][k][channels_in][channels_out]; caller owns; must outlive the handle */
@@ -219,6 +222,10 @@ typedef struct {
   int32_t reseed_interval;       /* as in mw_config_t (>= 0)                                            */
   float   loss_scale;            /* as in mw_config_t                                                   */
   int32_t plan;                  /* MW_PLAN_* bits; 0 = both                                            */
+  int32_t kernels;               /* MW_CONV_KERNELS_AUTO: layers with C_in % 4 == 0 and C_out % 32 == 0 run
+                                    kernels that gather the patch matrix inside the product (forward, Phase
+                                    III, weight gradient); MW_CONV_KERNELS_PATCH_MATRIX: every layer goes
+                                    through the patch buffer                                             */
   size_t  patch_bytes;           /* size of the buffer the image chunks' patch matrices are gathered into
                                     (0 = 256 MiB); at least one image's patches are always taken        */
   void* (*dev_alloc)(size_t bytes, void* ctx);

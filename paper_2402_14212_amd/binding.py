@@ -60,7 +60,7 @@ class _ConvLayer(C.Structure):
 
 class _ConvConfig(C.Structure):
     _fields_ = [("batch", C.c_int32), ("height", C.c_int32), ("width", C.c_int32), ("reseed_interval", C.c_int32),
-                ("loss_scale", C.c_float), ("plan", C.c_int32), ("patch_bytes", C.c_size_t),
+                ("loss_scale", C.c_float), ("plan", C.c_int32), ("kernels", C.c_int32), ("patch_bytes", C.c_size_t),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p)]
 
 
@@ -370,14 +370,20 @@ class MoonwalkNet:
             pass
 
 
+CONV_KERNELS_AUTO, CONV_KERNELS_PATCH_MATRIX = 0, 1
+
+
 class ConvMoonwalkNet:
     """A chain of submersive 2-D convolutional layers (channels-last) behind moonwalk_conv_*.
 
-    ws: kernels [k][k][C_in][C_out]; bs: biases or None; one stride and padding for all layers."""
+    ws: kernels [k][k][C_in][C_out]; bs: biases or None; one stride and padding for all layers.
+    kernels: CONV_KERNELS_AUTO (patch matrix gathered inside the products where the channel counts
+    allow it) or CONV_KERNELS_PATCH_MATRIX (always through the patch buffer)."""
 
     def __init__(self, ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, height: int, width: int, stride: int, pad: int, reseed_interval: int = 0,
-                 loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0):
+                 loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0,
+                 kernels: int = 0):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -417,7 +423,7 @@ class ConvMoonwalkNet:
             layers[i] = _ConvLayer(w.shape[2], w.shape[3], w.shape[0], self.stride, self.pad, _ptr(w),
                                    _ptr(_f32(b)) if b is not None else None, a)
         cfg = _ConvConfig(self.batch, self.height, self.width, int(reseed_interval), float(loss_scale), int(plan),
-                          int(patch_bytes), self._alloc_cb, self._free_cb, None)
+                          int(kernels), int(patch_bytes), self._alloc_cb, self._free_cb, None)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_conv_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()

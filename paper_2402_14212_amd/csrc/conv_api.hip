@@ -1,11 +1,15 @@
 // Moonwalk on submersive 2-D convolutional layers (lemma on submersive convolutional layers; the
 // paper's fully parallel 2-D setting): handle, buffer plan and the gradient drivers behind the C ABI.
 //
-// A convolution is run as the library's fp32 MFMA GEMMs on patch matrices: the images are taken in
-// chunks, each chunk's patches are gathered into one bounded buffer (im2col) and multiplied;
-// cotangents go back through the transposed gather (col2im, a fixed-order sum). The vijp of the
-// convolution, in the fully parallel case k <= p + s, is a triangular solve over channels at every
-// output position, done as one GEMM with the inverse of the channel-triangular tap.
+// A convolution is run as the library's fp32 MFMA GEMMs on patch matrices. Where the channel
+// counts allow it (C_in a multiple of 4, C_out of 32) the patch matrix never exists in memory: the
+// GEMM gathers its operand from the image (conv_gemm.h), the forward product ends in the
+// activation and the sign mask, Phase III is one kernel per layer (recomputed forward, channel
+// solve, vijp epilogue) and the weight gradient is split over the patch rows. Otherwise, and for
+// the input cotangent of Phase II in every case, the images are taken in chunks, each chunk's
+// patches go through one bounded buffer (im2col; back through col2im, a fixed-order sum). The vijp
+// of the convolution, in the fully parallel case k <= p + s, is a triangular solve over channels at
+// every output position, done as a product with the inverse of the channel-triangular tap.
 #include "../../include/moonwalk.h"
 
 #include <cmath>
@@ -47,6 +51,11 @@ struct ConvLayer {
   float* act = nullptr;         // backprop: stored output activation
   size_t dW_off = 0, db_off = 0;
   int chunk_images = 1;         // images per patch-buffer fill
+  bool gather = false;          // gathered-operand kernels for forward, Phase III and dW
+  int gchunk = 1;               // images per launch of those kernels (2 GiB operand limit)
+  ConvGeom geom() const { return ConvGeom{Hin, Win, Cin, Ho, Wo, k, s, p}; }
+  int64_t in_img() const { return (int64_t)Hin * Win * Cin; }     // floats per input image
+  int64_t out_img() const { return (int64_t)Ho * Wo * Cout; }     // floats per output image
 };
 
 }  // namespace
@@ -63,6 +72,7 @@ struct mw_conv_handle {
   mw_conv_memstats_t st{};
   size_t total_floats = 0;
   float *patches = nullptr, *zbuf = nullptr, *ctz = nullptr, *hsub = nullptr;
+  float *dw_part = nullptr, *colsum_part = nullptr;
   float *xa = nullptr, *xb = nullptr, *ha = nullptr, *hb = nullptr, *h0 = nullptr;
   uint32_t* status = nullptr;  // [0..1] sign mismatches (u64), [2] kernel not triangular / zero diagonal
   double* loss_scratch = nullptr;
@@ -127,6 +137,52 @@ int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, flo
   return MW_OK;
 }
 
+// forward of one layer for the whole batch: xout = act(conv(xin) + b); mask (may be NULL) gets the signs
+int conv_forward_layer(mw_conv_handle* h, const ConvLayer& l, const float* xin, float* xout, uint64_t* mask, hipStream_t s) {
+  if (l.gather) {
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+      const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+      uint32_t* m32 = mask ? reinterpret_cast<uint32_t*>(mask) + img0 * l.out_img() / 32 : nullptr;
+      CV_HIP(conv_fwd_act(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, xout + img0 * l.out_img(), m32, s));
+    }
+    return MW_OK;
+  }
+  const int64_t per_img = (int64_t)l.Ho * l.Wo;
+  for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+    const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+    int rc = conv_rows(h, l, xin, img0 * per_img, n_img * per_img, xout, s);
+    if (rc != MW_OK) return rc;
+  }
+  CV_HIP(ew_bias_act_mask(xout, nullptr, l.rows, l.Cout, l.alpha, xout, mask, s));  // in place: z -> x, signs packed
+  return MW_OK;
+}
+
+// dW (+ db) of one layer from its input activation and ct_z, both for the whole batch
+int conv_weight_grad(mw_conv_handle* h, const ConvLayer& l, const float* xin, const float* ctz, float scale, float* dW,
+                     float* db, hipStream_t s) {
+  bool first = true;
+  if (l.gather) {
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+      const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+      CV_HIP(conv_dw(l.geom(), n_img, xin + img0 * l.in_img(), ctz + img0 * l.out_img(), l.Cout, scale, first ? 0.f : 1.f, dW,
+                     h->dw_part, s));
+      first = false;
+    }
+  } else {
+    const int64_t per_img = (int64_t)l.Ho * l.Wo;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+      const int64_t r0 = img0 * per_img, R = n_img * per_img;
+      CV_HIP(cv_im2col(xin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, r0, R, h->patches, s));
+      CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, scale, h->patches, l.K, ctz + r0 * l.Cout, l.Cout,
+                        first ? 0.f : 1.f, dW, l.Cout, nullptr, s));
+      first = false;
+    }
+  }
+  CV_HIP(ew_colsum_wide(ctz, l.rows, l.Cout, scale, 0.f, db, h->colsum_part, s));
+  return MW_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -139,6 +195,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   if (cfg->reseed_interval < 0 || !(cfg->loss_scale > 0.f) || !std::isfinite(cfg->loss_scale)) return MW_ERR_INVALID_ARG;
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
+  if (cfg->kernels != MW_CONV_KERNELS_AUTO && cfg->kernels != MW_CONV_KERNELS_PATCH_MATRIX) return MW_ERR_INVALID_ARG;
   int Hc = cfg->height, Wc = cfg->width;
   const int64_t limit = (int64_t)0x7FFFFFFF;
   for (int i = 0; i < n_layers; ++i) {
@@ -170,7 +227,8 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   h->alloc_ctx = cfg->alloc_ctx;
   h->layers.resize(n_layers);
   const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
-  size_t off = 0, max_out = 0, max_patch = 0;
+  size_t off = 0, max_out = 0, max_patch = 0, max_part = 1, max_cout = 1;
+  bool any_patch_layer = false;
   Hc = cfg->height;
   Wc = cfg->width;
   for (int i = 0; i < n_layers; ++i) {
@@ -206,6 +264,17 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
       return MW_ERR_INVALID_ARG;  // a single image's patches do not fit a GEMM operand
     }
     l.chunk_images = (int)ci;
+    const ConvGeom g = l.geom();
+    const int64_t gmax = conv_gather_max_images(g, l.Cout);
+    l.gather = cfg->kernels == MW_CONV_KERNELS_AUTO && gmax >= 1 && conv_gather_ok(g, l.Cout, nullptr, l.w);
+    if (l.gather) {
+      l.gchunk = (int)(gmax < h->B ? gmax : h->B);
+      const size_t part = conv_dw_part_floats(g, l.gchunk, l.Cout);
+      if (part > max_part) max_part = part;
+    } else {
+      any_patch_layer = true;
+    }
+    if ((size_t)l.Cout > max_cout) max_cout = (size_t)l.Cout;
     if (ci * per_img > max_patch) max_patch = ci * per_img;
     if ((size_t)l.n_out > max_out) max_out = (size_t)l.n_out;
     Hc = l.Ho;
@@ -222,6 +291,8 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   bool ok = cv_alloc(h, &h->status, 4, &st.bytes_scratch);
   ok = ok && cv_alloc(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_scratch);
   ok = ok && cv_alloc(h, &h->patches, max_patch, &st.bytes_patches);
+  ok = ok && cv_alloc(h, &h->dw_part, max_part, &st.bytes_scratch);
+  ok = ok && cv_alloc(h, &h->colsum_part, (size_t)COLSUM_MAX_SLICES * max_cout, &st.bytes_scratch);
   if (!ok) return fail(MW_ERR_OOM);
   hipError_t e = ew_fill_u32(h->status, 0u, 4, stream);
   if (e != hipSuccess) return fail(record_hip_failure(e, "status init"));
@@ -244,9 +315,10 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
         if (j % h->Kre == 0) ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j - 1].n_out, &st.bytes_checkpoints);
     ok = ok && cv_alloc(h, &h->xa, max_out, &st.bytes_scratch) && cv_alloc(h, &h->xb, max_out, &st.bytes_scratch) &&
          cv_alloc(h, &h->ha, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hb, max_out, &st.bytes_scratch) &&
-         cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
-         cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch) &&
+         cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
          cv_alloc(h, &h->h0, (size_t)h->layers[0].n_in, &st.bytes_input_cotangent);
+    if (any_patch_layer)  // pre-activations and right-hand sides exist in memory only on the patch-matrix path
+      ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   if (h->plan & MW_PLAN_BACKPROP) {
@@ -273,6 +345,7 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
                        void* hip_stream) {
   if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
   if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  if (h->layers[0].gather && (reinterpret_cast<uintptr_t>(x) & 15)) return MW_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int L = h->L;
   unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
@@ -284,13 +357,8 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   for (int i = 0; i < L; ++i) {
     ConvLayer& l = h->layers[i];
     float* xout = xbuf[i & 1];
-    const int64_t per_img = (int64_t)l.Ho * l.Wo;
-    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
-      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
-      int rc = conv_rows(h, l, xin, img0 * per_img, n_img * per_img, xout, s);
-      if (rc != MW_OK) return rc;
-    }
-    CV_HIP(ew_bias_act_mask(xout, nullptr, l.rows, l.Cout, l.alpha, xout, l.mask, s));  // in place: z -> x, signs packed
+    int rc = conv_forward_layer(h, l, xin, xout, l.mask, s);
+    if (rc != MW_OK) return rc;
     xin = xout;
   }
   // ---------------- loss and output cotangent
@@ -321,25 +389,38 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
-    // vijp of the convolution: right-hand sides at the strided positions, then the channel solve as a product
-    CV_HIP(cv_strided_gather(hin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.Cout, l.s, l.rows, h->hsub, s));
-    const int64_t per_img = (int64_t)l.Ho * l.Wo;
-    bool first = true;
-    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
-      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
-      const int64_t r0 = img0 * per_img, R = n_img * per_img;
-      CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, h->hsub + r0 * l.Cout, l.Cout, l.Tinv, l.Cout, 0.f,
-                        h->ctz + r0 * l.Cout, l.Cout, nullptr, s));
-      int rc = conv_rows(h, l, xin, r0, R, h->zbuf, s);  // recompute z; the patches stay in the buffer
+    if (l.gather) {
+      // one kernel per image chunk: recomputed forward, channel solve at the strided positions, vijp epilogue
+      for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+        const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+        const int64_t o = img0 * l.out_img();
+        CV_HIP(conv_vijp_layer(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, hin + img0 * l.in_img(),
+                               l.Tinv, reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, h->ctz + o,
+                               mismatches, s));
+      }
+      int rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
       if (rc != MW_OK) return rc;
-      // dW[K][Cout] (+)= patches^T ct_z over the rows of this chunk
-      CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, inv_scale, h->patches, l.K, h->ctz + r0 * l.Cout, l.Cout,
-                        first ? 0.f : 1.f, grads_out + l.dW_off, l.Cout, nullptr, s));
-      first = false;
+    } else {
+      // vijp of the convolution: right-hand sides at the strided positions, then the channel solve as a product
+      CV_HIP(cv_strided_gather(hin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.Cout, l.s, l.rows, h->hsub, s));
+      const int64_t per_img = (int64_t)l.Ho * l.Wo;
+      bool first = true;
+      for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
+        const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
+        const int64_t r0 = img0 * per_img, R = n_img * per_img;
+        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, h->hsub + r0 * l.Cout, l.Cout, l.Tinv, l.Cout, 0.f,
+                          h->ctz + r0 * l.Cout, l.Cout, nullptr, s));
+        int rc = conv_rows(h, l, xin, r0, R, h->zbuf, s);  // recompute z; the patches stay in the buffer
+        if (rc != MW_OK) return rc;
+        // dW[K][Cout] (+)= patches^T ct_z over the rows of this chunk
+        CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, inv_scale, h->patches, l.K, h->ctz + r0 * l.Cout, l.Cout,
+                          first ? 0.f : 1.f, grads_out + l.dW_off, l.Cout, nullptr, s));
+        first = false;
+      }
+      CV_HIP(ew_colsum_wide(h->ctz, l.rows, l.Cout, inv_scale, 0.f, grads_out + l.db_off, h->colsum_part, s));
+      CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
+                              mismatches, s));
     }
-    CV_HIP(ew_colsum(h->ctz, l.rows, l.Cout, inv_scale, grads_out + l.db_off, s));
-    CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
-                            mismatches, s));
     xin = xout;
     hin = hout;
   }
@@ -350,19 +431,15 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
                        void* hip_stream) {
   if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
   if (!(h->plan & MW_PLAN_BACKPROP)) return MW_ERR_NOT_PLANNED;
+  if (h->layers[0].gather && (reinterpret_cast<uintptr_t>(x) & 15)) return MW_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int L = h->L;
   // forward, every activation stored (the sign is read back from it: x > 0 <=> z > 0)
   const float* xin = x;
   for (int i = 0; i < L; ++i) {
     ConvLayer& l = h->layers[i];
-    const int64_t per_img = (int64_t)l.Ho * l.Wo;
-    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
-      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
-      int rc = conv_rows(h, l, xin, img0 * per_img, n_img * per_img, l.act, s);
-      if (rc != MW_OK) return rc;
-    }
-    CV_HIP(ew_bias_act_mask(l.act, nullptr, l.rows, l.Cout, l.alpha, l.act, nullptr, s));
+    int rc = conv_forward_layer(h, l, xin, l.act, nullptr, s);
+    if (rc != MW_OK) return rc;
     xin = l.act;
   }
   {
@@ -376,17 +453,10 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     ConvLayer& l = h->layers[i];
     const float* xprev = (i == 0) ? x : h->layers[i - 1].act;
     CV_HIP(ew_scale_by_act_slope(hcur, l.act, l.n_out, l.alpha, h->ctz, s));
-    const int64_t per_img = (int64_t)l.Ho * l.Wo;
-    bool first = true;
-    for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
-      const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
-      const int64_t r0 = img0 * per_img, R = n_img * per_img;
-      CV_HIP(cv_im2col(xprev, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, r0, R, h->patches, s));
-      CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, inv_scale, h->patches, l.K, h->ctz + r0 * l.Cout, l.Cout,
-                        first ? 0.f : 1.f, grads_out + l.dW_off, l.Cout, nullptr, s));
-      first = false;
+    {
+      int rc = conv_weight_grad(h, l, xprev, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
+      if (rc != MW_OK) return rc;
     }
-    CV_HIP(ew_colsum(h->ctz, l.rows, l.Cout, inv_scale, grads_out + l.db_off, s));
     if (i > 0) {
       float* hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
       int rc = conv_input_grad(h, l, h->ctz, hout, s);

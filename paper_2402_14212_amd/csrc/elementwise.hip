@@ -522,13 +522,17 @@ k_vijp_epilogue(const float* __restrict__ z, float* __restrict__ ct_z, int64_t n
 // Thread j of a workgroup owns column j and walks a contiguous range of rows; partial sums over
 // COLSUM_SPLIT row ranges are combined in LDS in a fixed order.
 constexpr int COLSUM_COLS = 32, COLSUM_SPLIT = 32;
+// Workgroup (bx, by) sums rows [by * rows_per_block, ...) of columns [32 bx, 32 bx + 32) into
+// out[by * d + col] (times scale).
 __global__ void __launch_bounds__(COLSUM_COLS* COLSUM_SPLIT)
-k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* __restrict__ out) {
+k_colsum(const float* __restrict__ a, int64_t rows, int64_t rows_per_block, int d, float scale, float* __restrict__ out) {
   __shared__ float part[COLSUM_SPLIT][COLSUM_COLS];
   const int c = threadIdx.x % COLSUM_COLS, s = threadIdx.x / COLSUM_COLS;
   const int col = blockIdx.x * COLSUM_COLS + c;
-  const int64_t per = (rows + COLSUM_SPLIT - 1) / COLSUM_SPLIT;
-  const int64_t lo = s * per, hi = lo + per < rows ? lo + per : rows;
+  const int64_t first = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t last = first + rows_per_block < rows ? first + rows_per_block : rows;
+  const int64_t per = (last - first + COLSUM_SPLIT - 1) / COLSUM_SPLIT;
+  const int64_t lo = first + s * per, hi = lo + per < last ? lo + per : last;
   float acc = 0.f;
   if (col < d) {
     const float* p = a + col;
@@ -547,7 +551,36 @@ k_colsum(const float* __restrict__ a, int64_t rows, int d, float scale, float* _
   if (s == 0 && col < d) {
     float t = part[0][c];
     for (int k = 1; k < COLSUM_SPLIT; ++k) t += part[k][c];
-    out[col] = scale * t;
+    out[(int64_t)blockIdx.y * d + col] = scale * t;
+  }
+}
+
+// out[i] = scale * (part[0][i] + part[1][i] + ... in slice order) + beta * out[i]
+__global__ void __launch_bounds__(EW_THREADS)
+k_reduce_slices(const float* __restrict__ part, int slices, int64_t n, float scale, float beta, float* __restrict__ out,
+                int vec) {
+  const int64_t tid = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x;
+  if (vec) {
+    const int64_t e = tid * 4;
+    if (e >= n) return;
+    float4 t = *reinterpret_cast<const float4*>(part + e);
+    for (int k = 1; k < slices; ++k) {
+      const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + e);
+      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+    }
+    float4 r = make_float4(scale * t.x, scale * t.y, scale * t.z, scale * t.w);
+    if (beta != 0.f) {
+      const float4 o = *reinterpret_cast<const float4*>(out + e);
+      r.x += beta * o.x; r.y += beta * o.y; r.z += beta * o.z; r.w += beta * o.w;
+    }
+    *reinterpret_cast<float4*>(out + e) = r;
+  } else {
+    if (tid >= n) return;
+    float t = part[tid];
+    for (int k = 1; k < slices; ++k) t += part[(int64_t)k * n + tid];
+    float r = scale * t;
+    if (beta != 0.f) r += beta * out[tid];
+    out[tid] = r;
   }
 }
 
@@ -852,7 +885,40 @@ hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, fl
 hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream) {
   if (d <= 0) return hipSuccess;
   int blocks = (d + COLSUM_COLS - 1) / COLSUM_COLS;
-  hipLaunchKernelGGL(k_colsum, dim3(blocks), dim3(COLSUM_COLS * COLSUM_SPLIT), 0, stream, a, rows, d, scale, out);
+  hipLaunchKernelGGL(k_colsum, dim3(blocks), dim3(COLSUM_COLS * COLSUM_SPLIT), 0, stream, a, rows, rows > 0 ? rows : 1, d, scale,
+                     out);
+  return hipGetLastError();
+}
+
+int ew_colsum_slices(int64_t rows, int d) {
+  // enough workgroups to keep every memory channel busy, at least 1024 rows each
+  const int col_blocks = (d + COLSUM_COLS - 1) / COLSUM_COLS;
+  int64_t want = (2048 + col_blocks - 1) / col_blocks;
+  const int64_t most = (rows + 1023) / 1024;
+  if (want > most) want = most;
+  if (want > COLSUM_MAX_SLICES) want = COLSUM_MAX_SLICES;
+  return want < 1 ? 1 : (int)want;
+}
+
+hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, float beta, float* out, float* scratch,
+                          hipStream_t stream) {
+  if (d <= 0) return hipSuccess;
+  const int slices = ew_colsum_slices(rows, d);
+  const int64_t per = (rows + slices - 1) / slices;
+  const int col_blocks = (d + COLSUM_COLS - 1) / COLSUM_COLS;
+  hipLaunchKernelGGL(k_colsum, dim3(col_blocks, slices), dim3(COLSUM_COLS * COLSUM_SPLIT), 0, stream, a, rows, per > 0 ? per : 1,
+                     d, 1.f, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return ew_reduce_slices(scratch, slices, d, scale, beta, out, stream);
+}
+
+hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream) {
+  if (n <= 0 || slices <= 0) return hipSuccess;
+  const int vec = (n % 4 == 0) && al16(part) && al16(out);
+  const int64_t threads = vec ? n / 4 : n;
+  hipLaunchKernelGGL(k_reduce_slices, dim3((unsigned)((threads + EW_THREADS - 1) / EW_THREADS)), dim3(EW_THREADS), 0, stream,
+                     part, slices, n, scale, beta, out, vec);
   return hipGetLastError();
 }
 

@@ -120,8 +120,24 @@ struct Chunk {
 // flight while earlier tiles are multiplied: fetch() issues whatever extra loads it needs next
 // to the operand's own load, apply() runs just before the values are written to LDS.
 
+// Where operand A's chunks live. The default is a plain matrix: chunk (outer, inner) of an
+// [n_outer][n_inner] array with row stride ld. A transform that gathers A from somewhere else
+// (an image, for the patch matrix of a convolution) replaces these two functions.
+struct ALinearDev {
+  __device__ __forceinline__ Chunk chunk(int outer, int inner, int n_outer, int n_inner, int64_t ld) const {
+    Chunk c;
+    c.e = (uint32_t)outer * (uint32_t)ld + (uint32_t)inner;
+    const int left = n_inner - inner;
+    c.nvalid = (outer < n_outer && left > 0) ? (left < 4 ? left : 4) : 0;
+    return c;
+  }
+  __device__ __forceinline__ uint32_t extent(int n_outer, int n_inner, int64_t ld) const {
+    return extent_bytes(n_outer, n_inner, ld);
+  }
+};
+
 struct ANone {
-  struct Dev {
+  struct Dev : ALinearDev {
     struct Aux {};
     __device__ __forceinline__ Dev() {}
     __device__ __forceinline__ Dev(const ANone&, int, int, int64_t) {}
@@ -135,7 +151,7 @@ struct ANone {
 struct ASlopeFromAct {
   const float* act;  // same shape and row stride as A
   float alpha;
-  struct Dev {
+  struct Dev : ALinearDev {
     struct Aux { float4 a; };
     __amdgpu_buffer_rsrc_t rs;
     float alpha;
@@ -187,10 +203,7 @@ struct TileLoader {
       } else {
         outer = k0 + f / (R / 4); inner = row0 + 4 * (f % (R / 4)); n_outer = n_k; n_inner = n_rows;
       }
-      Chunk c;
-      c.e = (uint32_t)outer * (uint32_t)ld + (uint32_t)inner;
-      int left = n_inner - inner;
-      c.nvalid = (outer < n_outer && left > 0) ? (left < 4 ? left : 4) : 0;
+      const Chunk c = xf.chunk(outer, inner, n_outer, n_inner, ld);
       if (VEC) {
         v[i] = buf_load_f32x4(rs, c.nvalid ? c.e * 4u : OOB);
       } else {
@@ -309,7 +322,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
   const int wm = wave / (Cfg::WK * Cfg::WN);
   const int r = lane & 31, g = lane >> 5;
 
-  const uint32_t bytes_a = LA == KCONTIG ? extent_bytes(M, K, lda) : extent_bytes(K, M, lda);
+  const uint32_t bytes_a = LA == KCONTIG ? xf.extent(M, K, lda) : xf.extent(K, M, lda);
   const uint32_t bytes_b = LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb);
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, bytes_a);
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, bytes_b);

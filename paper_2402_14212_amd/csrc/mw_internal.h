@@ -133,6 +133,15 @@ hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, fl
                             const uint32_t* offsets, const float* frag, const uint64_t* base, uint64_t capacity,
                             float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream);
 hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream);
+// the same for tall matrices: row ranges summed by separate workgroups into scratch
+// (ew_colsum_slices(rows, d) * d floats, at most COLSUM_MAX_SLICES * d), then combined in range order;
+// out = scale * sums + beta * out
+constexpr int COLSUM_MAX_SLICES = 512;
+int ew_colsum_slices(int64_t rows, int d);
+hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, float beta, float* out, float* scratch,
+                          hipStream_t stream);
+// out[i] = scale * (part[0][i] + part[1][i] + ..., in that order) + beta * out[i]; part is [slices][n]
+hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream);
 constexpr int LOSS_BLOCKS = 2048;  // most workgroups (and scratch doubles) the loss reduction uses
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
                         double* scratch, hipStream_t stream);
@@ -164,6 +173,32 @@ hipError_t cv_strided_gather(const float* h, int H, int W, int C, int Ho, int Wo
                              hipStream_t stream);
 // Tinv = inverse of the lower-triangular n x n matrix T (row stride ld); *flag = 1 if T is not lower-triangular with non-zero diagonal
 hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_t* flag, hipStream_t stream);
+
+// ---- convolution with the patch matrix gathered inside the GEMM (conv_gemm.hip) ----
+struct ConvGeom {
+  int H, W, C;     // input image, channels-last
+  int Ho, Wo;      // output grid
+  int k, s, p;     // taps per side, stride, padding
+};
+// the gathered kernels need C % 4 == 0, C_out % 32 == 0 and 16-byte aligned operands (x may be NULL: not checked)
+bool conv_gather_ok(const ConvGeom& g, int Cout, const float* x, const float* w);
+// most images one launch may take (every operand below 2 GiB); 0 if not even one fits
+int64_t conv_gather_max_images(const ConvGeom& g, int Cout);
+// xout[r][c'] = act(patches(x)[r] . w[:, c'] + b[c']) for the n_img images at x; mask32 (may be NULL) gets
+// the sign bits of the same flat index, 32 per word
+hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
+                        float* xout, uint32_t* mask32, hipStream_t stream);
+// Phase III of a leaky convolutional layer for n_img images: z recomputed from x, ct_z = sub(h_in) Tinv^T,
+// x out, h out = ct_z / slope, sign check against mask32
+hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
+                           const float* hin, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
+                           unsigned long long* mismatches, hipStream_t stream);
+// dW[K1][Cout] = scale * patches(x)^T ct_z + beta * dW, the patch rows split into slices whose partial
+// products (part: conv_dw_part_floats floats) are added in slice order
+constexpr int CONV_DW_MAX_SLICES = 256;
+size_t conv_dw_part_floats(const ConvGeom& g, int n_img, int Cout);
+hipError_t conv_dw(const ConvGeom& g, int n_img, const float* x, const float* ctz, int Cout, float scale, float beta,
+                   float* dW, float* part, hipStream_t stream);
 
 // records the text of a failed HIP call for moonwalk_strerror and returns MW_ERR_HIP (moonwalk_api.hip)
 int record_hip_failure(hipError_t e, const char* where);

@@ -69,23 +69,31 @@ def _masks(net, wl):
 
 
 CONV_CASES = {
-    # name: (batch, side, channels, depth, k, s, p, alpha, K, patch_bytes)
-    "small":        (2, 16, 8, 2, 3, 2, 1, 0.3, 0, 0),
-    "odd_side":     (3, 21, 16, 2, 3, 2, 1, 0.3, 0, 0),
-    "chunks":       (5, 16, 8, 3, 3, 2, 1, 0.3, 0, 40000),      # patch buffer of about one image: several fills
-    "not_vec":      (2, 12, 6, 2, 3, 2, 1, 0.3, 0, 0),           # channels not a multiple of 4
-    "k2":           (2, 16, 8, 3, 2, 2, 0, 0.3, 0, 0),
-    "deep_reseed":  (2, 64, 16, 5, 3, 2, 1, 0.1, 2, 0),
-    "wide":         (2, 32, 64, 3, 3, 2, 1, 0.2, 0, 0),
+    # name: (batch, side, channels, depth, k, s, p, alpha, K, patch_bytes, kernels)
+    "small":        (2, 16, 8, 2, 3, 2, 1, 0.3, 0, 0, 0),
+    "odd_side":     (3, 21, 16, 2, 3, 2, 1, 0.3, 0, 0, 0),
+    "chunks":       (5, 16, 8, 3, 3, 2, 1, 0.3, 0, 40000, 0),   # patch buffer of about one image: several fills
+    "not_vec":      (2, 12, 6, 2, 3, 2, 1, 0.3, 0, 0, 0),        # channels not a multiple of 4
+    "k2":           (2, 16, 8, 3, 2, 2, 0, 0.3, 0, 0, 0),
+    "deep_reseed":  (2, 64, 16, 5, 3, 2, 1, 0.1, 2, 0, 0),
+    # channel counts that take the kernels gathering the patch matrix inside the product
+    "wide":         (2, 32, 64, 3, 3, 2, 1, 0.2, 0, 0, 0),
+    "wide_patches": (2, 32, 64, 3, 3, 2, 1, 0.2, 0, 0, 1),       # the same network through the patch buffer
+    "gather_odd":   (3, 21, 32, 3, 3, 2, 1, 0.3, 0, 0, 0),       # sides 21 -> 11 -> 6 -> 3: ragged tiles, padding on all edges
+    "gather_k2":    (2, 16, 32, 2, 2, 2, 0, 0.3, 0, 0, 0),
+    "gather_deep":  (2, 64, 32, 5, 3, 2, 1, 0.1, 2, 40000, 0),   # re-seeds; Phase II still in several patch fills
+    "gather_128":   (2, 128, 128, 2, 3, 2, 1, 0.3, 0, 0, 0),     # 8192 and 2048 rows, K = 1152: the split-K tiles
+    "gather_tall":  (1, 512, 32, 2, 3, 2, 1, 0.3, 0, 0, 0),      # 65536 rows: the 128-row tile, then 16384 rows
+    "gather_mid":   (2, 256, 32, 1, 3, 2, 1, 0.3, 0, 0, 0),      # 32768 rows: the 64 x 128 tile
 }
 
 
 @pytest.mark.parametrize("name", sorted(CONV_CASES))
 def test_conv_moonwalk_matches_the_oracle(mw, name):
-    B, side, C, depth, k, s, p, alpha, K, patch_bytes = CONV_CASES[name]
+    B, side, C, depth, k, s, p, alpha, K, patch_bytes, kernels = CONV_CASES[name]
     wl = make_convnet(B, side, C, depth, k=k, s=s, p=p, alpha=alpha, seed=1, name=name)
     print("conv", name, flush=True)
-    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels)
     res = net.moonwalk_grad(net.x, net.t)
     torch.cuda.synchronize()
     st = net.memory_stats()

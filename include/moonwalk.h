@@ -202,7 +202,9 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
  * other output position enters the equation of h[s i', s j', c'] (MW_ERR_INVALID_ARG otherwise);
  * alpha must be in (0, 1]. The vijp of the convolution is then, at every output position on its own,
  * the triangular solve T h'[i', j', :] = h[s i', s j', :C_out] with T = w[p][p][:C_out][:C_out]; the
- * library keeps T^{-1} per layer (moonwalk_conv_refresh recomputes it after the caller changed w).
+ * library keeps T^{-1} per layer, and for the layers on the gathered kernels a regrouped copy of the
+ * taps that BOTH gradient paths use: after changing w call moonwalk_conv_refresh before either
+ * moonwalk_conv_grad or backprop_conv_grad (it recomputes both, whatever the plan).
  * The gradient layout is per layer dw [k][k][C_in][C_out] then db [C_out].
  * ------------------------------------------------------------------------------------------ */
 typedef struct mw_conv_handle mw_conv_handle_t;
@@ -236,6 +238,8 @@ typedef struct {
 typedef struct {
   uint64_t bytes_masks;            /* 1-bit sign masks of all layer outputs                              */
   uint64_t bytes_tap_inverses;     /* T^{-1}, C_out^2 floats per layer                                   */
+  uint64_t bytes_packed_weights;   /* taps regrouped by stride class for the input-cotangent kernel: one
+                                      copy of every layer's weights that takes the gathered kernels      */
   uint64_t bytes_checkpoints;      /* re-seed cotangents                                                 */
   uint64_t bytes_input_cotangent;  /* h_0: as large as the network input                                 */
   uint64_t bytes_scratch;          /* ping-pong activations / cotangents, z, ct_z, right-hand sides      */

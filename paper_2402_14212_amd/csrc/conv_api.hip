@@ -45,6 +45,8 @@ struct ConvLayer {
   const float* b = nullptr;
   float alpha = 0.f;
   float* Tinv = nullptr;        // inverse of the tap at (p, p), [Cout][Cout]
+  float* wrev = nullptr;        // taps regrouped for the gathered input-cotangent product, [K][Cout] floats
+  bool gather_rev = false;      // that product instead of patches + col2im
   uint64_t* mask = nullptr;
   size_t mask_words = 0;
   float* ckpt = nullptr;        // kept cotangent at this layer's output
@@ -102,10 +104,13 @@ bool cv_alloc(mw_conv_handle* h, T** out, size_t count, uint64_t* item) {
   return *out != nullptr;
 }
 
-int build_tap_inverses(mw_conv_handle* h, hipStream_t s) {
+// everything the library derives from the weights: the tap inverses (Moonwalk) and the regrouped taps
+int build_from_weights(mw_conv_handle* h, hipStream_t s) {
   int32_t* flag = reinterpret_cast<int32_t*>(h->status + 2);
   CV_HIP(ew_fill_u32(h->status + 2, 0u, 1, s));
   for (auto& l : h->layers) {
+    if (l.wrev) CV_HIP(cv_pack_rev_weights(l.w, l.k, l.s, l.Cin, l.Cout, l.wrev, s));
+    if (!l.Tinv) continue;
     const float* tap = l.w + ((size_t)(l.p * l.k + l.p) * l.Cin) * l.Cout;  // w[p][p][.][.], [Cin][Cout]
     CV_HIP(cv_tri_inverse(tap, l.Cout, l.Cout, l.Tinv, flag, s));
   }
@@ -123,8 +128,28 @@ int conv_rows(mw_conv_handle* h, const ConvLayer& l, const float* xin, int64_t r
   return MW_OK;
 }
 
-// input cotangent of the layer from ct_z (whole layer), image chunk by image chunk
-int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, float* hout, hipStream_t s) {
+// input cotangent of the layer from ct_z (whole layer), image chunk by image chunk: hout (may be NULL
+// with ct_out) = h; ct_out (may be NULL) = h times the slope selected by the previous layer's mask.
+// Returns through *fused whether ct_out was written (only the gathered kernel can do that).
+int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, float* hout, float* ct_out,
+                    const ConvLayer* prev, bool* fused, hipStream_t s) {
+  if (fused) *fused = false;
+  if (l.gather_rev) {
+    // the mask of an image chunk must start on a 32-bit word
+    const bool fuse = ct_out && prev && l.Cin % 32 == 0;
+    if (!fuse && !hout) return MW_ERR_INVALID_ARG;
+    for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+      const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+      const int64_t o = img0 * l.in_img();
+      CV_HIP(conv_input_cotangent(l.geom(), n_img, l.Cout, ctz + img0 * l.out_img(), l.wrev, hout ? hout + o : nullptr,
+                                  fuse ? ct_out + o : nullptr,
+                                  fuse ? reinterpret_cast<const uint32_t*>(prev->mask) + o / 32 : nullptr,
+                                  fuse ? prev->alpha : 1.f, s));
+    }
+    if (fused) *fused = fuse;
+    return MW_OK;
+  }
+  if (!hout) return MW_ERR_INVALID_ARG;
   const int64_t per_img = (int64_t)l.Ho * l.Wo;
   for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
     const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
@@ -228,7 +253,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   h->layers.resize(n_layers);
   const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
   size_t off = 0, max_out = 0, max_patch = 0, max_part = 1, max_cout = 1;
-  bool any_patch_layer = false;
+  bool any_patch_layer = false, need_patches = false;
   Hc = cfg->height;
   Wc = cfg->width;
   for (int i = 0; i < n_layers; ++i) {
@@ -267,6 +292,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     const ConvGeom g = l.geom();
     const int64_t gmax = conv_gather_max_images(g, l.Cout);
     l.gather = cfg->kernels == MW_CONV_KERNELS_AUTO && gmax >= 1 && conv_gather_ok(g, l.Cout, nullptr, l.w);
+    l.gather_rev = l.gather && conv_rev_ok(g, l.Cout);
     if (l.gather) {
       l.gchunk = (int)(gmax < h->B ? gmax : h->B);
       const size_t part = conv_dw_part_floats(g, l.gchunk, l.Cout);
@@ -274,6 +300,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     } else {
       any_patch_layer = true;
     }
+    if (!l.gather || !l.gather_rev) need_patches = true;
     if ((size_t)l.Cout > max_cout) max_cout = (size_t)l.Cout;
     if (ci * per_img > max_patch) max_patch = ci * per_img;
     if ((size_t)l.n_out > max_out) max_out = (size_t)l.n_out;
@@ -290,7 +317,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   mw_conv_memstats_t& st = h->st;
   bool ok = cv_alloc(h, &h->status, 4, &st.bytes_scratch);
   ok = ok && cv_alloc(h, &h->loss_scratch, (size_t)LOSS_BLOCKS, &st.bytes_scratch);
-  ok = ok && cv_alloc(h, &h->patches, max_patch, &st.bytes_patches);
+  if (need_patches) ok = ok && cv_alloc(h, &h->patches, max_patch, &st.bytes_patches);
   ok = ok && cv_alloc(h, &h->dw_part, max_part, &st.bytes_scratch);
   ok = ok && cv_alloc(h, &h->colsum_part, (size_t)COLSUM_MAX_SLICES * max_cout, &st.bytes_scratch);
   if (!ok) return fail(MW_ERR_OOM);
@@ -308,8 +335,6 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
       }
     }
     if (!ok) return fail(MW_ERR_OOM);
-    int rc = build_tap_inverses(h, stream);
-    if (rc != MW_OK) return fail(rc);
     if (h->Kre > 0)
       for (int j = 1; j < n_layers; ++j)
         if (j % h->Kre == 0) ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j - 1].n_out, &st.bytes_checkpoints);
@@ -329,6 +354,13 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if (!ok) return fail(MW_ERR_OOM);
   }
   (void)B;
+  for (auto& l : h->layers)
+    if (l.gather_rev) ok = ok && cv_alloc(h, &l.wrev, (size_t)l.K * l.Cout, &st.bytes_packed_weights);
+  if (!ok) return fail(MW_ERR_OOM);
+  {
+    int rc = build_from_weights(h, stream);
+    if (rc != MW_OK) return fail(rc);
+  }
   e = hipStreamSynchronize(stream);
   if (e != hipSuccess) return fail(record_hip_failure(e, "setup sync"));
   *out = h;
@@ -337,8 +369,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
 
 int moonwalk_conv_refresh(mw_conv_handle_t* h, void* hip_stream) {
   if (!h) return MW_ERR_INVALID_ARG;
-  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
-  return build_tap_inverses(h, static_cast<hipStream_t>(hip_stream));
+  return build_from_weights(h, static_cast<hipStream_t>(hip_stream));
 }
 
 int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
@@ -366,22 +397,31 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     const ConvLayer& last = h->layers[L - 1];
     CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
   }
-  // ---------------- Phase II: reverse, input cotangent only
-  float* hbuf[2] = {h->ha, h->hb};
-  const float* hcur = h->ha;
-  for (int i = L - 1; i >= 0; --i) {
-    ConvLayer& l = h->layers[i];
-    CV_HIP(ew_rev_scale(hcur, l.mask, l.n_out, l.alpha, h->ctz, s));
-    float* hout;
-    if (i == 0) hout = h->h0;
-    else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
-    else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
-    int rc = conv_input_grad(h, l, h->ctz, hout, s);
-    if (rc != MW_OK) return rc;
-    hcur = hout;
+  // ---------------- Phase II: reverse, input cotangent only. ct_z travels between two buffers; the
+  // cotangent h itself is kept only where Phase III starts from it (h_0 and the re-seed points).
+  {
+    float* ctbuf[2] = {h->ctz, h->hb};
+    int cur = 0;
+    const ConvLayer& top = h->layers[L - 1];
+    CV_HIP(ew_rev_scale(h->ha, top.mask, top.n_out, top.alpha, ctbuf[0], s));
+    for (int i = L - 1; i >= 0; --i) {
+      ConvLayer& l = h->layers[i];
+      const ConvLayer* prev = i > 0 ? &h->layers[i - 1] : nullptr;
+      float* keep = (i == 0) ? h->h0 : prev->ckpt;  // may be NULL
+      float* ct_next = prev ? ctbuf[cur ^ 1] : nullptr;
+      bool fused = false;
+      // a layer that cannot scale in its epilogue leaves h somewhere: where it is kept, else in ha (free by now)
+      const bool can_fuse = l.gather_rev && prev && l.Cin % 32 == 0;
+      float* raw = keep ? keep : (can_fuse ? nullptr : h->ha);
+      int rc = conv_input_grad(h, l, ctbuf[cur], raw, ct_next, prev, &fused, s);
+      if (rc != MW_OK) return rc;
+      if (prev && !fused) CV_HIP(ew_rev_scale(raw, prev->mask, prev->n_out, prev->alpha, ct_next, s));
+      cur ^= 1;
+    }
   }
   // ---------------- Phase III: forward vijp sweep
   const float inv_scale = 1.0f / h->loss_scale;
+  float* hbuf[2] = {h->ha, h->hb};
   xin = x;
   const float* hin = h->h0;
   for (int i = 0; i < L; ++i) {
@@ -459,7 +499,7 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     }
     if (i > 0) {
       float* hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
-      int rc = conv_input_grad(h, l, h->ctz, hout, s);
+      int rc = conv_input_grad(h, l, h->ctz, hout, nullptr, nullptr, nullptr, s);
       if (rc != MW_OK) return rc;
       hcur = hout;
     }

@@ -11,14 +11,69 @@ namespace {
 AConvPatch make_gather(const ConvGeom& g, int n_img, int k, int s, int p, int c0, int csel) {
   AConvPatch a;
   a.H = g.H; a.W = g.W; a.C = g.C; a.Ho = g.Ho; a.Wo = g.Wo;
-  a.k = k; a.s = s; a.p = p; a.c0 = c0; a.Csel = csel;
+  a.kh = k; a.kw = k; a.s = s; a.py = p; a.px = p; a.c0 = c0; a.Csel = csel;
   a.row_off = 0;
   a.bytes = (uint32_t)((int64_t)n_img * g.H * g.W * g.C * 4);
   a.d_howo = FastDiv((uint32_t)(g.Ho * g.Wo));
   a.d_wo = FastDiv((uint32_t)g.Wo);
   a.d_csel = FastDiv((uint32_t)csel);
-  a.d_k = FastDiv((uint32_t)k);
+  a.d_kw = FastDiv((uint32_t)k);
+  a.d1 = (uint32_t)(g.W - g.Wo) * (uint32_t)(s * g.C);
+  a.d2 = (uint32_t)(g.H - g.Ho * s) * (uint32_t)(g.W * g.C);
   return a;
+}
+
+// taps ky < k with ky mod s == r
+int class_taps(int k, int s, int r) { return r < k ? (k - r + s - 1) / s : 0; }
+
+template <class Cfg>
+hipError_t rev_t(const ConvGeom& g, int n_img, int Cout, const float* ctz, const float* wrev, const EpiConvRev& epi,
+                 hipStream_t stream) {
+  ConvRevTask<Cfg> t;
+  t.N = g.C;
+  t.CT = ctz;
+  t.Wrev = wrev;
+  t.epi = epi;
+  t.tiles_n = ceil_div(g.C, Cfg::BN);
+  int n = 0, first = 0;
+  int64_t w_off = 0;
+  for (int ry = 0; ry < g.s; ++ry)
+    for (int rx = 0; rx < g.s; ++rx) {
+      const int nty = class_taps(g.k, g.s, ry), ntx = class_taps(g.k, g.s, rx);
+      // pixels iy with (iy + p) mod s == ry: iy + p = s q + ry for q in [q_lo, q_hi]
+      auto lo = [&](int r) { return (g.p - r + g.s - 1) / g.s; };             // ceil((p - r) / s), p >= 0 > r - s
+      auto hi = [&](int extent, int r) { return (extent + g.p - 1 - r) >= 0 ? (extent + g.p - 1 - r) / g.s : -1; };
+      const int qy_lo = lo(ry), qx_lo = lo(rx);
+      const int nqy = hi(g.H, ry) - qy_lo + 1, nqx = hi(g.W, rx) - qx_lo + 1;
+      const int64_t w_here = w_off;
+      w_off += (int64_t)nty * ntx * Cout * g.C;
+      if (nqy <= 0 || nqx <= 0) continue;
+      RevClass& rc = t.cls[n++];
+      AConvPatch& a = rc.g;
+      a.H = g.Ho; a.W = g.Wo; a.C = Cout; a.Ho = nqy; a.Wo = nqx;
+      a.kh = nty; a.kw = ntx; a.s = 1;
+      // tap slot ky' holds ky = ry + s (nty - 1 - ky'): its source row is q - (nty - 1 - ky')
+      a.py = nty - 1 - qy_lo; a.px = ntx - 1 - qx_lo;
+      a.c0 = 0; a.Csel = Cout; a.row_off = 0;
+      a.bytes = (uint32_t)((int64_t)n_img * g.Ho * g.Wo * Cout * 4);
+      a.d_howo = FastDiv((uint32_t)(nqy * nqx));
+      a.d_wo = FastDiv((uint32_t)nqx);
+      a.d_csel = FastDiv((uint32_t)Cout);
+      a.d_kw = FastDiv((uint32_t)(ntx > 0 ? ntx : 1));
+      a.d1 = 0; a.d2 = 0;  // rows never run along K in this product
+      rc.oy = g.s * qy_lo + ry - g.p;
+      rc.ox = g.s * qx_lo + rx - g.p;
+      rc.K = nty * ntx * Cout;
+      rc.M = n_img * nqy * nqx;
+      rc.tiles_m = ceil_div(rc.M, Cfg::BM);
+      rc.first = first;
+      rc.w_off = w_here;
+      first += (rc.tiles_m * t.tiles_n + 7) / 8 * 8;
+    }
+  t.n_cls = n;
+  t.total_blocks = first;
+  if (n == 0) return hipSuccess;
+  return launch_task<Cfg::NT>(t, stream);
 }
 
 template <class Cfg, bool MASK>
@@ -47,7 +102,10 @@ hipError_t vijp_t(const ConvGeom& g, int n_img, const float* x, const float* w, 
                       make_gather(g, n_img, g.k, g.s, g.p, 0, g.C),   // patches of x
                       make_gather(g, n_img, 1, g.s, 0, 0, Cout),      // h_in at (s i', s j'), first Cout channels
                       epi, ceil_div(M, Cfg::BM), ceil_div(Cout, Cfg::BN)};
-  return launch_task<Cfg::NT>(t, stream);
+  // two workgroups per CU wherever the LDS allows it: the epilogue (three stores and a mask word per
+  // element) is long, and a second workgroup's products fill it
+  constexpr int RESIDENT = (2 * ConvVijpTask<Cfg>::LDS_BYTES <= 160 * 1024 && Cfg::NT == 512) ? 2 : 1;
+  return launch_task_resident<Cfg::NT, RESIDENT>(t, stream);
 }
 
 struct DwPlan {
@@ -61,8 +119,9 @@ DwPlan plan_dw(int K1, int Cout, int64_t rows) {
   else if (Cout >= 128) { p.tile = TILE_64X128; bm = 64; bn = 128; }
   else { p.tile = TILE_64; bm = 64; bn = 64; }
   const int64_t tiles = (int64_t)ceil_div(K1, bm) * ceil_div(Cout, bn);
-  // about four workgroups per CU when the rows allow it, at least eight K tiles per slice
-  int64_t want = (1024 + tiles - 1) / tiles;
+  // four workgroups per CU when the rows allow it, never a few more than that (they would run on
+  // their own after all the others), and at least eight K tiles per slice
+  int64_t want = tiles >= 1024 ? 1 : 1024 / tiles;
   if (want > CONV_DW_MAX_SLICES) want = CONV_DW_MAX_SLICES;
   int64_t k_per = (rows + want - 1) / want;
   if (k_per < 256) k_per = 256;
@@ -82,10 +141,18 @@ hipError_t dw_t(const ConvGeom& g, int n_img, const float* x, const float* ctz, 
   return launch_task<Cfg::NT>(t, stream);
 }
 
+// The tile for a product whose K runs over (tap, channel) with csel channels per tap: what pick_tile
+// says, unless that tile's K step would straddle taps; then the 64 x 64 tile, whose K step is 32.
+int gather_tile(int M, int N, int K, int csel_a, int csel_b) {
+  const int t = pick_tile(M, N, K);
+  const int bk = t == TILE_64K2 ? 64 : (t == TILE_32K4 ? 128 : 32);
+  return (csel_a % bk == 0 && csel_b % bk == 0) ? t : TILE_64;
+}
+
 }  // namespace
 
 bool conv_gather_ok(const ConvGeom& g, int Cout, const float* x, const float* w) {
-  return g.C % 4 == 0 && Cout % 32 == 0 && aligned16(x) && aligned16(w) && (int64_t)g.k * g.k * g.C < (1 << 24);
+  return g.C % 32 == 0 && Cout % 32 == 0 && aligned16(x) && aligned16(w) && (int64_t)g.k * g.k * g.C < (1 << 24);
 }
 
 int64_t conv_gather_max_images(const ConvGeom& g, int Cout) {
@@ -100,7 +167,7 @@ hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const floa
                         float* xout, uint32_t* mask32, hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
   const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
-  switch (pick_tile(M, Cout, K1)) {
+  switch (gather_tile(M, Cout, K1, g.C, Cout)) {
     case TILE_128W8: return fwd_m<Tile128W8>(g, n_img, x, w, b, alpha, Cout, xout, mask32, stream);
     case TILE_64X128: return fwd_m<Tile64x128>(g, n_img, x, w, b, alpha, Cout, xout, mask32, stream);
     case TILE_64K2: return fwd_m<Tile64K2>(g, n_img, x, w, b, alpha, Cout, xout, mask32, stream);
@@ -117,12 +184,32 @@ hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const f
   // the leaky path of the epilogue reads the mask as 32-bit words, so a 4-byte aligned start is enough
   EpiVijp<false> epi{b, alpha, 1.0f / alpha, reinterpret_cast<const uint64_t*>(mask32), nullptr, nullptr, nullptr, 0,
                      xout, hout, ctz, mismatches};
-  switch (pick_tile(M, Cout, K1)) {  // the tile of conv_fwd_act: the recomputed signs must match bit for bit
+  switch (gather_tile(M, Cout, K1, g.C, Cout)) {  // the tile of conv_fwd_act: the recomputed signs must match bit for bit
     case TILE_128W8: return vijp_t<Tile128W8>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
     case TILE_64X128: return vijp_t<Tile64x128>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
     case TILE_64K2: return vijp_t<Tile64K2>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
     case TILE_32K4: return vijp_t<Tile32K4>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
     default: return vijp_t<Tile64>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
+  }
+}
+
+bool conv_rev_ok(const ConvGeom& g, int Cout) {
+  return g.s * g.s <= CONV_REV_MAX_CLASSES && Cout % 32 == 0 && g.C % 4 == 0;
+}
+
+hipError_t conv_input_cotangent(const ConvGeom& g, int n_img, int Cout, const float* ctz, const float* wrev, float* raw,
+                                float* ct, const uint32_t* mask32, float alpha, hipStream_t stream) {
+  if (n_img <= 0) return hipSuccess;
+  EpiConvRev epi{raw, ct, mask32, alpha, g.H, g.W, g.s, (uint32_t)((int64_t)n_img * g.H * g.W * g.C * 4)};
+  // the tile for the largest class: about a quarter of the input pixels, all taps of that class
+  const int M = n_img * ((g.H + g.s - 1) / g.s) * ((g.W + g.s - 1) / g.s);
+  const int K = class_taps(g.k, g.s, 0) * class_taps(g.k, g.s, 0) * Cout;
+  switch (gather_tile(M, g.C, K, Cout, Cout)) {
+    case TILE_128W8: return rev_t<Tile128W8>(g, n_img, Cout, ctz, wrev, epi, stream);
+    case TILE_64X128: return rev_t<Tile64x128>(g, n_img, Cout, ctz, wrev, epi, stream);
+    case TILE_64K2: return rev_t<Tile64K2>(g, n_img, Cout, ctz, wrev, epi, stream);
+    case TILE_32K4: return rev_t<Tile32K4>(g, n_img, Cout, ctz, wrev, epi, stream);
+    default: return rev_t<Tile64>(g, n_img, Cout, ctz, wrev, epi, stream);
   }
 }
 

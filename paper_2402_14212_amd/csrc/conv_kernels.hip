@@ -135,6 +135,31 @@ inline int cv_blocks(int64_t work_items) {
 }
 inline bool al16p(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// Weights regrouped for the input-cotangent products. Taps are classed by (ky mod s, kx mod s); class
+// (ry, rx) holds, for tap slots ky' < nty, kx' < ntx (ky = ry + s (nty - 1 - ky'), likewise kx), the
+// matrix [C_out][C_in] = w[ky][kx]^T, slots in row-major order, classes in (ry, rx) order.
+__device__ __forceinline__ int taps_of_class(int k, int s, int r) { return r < k ? (k - r + s - 1) / s : 0; }
+
+__global__ void __launch_bounds__(256)
+k_pack_rev_weights(const float* __restrict__ w, int k, int s, int Cin, int Cout, float* __restrict__ wrev) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n = (int64_t)k * k * Cin * Cout;
+  if (idx >= n) return;
+  const int co = (int)(idx % Cout);
+  int64_t r = idx / Cout;
+  const int ci = (int)(r % Cin);
+  r /= Cin;
+  const int kx = (int)(r % k), ky = (int)(r / k);
+  const int ry = ky % s, rx = kx % s;
+  const int nty = taps_of_class(k, s, ry), ntx = taps_of_class(k, s, rx);
+  const int kyp = nty - 1 - ky / s, kxp = ntx - 1 - kx / s;
+  int64_t taps_before = 0;  // taps of the classes before (ry, rx)
+  for (int a = 0; a < ry; ++a) taps_before += (int64_t)taps_of_class(k, s, a) * k;
+  for (int b = 0; b < rx; ++b) taps_before += (int64_t)nty * taps_of_class(k, s, b);
+  const int64_t dst = ((taps_before + (int64_t)kyp * ntx + kxp) * Cout + co) * Cin + ci;
+  wrev[dst] = w[idx];
+}
+
 }  // namespace
 
 hipError_t cv_im2col(const float* x, int H, int W, int C, int Ho, int Wo, int k, int s, int p, int64_t row0,
@@ -169,6 +194,13 @@ hipError_t cv_strided_gather(const float* h, int H, int W, int C, int Ho, int Wo
   if (n_rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(k_strided_gather, dim3(cv_blocks(n_rows * Co)), dim3(CV_THREADS), 0, stream, h, H, W, C, Ho, Wo, Co, s,
                      n_rows, out);
+  return hipGetLastError();
+}
+
+hipError_t cv_pack_rev_weights(const float* w, int k, int s, int Cin, int Cout, float* wrev, hipStream_t stream) {
+  const int64_t n = (int64_t)k * k * Cin * Cout;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_pack_rev_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, k, s, Cin, Cout, wrev);
   return hipGetLastError();
 }
 

@@ -124,7 +124,15 @@ struct Chunk {
 // [n_outer][n_inner] array with row stride ld. A transform that gathers A from somewhere else
 // (an image, for the patch matrix of a convolution) replaces these two functions.
 struct ALinearDev {
-  __device__ __forceinline__ Chunk chunk(int outer, int inner, int n_outer, int n_inner, int64_t ld) const {
+  // Called once by the main loop before the first tile is requested (row0: the tile's first row of
+  // the operand; n_rows, n_k: its extents), and once after every tile request, in tile order.
+  template <int LAYOUT, int R, int BK, int NT>
+  __device__ __forceinline__ void prepare(int /*row0*/, int /*n_rows*/, int /*n_k*/) {}
+  template <int LAYOUT, int BK>
+  __device__ __forceinline__ void advance() {}
+  // i: which of the thread's chunks of the tile this is
+  template <int LAYOUT>
+  __device__ __forceinline__ Chunk chunk(int /*i*/, int outer, int inner, int n_outer, int n_inner, int64_t ld) const {
     Chunk c;
     c.e = (uint32_t)outer * (uint32_t)ld + (uint32_t)inner;
     const int left = n_inner - inner;
@@ -203,7 +211,7 @@ struct TileLoader {
       } else {
         outer = k0 + f / (R / 4); inner = row0 + 4 * (f % (R / 4)); n_outer = n_k; n_inner = n_rows;
       }
-      const Chunk c = xf.chunk(outer, inner, n_outer, n_inner, ld);
+      const Chunk c = xf.template chunk<LAYOUT>(i, outer, inner, n_outer, n_inner, ld);
       if (VEC) {
         v[i] = buf_load_f32x4(rs, c.nvalid ? c.e * 4u : OOB);
       } else {
@@ -307,7 +315,7 @@ enum { CHAIN_NONE = 0, CHAIN_FIRST = 1, CHAIN_SECOND = 2 };
 template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, int CHAIN, class XfDev>
 __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A, int64_t lda,
                                                     const float* __restrict__ B, int64_t ldb, int M, int N, int K,
-                                                    int m0, int n0, float* __restrict__ lds, const XfDev& xf,
+                                                    int m0, int n0, float* __restrict__ lds, XfDev& xf,
                                                     f32x16 (&acc)[Cfg::NACC], float (&asum)[Cfg::WTM],
                                                     TilePipe<Cfg, LA, LB, VEC, XfDev>& p,
                                                     const float* __restrict__ A2, const float* __restrict__ B2) {
@@ -344,6 +352,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
       p.a[slot].load(ra, lda, m0, idx_ * BK, M, K, xf);                              \
       p.b[slot].load(rb, ldb, n0, idx_ * BK, N, K, none);                            \
     }                                                                                \
+    xf.template advance<LA, BK>();                                                   \
   } while (0)
 #define MW_TO_LDS(slot, stage)                                  \
   do {                                                          \
@@ -354,6 +363,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
   mma_stage<Cfg, LA, LB, COLSUM>(lds + (stage) * STAGE, lds + (stage) * STAGE + A_FLOATS, wm, wn, wk, r, g, acc, asum)
 
   if (CHAIN != CHAIN_SECOND) {
+    xf.template prepare<LA, BM, BK, Cfg::NT>(m0, M, K);
 #pragma unroll
     for (int j = 0; j < ST; ++j) MW_REQUEST(j, j);
     MW_TO_LDS(0, 0);
@@ -391,7 +401,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
 template <class Cfg, int LA, int LB, bool VEC, bool COLSUM, class XfDev>
 __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
                                               int64_t ldb, int M, int N, int K, int m0, int n0,
-                                              float* __restrict__ lds, const XfDev& xf, f32x16 (&acc)[Cfg::NACC],
+                                              float* __restrict__ lds, XfDev& xf, f32x16 (&acc)[Cfg::NACC],
                                               float (&asum)[Cfg::WTM]) {
   TilePipe<Cfg, LA, LB, VEC, XfDev> p;
   gemm_mainloop_chain<Cfg, LA, LB, VEC, COLSUM, CHAIN_NONE>(A, lda, B, ldb, M, N, K, m0, n0, lds, xf, acc, asum, p,

@@ -320,7 +320,7 @@ struct GemmTask {
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
     {
-      const typename Xf::Dev xd(xf, LA == KCONTIG ? M : K, LA == KCONTIG ? K : M, lda);
+      typename Xf::Dev xd(xf, LA == KCONTIG ? M : K, LA == KCONTIG ? K : M, lda);
       gemm_mainloop<Cfg, LA, LB, VEC, COLSUM>(A, lda, B, ldb, M, N, K, m0, n0, lds, xd, acc[0], asum);
     }
     if (COLSUM) {
@@ -379,7 +379,7 @@ struct VijpTask {
 #pragma unroll
     for (int t = 0; t < Cfg::WTM; ++t) asum[t] = 0.f;
 
-    const ANone::Dev none;
+    ANone::Dev none;
     if (K > 0 && K % (Cfg::ST * Cfg::BK) == 0) {
       // the second product's first tiles are fetched under the first product's last ones
       TilePipe<Cfg, KCONTIG, KCONTIG, VEC, ANone::Dev> pipe;
@@ -399,6 +399,15 @@ struct VijpTask {
 
 template <int NT, class Task>
 __global__ void __launch_bounds__(NT) task_kernel(Task t) {
+  extern __shared__ __align__(16) float lds[];
+  t.run((int)blockIdx.x, lds);
+}
+
+// The same with a floor on the workgroups resident per CU (the compiler keeps the register count low
+// enough for it): for kernels whose long epilogue should overlap another workgroup's main loop.
+template <int NT, int MIN_WG, class Task>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MIN_WG * NT / 256, 8)))
+task_kernel_resident(Task t) {
   extern __shared__ __align__(16) float lds[];
   t.run((int)blockIdx.x, lds);
 }
@@ -443,6 +452,15 @@ inline hipError_t ensure_lds(KernelT kernel, int bytes) {
 template <int NT, class Task>
 inline hipError_t launch_task(const Task& t, hipStream_t stream) {
   auto kernel = task_kernel<NT, Task>;
+  static hipError_t attr = ensure_lds(kernel, Task::LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kernel, dim3(t.blocks()), dim3(NT), Task::LDS_BYTES, stream, t);
+  return hipGetLastError();
+}
+
+template <int NT, int MIN_WG, class Task>
+inline hipError_t launch_task_resident(const Task& t, hipStream_t stream) {
+  auto kernel = task_kernel_resident<NT, MIN_WG, Task>;
   static hipError_t attr = ensure_lds(kernel, Task::LDS_BYTES);
   if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kernel, dim3(t.blocks()), dim3(NT), Task::LDS_BYTES, stream, t);

@@ -200,6 +200,16 @@ size_t conv_dw_part_floats(const ConvGeom& g, int n_img, int Cout);
 hipError_t conv_dw(const ConvGeom& g, int n_img, const float* x, const float* ctz, int Cout, float scale, float beta,
                    float* dW, float* part, hipStream_t stream);
 
+// whether conv_input_cotangent can be used (stride classes fit the task, channels in fours)
+bool conv_rev_ok(const ConvGeom& g, int Cout);
+// input cotangent of the layer for n_img images from ct_z [n_img][Ho][Wo][Cout]: raw (may be NULL) = h,
+// ct (may be NULL; needs C % 32 == 0) = h times the slope the previous layer's sign bits (mask32, flat
+// index of the input element) select: 1 or alpha. wrev: weights packed by cv_pack_rev_weights.
+hipError_t conv_input_cotangent(const ConvGeom& g, int n_img, int Cout, const float* ctz, const float* wrev, float* raw,
+                                float* ct, const uint32_t* mask32, float alpha, hipStream_t stream);
+// wrev (k k Cin Cout floats) = the per-stride-class transposed taps conv_input_cotangent multiplies with
+hipError_t cv_pack_rev_weights(const float* w, int k, int s, int Cin, int Cout, float* wrev, hipStream_t stream);
+
 // records the text of a failed HIP call for moonwalk_strerror and returns MW_ERR_HIP (moonwalk_api.hip)
 int record_hip_failure(hipError_t e, const char* where);
 

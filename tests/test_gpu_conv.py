@@ -167,3 +167,26 @@ def test_conv_refresh_follows_the_kernel(mw):
     T = net.ws[0][1, 1].cpu().numpy().astype(np.float64)
     assert O.normwise_rel_err(net.fetch_tap_inverse(0), np.linalg.inv(T)) < 1e-5
     net.close()
+
+
+def test_conv_refresh_rebuilds_what_both_paths_derive_from_the_weights(mw):
+    """After a weight change and refresh(), Moonwalk and the library's backprop follow the new weights
+    (tap inverses and the regrouped taps of the input-cotangent kernel)."""
+    wl = make_convnet(2, 16, 32, 2, seed=3)
+    net = mw.ConvMoonwalkNet.from_workload(wl)
+    net.moonwalk_grad(net.x, net.t)
+    for w in net.ws:
+        w.mul_(torch.tril(torch.full((32, 32), 1.25, device=w.device)) + torch.triu(torch.full((32, 32), 0.8, device=w.device), 1))
+    net.refresh()
+    w_new = [w.cpu().numpy() for w in net.ws]
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    masks = _masks(net, wl)
+    ref = CO.conv_backprop(w_new, wl.b, wl.alphas, wl.s, wl.p, wl.x, wl.t, forced_masks=masks)
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert O.normwise_rel_err(net.fetch_h0().reshape(wl.x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    bp = net.backprop_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()

@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (convolutional configurations)")
+    ap.add_argument("--h0", choices=["full", "as_read"], default="full",
+                    help="convolutional configurations: compute the input cotangent for every input element (a network with "
+                         "layers before the chain needs it; backprop then computes it too), or only what the first vijp reads")
     ap.add_argument("--segment", type=int, default=0,
                     help="segment length S of Moonwalk with rematerialisation (0 = off: the metric's configuration)")
     ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
@@ -106,10 +109,14 @@ def bench_conv(args):
     on_device = args.gen == "torch" or args.config == "conv2d"
     wl = (make_convnet_on_device if on_device else make_convnet)(c["batch"], c["side"], c["channels"], c["depth"], alpha=c["alpha"],
                                                                  seed=0, name=args.config)
-    flops_mw, flops_bp = conv_moonwalk_flops(wl), conv_backprop_flops(wl)
+    h0_full = args.h0 == "full"
+    flops_mw, flops_bp = conv_moonwalk_flops(wl, h0_full), conv_backprop_flops(wl, h0_full)
     K = args.reseed if args.reseed is not None else 2
+    h0_mode = mw.CONV_H0_FULL if h0_full else mw.CONV_H0_AS_READ
+    grads_probe = None
+    # --- Moonwalk handle only (so that its memory is its own)
     t0 = time.perf_counter()
-    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, plan=mw.PLAN_MOONWALK | (0 if args.no_backprop else mw.PLAN_BACKPROP))
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, plan=mw.PLAN_MOONWALK, input_cotangent=h0_mode)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
     grads = net.new_grads()
@@ -117,11 +124,22 @@ def bench_conv(args):
     ms_mw, wall_mw = time_steps(lambda: net.moonwalk_grad(net.x, net.t, grads, loss), args.steps, args.warmup)
     st = net.memory_stats()
     bp = {}
+    mem_bp = {}
     if not args.no_backprop:
+        grads_probe = grads.clone()
+        net.close()
+        net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_BACKPROP, input_cotangent=h0_mode)
         ms_bp, _ = time_steps(lambda: net.backprop_grad(net.x, net.t, grads, loss), args.steps, args.warmup)
-        bp = {"steps_per_s": 1e3 / ms_bp, "ms_per_step": ms_bp, "tflops": flops_bp / (ms_bp * 1e-3) / 1e12}
+        sb = net.memory_stats()
+        # the two paths' gradients against each other (each is checked against the oracle in the tests)
+        agree = float(((grads - grads_probe).double().norm() / grads.double().norm()).item())
+        bp = {"steps_per_s": 1e3 / ms_bp, "ms_per_step": ms_bp, "tflops": flops_bp / (ms_bp * 1e-3) / 1e12,
+              "flop_per_step": flops_bp, "moonwalk_vs_backprop_grad_rel_diff": agree}
+        mem_bp = {"bytes_residual": sb["bytes_bp_activations"], "bytes_input_cotangent": sb["bytes_input_cotangent"],
+                  "bytes_scratch": sb["bytes_bp_scratch"] + sb["bytes_scratch"] + sb["bytes_patches"],
+                  "bytes_packed_weights": sb["bytes_packed_weights"], "bytes_total": sb["bytes_peak"]}
     achieved = flops_mw / (ms_mw * 1e-3) / 1e12
-    residual_mw = st["bytes_masks"] + st["bytes_checkpoints"] + st["bytes_tap_inverses"]
+    residual_mw = st["bytes_masks"] + st["bytes_checkpoints"]
     out = {
         "metric": "gradient steps/s (mixed-mode Moonwalk on submersive 2-D convolutional layers, one full moonwalk_conv_grad per step)",
         "value": 1e3 / ms_mw, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -129,18 +147,19 @@ def bench_conv(args):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic (seeded, generator: %s)" % ("torch" if on_device else "numpy"),
         "config": {"workload": f"{args.config}: {wl.depth} layers of {wl.k}x{wl.k}x{wl.channels}x{wl.channels} convolution, stride {wl.s}, "
                                f"padding {wl.p}, input {wl.side}x{wl.side}x{wl.channels}, batch {wl.batch}, alpha {wl.alphas[0]}, "
-                               f"reseed K={K}"},
+                               f"reseed K={K}, input cotangent {'for every input element' if h0_full else 'as the first vijp reads it'}"},
         "tflops": achieved, "flop_per_step": flops_mw,
         "mfma_frac_whole_step": achieved / MFMA_F32_PEAK_TFLOPS,
-        "roofline": {"bound": "mfma", "kernel": "whole step (GEMMs on gathered patch matrices, gathers and elementwise kernels included)",
+        "roofline": {"bound": "mfma", "kernel": "whole step (products with gathered patch matrices, reductions and elementwise kernels included)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None},
         "setup_s": setup_s,
         "memory": {"moonwalk": {"bytes_masks": st["bytes_masks"], "bytes_checkpoints": st["bytes_checkpoints"],
-                                "bytes_tap_inverses": st["bytes_tap_inverses"], "bytes_residual": residual_mw,
-                                "bytes_input_cotangent": st["bytes_input_cotangent"], "bytes_scratch": st["bytes_scratch"],
-                                "bytes_patches": st["bytes_patches"]},
-                   "backprop": {"bytes_residual": st["bytes_bp_activations"], "bytes_scratch": st["bytes_bp_scratch"]},
+                                "bytes_residual": residual_mw, "bytes_tap_inverses": st["bytes_tap_inverses"],
+                                "bytes_packed_weights": st["bytes_packed_weights"],
+                                "bytes_input_cotangent": st["bytes_input_cotangent"],
+                                "bytes_scratch": st["bytes_scratch"] + st["bytes_patches"], "bytes_total": st["bytes_peak"]},
+                   "backprop": mem_bp,
                    "bytes_input": int(wl.batch) * wl.side * wl.side * wl.channels * 4},
         "backprop": bp,
     }

@@ -211,6 +211,8 @@ typedef struct mw_conv_handle mw_conv_handle_t;
 
 #define MW_CONV_KERNELS_AUTO 0
 #define MW_CONV_KERNELS_PATCH_MATRIX 1
+#define MW_CONV_H0_FULL 0
+#define MW_CONV_H0_AS_READ 1
 
 typedef struct {
   int32_t channels_in, channels_out, k, stride, pad;
@@ -228,6 +230,14 @@ typedef struct {
                                     kernels that gather the patch matrix inside the product (forward, Phase
                                     III, weight gradient); MW_CONV_KERNELS_PATCH_MATRIX: every layer goes
                                     through the patch buffer                                             */
+  int32_t input_cotangent;       /* MW_CONV_H0_FULL: Phase II ends with h_0 for every input element (a caller
+                                    with layers before this chain continues its own reverse pass from it),
+                                    and backprop_conv_grad computes the same h_0 at the end of its sweep;
+                                    MW_CONV_H0_AS_READ: only the entries the first layer's vijp reads are
+                                    computed and kept, [B][H'][W'][C_out] of layer 0 (the strided positions,
+                                    the first C_out channels), and the first layer's reverse product is
+                                    skipped                                                              */
+  int32_t reserved;
   size_t  patch_bytes;           /* size of the buffer the image chunks' patch matrices are gathered into
                                     (0 = 256 MiB); at least one image's patches are always taken        */
   void* (*dev_alloc)(size_t bytes, void* ctx);
@@ -240,8 +250,9 @@ typedef struct {
   uint64_t bytes_tap_inverses;     /* T^{-1}, C_out^2 floats per layer                                   */
   uint64_t bytes_packed_weights;   /* taps regrouped by stride class for the input-cotangent kernel: one
                                       copy of every layer's weights that takes the gathered kernels      */
-  uint64_t bytes_checkpoints;      /* re-seed cotangents                                                 */
-  uint64_t bytes_input_cotangent;  /* h_0: as large as the network input                                 */
+  uint64_t bytes_checkpoints;      /* re-seed cotangents, each as the next layer's vijp reads it:
+                                      [B][H'][W'][C_out] of that layer                                   */
+  uint64_t bytes_input_cotangent;  /* h_0: as large as the network input, or as read (see the config)   */
   uint64_t bytes_scratch;          /* ping-pong activations / cotangents, z, ct_z, right-hand sides      */
   uint64_t bytes_patches;          /* the patch buffer (shared by both paths)                            */
   uint64_t bytes_bp_activations;   /* backprop: stored layer outputs                                     */
@@ -262,7 +273,9 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
                        void* hip_stream);
 int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
 int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out);
-/* what: MW_FETCH_MASK, MW_FETCH_H0, MW_FETCH_P (here: T^{-1}, float[C_out^2]) or MW_FETCH_CHECKPOINT. */
+/* what: MW_FETCH_MASK, MW_FETCH_H0 (whole or as read, see the config), MW_FETCH_P (here: T^{-1},
+   float[C_out^2]) or MW_FETCH_CHECKPOINT (the cotangent kept at the output of `layer`, in the
+   [B][H'][W'][C_out] form of layer + 1). */
 int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap, size_t* n_bytes);
 void moonwalk_conv_destroy(mw_conv_handle_t* h);
 

@@ -178,14 +178,15 @@ def conv_backprop(ws, bs, alphas, s: int, p: int, x0, t, forced_masks=None) -> D
     xs, zs, masks = conv_forward(ws, bs, alphas, s, p, x0, forced_masks)
     loss, h = loss_and_cotangent(xs[-1], t)
     L = len(ws)
-    dW, db = [None] * L, [None] * L
+    dW, db, hs = [None] * L, [None] * L, [None] * L
     for i in range(L - 1, -1, -1):
         ct_z = h * np.where(masks[i], 1.0, alphas[i])
         k = np.shape(ws[i])[0]
         dW[i] = conv2d_weight_grad(xs[i], ct_z, k, s, p)
         db[i] = ct_z.sum(axis=(0, 1, 2))
         h = conv2d_input_grad(ct_z, ws[i], s, p, xs[i].shape[1:3])
-    return {"dW": dW, "db": db, "loss": loss, "masks": masks, "h0": h, "xs": xs}
+        hs[i] = h  # the cotangent at the input of layer i (hs[0] is h_0)
+    return {"dW": dW, "db": db, "loss": loss, "masks": masks, "h0": h, "hs": hs, "xs": xs}
 
 
 def conv_moonwalk(ws, bs, alphas, s: int, p: int, x0, t, forced_masks=None, loss_scale: float = 1.0,

@@ -60,7 +60,8 @@ class _ConvLayer(C.Structure):
 
 class _ConvConfig(C.Structure):
     _fields_ = [("batch", C.c_int32), ("height", C.c_int32), ("width", C.c_int32), ("reseed_interval", C.c_int32),
-                ("loss_scale", C.c_float), ("plan", C.c_int32), ("kernels", C.c_int32), ("patch_bytes", C.c_size_t),
+                ("loss_scale", C.c_float), ("plan", C.c_int32), ("kernels", C.c_int32), ("input_cotangent", C.c_int32),
+                ("reserved", C.c_int32), ("patch_bytes", C.c_size_t),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p)]
 
 
@@ -371,6 +372,7 @@ class MoonwalkNet:
 
 
 CONV_KERNELS_AUTO, CONV_KERNELS_PATCH_MATRIX = 0, 1
+CONV_H0_FULL, CONV_H0_AS_READ = 0, 1
 
 
 class ConvMoonwalkNet:
@@ -378,12 +380,14 @@ class ConvMoonwalkNet:
 
     ws: kernels [k][k][C_in][C_out]; bs: biases or None; one stride and padding for all layers.
     kernels: CONV_KERNELS_AUTO (patch matrix gathered inside the products where the channel counts
-    allow it) or CONV_KERNELS_PATCH_MATRIX (always through the patch buffer)."""
+    allow it) or CONV_KERNELS_PATCH_MATRIX (always through the patch buffer).
+    input_cotangent: CONV_H0_FULL (h_0 for every input element) or CONV_H0_AS_READ (only the entries
+    the first layer's vijp reads; the first layer's reverse product is skipped)."""
 
     def __init__(self, ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, height: int, width: int, stride: int, pad: int, reseed_interval: int = 0,
                  loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0,
-                 kernels: int = 0):
+                 kernels: int = 0, input_cotangent: int = 0):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -423,7 +427,7 @@ class ConvMoonwalkNet:
             layers[i] = _ConvLayer(w.shape[2], w.shape[3], w.shape[0], self.stride, self.pad, _ptr(w),
                                    _ptr(_f32(b)) if b is not None else None, a)
         cfg = _ConvConfig(self.batch, self.height, self.width, int(reseed_interval), float(loss_scale), int(plan),
-                          int(kernels), int(patch_bytes), self._alloc_cb, self._free_cb, None)
+                          int(kernels), int(input_cotangent), 0, int(patch_bytes), self._alloc_cb, self._free_cb, None)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_conv_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()
@@ -493,6 +497,10 @@ class ConvMoonwalkNet:
 
     def fetch_h0(self) -> np.ndarray:
         return self._fetch(0, FETCH_H0, np.float32)
+
+    def fetch_checkpoint(self, layer: int) -> np.ndarray:
+        """The cotangent kept at the output of `layer`, as layer + 1 reads it: [B][H'][W'][C_out] of layer + 1."""
+        return self._fetch(layer, FETCH_CHECKPOINT, np.float32)
 
     def fetch_tap_inverse(self, layer: int) -> np.ndarray:
         c = self.ws[layer].shape[3]

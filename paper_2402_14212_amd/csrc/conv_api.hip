@@ -49,7 +49,8 @@ struct ConvLayer {
   bool gather_rev = false;      // that product instead of patches + col2im
   uint64_t* mask = nullptr;
   size_t mask_words = 0;
-  float* ckpt = nullptr;        // kept cotangent at this layer's output
+  float* ckpt = nullptr;        // kept cotangent at this layer's output, as the next layer's vijp reads it:
+                                // [next.rows][next.Cout] = the strided positions, the first next.Cout channels
   float* act = nullptr;         // backprop: stored output activation
   size_t dW_off = 0, db_off = 0;
   int chunk_images = 1;         // images per patch-buffer fill
@@ -65,6 +66,7 @@ struct ConvLayer {
 struct mw_conv_handle {
   std::vector<ConvLayer> layers;
   int B = 0, L = 0, Kre = 0, plan = 0;
+  bool h0_full = true;          // h_0 for every input element (else only what the first layer's vijp reads)
   float loss_scale = 1.f;
   void* (*dev_alloc)(size_t, void*) = nullptr;
   void (*dev_free)(void*, void*) = nullptr;
@@ -162,6 +164,21 @@ int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, flo
   return MW_OK;
 }
 
+// The part of the layer's input cotangent its own vijp reads, sub(h)[:, :Cout] (the strided positions,
+// the first Cout channels), straight from ct_z: in the fully parallel case only the tap at (p, p)
+// reaches those entries, so it is ct_z T^T with T the first Cout rows of that tap (Alg. 2 read backwards).
+int conv_kept_cotangent(mw_conv_handle* h, const ConvLayer& l, const float* ctz, float* kept, hipStream_t s) {
+  const float* tap = l.w + ((size_t)(l.p * l.k + l.p) * l.Cin) * l.Cout;  // [Cin][Cout]; rows c < Cout are T
+  const int64_t per_img = (int64_t)l.Ho * l.Wo;
+  for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+    const int64_t n_img = (img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0;
+    const int64_t r0 = img0 * per_img, R = n_img * per_img;
+    CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, ctz + r0 * l.Cout, l.Cout, tap, l.Cout, 0.f,
+                      kept + r0 * l.Cout, l.Cout, nullptr, s));
+  }
+  return MW_OK;
+}
+
 // forward of one layer for the whole batch: xout = act(conv(xin) + b); mask (may be NULL) gets the signs
 int conv_forward_layer(mw_conv_handle* h, const ConvLayer& l, const float* xin, float* xout, uint64_t* mask, hipStream_t s) {
   if (l.gather) {
@@ -221,6 +238,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
   if (cfg->kernels != MW_CONV_KERNELS_AUTO && cfg->kernels != MW_CONV_KERNELS_PATCH_MATRIX) return MW_ERR_INVALID_ARG;
+  if (cfg->input_cotangent != MW_CONV_H0_FULL && cfg->input_cotangent != MW_CONV_H0_AS_READ) return MW_ERR_INVALID_ARG;
   int Hc = cfg->height, Wc = cfg->width;
   const int64_t limit = (int64_t)0x7FFFFFFF;
   for (int i = 0; i < n_layers; ++i) {
@@ -247,12 +265,13 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   h->Kre = cfg->reseed_interval;
   h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
   h->loss_scale = cfg->loss_scale;
+  h->h0_full = cfg->input_cotangent == MW_CONV_H0_FULL;
   h->dev_alloc = cfg->dev_alloc ? cfg->dev_alloc : cv_default_alloc;
   h->dev_free = cfg->dev_free ? cfg->dev_free : cv_default_free;
   h->alloc_ctx = cfg->alloc_ctx;
   h->layers.resize(n_layers);
   const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
-  size_t off = 0, max_out = 0, max_patch = 0, max_part = 1, max_cout = 1;
+  size_t off = 0, max_out = 0, max_odd = 1, max_patch = 0, max_part = 1, max_cout = 1;
   bool any_patch_layer = false, need_patches = false;
   Hc = cfg->height;
   Wc = cfg->width;
@@ -291,10 +310,14 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     l.chunk_images = (int)ci;
     const ConvGeom g = l.geom();
     const int64_t gmax = conv_gather_max_images(g, l.Cout);
-    l.gather = cfg->kernels == MW_CONV_KERNELS_AUTO && gmax >= 1 && conv_gather_ok(g, l.Cout, nullptr, l.w);
+    if (gmax < 1) {
+      delete h;
+      return MW_ERR_INVALID_ARG;  // a single image does not fit a GEMM operand
+    }
+    l.gchunk = (int)(gmax < h->B ? gmax : h->B);
+    l.gather = cfg->kernels == MW_CONV_KERNELS_AUTO && conv_gather_ok(g, l.Cout, nullptr, l.w);
     l.gather_rev = l.gather && conv_rev_ok(g, l.Cout);
     if (l.gather) {
-      l.gchunk = (int)(gmax < h->B ? gmax : h->B);
       const size_t part = conv_dw_part_floats(g, l.gchunk, l.Cout);
       if (part > max_part) max_part = part;
     } else {
@@ -304,6 +327,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if ((size_t)l.Cout > max_cout) max_cout = (size_t)l.Cout;
     if (ci * per_img > max_patch) max_patch = ci * per_img;
     if ((size_t)l.n_out > max_out) max_out = (size_t)l.n_out;
+    if ((i & 1) && (size_t)l.n_out > max_odd) max_odd = (size_t)l.n_out;
     Hc = l.Ho;
     Wc = l.Wo;
   }
@@ -337,19 +361,25 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if (!ok) return fail(MW_ERR_OOM);
     if (h->Kre > 0)
       for (int j = 1; j < n_layers; ++j)
-        if (j % h->Kre == 0) ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j - 1].n_out, &st.bytes_checkpoints);
-    ok = ok && cv_alloc(h, &h->xa, max_out, &st.bytes_scratch) && cv_alloc(h, &h->xb, max_out, &st.bytes_scratch) &&
-         cv_alloc(h, &h->ha, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hb, max_out, &st.bytes_scratch) &&
+        if (j % h->Kre == 0)
+          ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j].rows * h->layers[j].Cout, &st.bytes_checkpoints);
+    // activations and cotangents alternate between an "even layer" and an "odd layer" buffer; the odd
+    // ones never hold the first layer's output, the largest by far when the resolution shrinks
+    ok = ok && cv_alloc(h, &h->xa, max_out, &st.bytes_scratch) && cv_alloc(h, &h->xb, max_odd, &st.bytes_scratch) &&
+         cv_alloc(h, &h->ha, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hb, max_odd, &st.bytes_scratch) &&
          cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
-         cv_alloc(h, &h->h0, (size_t)h->layers[0].n_in, &st.bytes_input_cotangent);
+         cv_alloc(h, &h->h0, h->h0_full ? (size_t)h->layers[0].n_in : (size_t)h->layers[0].rows * h->layers[0].Cout,
+                  &st.bytes_input_cotangent);
     if (any_patch_layer)  // pre-activations and right-hand sides exist in memory only on the patch-matrix path
       ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   if (h->plan & MW_PLAN_BACKPROP) {
     for (auto& l : h->layers) ok = ok && cv_alloc(h, &l.act, (size_t)l.n_out, &st.bytes_bp_activations);
+    if (!(h->plan & MW_PLAN_MOONWALK) && h->h0_full)
+      ok = ok && cv_alloc(h, &h->h0, (size_t)h->layers[0].n_in, &st.bytes_input_cotangent);
     if (!(h->plan & MW_PLAN_MOONWALK))
-      ok = ok && cv_alloc(h, &h->ha, max_out, &st.bytes_bp_scratch) && cv_alloc(h, &h->hb, max_out, &st.bytes_bp_scratch) &&
+      ok = ok && cv_alloc(h, &h->ha, max_out, &st.bytes_bp_scratch) && cv_alloc(h, &h->hb, max_odd, &st.bytes_bp_scratch) &&
            cv_alloc(h, &h->ctz, max_out, &st.bytes_bp_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
@@ -397,26 +427,31 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     const ConvLayer& last = h->layers[L - 1];
     CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
   }
-  // ---------------- Phase II: reverse, input cotangent only. ct_z travels between two buffers; the
-  // cotangent h itself is kept only where Phase III starts from it (h_0 and the re-seed points).
+  // ---------------- Phase II: reverse, input cotangent only. ct_z of layer i lives in ctbuf[i % 2]; the
+  // cotangent h itself is kept only where Phase III starts from it (h_0 and the re-seed points), and
+  // there in the form the vijp reads it.
   {
     float* ctbuf[2] = {h->ctz, h->hb};
-    int cur = 0;
     const ConvLayer& top = h->layers[L - 1];
-    CV_HIP(ew_rev_scale(h->ha, top.mask, top.n_out, top.alpha, ctbuf[0], s));
+    CV_HIP(ew_rev_scale(h->ha, top.mask, top.n_out, top.alpha, ctbuf[(L - 1) & 1], s));
     for (int i = L - 1; i >= 0; --i) {
       ConvLayer& l = h->layers[i];
       const ConvLayer* prev = i > 0 ? &h->layers[i - 1] : nullptr;
-      float* keep = (i == 0) ? h->h0 : prev->ckpt;  // may be NULL
-      float* ct_next = prev ? ctbuf[cur ^ 1] : nullptr;
+      const float* ct = ctbuf[i & 1];
+      float* kept = prev ? prev->ckpt : (h->h0_full ? nullptr : h->h0);
+      if (kept) {
+        int rc = conv_kept_cotangent(h, l, ct, kept, s);
+        if (rc != MW_OK) return rc;
+      }
+      if (!prev && !h->h0_full) break;  // nothing else reads h_0
+      float* ct_next = prev ? ctbuf[(i - 1) & 1] : nullptr;
       bool fused = false;
-      // a layer that cannot scale in its epilogue leaves h somewhere: where it is kept, else in ha (free by now)
+      // a layer that cannot scale in its epilogue leaves h in ha (free since the line above the loop)
       const bool can_fuse = l.gather_rev && prev && l.Cin % 32 == 0;
-      float* raw = keep ? keep : (can_fuse ? nullptr : h->ha);
-      int rc = conv_input_grad(h, l, ctbuf[cur], raw, ct_next, prev, &fused, s);
+      float* raw = prev ? (can_fuse ? nullptr : h->ha) : h->h0;
+      int rc = conv_input_grad(h, l, ct, raw, ct_next, prev, &fused, s);
       if (rc != MW_OK) return rc;
       if (prev && !fused) CV_HIP(ew_rev_scale(raw, prev->mask, prev->n_out, prev->alpha, ct_next, s));
-      cur ^= 1;
     }
   }
   // ---------------- Phase III: forward vijp sweep
@@ -424,9 +459,13 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   float* hbuf[2] = {h->ha, h->hb};
   xin = x;
   const float* hin = h->h0;
+  bool hin_as_read = !h->h0_full;  // hin holds [rows][Cout] = what this layer's vijp reads, not a whole activation
   for (int i = 0; i < L; ++i) {
     ConvLayer& l = h->layers[i];
-    if (i > 0 && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
+    if (i > 0 && h->layers[i - 1].ckpt) {  // re-seed
+      hin = h->layers[i - 1].ckpt;
+      hin_as_read = true;
+    }
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
     if (l.gather) {
@@ -434,21 +473,25 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
       for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
         const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
         const int64_t o = img0 * l.out_img();
-        CV_HIP(conv_vijp_layer(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, hin + img0 * l.in_img(),
-                               l.Tinv, reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, h->ctz + o,
+        CV_HIP(conv_vijp_layer(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout,
+                               hin + img0 * (hin_as_read ? l.out_img() : l.in_img()), hin_as_read ? 1 : 0, l.Tinv, reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, h->ctz + o,
                                mismatches, s));
       }
       int rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
       if (rc != MW_OK) return rc;
     } else {
       // vijp of the convolution: right-hand sides at the strided positions, then the channel solve as a product
-      CV_HIP(cv_strided_gather(hin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.Cout, l.s, l.rows, h->hsub, s));
+      const float* rhs = hin;
+      if (!hin_as_read) {
+        CV_HIP(cv_strided_gather(hin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.Cout, l.s, l.rows, h->hsub, s));
+        rhs = h->hsub;
+      }
       const int64_t per_img = (int64_t)l.Ho * l.Wo;
       bool first = true;
       for (int64_t img0 = 0; img0 < h->B; img0 += l.chunk_images) {
         const int64_t n_img = (img0 + l.chunk_images <= h->B) ? l.chunk_images : h->B - img0;
         const int64_t r0 = img0 * per_img, R = n_img * per_img;
-        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, h->hsub + r0 * l.Cout, l.Cout, l.Tinv, l.Cout, 0.f,
+        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, rhs + r0 * l.Cout, l.Cout, l.Tinv, l.Cout, 0.f,
                           h->ctz + r0 * l.Cout, l.Cout, nullptr, s));
         int rc = conv_rows(h, l, xin, r0, R, h->zbuf, s);  // recompute z; the patches stay in the buffer
         if (rc != MW_OK) return rc;
@@ -463,6 +506,7 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     }
     xin = xout;
     hin = hout;
+    hin_as_read = false;
   }
   return MW_OK;
 }
@@ -497,8 +541,10 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
       int rc = conv_weight_grad(h, l, xprev, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
       if (rc != MW_OK) return rc;
     }
-    if (i > 0) {
-      float* hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
+    if (i > 0 || h->h0_full) {
+      // the cotangent at the output of layer j < L - 1 lives in hbuf[j % 2] (hb is sized for the odd layers
+      // only); h_L was in ha and has gone into ct_z by now, so ha may be written even when it held h_L
+      float* hout = i > 0 ? hbuf[(i - 1) & 1] : h->h0;
       int rc = conv_input_grad(h, l, h->ctz, hout, nullptr, nullptr, nullptr, s);
       if (rc != MW_OK) return rc;
       hcur = hout;
@@ -537,9 +583,16 @@ int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* 
   size_t bytes = 0;
   switch (what) {
     case MW_FETCH_MASK: src = h->layers[layer].mask; bytes = h->layers[layer].mask_words * 8; break;
-    case MW_FETCH_H0: src = h->h0; bytes = (size_t)h->layers[0].n_in * 4; break;
+    case MW_FETCH_H0:
+      src = h->h0;
+      bytes = (h->h0_full ? (size_t)h->layers[0].n_in : (size_t)h->layers[0].rows * h->layers[0].Cout) * 4;
+      break;
     case MW_FETCH_P: src = h->layers[layer].Tinv; bytes = (size_t)h->layers[layer].Cout * h->layers[layer].Cout * 4; break;
-    case MW_FETCH_CHECKPOINT: src = h->layers[layer].ckpt; bytes = (size_t)h->layers[layer].n_out * 4; break;
+    case MW_FETCH_CHECKPOINT:
+      if (layer + 1 >= h->L) return MW_ERR_INVALID_ARG;
+      src = h->layers[layer].ckpt;
+      bytes = (size_t)h->layers[layer + 1].rows * h->layers[layer + 1].Cout * 4;
+      break;
     default: return MW_ERR_INVALID_ARG;
   }
   if (!src) return MW_ERR_INVALID_ARG;

@@ -95,12 +95,15 @@ hipError_t fwd_m(const ConvGeom& g, int n_img, const float* x, const float* w, c
 }
 
 template <class Cfg>
-hipError_t vijp_t(const ConvGeom& g, int n_img, const float* x, const float* w, int Cout, const float* hin,
+hipError_t vijp_t(const ConvGeom& g, int n_img, const float* x, const float* w, int Cout, const float* hin, int hin_as_read,
                   const float* Tinv, const EpiVijp<false>& epi, hipStream_t stream) {
   const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
+  // the right-hand sides: h_in at (s i', s j'), first Cout channels, or already laid out that way
+  const ConvGeom rows_only{g.Ho, g.Wo, Cout, g.Ho, g.Wo, 1, 1, 0};
+  const AConvPatch gh = hin_as_read ? make_gather(rows_only, n_img, 1, 1, 0, 0, Cout) : make_gather(g, n_img, 1, g.s, 0, 0, Cout);
   ConvVijpTask<Cfg> t{M, Cout, K1, x, w, hin, Tinv,
                       make_gather(g, n_img, g.k, g.s, g.p, 0, g.C),   // patches of x
-                      make_gather(g, n_img, 1, g.s, 0, 0, Cout),      // h_in at (s i', s j'), first Cout channels
+                      gh,
                       epi, ceil_div(M, Cfg::BM), ceil_div(Cout, Cfg::BN)};
   // two workgroups per CU wherever the LDS allows it: the epilogue (three stores and a mask word per
   // element) is long, and a second workgroup's products fill it
@@ -177,7 +180,7 @@ hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const floa
 }
 
 hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
-                           const float* hin, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
+                           const float* hin, int hin_as_read, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
                            unsigned long long* mismatches, hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
   const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
@@ -185,11 +188,11 @@ hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const f
   EpiVijp<false> epi{b, alpha, 1.0f / alpha, reinterpret_cast<const uint64_t*>(mask32), nullptr, nullptr, nullptr, 0,
                      xout, hout, ctz, mismatches};
   switch (gather_tile(M, Cout, K1, g.C, Cout)) {  // the tile of conv_fwd_act: the recomputed signs must match bit for bit
-    case TILE_128W8: return vijp_t<Tile128W8>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
-    case TILE_64X128: return vijp_t<Tile64x128>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
-    case TILE_64K2: return vijp_t<Tile64K2>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
-    case TILE_32K4: return vijp_t<Tile32K4>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
-    default: return vijp_t<Tile64>(g, n_img, x, w, Cout, hin, Tinv, epi, stream);
+    case TILE_128W8: return vijp_t<Tile128W8>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
+    case TILE_64X128: return vijp_t<Tile64x128>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
+    case TILE_64K2: return vijp_t<Tile64K2>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
+    case TILE_32K4: return vijp_t<Tile32K4>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
+    default: return vijp_t<Tile64>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
   }
 }
 

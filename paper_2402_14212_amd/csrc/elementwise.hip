@@ -555,6 +555,30 @@ k_colsum(const float* __restrict__ a, int64_t rows, int64_t rows_per_block, int 
   }
 }
 
+// The same sum for short vectors and many slices, where one thread per element would walk the slices
+// one memory round trip at a time: REDUCE_GROUPS threads share an element, thread g adds the slices
+// g, g + REDUCE_GROUPS, ... and the group sums are added in group order. (A different, equally fixed,
+// association of the same terms.)
+constexpr int REDUCE_ELEMS = 16, REDUCE_GROUPS = 16;
+__global__ void __launch_bounds__(REDUCE_ELEMS* REDUCE_GROUPS)
+k_reduce_slices_short(const float* __restrict__ part, int slices, int64_t n, float scale, float beta, float* __restrict__ out) {
+  __shared__ float sums[REDUCE_GROUPS][REDUCE_ELEMS];
+  const int e = threadIdx.x % REDUCE_ELEMS, g = threadIdx.x / REDUCE_ELEMS;
+  const int64_t i = (int64_t)blockIdx.x * REDUCE_ELEMS + e;
+  float t = 0.f;
+  if (i < n)
+    for (int k = g; k < slices; k += REDUCE_GROUPS) t += part[(int64_t)k * n + i];
+  sums[g][e] = t;
+  __syncthreads();
+  if (g == 0 && i < n) {
+    float r = sums[0][e];
+    for (int q = 1; q < REDUCE_GROUPS; ++q) r += sums[q][e];
+    r *= scale;
+    if (beta != 0.f) r += beta * out[i];
+    out[i] = r;
+  }
+}
+
 // out[i] = scale * (part[0][i] + part[1][i] + ... in slice order) + beta * out[i]
 __global__ void __launch_bounds__(EW_THREADS)
 k_reduce_slices(const float* __restrict__ part, int slices, int64_t n, float scale, float beta, float* __restrict__ out,
@@ -893,7 +917,7 @@ hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* ou
 int ew_colsum_slices(int64_t rows, int d) {
   // enough workgroups to keep every memory channel busy, at least 1024 rows each
   const int col_blocks = (d + COLSUM_COLS - 1) / COLSUM_COLS;
-  int64_t want = (2048 + col_blocks - 1) / col_blocks;
+  int64_t want = (1024 + col_blocks - 1) / col_blocks;
   const int64_t most = (rows + 1023) / 1024;
   if (want > most) want = most;
   if (want > COLSUM_MAX_SLICES) want = COLSUM_MAX_SLICES;
@@ -915,6 +939,11 @@ hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, floa
 
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream) {
   if (n <= 0 || slices <= 0) return hipSuccess;
+  if (n <= 8192 && slices >= 2 * REDUCE_GROUPS) {
+    hipLaunchKernelGGL(k_reduce_slices_short, dim3((unsigned)((n + REDUCE_ELEMS - 1) / REDUCE_ELEMS)),
+                       dim3(REDUCE_ELEMS * REDUCE_GROUPS), 0, stream, part, slices, n, scale, beta, out);
+    return hipGetLastError();
+  }
   const int vec = (n % 4 == 0) && al16(part) && al16(out);
   const int64_t threads = vec ? n / 4 : n;
   hipLaunchKernelGGL(k_reduce_slices, dim3((unsigned)((threads + EW_THREADS - 1) / EW_THREADS)), dim3(EW_THREADS), 0, stream,

@@ -140,7 +140,7 @@ constexpr int COLSUM_MAX_SLICES = 512;
 int ew_colsum_slices(int64_t rows, int d);
 hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, float beta, float* out, float* scratch,
                           hipStream_t stream);
-// out[i] = scale * (part[0][i] + part[1][i] + ..., in that order) + beta * out[i]; part is [slices][n]
+// out[i] = scale * (sum over the slices of part[.][i], in an order fixed by slices and n) + beta * out[i]; part is [slices][n]
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream);
 constexpr int LOSS_BLOCKS = 2048;  // most workgroups (and scratch doubles) the loss reduction uses
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
@@ -189,9 +189,10 @@ int64_t conv_gather_max_images(const ConvGeom& g, int Cout);
 hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                         float* xout, uint32_t* mask32, hipStream_t stream);
 // Phase III of a leaky convolutional layer for n_img images: z recomputed from x, ct_z = sub(h_in) Tinv^T,
-// x out, h out = ct_z / slope, sign check against mask32
+// x out, h out = ct_z / slope, sign check against mask32. hin_as_read: hin is sub(h_in) itself,
+// [rows][Cout], instead of the whole input cotangent [n_img][H][W][C]
 hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
-                           const float* hin, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
+                           const float* hin, int hin_as_read, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
                            unsigned long long* mismatches, hipStream_t stream);
 // dW[K1][Cout] = scale * patches(x)^T ct_z + beta * dW, the patch rows split into slices whose partial
 // products (part: conv_dw_part_floats floats) are added in slice order

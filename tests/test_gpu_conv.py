@@ -112,6 +112,13 @@ def test_conv_moonwalk_matches_the_oracle(mw, name):
     assert max(eb) <= GRAD_TOL, eb
     h0 = net.fetch_h0().reshape(wl.x.shape).astype(np.float64)
     assert O.normwise_rel_err(h0, ref["h0"]) <= 1e-4
+    # the re-seed cotangents: kept as the next layer's vijp reads them (strided positions, its C_out channels)
+    if K > 0:
+        for j in range(K, depth, K):
+            side = wl.sides[j + 1]
+            want = ref["hs"][j][:, ::s, ::s, :C][:, :side, :side]
+            got = net.fetch_checkpoint(j - 1).reshape(want.shape).astype(np.float64)
+            assert O.normwise_rel_err(got, want) <= 1e-4, j
     # the tap inverses
     for i in range(depth):
         T = wl.w[i][p, p].astype(np.float64)
@@ -121,6 +128,7 @@ def test_conv_moonwalk_matches_the_oracle(mw, name):
     torch.cuda.synchronize()
     assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
     assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.db, ref["db"])) <= 1e-4
+    assert O.normwise_rel_err(net.fetch_h0().reshape(wl.x.shape).astype(np.float64), ref["h0"]) <= 1e-5   # backprop's h_0
     # determinism
     res2 = net.moonwalk_grad(net.x, net.t)
     torch.cuda.synchronize()
@@ -189,4 +197,35 @@ def test_conv_refresh_rebuilds_what_both_paths_derive_from_the_weights(mw):
     bp = net.backprop_grad(net.x, net.t)
     torch.cuda.synchronize()
     assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()
+
+
+@pytest.mark.parametrize("name", ["small", "gather_odd", "gather_deep", "wide_patches"])
+def test_conv_moonwalk_with_the_input_cotangent_as_read(mw, name):
+    """CONV_H0_AS_READ: Phase II stops at what the first layer's vijp reads; the gradients are the same
+    (to rounding: the first layer's right-hand sides are the same numbers) and h_0 shrinks to
+    [B][H'][W'][C_out]."""
+    B, side, C, depth, k, s, p, alpha, K, patch_bytes, kernels = CONV_CASES[name]
+    wl = make_convnet(B, side, C, depth, k=k, s=s, p=p, alpha=alpha, seed=1, name=name)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels,
+                                           plan=mw.PLAN_MOONWALK, input_cotangent=mw.CONV_H0_AS_READ)
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    st = net.memory_stats()
+    assert st["sign_mismatches"] == 0
+    masks = _masks(net, wl)
+    ref = CO.conv_backprop(wl.w, wl.b, wl.alphas, s, p, wl.x, wl.t, forced_masks=masks)
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    s1 = wl.sides[1]
+    want = ref["h0"][:, ::s, ::s, :C][:, :s1, :s1]
+    got = net.fetch_h0().reshape(want.shape).astype(np.float64)
+    assert O.normwise_rel_err(got, want) <= 1e-4
+    assert st["bytes_input_cotangent"] == 4 * want.size
+    full = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels,
+                                            plan=mw.PLAN_MOONWALK)
+    res_full = full.moonwalk_grad(full.x, full.t)
+    torch.cuda.synchronize()
+    assert O.normwise_rel_err(res.flat.cpu().numpy(), res_full.flat.cpu().numpy().astype(np.float64)) <= 1e-5
+    full.close()
     net.close()

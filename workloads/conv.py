@@ -69,21 +69,27 @@ def make_convnet(batch: int, side: int, channels: int, depth: int, k: int = 3, s
                         w=ws, b=bs, x=x, t=t, sides=sides, seed=int(seed), name=name)
 
 
-def conv_moonwalk_flops(wl: ConvWorkload) -> int:
-    """Algorithmic flops of one Moonwalk step: per layer three products of 2 rows' (k k C) C (forward,
-    recompute, weight gradient), the input-gradient product of the same size, and the channel solve."""
+def conv_moonwalk_flops(wl: ConvWorkload, h0_full: bool = True) -> int:
+    """Algorithmic flops of one Moonwalk step. Per layer, with P = 2 rows' (k k C) C the flops of one
+    product with the patch matrix: forward, recomputed forward and weight gradient (3 P), the input
+    cotangent (P; not for the first layer unless h_0 is wanted for every input element), and the
+    channel solve of the vijp (2 rows' C C)."""
     total = 0
     for i in range(wl.depth):
         rows = wl.batch * wl.sides[i + 1] ** 2
-        total += 4 * 2 * rows * wl.k * wl.k * wl.channels * wl.channels + 2 * rows * wl.channels * wl.channels
+        P = 2 * rows * wl.k * wl.k * wl.channels * wl.channels
+        total += 3 * P + (P if (i > 0 or h0_full) else 0) + 2 * rows * wl.channels * wl.channels
     return total
 
 
-def conv_backprop_flops(wl: ConvWorkload) -> int:
+def conv_backprop_flops(wl: ConvWorkload, h0_full: bool = True) -> int:
+    """Forward and weight gradient per layer (2 P), the input cotangent (P) for every layer but the first,
+    and for the first as well when h_0 is wanted."""
     total = 0
     for i in range(wl.depth):
         rows = wl.batch * wl.sides[i + 1] ** 2
-        total += 3 * 2 * rows * wl.k * wl.k * wl.channels * wl.channels
+        P = 2 * rows * wl.k * wl.k * wl.channels * wl.channels
+        total += 2 * P + (P if (i > 0 or h0_full) else 0)
     return total
 
 

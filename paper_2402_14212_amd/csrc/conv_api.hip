@@ -314,7 +314,11 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
       delete h;
       return MW_ERR_INVALID_ARG;  // a single image does not fit a GEMM operand
     }
-    l.gchunk = (int)(gmax < h->B ? gmax : h->B);
+    {
+      // as few launches as the 2 GiB operand limit allows, of equal size
+      const int64_t n_chunks = (h->B + gmax - 1) / gmax;
+      l.gchunk = (int)((h->B + n_chunks - 1) / n_chunks);
+    }
     l.gather = cfg->kernels == MW_CONV_KERNELS_AUTO && conv_gather_ok(g, l.Cout, nullptr, l.w);
     l.gather_rev = l.gather && conv_rev_ok(g, l.Cout);
     if (l.gather) {

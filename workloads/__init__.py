@@ -1,4 +1,4 @@
-"""Seeded synthetic MLP workloads.
+"""Seeded synthetic workloads (dense, 2-D convolutional, 1-D convolutional).
 
 This package only draws inputs (weights, biases, data). It contains none of the
 gradient method's arithmetic and is the single piece of code that both the CPU
@@ -10,6 +10,8 @@ from .mlp import (CONFIGS, MLPWorkload, config_widths, haar_orthonormal_columns,
 from .conv import (ConvWorkload, make_convnet, make_convnet_on_device, conv_out_side, conv_moonwalk_flops,
                    conv_backprop_flops, CONV_CONFIGS)
 
-__all__ = ["ConvWorkload", "make_convnet", "make_convnet_on_device", "CONV_CONFIGS", "conv_out_side", "conv_moonwalk_flops", "conv_backprop_flops",
+from .conv1d import FragWorkload, make_fragnet, frag_moonwalk_flops, frag_backprop_flops, FRAG_CONFIGS
+
+__all__ = ["FragWorkload", "make_fragnet", "frag_moonwalk_flops", "frag_backprop_flops", "FRAG_CONFIGS", "ConvWorkload", "make_convnet", "make_convnet_on_device", "CONV_CONFIGS", "conv_out_side", "conv_moonwalk_flops", "conv_backprop_flops",
            "CONFIGS", "MLPWorkload", "config_widths", "haar_orthonormal_columns",
            "make_mlp", "make_mlp_on_device", "make_config", "moonwalk_flops", "backprop_flops"]

@@ -206,11 +206,26 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
  * taps that BOTH gradient paths use: after changing w call moonwalk_conv_refresh before either
  * moonwalk_conv_grad or backprop_conv_grad (it recomputes both, whatever the plan).
  * The gradient layout is per layer dw [k][k][C_in][C_out] then db [C_out].
+ *
+ * Fragmental 1-D layers (section on fragmental gradient checkpointing, its appendix and the
+ * fragmental vijp algorithm): kind = MW_CONV_FRAGMENTAL_1D. The input is a one-row image
+ * ([B][1][N][C], cfg.height = 1), the kernel is [k][C_in][C_out] with k odd, stride 1 and padding
+ * (k - 1) / 2, so every layer keeps the length N; C_in and C_out must be multiples of 32,
+ * C_out <= C_in, N a multiple of `block`, block >= k - 1 (MW_ERR_INVALID_ARG otherwise). Such a layer
+ * is not submersive. The tap w[0] must be channel-triangular (w[0][c][c'] = 0 for c < c') with
+ * non-zero diagonal (MW_ERR_NOT_SUBMERSIVE otherwise). Phase II keeps, per layer, the first k - 1
+ * positions of every block of the convolution's output cotangent ((k - 1) / block of an activation);
+ * Phase III rebuilds the other positions of a block one after the other,
+ *   T ct[t, :] = h[t - p, :C_out] - sum_{u = 1}^{k-1} w[u][:C_out]^T-contracted ct[t - u, :],
+ * all blocks and samples at once. h_0 is computed whole (MW_CONV_H0_FULL is required).
+ * The gradient layout is per layer dw [k][C_in][C_out] then db [C_out].
  * ------------------------------------------------------------------------------------------ */
 typedef struct mw_conv_handle mw_conv_handle_t;
 
 #define MW_CONV_KERNELS_AUTO 0
 #define MW_CONV_KERNELS_PATCH_MATRIX 1
+#define MW_CONV_SUBMERSIVE 0
+#define MW_CONV_FRAGMENTAL_1D 1
 #define MW_CONV_H0_FULL 0
 #define MW_CONV_H0_AS_READ 1
 
@@ -219,6 +234,9 @@ typedef struct {
   const float* w;   /* device, [k][k][channels_in][channels_out]; caller owns; must outlive the handle */
   const float* b;   /* device [channels_out]; NULL means zero bias                                     */
   float alpha;      /* leaky-ReLU slope in (0, 1]                                                      */
+  int32_t kind;     /* MW_CONV_SUBMERSIVE (the lemma's layer, 2-D, vijp in closed form) or
+                       MW_CONV_FRAGMENTAL_1D (see below); the same for every layer of a chain             */
+  int32_t block;    /* MW_CONV_FRAGMENTAL_1D: positions per block of the fragment store                  */
 } mw_conv_layer_t;
 
 typedef struct {
@@ -250,6 +268,8 @@ typedef struct {
   uint64_t bytes_tap_inverses;     /* T^{-1}, C_out^2 floats per layer                                   */
   uint64_t bytes_packed_weights;   /* taps regrouped by stride class for the input-cotangent kernel: one
                                       copy of every layer's weights that takes the gathered kernels      */
+  uint64_t bytes_fragments;        /* fragmental layers: the first k - 1 positions of every block of each
+                                      layer's ct_z, (k - 1) / block of an activation per layer           */
   uint64_t bytes_checkpoints;      /* re-seed cotangents, each as the next layer's vijp reads it:
                                       [B][H'][W'][C_out] of that layer                                   */
   uint64_t bytes_input_cotangent;  /* h_0: as large as the network input, or as read (see the config)   */
@@ -274,7 +294,7 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
 int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
 int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out);
 /* what: MW_FETCH_MASK, MW_FETCH_H0 (whole or as read, see the config), MW_FETCH_P (here: T^{-1},
-   float[C_out^2]) or MW_FETCH_CHECKPOINT (the cotangent kept at the output of `layer`, in the
+   float[C_out^2]), MW_FETCH_FRAG (fragmental layers: float[B N / block][k - 1][C_out]) or MW_FETCH_CHECKPOINT (the cotangent kept at the output of `layer`, in the
    [B][H'][W'][C_out] form of layer + 1). */
 int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* host_dst, size_t cap, size_t* n_bytes);
 void moonwalk_conv_destroy(mw_conv_handle_t* h);

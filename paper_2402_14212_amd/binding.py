@@ -55,7 +55,8 @@ class _Config(C.Structure):
 
 class _ConvLayer(C.Structure):
     _fields_ = [("channels_in", C.c_int32), ("channels_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
-                ("pad", C.c_int32), ("w", C.c_void_p), ("b", C.c_void_p), ("alpha", C.c_float)]
+                ("pad", C.c_int32), ("w", C.c_void_p), ("b", C.c_void_p), ("alpha", C.c_float),
+                ("kind", C.c_int32), ("block", C.c_int32)]
 
 
 class _ConvConfig(C.Structure):
@@ -67,7 +68,7 @@ class _ConvConfig(C.Structure):
 
 class _ConvMemStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
-        "bytes_masks", "bytes_tap_inverses", "bytes_packed_weights", "bytes_checkpoints", "bytes_input_cotangent",
+        "bytes_masks", "bytes_tap_inverses", "bytes_packed_weights", "bytes_fragments", "bytes_checkpoints", "bytes_input_cotangent",
         "bytes_scratch", "bytes_patches", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak", "sign_mismatches")]
 
 
@@ -373,6 +374,7 @@ class MoonwalkNet:
 
 CONV_KERNELS_AUTO, CONV_KERNELS_PATCH_MATRIX = 0, 1
 CONV_H0_FULL, CONV_H0_AS_READ = 0, 1
+CONV_SUBMERSIVE, CONV_FRAGMENTAL_1D = 0, 1
 
 
 class ConvMoonwalkNet:
@@ -382,12 +384,14 @@ class ConvMoonwalkNet:
     kernels: CONV_KERNELS_AUTO (patch matrix gathered inside the products where the channel counts
     allow it) or CONV_KERNELS_PATCH_MATRIX (always through the patch buffer).
     input_cotangent: CONV_H0_FULL (h_0 for every input element) or CONV_H0_AS_READ (only the entries
-    the first layer's vijp reads; the first layer's reverse product is skipped)."""
+    the first layer's vijp reads; the first layer's reverse product is skipped).
+    kind = CONV_FRAGMENTAL_1D: length-preserving 1-D layers with fragmental checkpointing; ws are
+    [k][C_in][C_out], height must be 1, stride 1, pad (k - 1) / 2, block = positions per block."""
 
     def __init__(self, ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, height: int, width: int, stride: int, pad: int, reseed_interval: int = 0,
                  loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0,
-                 kernels: int = 0, input_cotangent: int = 0):
+                 kernels: int = 0, input_cotangent: int = 0, kind: int = 0, block: int = 0):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -422,10 +426,16 @@ class ConvMoonwalkNet:
         n = len(self.ws)
         layers = (_ConvLayer * n)()
         for i, (w, b, a) in enumerate(zip(self.ws, self.bs, self.alphas)):
+            if kind == CONV_FRAGMENTAL_1D:
+                if w.dim() != 3:
+                    raise ValueError("kernels of 1-D layers must be [k][C_in][C_out]")
+                layers[i] = _ConvLayer(w.shape[1], w.shape[2], w.shape[0], self.stride, self.pad, _ptr(w),
+                                       _ptr(_f32(b)) if b is not None else None, a, int(kind), int(block))
+                continue
             if w.dim() != 4 or w.shape[0] != w.shape[1]:
                 raise ValueError("kernels must be [k][k][C_in][C_out]")
             layers[i] = _ConvLayer(w.shape[2], w.shape[3], w.shape[0], self.stride, self.pad, _ptr(w),
-                                   _ptr(_f32(b)) if b is not None else None, a)
+                                   _ptr(_f32(b)) if b is not None else None, a, int(kind), int(block))
         cfg = _ConvConfig(self.batch, self.height, self.width, int(reseed_interval), float(loss_scale), int(plan),
                           int(kernels), int(input_cotangent), 0, int(patch_bytes), self._alloc_cb, self._free_cb, None)
         with torch.cuda.device(self.device):
@@ -445,7 +455,11 @@ class ConvMoonwalkNet:
                 return a.to(device=dev, dtype=torch.float32).contiguous()
             return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
 
-        net = cls([put(w) for w in wl.w], [put(b) for b in wl.b], wl.alphas, wl.batch, wl.side, wl.side, wl.s, wl.p, **kw)
+        if hasattr(wl, "block"):   # a 1-D network with fragmental checkpointing: [S][N][C] is a one-row image
+            net = cls([put(w) for w in wl.w], [put(b) for b in wl.b], wl.alphas, wl.batch, 1, wl.length, 1, (wl.k - 1) // 2,
+                      kind=CONV_FRAGMENTAL_1D, block=wl.block, **kw)
+        else:
+            net = cls([put(w) for w in wl.w], [put(b) for b in wl.b], wl.alphas, wl.batch, wl.side, wl.side, wl.s, wl.p, **kw)
         net.x = put(wl.x)
         net.t = put(wl.t)
         return net
@@ -461,7 +475,7 @@ class ConvMoonwalkNet:
         dW, db = [], []
         for i, w in enumerate(self.ws):
             dW.append(flat[self.dW_off[i]: self.dW_off[i] + w.numel()].view(w.shape))
-            db.append(flat[self.db_off[i]: self.db_off[i] + w.shape[3]])
+            db.append(flat[self.db_off[i]: self.db_off[i] + w.shape[-1]])
         return GradResult(flat, dW, db, loss)
 
     def moonwalk_grad(self, x, target, grads_out=None, loss_out=None) -> GradResult:
@@ -502,8 +516,12 @@ class ConvMoonwalkNet:
         """The cotangent kept at the output of `layer`, as layer + 1 reads it: [B][H'][W'][C_out] of layer + 1."""
         return self._fetch(layer, FETCH_CHECKPOINT, np.float32)
 
+    def fetch_fragments(self, layer: int) -> np.ndarray:
+        """Fragmental layers: the stored positions of ct_z, [B N / block][k - 1][C_out] flattened."""
+        return self._fetch(layer, FETCH_FRAG, np.float32)
+
     def fetch_tap_inverse(self, layer: int) -> np.ndarray:
-        c = self.ws[layer].shape[3]
+        c = self.ws[layer].shape[-1]
         return self._fetch(layer, FETCH_P, np.float32).reshape(c, c)
 
     def close(self):

@@ -37,6 +37,11 @@ void cv_default_free(void* p, void*) { (void)hipFree(p); }
 
 struct ConvLayer {
   int Cin = 0, Cout = 0, k = 0, s = 0, p = 0;
+  int kind = MW_CONV_SUBMERSIVE;
+  int kh = 0, kw = 0, ph = 0, pw = 0;  // the kernel as the products see it: k x k with padding p, or 1 x k for a 1-D layer
+  int block = 0;                // fragmental layers: positions per block
+  float* frag = nullptr;        // fragmental layers: [B W / block][k - 1][Cout], the first k - 1 positions of every block of ct_z
+  float* Arec = nullptr;        // fragmental layers: [k - 1][Cout][Cout], T^{-1} w[u][:Cout] for u = 1 .. k - 1
   int Hin = 0, Win = 0, Ho = 0, Wo = 0;
   int K = 0;            // k k Cin: columns of the patch matrix
   int64_t rows = 0;     // B Ho Wo: rows of the patch matrix
@@ -56,7 +61,11 @@ struct ConvLayer {
   int chunk_images = 1;         // images per patch-buffer fill
   bool gather = false;          // gathered-operand kernels for forward, Phase III and dW
   int gchunk = 1;               // images per launch of those kernels (2 GiB operand limit)
-  ConvGeom geom() const { return ConvGeom{Hin, Win, Cin, Ho, Wo, k, s, p}; }
+  ConvGeom geom() const { return ConvGeom{Hin, Win, Cin, Ho, Wo, kh, kw, s, ph, pw}; }
+  // the tap whose first Cout rows are the triangular T: (p, p) of a submersive layer, u = 0 of a fragmental one
+  const float* tri_tap() const {
+    return kind == MW_CONV_FRAGMENTAL_1D ? w : w + ((size_t)(p * k + p) * Cin) * Cout;
+  }
   int64_t in_img() const { return (int64_t)Hin * Win * Cin; }     // floats per input image
   int64_t out_img() const { return (int64_t)Ho * Wo * Cout; }     // floats per output image
 };
@@ -111,10 +120,13 @@ int build_from_weights(mw_conv_handle* h, hipStream_t s) {
   int32_t* flag = reinterpret_cast<int32_t*>(h->status + 2);
   CV_HIP(ew_fill_u32(h->status + 2, 0u, 1, s));
   for (auto& l : h->layers) {
-    if (l.wrev) CV_HIP(cv_pack_rev_weights(l.w, l.k, l.s, l.Cin, l.Cout, l.wrev, s));
+    if (l.wrev) CV_HIP(cv_pack_rev_weights(l.w, l.kh, l.kw, l.s, l.Cin, l.Cout, l.wrev, s));
     if (!l.Tinv) continue;
-    const float* tap = l.w + ((size_t)(l.p * l.k + l.p) * l.Cin) * l.Cout;  // w[p][p][.][.], [Cin][Cout]
-    CV_HIP(cv_tri_inverse(tap, l.Cout, l.Cout, l.Tinv, flag, s));
+    CV_HIP(cv_tri_inverse(l.tri_tap(), l.Cout, l.Cout, l.Tinv, flag, s));
+    // fragmental layers: the recurrence matrices T^{-1} w[u][:Cout], u = 1 .. k - 1
+    for (int u = 1; l.Arec && u < l.k; ++u)
+      CV_HIP(gemm_plain(OP_NN, TILE_AUTO, l.Cout, l.Cout, l.Cout, 1.f, l.Tinv, l.Cout, l.w + (size_t)u * l.Cin * l.Cout, l.Cout, 0.f,
+                        l.Arec + (size_t)(u - 1) * l.Cout * l.Cout, l.Cout, nullptr, s));
   }
   int32_t bad = 0;
   CV_HIP(hipStreamSynchronize(s));
@@ -168,7 +180,7 @@ int conv_input_grad(mw_conv_handle* h, const ConvLayer& l, const float* ctz, flo
 // the first Cout channels), straight from ct_z: in the fully parallel case only the tap at (p, p)
 // reaches those entries, so it is ct_z T^T with T the first Cout rows of that tap (Alg. 2 read backwards).
 int conv_kept_cotangent(mw_conv_handle* h, const ConvLayer& l, const float* ctz, float* kept, hipStream_t s) {
-  const float* tap = l.w + ((size_t)(l.p * l.k + l.p) * l.Cin) * l.Cout;  // [Cin][Cout]; rows c < Cout are T
+  const float* tap = l.tri_tap();  // [Cin][Cout]; rows c < Cout are T
   const int64_t per_img = (int64_t)l.Ho * l.Wo;
   for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
     const int64_t n_img = (img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0;
@@ -176,6 +188,42 @@ int conv_kept_cotangent(mw_conv_handle* h, const ConvLayer& l, const float* ctz,
     CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, ctz + r0 * l.Cout, l.Cout, tap, l.Cout, 0.f,
                       kept + r0 * l.Cout, l.Cout, nullptr, s));
   }
+  return MW_OK;
+}
+
+// Fragmental layer: ct_z of the whole layer from the incoming cotangent hin [B][1][W][Cin] and the stored
+// fragments (section on fragmental gradient checkpointing, its appendix and the fragmental vijp
+// algorithm). Rows are (sample, block); position j of every block is one column group of a matrix with
+// row stride block * C, so each step of the recurrence
+//     ct[., j] = hin[., j - p][:Cout] T^{-T} - sum_{u = 1}^{k-1} ct[., j - u] (T^{-1} w[u][:Cout])^T
+// is k plain products over all blocks at once; the steps j = k - 1 .. block - 1 follow one another.
+int frag_rebuild(mw_conv_handle* h, const ConvLayer& l, const float* hin, float* ctz, hipStream_t s) {
+  const int64_t blocks_per_img = l.Wo / l.block;
+  const int64_t ld_ct = (int64_t)l.block * l.Cout, ld_h = (int64_t)l.block * l.Cin;
+  const int nfrag = (l.k - 1) * l.Cout;
+  for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+    const int64_t n_img = (img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0;
+    const int64_t r0 = img0 * blocks_per_img, R = n_img * blocks_per_img;
+    float* ct = ctz + r0 * ld_ct;
+    const float* hi = hin + r0 * ld_h;
+    if (nfrag > 0) CV_HIP(cv_copy_rows(l.frag + r0 * nfrag, nfrag, ct, ld_ct, R, nfrag, s));
+    for (int j = l.k - 1; j < l.block; ++j) {
+      CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, hi + (int64_t)(j - l.p) * l.Cin, ld_h, l.Tinv, l.Cout, 0.f,
+                        ct + (int64_t)j * l.Cout, ld_ct, nullptr, s));
+      for (int u = 1; u < l.k; ++u)
+        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, -1.f, ct + (int64_t)(j - u) * l.Cout, ld_ct,
+                          l.Arec + (size_t)(u - 1) * l.Cout * l.Cout, l.Cout, 1.f, ct + (int64_t)j * l.Cout, ld_ct, nullptr, s));
+    }
+  }
+  return MW_OK;
+}
+
+// Phase II of a fragmental layer: keep the first k - 1 positions of every block of ct_z
+int frag_store(mw_conv_handle* h, const ConvLayer& l, const float* ctz, hipStream_t s) {
+  const int nfrag = (l.k - 1) * l.Cout;
+  if (nfrag == 0) return MW_OK;
+  const int64_t rows = (int64_t)h->B * (l.Wo / l.block);
+  CV_HIP(cv_copy_rows(ctz, (int64_t)l.block * l.Cout, l.frag, nfrag, rows, nfrag, s));
   return MW_OK;
 }
 
@@ -246,6 +294,20 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if (l.channels_in <= 0 || l.channels_out <= 0 || l.k <= 0 || l.stride <= 0 || l.pad < 0 || !l.w) return MW_ERR_INVALID_ARG;
     if (!(l.alpha > 0.f && l.alpha <= 1.f)) return MW_ERR_INVALID_ARG;
     if (i > 0 && l.channels_in != layers[i - 1].channels_out) return MW_ERR_INVALID_ARG;
+    if (l.kind != MW_CONV_SUBMERSIVE && l.kind != MW_CONV_FRAGMENTAL_1D) return MW_ERR_INVALID_ARG;
+    if (l.kind != layers[0].kind) return MW_ERR_INVALID_ARG;  // one kind of layer per chain
+    if (l.kind == MW_CONV_FRAGMENTAL_1D) {
+      // a length-preserving 1-D convolution on a one-row image, cut into whole blocks of at least k - 1
+      // positions; channel counts the gathered kernels take; h_0 is needed whole (the rebuild reads every position)
+      if (Hc != 1 || l.stride != 1 || l.k % 2 != 1 || l.pad != (l.k - 1) / 2) return MW_ERR_INVALID_ARG;
+      if (l.block < l.k - 1 || l.block < 1 || Wc % l.block) return MW_ERR_INVALID_ARG;
+      if (l.channels_out > l.channels_in) return MW_ERR_INVALID_ARG;
+      if (l.channels_in % 32 || l.channels_out % 32 || cfg->kernels != MW_CONV_KERNELS_AUTO) return MW_ERR_INVALID_ARG;
+      if (cfg->input_cotangent != MW_CONV_H0_FULL) return MW_ERR_INVALID_ARG;
+      if ((int64_t)l.k * l.channels_in * l.channels_out * 4 >= limit) return MW_ERR_INVALID_ARG;
+      if ((int64_t)Wc * l.channels_in >= limit / 4) return MW_ERR_INVALID_ARG;
+      continue;  // the length and the single row are kept
+    }
     if (Hc + 2 * l.pad < l.k || Wc + 2 * l.pad < l.k) return MW_ERR_INVALID_ARG;
     const int Ho = (Hc + 2 * l.pad - l.k) / l.stride + 1, Wo = (Wc + 2 * l.pad - l.k) / l.stride + 1;
     // conditions (i) of the lemma, and m' <= m
@@ -272,7 +334,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   h->layers.resize(n_layers);
   const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
   size_t off = 0, max_out = 0, max_odd = 1, max_patch = 0, max_part = 1, max_cout = 1;
-  bool any_patch_layer = false, need_patches = false;
+  bool any_patch_layer = false, need_patches = false, any_frag = false;
   Hc = cfg->height;
   Wc = cfg->width;
   for (int i = 0; i < n_layers; ++i) {
@@ -282,14 +344,21 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     l.k = layers[i].k;
     l.s = layers[i].stride;
     l.p = layers[i].pad;
+    l.kind = layers[i].kind;
+    l.block = layers[i].block;
+    const bool frag1d = l.kind == MW_CONV_FRAGMENTAL_1D;
+    l.kh = frag1d ? 1 : l.k;
+    l.kw = l.k;
+    l.ph = frag1d ? 0 : l.p;
+    l.pw = l.p;
     l.w = layers[i].w;
     l.b = layers[i].b;
     l.alpha = layers[i].alpha;
     l.Hin = Hc;
     l.Win = Wc;
-    l.Ho = (Hc + 2 * l.p - l.k) / l.s + 1;
-    l.Wo = (Wc + 2 * l.p - l.k) / l.s + 1;
-    l.K = l.k * l.k * l.Cin;
+    l.Ho = (Hc + 2 * l.ph - l.kh) / l.s + 1;
+    l.Wo = (Wc + 2 * l.pw - l.kw) / l.s + 1;
+    l.K = l.kh * l.kw * l.Cin;
     l.rows = (int64_t)h->B * l.Ho * l.Wo;
     l.n_in = (int64_t)h->B * l.Hin * l.Win * l.Cin;
     l.n_out = l.rows * l.Cout;
@@ -328,6 +397,13 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
       any_patch_layer = true;
     }
     if (!l.gather || !l.gather_rev) need_patches = true;
+    if (frag1d) {
+      any_frag = true;
+      if (!l.gather || !l.gather_rev) {  // setup's checks should have made this impossible
+        delete h;
+        return MW_ERR_INVALID_ARG;
+      }
+    }
     if ((size_t)l.Cout > max_cout) max_cout = (size_t)l.Cout;
     if (ci * per_img > max_patch) max_patch = ci * per_img;
     if ((size_t)l.n_out > max_out) max_out = (size_t)l.n_out;
@@ -355,6 +431,10 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   if (h->plan & MW_PLAN_MOONWALK) {
     for (auto& l : h->layers) {
       ok = ok && cv_alloc(h, &l.Tinv, (size_t)l.Cout * l.Cout, &st.bytes_tap_inverses);
+      if (l.kind == MW_CONV_FRAGMENTAL_1D && l.k > 1) {
+        ok = ok && cv_alloc(h, &l.Arec, (size_t)(l.k - 1) * l.Cout * l.Cout, &st.bytes_tap_inverses);
+        ok = ok && cv_alloc(h, &l.frag, (size_t)(l.rows / l.block) * (l.k - 1) * l.Cout, &st.bytes_fragments);
+      }
       l.mask_words = ((size_t)l.n_out + 63) / 64;
       ok = ok && cv_alloc(h, &l.mask, l.mask_words, &st.bytes_masks);
       if (ok) {
@@ -365,8 +445,11 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if (!ok) return fail(MW_ERR_OOM);
     if (h->Kre > 0)
       for (int j = 1; j < n_layers; ++j)
-        if (j % h->Kre == 0)
-          ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt, (size_t)h->layers[j].rows * h->layers[j].Cout, &st.bytes_checkpoints);
+        if (j % h->Kre == 0)  // as the next layer reads it: a fragmental layer reads every position
+          ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt,
+                              h->layers[j].kind == MW_CONV_FRAGMENTAL_1D ? (size_t)h->layers[j].n_in
+                                                                         : (size_t)h->layers[j].rows * h->layers[j].Cout,
+                              &st.bytes_checkpoints);
     // activations and cotangents alternate between an "even layer" and an "odd layer" buffer; the odd
     // ones never hold the first layer's output, the largest by far when the resolution shrinks
     ok = ok && cv_alloc(h, &h->xa, max_out, &st.bytes_scratch) && cv_alloc(h, &h->xb, max_odd, &st.bytes_scratch) &&
@@ -374,8 +457,10 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
          cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
          cv_alloc(h, &h->h0, h->h0_full ? (size_t)h->layers[0].n_in : (size_t)h->layers[0].rows * h->layers[0].Cout,
                   &st.bytes_input_cotangent);
-    if (any_patch_layer)  // pre-activations and right-hand sides exist in memory only on the patch-matrix path
-      ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
+    // pre-activations exist in memory on the patch-matrix path and for fragmental layers (whose ct_z is
+    // rebuilt by separate products); right-hand sides only on the patch-matrix path
+    if (any_patch_layer || any_frag) ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch);
+    if (any_patch_layer) ok = ok && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   if (h->plan & MW_PLAN_BACKPROP) {
@@ -442,8 +527,13 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
       ConvLayer& l = h->layers[i];
       const ConvLayer* prev = i > 0 ? &h->layers[i - 1] : nullptr;
       const float* ct = ctbuf[i & 1];
+      const bool frag1d = l.kind == MW_CONV_FRAGMENTAL_1D;
+      if (frag1d) {
+        int rc = frag_store(h, l, ct, s);
+        if (rc != MW_OK) return rc;
+      }
       float* kept = prev ? prev->ckpt : (h->h0_full ? nullptr : h->h0);
-      if (kept) {
+      if (kept && !frag1d) {
         int rc = conv_kept_cotangent(h, l, ct, kept, s);
         if (rc != MW_OK) return rc;
       }
@@ -453,6 +543,7 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
       // a layer that cannot scale in its epilogue leaves h in ha (free since the line above the loop)
       const bool can_fuse = l.gather_rev && prev && l.Cin % 32 == 0;
       float* raw = prev ? (can_fuse ? nullptr : h->ha) : h->h0;
+      if (frag1d && kept) raw = kept;  // a fragmental layer reads every position of its input cotangent
       int rc = conv_input_grad(h, l, ct, raw, ct_next, prev, &fused, s);
       if (rc != MW_OK) return rc;
       if (prev && !fused) CV_HIP(ew_rev_scale(raw, prev->mask, prev->n_out, prev->alpha, ct_next, s));
@@ -466,13 +557,26 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   bool hin_as_read = !h->h0_full;  // hin holds [rows][Cout] = what this layer's vijp reads, not a whole activation
   for (int i = 0; i < L; ++i) {
     ConvLayer& l = h->layers[i];
+    const bool frag1d = l.kind == MW_CONV_FRAGMENTAL_1D;
     if (i > 0 && h->layers[i - 1].ckpt) {  // re-seed
       hin = h->layers[i - 1].ckpt;
-      hin_as_read = true;
+      hin_as_read = !frag1d;
     }
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
-    if (l.gather) {
+    if (frag1d) {
+      // ct_z from the incoming cotangent and the fragments, then the pre-activation again and the vijp of the activation
+      int rc = frag_rebuild(h, l, hin, h->ctz, s);
+      if (rc != MW_OK) return rc;
+      for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+        const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+        CV_HIP(conv_fwd_z(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.Cout, h->zbuf + img0 * l.out_img(), s));
+      }
+      CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
+                              mismatches, s));
+      rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
+      if (rc != MW_OK) return rc;
+    } else if (l.gather) {
       // one kernel per image chunk: recomputed forward, channel solve at the strided positions, vijp epilogue
       for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
         const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
@@ -595,7 +699,14 @@ int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* 
     case MW_FETCH_CHECKPOINT:
       if (layer + 1 >= h->L) return MW_ERR_INVALID_ARG;
       src = h->layers[layer].ckpt;
-      bytes = (size_t)h->layers[layer + 1].rows * h->layers[layer + 1].Cout * 4;
+      bytes = (h->layers[layer + 1].kind == MW_CONV_FRAGMENTAL_1D ? (size_t)h->layers[layer + 1].n_in
+                                                                  : (size_t)h->layers[layer + 1].rows * h->layers[layer + 1].Cout) * 4;
+      break;
+    case MW_FETCH_FRAG:
+      src = h->layers[layer].frag;
+      bytes = h->layers[layer].frag ? (size_t)(h->layers[layer].rows / h->layers[layer].block) * (h->layers[layer].k - 1) *
+                                          h->layers[layer].Cout * 4
+                                    : 0;
       break;
     default: return MW_ERR_INVALID_ARG;
   }

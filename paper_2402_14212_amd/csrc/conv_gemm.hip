@@ -8,16 +8,16 @@ namespace mw {
 
 namespace {
 
-AConvPatch make_gather(const ConvGeom& g, int n_img, int k, int s, int p, int c0, int csel) {
+AConvPatch make_gather(const ConvGeom& g, int n_img, int kh, int kw, int s, int ph, int pw, int c0, int csel) {
   AConvPatch a;
   a.H = g.H; a.W = g.W; a.C = g.C; a.Ho = g.Ho; a.Wo = g.Wo;
-  a.kh = k; a.kw = k; a.s = s; a.py = p; a.px = p; a.c0 = c0; a.Csel = csel;
+  a.kh = kh; a.kw = kw; a.s = s; a.py = ph; a.px = pw; a.c0 = c0; a.Csel = csel;
   a.row_off = 0;
   a.bytes = (uint32_t)((int64_t)n_img * g.H * g.W * g.C * 4);
   a.d_howo = FastDiv((uint32_t)(g.Ho * g.Wo));
   a.d_wo = FastDiv((uint32_t)g.Wo);
   a.d_csel = FastDiv((uint32_t)csel);
-  a.d_kw = FastDiv((uint32_t)k);
+  a.d_kw = FastDiv((uint32_t)kw);
   a.d1 = (uint32_t)(g.W - g.Wo) * (uint32_t)(s * g.C);
   a.d2 = (uint32_t)(g.H - g.Ho * s) * (uint32_t)(g.W * g.C);
   return a;
@@ -39,12 +39,12 @@ hipError_t rev_t(const ConvGeom& g, int n_img, int Cout, const float* ctz, const
   int64_t w_off = 0;
   for (int ry = 0; ry < g.s; ++ry)
     for (int rx = 0; rx < g.s; ++rx) {
-      const int nty = class_taps(g.k, g.s, ry), ntx = class_taps(g.k, g.s, rx);
+      const int nty = class_taps(g.kh, g.s, ry), ntx = class_taps(g.kw, g.s, rx);
       // pixels iy with (iy + p) mod s == ry: iy + p = s q + ry for q in [q_lo, q_hi]
-      auto lo = [&](int r) { return (g.p - r + g.s - 1) / g.s; };             // ceil((p - r) / s), p >= 0 > r - s
-      auto hi = [&](int extent, int r) { return (extent + g.p - 1 - r) >= 0 ? (extent + g.p - 1 - r) / g.s : -1; };
-      const int qy_lo = lo(ry), qx_lo = lo(rx);
-      const int nqy = hi(g.H, ry) - qy_lo + 1, nqx = hi(g.W, rx) - qx_lo + 1;
+      auto lo = [&](int p, int r) { return (p - r + g.s - 1) / g.s; };        // ceil((p - r) / s), p >= 0 > r - s
+      auto hi = [&](int extent, int p, int r) { return (extent + p - 1 - r) >= 0 ? (extent + p - 1 - r) / g.s : -1; };
+      const int qy_lo = lo(g.ph, ry), qx_lo = lo(g.pw, rx);
+      const int nqy = hi(g.H, g.ph, ry) - qy_lo + 1, nqx = hi(g.W, g.pw, rx) - qx_lo + 1;
       const int64_t w_here = w_off;
       w_off += (int64_t)nty * ntx * Cout * g.C;
       if (nqy <= 0 || nqx <= 0) continue;
@@ -61,8 +61,8 @@ hipError_t rev_t(const ConvGeom& g, int n_img, int Cout, const float* ctz, const
       a.d_csel = FastDiv((uint32_t)Cout);
       a.d_kw = FastDiv((uint32_t)(ntx > 0 ? ntx : 1));
       a.d1 = 0; a.d2 = 0;  // rows never run along K in this product
-      rc.oy = g.s * qy_lo + ry - g.p;
-      rc.ox = g.s * qx_lo + rx - g.p;
+      rc.oy = g.s * qy_lo + ry - g.ph;
+      rc.ox = g.s * qx_lo + rx - g.pw;
       rc.K = nty * ntx * Cout;
       rc.M = n_img * nqy * nqx;
       rc.tiles_m = ceil_div(rc.M, Cfg::BM);
@@ -79,11 +79,21 @@ hipError_t rev_t(const ConvGeom& g, int n_img, int Cout, const float* ctz, const
 template <class Cfg, bool MASK>
 hipError_t fwd_t(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                  float* xout, uint32_t* mask32, hipStream_t stream) {
-  const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
-  const AConvPatch xf = make_gather(g, n_img, g.k, g.s, g.p, 0, g.C);
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
+  const AConvPatch xf = make_gather(g, n_img, g.kh, g.kw, g.s, g.ph, g.pw, 0, g.C);
   EpiFwdAct<MASK> epi{xout, b, alpha, mask32};
   auto t = make_gemm_task<Cfg, KCONTIG, RCONTIG, true, AConvPatch, EpiFwdAct<MASK>, false>(M, Cout, K1, x, 0, w, Cout, xf, epi,
                                                                                          nullptr, 0.f);
+  return launch_task<Cfg::NT>(t, stream);
+}
+
+template <class Cfg>
+hipError_t fwd_z_t(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
+                   hipStream_t stream) {
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
+  const AConvPatch xf = make_gather(g, n_img, g.kh, g.kw, g.s, g.ph, g.pw, 0, g.C);
+  EpiStore epi{z, Cout, 1.f, 0.f, b};
+  auto t = make_gemm_task<Cfg, KCONTIG, RCONTIG, true, AConvPatch, EpiStore, false>(M, Cout, K1, x, 0, w, Cout, xf, epi, nullptr, 0.f);
   return launch_task<Cfg::NT>(t, stream);
 }
 
@@ -97,12 +107,13 @@ hipError_t fwd_m(const ConvGeom& g, int n_img, const float* x, const float* w, c
 template <class Cfg>
 hipError_t vijp_t(const ConvGeom& g, int n_img, const float* x, const float* w, int Cout, const float* hin, int hin_as_read,
                   const float* Tinv, const EpiVijp<false>& epi, hipStream_t stream) {
-  const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
   // the right-hand sides: h_in at (s i', s j'), first Cout channels, or already laid out that way
-  const ConvGeom rows_only{g.Ho, g.Wo, Cout, g.Ho, g.Wo, 1, 1, 0};
-  const AConvPatch gh = hin_as_read ? make_gather(rows_only, n_img, 1, 1, 0, 0, Cout) : make_gather(g, n_img, 1, g.s, 0, 0, Cout);
+  const ConvGeom rows_only{g.Ho, g.Wo, Cout, g.Ho, g.Wo, 1, 1, 1, 0, 0};
+  const AConvPatch gh =
+      hin_as_read ? make_gather(rows_only, n_img, 1, 1, 1, 0, 0, 0, Cout) : make_gather(g, n_img, 1, 1, g.s, 0, 0, 0, Cout);
   ConvVijpTask<Cfg> t{M, Cout, K1, x, w, hin, Tinv,
-                      make_gather(g, n_img, g.k, g.s, g.p, 0, g.C),   // patches of x
+                      make_gather(g, n_img, g.kh, g.kw, g.s, g.ph, g.pw, 0, g.C),   // patches of x
                       gh,
                       epi, ceil_div(M, Cfg::BM), ceil_div(Cout, Cfg::BN)};
   // two workgroups per CU wherever the LDS allows it: the epilogue (three stores and a mask word per
@@ -138,8 +149,8 @@ DwPlan plan_dw(int K1, int Cout, int64_t rows) {
 template <class Cfg>
 hipError_t dw_t(const ConvGeom& g, int n_img, const float* x, const float* ctz, int Cout, const DwPlan& p, float* part,
                 hipStream_t stream) {
-  const int rows = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
-  SplitKTnTask<Cfg, AConvPatch> t{K1, Cout, rows, x, 0, ctz, Cout, make_gather(g, n_img, g.k, g.s, g.p, 0, g.C), part,
+  const int rows = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
+  SplitKTnTask<Cfg, AConvPatch> t{K1, Cout, rows, x, 0, ctz, Cout, make_gather(g, n_img, g.kh, g.kw, g.s, g.ph, g.pw, 0, g.C), part,
                                   p.slices, p.k_per, ceil_div(K1, Cfg::BM), ceil_div(Cout, Cfg::BN)};
   return launch_task<Cfg::NT>(t, stream);
 }
@@ -155,7 +166,7 @@ int gather_tile(int M, int N, int K, int csel_a, int csel_b) {
 }  // namespace
 
 bool conv_gather_ok(const ConvGeom& g, int Cout, const float* x, const float* w) {
-  return g.C % 32 == 0 && Cout % 32 == 0 && aligned16(x) && aligned16(w) && (int64_t)g.k * g.k * g.C < (1 << 24);
+  return g.C % 32 == 0 && Cout % 32 == 0 && aligned16(x) && aligned16(w) && (int64_t)g.taps() * g.C < (1 << 24);
 }
 
 int64_t conv_gather_max_images(const ConvGeom& g, int Cout) {
@@ -169,7 +180,7 @@ int64_t conv_gather_max_images(const ConvGeom& g, int Cout) {
 hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                         float* xout, uint32_t* mask32, hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
-  const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
   switch (gather_tile(M, Cout, K1, g.C, Cout)) {
     case TILE_128W8: return fwd_m<Tile128W8>(g, n_img, x, w, b, alpha, Cout, xout, mask32, stream);
     case TILE_64X128: return fwd_m<Tile64x128>(g, n_img, x, w, b, alpha, Cout, xout, mask32, stream);
@@ -179,11 +190,24 @@ hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const floa
   }
 }
 
+hipError_t conv_fwd_z(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
+                      hipStream_t stream) {
+  if (n_img <= 0) return hipSuccess;
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
+  switch (gather_tile(M, Cout, K1, g.C, Cout)) {  // the tile of conv_fwd_act
+    case TILE_128W8: return fwd_z_t<Tile128W8>(g, n_img, x, w, b, Cout, z, stream);
+    case TILE_64X128: return fwd_z_t<Tile64x128>(g, n_img, x, w, b, Cout, z, stream);
+    case TILE_64K2: return fwd_z_t<Tile64K2>(g, n_img, x, w, b, Cout, z, stream);
+    case TILE_32K4: return fwd_z_t<Tile32K4>(g, n_img, x, w, b, Cout, z, stream);
+    default: return fwd_z_t<Tile64>(g, n_img, x, w, b, Cout, z, stream);
+  }
+}
+
 hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                            const float* hin, int hin_as_read, const float* Tinv, const uint32_t* mask32, float* xout, float* hout, float* ctz,
                            unsigned long long* mismatches, hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
-  const int M = n_img * g.Ho * g.Wo, K1 = g.k * g.k * g.C;
+  const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
   // the leaky path of the epilogue reads the mask as 32-bit words, so a 4-byte aligned start is enough
   EpiVijp<false> epi{b, alpha, 1.0f / alpha, reinterpret_cast<const uint64_t*>(mask32), nullptr, nullptr, nullptr, 0,
                      xout, hout, ctz, mismatches};
@@ -206,7 +230,7 @@ hipError_t conv_input_cotangent(const ConvGeom& g, int n_img, int Cout, const fl
   EpiConvRev epi{raw, ct, mask32, alpha, g.H, g.W, g.s, (uint32_t)((int64_t)n_img * g.H * g.W * g.C * 4)};
   // the tile for the largest class: about a quarter of the input pixels, all taps of that class
   const int M = n_img * ((g.H + g.s - 1) / g.s) * ((g.W + g.s - 1) / g.s);
-  const int K = class_taps(g.k, g.s, 0) * class_taps(g.k, g.s, 0) * Cout;
+  const int K = class_taps(g.kh, g.s, 0) * class_taps(g.kw, g.s, 0) * Cout;
   switch (gather_tile(M, g.C, K, Cout, Cout)) {
     case TILE_128W8: return rev_t<Tile128W8>(g, n_img, Cout, ctz, wrev, epi, stream);
     case TILE_64X128: return rev_t<Tile64x128>(g, n_img, Cout, ctz, wrev, epi, stream);
@@ -218,7 +242,7 @@ hipError_t conv_input_cotangent(const ConvGeom& g, int n_img, int Cout, const fl
 
 size_t conv_dw_part_floats(const ConvGeom& g, int n_img, int Cout) {
   // the most slices any chunk of at most n_img images is split into
-  const int K1 = g.k * g.k * g.C;
+  const int K1 = g.taps() * g.C;
   int most = 1;
   for (int n = 1; n <= n_img; ++n) {
     const int sl = plan_dw(K1, Cout, (int64_t)n * g.Ho * g.Wo).slices;
@@ -230,7 +254,7 @@ size_t conv_dw_part_floats(const ConvGeom& g, int n_img, int Cout) {
 hipError_t conv_dw(const ConvGeom& g, int n_img, const float* x, const float* ctz, int Cout, float scale, float beta,
                    float* dW, float* part, hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
-  const int K1 = g.k * g.k * g.C;
+  const int K1 = g.taps() * g.C;
   const DwPlan p = plan_dw(K1, Cout, (int64_t)n_img * g.Ho * g.Wo);
   hipError_t e;
   switch (p.tile) {

@@ -135,27 +135,38 @@ inline int cv_blocks(int64_t work_items) {
 }
 inline bool al16p(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// rows of `w4` float4 each, from one row stride to another (the fragment store of the 1-D layers: the
+// first positions of every block of a cotangent, out of it in Phase II and back into it in Phase III)
+__global__ void __launch_bounds__(256)
+k_copy_rows(const float* __restrict__ src, int64_t src_ld, float* __restrict__ dst, int64_t dst_ld, int64_t rows, int w4) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * w4) return;
+  const int64_t r = i / w4;
+  const int c = (int)(i - r * w4);
+  *reinterpret_cast<float4*>(dst + r * dst_ld + 4 * c) = *reinterpret_cast<const float4*>(src + r * src_ld + 4 * c);
+}
+
 // Weights regrouped for the input-cotangent products. Taps are classed by (ky mod s, kx mod s); class
 // (ry, rx) holds, for tap slots ky' < nty, kx' < ntx (ky = ry + s (nty - 1 - ky'), likewise kx), the
 // matrix [C_out][C_in] = w[ky][kx]^T, slots in row-major order, classes in (ry, rx) order.
 __device__ __forceinline__ int taps_of_class(int k, int s, int r) { return r < k ? (k - r + s - 1) / s : 0; }
 
 __global__ void __launch_bounds__(256)
-k_pack_rev_weights(const float* __restrict__ w, int k, int s, int Cin, int Cout, float* __restrict__ wrev) {
+k_pack_rev_weights(const float* __restrict__ w, int kh, int kw, int s, int Cin, int Cout, float* __restrict__ wrev) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t n = (int64_t)k * k * Cin * Cout;
+  const int64_t n = (int64_t)kh * kw * Cin * Cout;
   if (idx >= n) return;
   const int co = (int)(idx % Cout);
   int64_t r = idx / Cout;
   const int ci = (int)(r % Cin);
   r /= Cin;
-  const int kx = (int)(r % k), ky = (int)(r / k);
+  const int kx = (int)(r % kw), ky = (int)(r / kw);
   const int ry = ky % s, rx = kx % s;
-  const int nty = taps_of_class(k, s, ry), ntx = taps_of_class(k, s, rx);
+  const int nty = taps_of_class(kh, s, ry), ntx = taps_of_class(kw, s, rx);
   const int kyp = nty - 1 - ky / s, kxp = ntx - 1 - kx / s;
   int64_t taps_before = 0;  // taps of the classes before (ry, rx)
-  for (int a = 0; a < ry; ++a) taps_before += (int64_t)taps_of_class(k, s, a) * k;
-  for (int b = 0; b < rx; ++b) taps_before += (int64_t)nty * taps_of_class(k, s, b);
+  for (int a = 0; a < ry; ++a) taps_before += (int64_t)taps_of_class(kh, s, a) * kw;
+  for (int b = 0; b < rx; ++b) taps_before += (int64_t)nty * taps_of_class(kw, s, b);
   const int64_t dst = ((taps_before + (int64_t)kyp * ntx + kxp) * Cout + co) * Cin + ci;
   wrev[dst] = w[idx];
 }
@@ -197,10 +208,19 @@ hipError_t cv_strided_gather(const float* h, int H, int W, int C, int Ho, int Wo
   return hipGetLastError();
 }
 
-hipError_t cv_pack_rev_weights(const float* w, int k, int s, int Cin, int Cout, float* wrev, hipStream_t stream) {
-  const int64_t n = (int64_t)k * k * Cin * Cout;
+hipError_t cv_pack_rev_weights(const float* w, int kh, int kw, int s, int Cin, int Cout, float* wrev, hipStream_t stream) {
+  const int64_t n = (int64_t)kh * kw * Cin * Cout;
   if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_pack_rev_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, k, s, Cin, Cout, wrev);
+  hipLaunchKernelGGL(k_pack_rev_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, kh, kw, s, Cin, Cout, wrev);
+  return hipGetLastError();
+}
+
+hipError_t cv_copy_rows(const float* src, int64_t src_ld, float* dst, int64_t dst_ld, int64_t rows, int width, hipStream_t stream) {
+  if (rows <= 0 || width <= 0) return hipSuccess;
+  if (width % 4 || src_ld % 4 || dst_ld % 4 || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
+    return hipErrorInvalidValue;
+  const int64_t n4 = rows * (width / 4);
+  hipLaunchKernelGGL(k_copy_rows, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, src, src_ld, dst, dst_ld, rows, width / 4);
   return hipGetLastError();
 }
 

@@ -178,7 +178,10 @@ hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_
 struct ConvGeom {
   int H, W, C;     // input image, channels-last
   int Ho, Wo;      // output grid
-  int k, s, p;     // taps per side, stride, padding
+  int kh, kw;      // taps in y and x (a 1-D convolution is a one-row image with kh = 1)
+  int s;           // stride, both directions
+  int ph, pw;      // padding in y and x
+  int taps() const { return kh * kw; }
 };
 // the gathered kernels need C % 4 == 0, C_out % 32 == 0 and 16-byte aligned operands (x may be NULL: not checked)
 bool conv_gather_ok(const ConvGeom& g, int Cout, const float* x, const float* w);
@@ -188,6 +191,9 @@ int64_t conv_gather_max_images(const ConvGeom& g, int Cout);
 // the sign bits of the same flat index, 32 per word
 hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                         float* xout, uint32_t* mask32, hipStream_t stream);
+// the pre-activation alone, z = patches(x) w + b, same tile and therefore the same bits as conv_fwd_act's z
+hipError_t conv_fwd_z(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
+                      hipStream_t stream);
 // Phase III of a leaky convolutional layer for n_img images: z recomputed from x, ct_z = sub(h_in) Tinv^T,
 // x out, h out = ct_z / slope, sign check against mask32. hin_as_read: hin is sub(h_in) itself,
 // [rows][Cout], instead of the whole input cotangent [n_img][H][W][C]
@@ -208,8 +214,10 @@ bool conv_rev_ok(const ConvGeom& g, int Cout);
 // index of the input element) select: 1 or alpha. wrev: weights packed by cv_pack_rev_weights.
 hipError_t conv_input_cotangent(const ConvGeom& g, int n_img, int Cout, const float* ctz, const float* wrev, float* raw,
                                 float* ct, const uint32_t* mask32, float alpha, hipStream_t stream);
-// wrev (k k Cin Cout floats) = the per-stride-class transposed taps conv_input_cotangent multiplies with
-hipError_t cv_pack_rev_weights(const float* w, int k, int s, int Cin, int Cout, float* wrev, hipStream_t stream);
+// wrev (kh kw Cin Cout floats) = the per-stride-class transposed taps conv_input_cotangent multiplies with
+hipError_t cv_pack_rev_weights(const float* w, int kh, int kw, int s, int Cin, int Cout, float* wrev, hipStream_t stream);
+// rows x width floats from src (row stride src_ld) to dst (row stride dst_ld); all three multiples of 4, 16-byte aligned
+hipError_t cv_copy_rows(const float* src, int64_t src_ld, float* dst, int64_t dst_ld, int64_t rows, int width, hipStream_t stream);
 
 // records the text of a failed HIP call for moonwalk_strerror and returns MW_ERR_HIP (moonwalk_api.hip)
 int record_hip_failure(hipError_t e, const char* where);

@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backprop", action="store_true")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size (convolutional configurations)")
+    ap.add_argument("--block", type=int, default=None, help="conv1d configurations: positions per block of the fragment store")
     ap.add_argument("--h0", choices=["full", "as_read"], default="full",
                     help="convolutional configurations: compute the input cotangent for every input element (a network with "
                          "layers before the chain needs it; backprop then computes it too), or only what the first vijp reads")
@@ -98,20 +99,30 @@ def bench_conv(args):
     import numpy as np
     import torch
     import paper_2402_14212_amd as mw
-    from workloads import CONV_CONFIGS, make_convnet, make_convnet_on_device, conv_moonwalk_flops, conv_backprop_flops
+    from workloads import (CONV_CONFIGS, FRAG_CONFIGS, make_convnet, make_convnet_on_device, make_fragnet, conv_moonwalk_flops,
+                           conv_backprop_flops, frag_moonwalk_flops, frag_backprop_flops)
 
-    c = dict(CONV_CONFIGS[args.config])
+    frag1d = args.config.startswith("conv1d")
+    c = dict((FRAG_CONFIGS if frag1d else CONV_CONFIGS)[args.config])
     if args.depth is not None:
         c["depth"] = args.depth
     if args.batch is not None:
         c["batch"] = args.batch
+    if args.block is not None:
+        c["block"] = args.block
     torch.cuda.set_device(0)
-    on_device = args.gen == "torch" or args.config == "conv2d"
-    wl = (make_convnet_on_device if on_device else make_convnet)(c["batch"], c["side"], c["channels"], c["depth"], alpha=c["alpha"],
-                                                                 seed=0, name=args.config)
-    h0_full = args.h0 == "full"
-    flops_mw, flops_bp = conv_moonwalk_flops(wl, h0_full), conv_backprop_flops(wl, h0_full)
-    K = args.reseed if args.reseed is not None else 2
+    on_device = (args.gen == "torch" or args.config == "conv2d") and not frag1d
+    if frag1d:
+        wl = make_fragnet(c["batch"], c["length"], c["channels"], c["depth"], block=c["block"], alpha=c["alpha"], seed=0,
+                          name=args.config)
+        h0_full = True
+        flops_mw, flops_bp = frag_moonwalk_flops(wl), frag_backprop_flops(wl, True)
+    else:
+        wl = (make_convnet_on_device if on_device else make_convnet)(c["batch"], c["side"], c["channels"], c["depth"],
+                                                                     alpha=c["alpha"], seed=0, name=args.config)
+        h0_full = args.h0 == "full"
+        flops_mw, flops_bp = conv_moonwalk_flops(wl, h0_full), conv_backprop_flops(wl, h0_full)
+    K = args.reseed if args.reseed is not None else (0 if frag1d else 2)
     h0_mode = mw.CONV_H0_FULL if h0_full else mw.CONV_H0_AS_READ
     grads_probe = None
     # --- Moonwalk handle only (so that its memory is its own)
@@ -139,32 +150,54 @@ def bench_conv(args):
                   "bytes_scratch": sb["bytes_bp_scratch"] + sb["bytes_scratch"] + sb["bytes_patches"],
                   "bytes_packed_weights": sb["bytes_packed_weights"], "bytes_total": sb["bytes_peak"]}
     achieved = flops_mw / (ms_mw * 1e-3) / 1e12
-    residual_mw = st["bytes_masks"] + st["bytes_checkpoints"]
+    residual_mw = st["bytes_masks"] + st["bytes_checkpoints"] + st["bytes_fragments"]
+    if frag1d:
+        what = (f"{args.config}: {wl.depth} layers of 1-D convolution {wl.k}x{wl.channels}x{wl.channels}, stride 1, padding {(wl.k - 1) // 2}, "
+                f"input {wl.length}x{wl.channels}, batch {wl.batch}, alpha {wl.alphas[0]}, fragment blocks of {wl.block}, reseed K={K}")
+        metric = ("gradient steps/s (mixed-mode Moonwalk with fragmental checkpointing on 1-D convolutional layers, one full "
+                  "moonwalk_conv_grad per step)")
+    else:
+        what = (f"{args.config}: {wl.depth} layers of {wl.k}x{wl.k}x{wl.channels}x{wl.channels} convolution, stride {wl.s}, "
+                f"padding {wl.p}, input {wl.side}x{wl.side}x{wl.channels}, batch {wl.batch}, alpha {wl.alphas[0]}, "
+                f"reseed K={K}, input cotangent {'for every input element' if h0_full else 'as the first vijp reads it'}")
+        metric = "gradient steps/s (mixed-mode Moonwalk on submersive 2-D convolutional layers, one full moonwalk_conv_grad per step)"
     out = {
-        "metric": "gradient steps/s (mixed-mode Moonwalk on submersive 2-D convolutional layers, one full moonwalk_conv_grad per step)",
+        "metric": metric,
         "value": 1e3 / ms_mw, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_mw, "ms_per_step_wall": wall_mw, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic (seeded, generator: %s)" % ("torch" if on_device else "numpy"),
-        "config": {"workload": f"{args.config}: {wl.depth} layers of {wl.k}x{wl.k}x{wl.channels}x{wl.channels} convolution, stride {wl.s}, "
-                               f"padding {wl.p}, input {wl.side}x{wl.side}x{wl.channels}, batch {wl.batch}, alpha {wl.alphas[0]}, "
-                               f"reseed K={K}, input cotangent {'for every input element' if h0_full else 'as the first vijp reads it'}"},
+        "config": {"workload": what},
         "tflops": achieved, "flop_per_step": flops_mw,
         "mfma_frac_whole_step": achieved / MFMA_F32_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "whole step (products with gathered patch matrices, reductions and elementwise kernels included)",
                      "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None},
         "setup_s": setup_s,
-        "memory": {"moonwalk": {"bytes_masks": st["bytes_masks"], "bytes_checkpoints": st["bytes_checkpoints"],
+        "memory": {"moonwalk": {"bytes_masks": st["bytes_masks"], "bytes_fragments": st["bytes_fragments"],
+                                "bytes_checkpoints": st["bytes_checkpoints"],
                                 "bytes_residual": residual_mw, "bytes_tap_inverses": st["bytes_tap_inverses"],
                                 "bytes_packed_weights": st["bytes_packed_weights"],
                                 "bytes_input_cotangent": st["bytes_input_cotangent"],
                                 "bytes_scratch": st["bytes_scratch"] + st["bytes_patches"], "bytes_total": st["bytes_peak"]},
                    "backprop": mem_bp,
-                   "bytes_input": int(wl.batch) * wl.side * wl.side * wl.channels * 4},
+                   "bytes_input": int(wl.x.numel() if hasattr(wl.x, "numel") else wl.x.size) * 4},
         "backprop": bp,
     }
     net.close()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and frag1d:
+        from oracle import frag_oracle as FO
+        sample = make_fragnet(2, min(wl.length, 256), wl.channels, min(wl.depth, 3), block=wl.block, alpha=c["alpha"], seed=0)
+        t0, n = time.perf_counter(), 0
+        while n < 1 or time.perf_counter() - t0 < 10.0:
+            FO.frag_moonwalk(sample.w, sample.b, sample.alphas, sample.x, sample.t, sample.block)
+            n += 1
+        per = (time.perf_counter() - t0) / n
+        fl = frag_moonwalk_flops(sample)
+        out["cpu_baseline"] = {"value": (fl / per) / flops_mw, "unit": "steps/s", "cores": int(os.cpu_count() or 1), "kind": "oracle",
+                               "sample": f"{n} fp64 oracle step(s) of a {sample.depth}-layer, {sample.length}x{sample.channels}, "
+                                         f"batch-2 cut of the workload; steps/s scaled by the flop ratio to the full workload",
+                               "gflops": fl / per / 1e9}
+    elif not args.no_cpu_baseline:
         from oracle import conv_oracle as CO
         sample = make_convnet(1, min(wl.side, 32), wl.channels, min(wl.depth, 3), alpha=c["alpha"], seed=0)
         t0, n = time.perf_counter(), 0
@@ -185,7 +218,7 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
-    if args.config.startswith("conv2d"):
+    if args.config.startswith("conv2d") or args.config.startswith("conv1d"):
         return bench_conv(args)
     import torch
     import paper_2402_14212_amd as mw

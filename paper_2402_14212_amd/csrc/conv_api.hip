@@ -334,7 +334,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   h->layers.resize(n_layers);
   const size_t patch_cap_floats = (cfg->patch_bytes > 0 ? cfg->patch_bytes : ((size_t)256 << 20)) / 4;
   size_t off = 0, max_out = 0, max_odd = 1, max_patch = 0, max_part = 1, max_cout = 1;
-  bool any_patch_layer = false, need_patches = false, any_frag = false;
+  bool any_patch_layer = false, need_patches = false;
   Hc = cfg->height;
   Wc = cfg->width;
   for (int i = 0; i < n_layers; ++i) {
@@ -398,7 +398,6 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     }
     if (!l.gather || !l.gather_rev) need_patches = true;
     if (frag1d) {
-      any_frag = true;
       if (!l.gather || !l.gather_rev) {  // setup's checks should have made this impossible
         delete h;
         return MW_ERR_INVALID_ARG;
@@ -457,10 +456,8 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
          cv_alloc(h, &h->ctz, max_out, &st.bytes_scratch) &&
          cv_alloc(h, &h->h0, h->h0_full ? (size_t)h->layers[0].n_in : (size_t)h->layers[0].rows * h->layers[0].Cout,
                   &st.bytes_input_cotangent);
-    // pre-activations exist in memory on the patch-matrix path and for fragmental layers (whose ct_z is
-    // rebuilt by separate products); right-hand sides only on the patch-matrix path
-    if (any_patch_layer || any_frag) ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch);
-    if (any_patch_layer) ok = ok && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
+    if (any_patch_layer)  // pre-activations and right-hand sides exist in memory only on the patch-matrix path
+      ok = ok && cv_alloc(h, &h->zbuf, max_out, &st.bytes_scratch) && cv_alloc(h, &h->hsub, max_out, &st.bytes_scratch);
     if (!ok) return fail(MW_ERR_OOM);
   }
   if (h->plan & MW_PLAN_BACKPROP) {
@@ -565,15 +562,16 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
     if (frag1d) {
-      // ct_z from the incoming cotangent and the fragments, then the pre-activation again and the vijp of the activation
+      // ct_z from the incoming cotangent and the fragments, then one kernel: the pre-activation again, the sign
+      // check and the vijp of the activation
       int rc = frag_rebuild(h, l, hin, h->ctz, s);
       if (rc != MW_OK) return rc;
       for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
         const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
-        CV_HIP(conv_fwd_z(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.Cout, h->zbuf + img0 * l.out_img(), s));
+        const int64_t o = img0 * l.out_img();
+        CV_HIP(conv_vijp_given(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, h->ctz + o,
+                               reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, mismatches, s));
       }
-      CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
-                              mismatches, s));
       rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
       if (rc != MW_OK) return rc;
     } else if (l.gather) {

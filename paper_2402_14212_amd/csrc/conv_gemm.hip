@@ -88,12 +88,12 @@ hipError_t fwd_t(const ConvGeom& g, int n_img, const float* x, const float* w, c
 }
 
 template <class Cfg>
-hipError_t fwd_z_t(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
-                   hipStream_t stream) {
+hipError_t fwd_given_t(const ConvGeom& g, int n_img, const float* x, const float* w, int Cout, const EpiVijpGiven& epi,
+                       hipStream_t stream) {
   const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
   const AConvPatch xf = make_gather(g, n_img, g.kh, g.kw, g.s, g.ph, g.pw, 0, g.C);
-  EpiStore epi{z, Cout, 1.f, 0.f, b};
-  auto t = make_gemm_task<Cfg, KCONTIG, RCONTIG, true, AConvPatch, EpiStore, false>(M, Cout, K1, x, 0, w, Cout, xf, epi, nullptr, 0.f);
+  auto t = make_gemm_task<Cfg, KCONTIG, RCONTIG, true, AConvPatch, EpiVijpGiven, false>(M, Cout, K1, x, 0, w, Cout, xf, epi, nullptr,
+                                                                                      0.f);
   return launch_task<Cfg::NT>(t, stream);
 }
 
@@ -190,16 +190,20 @@ hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const floa
   }
 }
 
-hipError_t conv_fwd_z(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
-                      hipStream_t stream) {
+hipError_t conv_vijp_given(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
+                           const float* ctz, const uint32_t* mask32, float* xout, float* hout, unsigned long long* mismatches,
+                           hipStream_t stream) {
   if (n_img <= 0) return hipSuccess;
   const int M = n_img * g.Ho * g.Wo, K1 = g.taps() * g.C;
-  switch (gather_tile(M, Cout, K1, g.C, Cout)) {  // the tile of conv_fwd_act
-    case TILE_128W8: return fwd_z_t<Tile128W8>(g, n_img, x, w, b, Cout, z, stream);
-    case TILE_64X128: return fwd_z_t<Tile64x128>(g, n_img, x, w, b, Cout, z, stream);
-    case TILE_64K2: return fwd_z_t<Tile64K2>(g, n_img, x, w, b, Cout, z, stream);
-    case TILE_32K4: return fwd_z_t<Tile32K4>(g, n_img, x, w, b, Cout, z, stream);
-    default: return fwd_z_t<Tile64>(g, n_img, x, w, b, Cout, z, stream);
+  EpiVijpGiven epi{EpiVijp<false>{b, alpha, 1.0f / alpha, reinterpret_cast<const uint64_t*>(mask32), nullptr, nullptr, nullptr, 0,
+                                  xout, hout, nullptr, mismatches},
+                   ctz};
+  switch (gather_tile(M, Cout, K1, g.C, Cout)) {  // the tile of conv_fwd_act: the recomputed signs must match bit for bit
+    case TILE_128W8: return fwd_given_t<Tile128W8>(g, n_img, x, w, Cout, epi, stream);
+    case TILE_64X128: return fwd_given_t<Tile64x128>(g, n_img, x, w, Cout, epi, stream);
+    case TILE_64K2: return fwd_given_t<Tile64K2>(g, n_img, x, w, Cout, epi, stream);
+    case TILE_32K4: return fwd_given_t<Tile32K4>(g, n_img, x, w, Cout, epi, stream);
+    default: return fwd_given_t<Tile64>(g, n_img, x, w, Cout, epi, stream);
   }
 }
 

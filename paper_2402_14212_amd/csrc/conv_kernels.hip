@@ -127,6 +127,38 @@ k_tri_inverse(const float* __restrict__ T, int64_t ld, int n, float* __restrict_
   }
 }
 
+// The same with the columns' partial results in LDS (one wavefront per 64 columns, x[i][lane]): the
+// entries of T are the same for every lane (scalar loads), and the running column no longer goes
+// through global memory between one row and the next. Needs n * 256 bytes of LDS.
+__global__ void __launch_bounds__(64)
+k_tri_inverse_lds(const float* __restrict__ T, int64_t ld, int n, float* __restrict__ Tinv, int32_t* __restrict__ flag) {
+  extern __shared__ __align__(16) float xs[];  // [n][64]
+  const int lane = threadIdx.x;
+  const int j = blockIdx.x * 64 + lane;
+  const bool live = j < n;
+  bool bad = false;
+  if (live) {
+    bad = (T[(int64_t)j * ld + j] == 0.f);
+    for (int c = 0; c < j; ++c) bad = bad || (T[(int64_t)c * ld + j] != 0.f);  // row c < column j must be 0
+    if (bad) *flag = 1;
+  }
+  const int j0 = blockIdx.x * 64;  // the first row in which any column of this wavefront is non-zero
+  for (int i = j0; i < n; ++i) {
+    float acc = 0.f;
+    for (int t = j0; t < i; ++t) acc += T[(int64_t)i * ld + t] * xs[t * 64 + lane];  // xs[t] = 0 above the diagonal
+    float v;
+    if (i < j) v = 0.f;
+    else if (i == j) v = 1.f / T[(int64_t)i * ld + i];
+    else v = -acc / T[(int64_t)i * ld + i];
+    if (bad) v = (i == j) ? 1.f : 0.f;
+    xs[i * 64 + lane] = v;
+  }
+  if (live) {
+    for (int i = 0; i < j0; ++i) Tinv[(int64_t)i * n + j] = 0.f;
+    for (int i = j0; i < n; ++i) Tinv[(int64_t)i * n + j] = xs[i * 64 + lane];
+  }
+}
+
 inline int cv_blocks(int64_t work_items) {
   int64_t b = (work_items + CV_THREADS - 1) / CV_THREADS;
   if (b < 1) b = 1;
@@ -226,6 +258,14 @@ hipError_t cv_copy_rows(const float* src, int64_t src_ld, float* dst, int64_t ds
 
 hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_t* flag, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
+  const size_t lds = (size_t)n * 64 * sizeof(float);
+  if (lds <= 128 * 1024) {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse_lds),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(k_tri_inverse_lds, dim3((n + 63) / 64), dim3(64), lds, stream, T, ld, n, Tinv, flag);
+    return hipGetLastError();
+  }
   const int threads = n < 1024 ? ((n + 63) / 64) * 64 : 1024;
   hipLaunchKernelGGL(k_tri_inverse, dim3((n + threads - 1) / threads), dim3(threads), 0, stream, T, ld, n, Tinv, flag);
   return hipGetLastError();

@@ -140,7 +140,7 @@ struct EpiVijp {
       rfrag = make_rsrc(RELU ? p.frag + base : nullptr, (uint32_t)room * 4u);
       rx = make_rsrc(p.X, extent_bytes(M, N, N));
       rh = make_rsrc(p.H, extent_bytes(M, N, N));
-      rc = make_rsrc(p.CTZ, extent_bytes(M, N, N));
+      rc = make_rsrc(p.CTZ, p.CTZ ? extent_bytes(M, N, N) : 0u);  // NULL: ct_z is not written (stores dropped)
     }
     template <int CNT>
     __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
@@ -200,6 +200,33 @@ struct EpiVijp {
     __device__ __forceinline__ void finish() const {
       if (mism) atomicAdd(mismatches, (unsigned long long)mism);
     }
+  };
+};
+
+// The leaky Phase-III epilogue for a layer whose ct_z is already in memory (rebuilt from fragments):
+// the product is x_{i-1} W^T only, ct_z is read instead of computed, and not written back.
+struct EpiVijpGiven {
+  EpiVijp<false> inner;  // inner.CTZ must be NULL
+  const float* CT;       // [M][N]
+  struct Dev {
+    EpiVijp<false>::Dev d;
+    __amdgpu_buffer_rsrc_t rct;
+    __device__ __forceinline__ Dev(const EpiVijpGiven& p, int M, int N) : d(p.inner, M, N) {
+      rct = make_rsrc(p.CT, extent_bytes(M, N, N));
+    }
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0, const float (&v)[1][CNT]) {
+      float w[2][CNT];
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        const int row = row_base + acc_row(i0 + j, g);
+        const bool valid = col < N && row < M;
+        w[0][j] = v[0][j];
+        w[1][j] = buf_load_f32(rct, valid ? ((uint32_t)row * (uint32_t)N + (uint32_t)col) * 4u : OOB);
+      }
+      d.template part<CNT>(M, N, row_base, col, g, i0, w);
+    }
+    __device__ __forceinline__ void finish() const { d.finish(); }
   };
 };
 

@@ -191,9 +191,11 @@ int64_t conv_gather_max_images(const ConvGeom& g, int Cout);
 // the sign bits of the same flat index, 32 per word
 hipError_t conv_fwd_act(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
                         float* xout, uint32_t* mask32, hipStream_t stream);
-// the pre-activation alone, z = patches(x) w + b, same tile and therefore the same bits as conv_fwd_act's z
-hipError_t conv_fwd_z(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, int Cout, float* z,
-                      hipStream_t stream);
+// Phase III of a layer whose ct_z [rows][Cout] is already in memory: z recomputed from x (the tile of
+// conv_fwd_act, hence the same bits), x out, h out = ct_z / slope, sign check against mask32
+hipError_t conv_vijp_given(const ConvGeom& g, int n_img, const float* x, const float* w, const float* b, float alpha, int Cout,
+                           const float* ctz, const uint32_t* mask32, float* xout, float* hout, unsigned long long* mismatches,
+                           hipStream_t stream);
 // Phase III of a leaky convolutional layer for n_img images: z recomputed from x, ct_z = sub(h_in) Tinv^T,
 // x out, h out = ct_z / slope, sign check against mask32. hin_as_read: hin is sub(h_in) itself,
 // [rows][Cout], instead of the whole input cotangent [n_img][H][W][C]

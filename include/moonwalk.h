@@ -308,6 +308,29 @@ int mw_conv_im2col(const float* x, int32_t H, int32_t W, int32_t C, int32_t k, i
 int mw_conv_col2im(const float* dpatches, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad,
                    int64_t img0, int64_t n_img, float* h, void* hip_stream);
 
+/* The three products that gather the patch matrix inside the MFMA main loop (kernel-level, for the
+   unit tests; the convolution of the lemma on submersive convolutional layers, its vjp and its parameter
+   vjp, for any kernel kh x kw, stride and paddings, not only the layers Moonwalk accepts). All tensors
+   device, channels-last; w is [kh][kw][C_in][C_out]; H', W' = (H + 2 ph - kh) / stride + 1, likewise W'.
+   C_in and C_out must be multiples of 32, every tensor below 2 GiB, stride * stride <= 9 for the input
+   cotangent (MW_ERR_INVALID_ARG otherwise).
+     mw_conv_forward:         xout [B][H'][W'][C_out] = act(conv(x, w) + b) with act = leaky ReLU of slope alpha
+                              (alpha = 1: none); b may be NULL; mask (may be NULL) gets the packed signs of z.
+     mw_conv_input_cotangent: h [B][H][W][C_in] = vjp of the convolution w.r.t. its input applied to ctz
+                              [B][H'][W'][C_out]; work: kh kw C_in C_out floats (regrouped taps).
+     mw_conv_weight_grad:     dw [kh][kw][C_in][C_out] = scale * vjp w.r.t. the kernel, db [C_out] = scale * sums of
+                              ctz over all positions; work: mw_conv_weight_grad_work_floats(...) floats. */
+typedef struct {
+  int32_t batch, height, width, channels_in, channels_out, kh, kw, stride, pad_h, pad_w;
+} mw_conv_shape_t;
+int mw_conv_forward(const mw_conv_shape_t* shape, const float* x, const float* w, const float* b, float alpha, float* xout,
+                    uint64_t* mask, void* hip_stream);
+int mw_conv_input_cotangent(const mw_conv_shape_t* shape, const float* ctz, const float* w, float* h, float* work,
+                            void* hip_stream);
+size_t mw_conv_weight_grad_work_floats(const mw_conv_shape_t* shape);
+int mw_conv_weight_grad(const mw_conv_shape_t* shape, const float* x, const float* ctz, float scale, float* dw, float* db,
+                        float* work, void* hip_stream);
+
 /* Measurement aid: run the gradient drivers with only ONE class of kernel launches enabled, so
    that a caller can time that class alone between two events on its stream (the launches then run
    back to back over the handle's real buffers, layer after layer, with the real shapes and cold

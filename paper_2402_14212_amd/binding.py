@@ -23,7 +23,8 @@ EXPORTED_SYMBOLS = [
     "mw_probe_operand_stream",
     "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
     "moonwalk_conv_grad_layout", "moonwalk_conv_memory_stats", "moonwalk_conv_fetch", "moonwalk_conv_destroy",
-    "mw_conv_im2col", "mw_conv_col2im",
+    "mw_conv_im2col", "mw_conv_col2im", "mw_conv_forward", "mw_conv_input_cotangent", "mw_conv_weight_grad_work_floats",
+    "mw_conv_weight_grad",
 ]
 
 
@@ -57,6 +58,11 @@ class _ConvLayer(C.Structure):
     _fields_ = [("channels_in", C.c_int32), ("channels_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32),
                 ("pad", C.c_int32), ("w", C.c_void_p), ("b", C.c_void_p), ("alpha", C.c_float),
                 ("kind", C.c_int32), ("block", C.c_int32)]
+
+
+class _ConvShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("batch", "height", "width", "channels_in", "channels_out", "kh", "kw", "stride",
+                                         "pad_h", "pad_w")]
 
 
 class _ConvConfig(C.Structure):
@@ -134,6 +140,11 @@ def load_library() -> C.CDLL:
     lib.moonwalk_conv_destroy.argtypes = [vp]
     lib.moonwalk_conv_destroy.restype = None
     lib.mw_conv_im2col.argtypes = [vp, i32, i32, i32, i32, i32, i32, i64, i64, vp, vp]
+    lib.mw_conv_forward.argtypes = [C.POINTER(_ConvShape), vp, vp, vp, C.c_float, vp, vp, vp]
+    lib.mw_conv_input_cotangent.argtypes = [C.POINTER(_ConvShape), vp, vp, vp, vp, vp]
+    lib.mw_conv_weight_grad_work_floats.argtypes = [C.POINTER(_ConvShape)]
+    lib.mw_conv_weight_grad_work_floats.restype = C.c_size_t
+    lib.mw_conv_weight_grad.argtypes = [C.POINTER(_ConvShape), vp, vp, C.c_float, vp, vp, vp, vp]
     lib.mw_conv_col2im.argtypes = [vp, i32, i32, i32, i32, i32, i32, i64, i64, vp, vp]
     _lib = lib
     return lib
@@ -556,6 +567,56 @@ def conv_col2im(dpatches: torch.Tensor, shape, k: int, stride: int, pad: int) ->
     out = torch.empty(B, H, W, Cc, dtype=torch.float32, device=dpatches.device)
     _check(load_library().mw_conv_col2im(_ptr(_f32(dpatches)), H, W, Cc, k, stride, pad, 0, B, _ptr(out), _stream()))
     return out
+
+
+def _conv_shape(x_shape, w: torch.Tensor, stride: int, pad_h: int, pad_w: int) -> "_ConvShape":
+    B, H, W, Ci = x_shape
+    kh, kw, ci, co = w.shape
+    if ci != Ci:
+        raise ValueError("kernel and input channel counts differ")
+    return _ConvShape(B, H, W, Ci, co, kh, kw, int(stride), int(pad_h), int(pad_w))
+
+
+def conv_forward(x: torch.Tensor, w: torch.Tensor, b: Optional[torch.Tensor], stride: int, pad_h: int, pad_w: int,
+                 alpha: float = 1.0, want_mask: bool = False):
+    """act(conv(x, w) + b) by the product that gathers the patch matrix; x [B][H][W][C_in], w [kh][kw][C_in][C_out].
+    Returns xout, or (xout, mask words) with want_mask."""
+    _require_gpu()
+    sh = _conv_shape(x.shape, w, stride, pad_h, pad_w)
+    Ho, Wo = (sh.height + 2 * sh.pad_h - sh.kh) // sh.stride + 1, (sh.width + 2 * sh.pad_w - sh.kw) // sh.stride + 1
+    out = torch.empty(sh.batch, Ho, Wo, sh.channels_out, dtype=torch.float32, device=x.device)
+    mask = torch.zeros((out.numel() + 63) // 64, dtype=torch.int64, device=x.device) if want_mask else None
+    _check(load_library().mw_conv_forward(C.byref(sh), _ptr(_f32(x)), _ptr(_f32(w)), _ptr(_f32(b)) if b is not None else None,
+                                          float(alpha), _ptr(out), _ptr(mask) if want_mask else None, _stream()))
+    return (out, mask) if want_mask else out
+
+
+def conv_input_cotangent(ctz: torch.Tensor, w: torch.Tensor, in_hw, stride: int, pad_h: int, pad_w: int) -> torch.Tensor:
+    """vjp of the convolution w.r.t. its input, applied to ctz [B][H'][W'][C_out]; returns h [B][H][W][C_in]."""
+    _require_gpu()
+    B = ctz.shape[0]
+    sh = _conv_shape((B, in_hw[0], in_hw[1], w.shape[2]), w, stride, pad_h, pad_w)
+    h = torch.empty(B, in_hw[0], in_hw[1], w.shape[2], dtype=torch.float32, device=ctz.device)
+    work = torch.empty(w.numel(), dtype=torch.float32, device=ctz.device)
+    _check(load_library().mw_conv_input_cotangent(C.byref(sh), _ptr(_f32(ctz)), _ptr(_f32(w)), _ptr(h), _ptr(work), _stream()))
+    return h
+
+
+def conv_weight_grad(x: torch.Tensor, ctz: torch.Tensor, kh: int, kw: int, stride: int, pad_h: int, pad_w: int, scale: float = 1.0):
+    """(dw [kh][kw][C_in][C_out], db [C_out]) = scale * the parameter vjp of the convolution."""
+    _require_gpu()
+    B, H, W, Ci = x.shape
+    Co = ctz.shape[3]
+    sh = _ConvShape(B, H, W, Ci, Co, int(kh), int(kw), int(stride), int(pad_h), int(pad_w))
+    lib = load_library()
+    n_work = int(lib.mw_conv_weight_grad_work_floats(C.byref(sh)))
+    if n_work == 0:
+        raise MoonwalkError(-1, "shape not supported by the gathered weight-gradient kernel")
+    work = torch.empty(n_work, dtype=torch.float32, device=x.device)
+    dw = torch.empty(kh, kw, Ci, Co, dtype=torch.float32, device=x.device)
+    db = torch.empty(Co, dtype=torch.float32, device=x.device)
+    _check(lib.mw_conv_weight_grad(C.byref(sh), _ptr(_f32(x)), _ptr(_f32(ctz)), float(scale), _ptr(dw), _ptr(db), _ptr(work), _stream()))
+    return dw, db
 
 
 # ---------------------------------------------------------------------- kernel-level entries

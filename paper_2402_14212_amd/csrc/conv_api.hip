@@ -734,6 +734,61 @@ int mw_conv_im2col(const float* x, int32_t H, int32_t W, int32_t C, int32_t k, i
   return MW_OK;
 }
 
+namespace {
+
+// geometry of a kernel-level call, or false if the gathered kernels cannot take it
+bool shape_geom(const mw_conv_shape_t* sh, ConvGeom* g) {
+  if (!sh || sh->batch <= 0 || sh->height <= 0 || sh->width <= 0 || sh->channels_in <= 0 || sh->channels_out <= 0) return false;
+  if (sh->kh <= 0 || sh->kw <= 0 || sh->stride <= 0 || sh->pad_h < 0 || sh->pad_w < 0) return false;
+  if (sh->height + 2 * sh->pad_h < sh->kh || sh->width + 2 * sh->pad_w < sh->kw) return false;
+  if (sh->channels_in % 32 || sh->channels_out % 32) return false;
+  const int Ho = (sh->height + 2 * sh->pad_h - sh->kh) / sh->stride + 1, Wo = (sh->width + 2 * sh->pad_w - sh->kw) / sh->stride + 1;
+  *g = ConvGeom{sh->height, sh->width, sh->channels_in, Ho, Wo, sh->kh, sh->kw, sh->stride, sh->pad_h, sh->pad_w};
+  if ((int64_t)g->taps() * g->C >= (1 << 24)) return false;
+  return conv_gather_max_images(*g, sh->channels_out) >= sh->batch;  // one launch: everything below 2 GiB
+}
+bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+int mw_conv_forward(const mw_conv_shape_t* shape, const float* x, const float* w, const float* b, float alpha, float* xout,
+                    uint64_t* mask, void* hip_stream) {
+  ConvGeom g;
+  if (!shape_geom(shape, &g) || !x || !w || !xout || !al16(x) || !al16(w) || !(alpha > 0.f)) return MW_ERR_INVALID_ARG;
+  CV_HIP(conv_fwd_act(g, shape->batch, x, w, b, alpha, shape->channels_out, xout, reinterpret_cast<uint32_t*>(mask),
+                      static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+int mw_conv_input_cotangent(const mw_conv_shape_t* shape, const float* ctz, const float* w, float* h, float* work,
+                            void* hip_stream) {
+  ConvGeom g;
+  if (!shape_geom(shape, &g) || !ctz || !w || !h || !work || !al16(ctz) || !al16(work)) return MW_ERR_INVALID_ARG;
+  if (!conv_rev_ok(g, shape->channels_out)) return MW_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CV_HIP(cv_pack_rev_weights(w, g.kh, g.kw, g.s, g.C, shape->channels_out, work, s));
+  CV_HIP(conv_input_cotangent(g, shape->batch, shape->channels_out, ctz, work, h, nullptr, nullptr, 1.f, s));
+  return MW_OK;
+}
+
+size_t mw_conv_weight_grad_work_floats(const mw_conv_shape_t* shape) {
+  ConvGeom g;
+  if (!shape_geom(shape, &g)) return 0;
+  return conv_dw_part_floats(g, shape->batch, shape->channels_out) + (size_t)COLSUM_MAX_SLICES * shape->channels_out;
+}
+
+int mw_conv_weight_grad(const mw_conv_shape_t* shape, const float* x, const float* ctz, float scale, float* dw, float* db,
+                        float* work, void* hip_stream) {
+  ConvGeom g;
+  if (!shape_geom(shape, &g) || !x || !ctz || !dw || !db || !work || !al16(x) || !al16(ctz) || !al16(work) || !al16(dw))
+    return MW_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t part = conv_dw_part_floats(g, shape->batch, shape->channels_out);
+  CV_HIP(conv_dw(g, shape->batch, x, ctz, shape->channels_out, scale, 0.f, dw, work, s));
+  CV_HIP(ew_colsum_wide(ctz, (int64_t)shape->batch * g.Ho * g.Wo, shape->channels_out, scale, 0.f, db, work + part, s));
+  return MW_OK;
+}
+
 int mw_conv_col2im(const float* dpatches, int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad,
                    int64_t img0, int64_t n_img, float* h, void* hip_stream) {
   if (!dpatches || !h || H <= 0 || W <= 0 || C <= 0 || k <= 0 || stride <= 0 || pad < 0 || img0 < 0 || n_img < 0)

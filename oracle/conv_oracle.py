@@ -228,3 +228,23 @@ def conv_moonwalk(ws, bs, alphas, s: int, p: int, x0, t, forced_masks=None, loss
         h = (ct_z / slope).astype(dtype)
         x = np.where(masks[i], z, dtype(alphas[i]) * z).astype(dtype)
     return {"dW": dW, "db": db, "loss": loss, "masks": masks, "h0": h0}
+
+
+def project_constrained(w, p: int):
+    """The lemma constrains the tap at (p, p): w[p, p, c, c'] = 0 for c < c' (within the first C_out rows).
+    A training step must leave those entries at zero; this puts them back."""
+    w = np.array(_as64(w))
+    Co = w.shape[3]
+    w[p, p, :Co, :] = np.tril(w[p, p, :Co, :])
+    return w
+
+
+def conv_sgd_step(ws, bs, alphas, s: int, p: int, x0, t, lr: float, forced_masks=None) -> Dict[str, object]:
+    """One training step (Algorithm 1 with "Apply g_i"): theta_i <- theta_i - lr g_i with the gradients of
+    conv_moonwalk, the constrained entries of the (p, p) taps kept at zero (a projected step, so that the
+    layers stay submersive). Returns the new kernels and biases and the loss before the update."""
+    g = conv_moonwalk(ws, bs, alphas, s, p, x0, t, forced_masks=forced_masks)
+    new_w = [project_constrained(_as64(w) - lr * dw, p) for w, dw in zip(ws, g["dW"])]
+    new_b = [_as64(b) - lr * db for b, db in zip(bs, g["db"])]
+    return {"w": new_w, "b": new_b, "loss": g["loss"], "masks": g["masks"]}
+

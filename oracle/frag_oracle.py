@@ -216,3 +216,22 @@ def frag_moonwalk(ws, bs, alphas, x0, t, block: int, forced_masks=None, loss_sca
         x = np.where(masks[i], z, alphas[i] * z).astype(dtype)
     return {"dW": dW, "db": db, "loss": loss, "masks": masks, "h0": h0, "frags": frags,
             "sign_mismatches": mismatches}
+
+
+def project_constrained(w):
+    """The fragmental update constrains the tap u = 0: w[0, c, c'] = 0 for c < c' (within the first C_out
+    rows). A training step must leave those entries at zero; this puts them back."""
+    w = np.array(_as64(w))
+    Co = w.shape[2]
+    w[0, :Co, :] = np.tril(w[0, :Co, :])
+    return w
+
+
+def frag_sgd_step(ws, bs, alphas, x0, t, lr: float, block: int, forced_masks=None) -> Dict[str, object]:
+    """One training step (Algorithm 1 with "Apply g_i"): theta_i <- theta_i - lr g_i with the gradients of
+    frag_moonwalk, the constrained entries of the taps u = 0 kept at zero (a projected step)."""
+    g = frag_moonwalk(ws, bs, alphas, x0, t, block, forced_masks=forced_masks)
+    new_w = [project_constrained(_as64(w) - lr * dw) for w, dw in zip(ws, g["dW"])]
+    new_b = [_as64(b) - lr * db for b, db in zip(bs, g["db"])]
+    return {"w": new_w, "b": new_b, "loss": g["loss"], "masks": g["masks"]}
+

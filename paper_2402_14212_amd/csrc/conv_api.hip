@@ -1,15 +1,20 @@
-// Moonwalk on submersive 2-D convolutional layers (lemma on submersive convolutional layers; the
-// paper's fully parallel 2-D setting): handle, buffer plan and the gradient drivers behind the C ABI.
+// Moonwalk on convolutional layers: handle, buffer plan and the gradient drivers behind the C ABI.
+// Two kinds of layer: submersive 2-D convolutions (lemma on submersive convolutional layers; the
+// paper's fully parallel 2-D setting), and length-preserving 1-D convolutions with fragmental
+// checkpointing (section on fragmental gradient checkpointing and its appendix).
 //
 // A convolution is run as the library's fp32 MFMA GEMMs on patch matrices. Where the channel
-// counts allow it (C_in a multiple of 4, C_out of 32) the patch matrix never exists in memory: the
-// GEMM gathers its operand from the image (conv_gemm.h), the forward product ends in the
-// activation and the sign mask, Phase III is one kernel per layer (recomputed forward, channel
-// solve, vijp epilogue) and the weight gradient is split over the patch rows. Otherwise, and for
-// the input cotangent of Phase II in every case, the images are taken in chunks, each chunk's
-// patches go through one bounded buffer (im2col; back through col2im, a fixed-order sum). The vijp
-// of the convolution, in the fully parallel case k <= p + s, is a triangular solve over channels at
-// every output position, done as a product with the inverse of the channel-triangular tap.
+// counts allow it (C_in and C_out multiples of 32) the patch matrix never exists in memory: the
+// products gather their operand from the image (conv_gemm.h). The forward product ends in the
+// activation and the sign mask; the input cotangent is one product per stride class of input
+// pixels, ending in the previous layer's slope; Phase III of a submersive layer is one kernel
+// (recomputed forward, channel solve, vijp epilogue), of a fragmental layer the block-wise rebuild
+// of ct_z followed by one kernel (recomputed forward, vijp epilogue); the weight gradient is split
+// over the patch rows. Submersive layers with other channel counts go through a bounded patch
+// buffer in image chunks instead (im2col, plain GEMMs, col2im, a fixed-order sum).
+// The vijp of a submersive convolution, in the fully parallel case k <= p + s, is a triangular
+// solve over channels at every output position, done as a product with the inverse of the
+// channel-triangular tap; the cotangents Phase III starts from are kept in the form it reads them.
 #include "../../include/moonwalk.h"
 
 #include <cmath>

@@ -120,3 +120,31 @@ def test_conv_moonwalk_equals_backprop(k, s, p, H):
         assert np.linalg.norm(a - b) < 1e-9 * np.linalg.norm(b)
     for a, b in zip(mw["db"], ref["db"]):
         assert np.linalg.norm(a - b) < 1e-9 * np.linalg.norm(b)
+
+
+def test_sgd_step_is_a_projected_descent_step():
+    """The training step: stays submersive, leaves the constrained entries at exactly zero, moves every other
+    entry by -lr times the gradient backprop gives, and lowers the loss by lr ||projected gradient||^2 to
+    first order (pins the sign and the scale of the update)."""
+    wl = make_convnet(2, 8, 4, 2, alpha=0.3, seed=5)
+    ref = CO.conv_backprop(wl.w, wl.b, wl.alphas, wl.s, wl.p, wl.x, wl.t)
+    for lr in (1e-3, 1e-4):
+        out = CO.conv_sgd_step(wl.w, wl.b, wl.alphas, wl.s, wl.p, wl.x, wl.t, lr)
+        assert abs(out["loss"] - ref["loss"]) < 1e-12
+        gnorm2 = 0.0
+        for w0, w1, dw in zip(wl.w, out["w"], ref["dW"]):
+            free = np.ones(w0.shape, dtype=bool)
+            free[wl.p, wl.p] = np.tril(np.ones((4, 4), dtype=bool))
+            assert np.all(w1[~free] == 0.0)
+            assert np.allclose(w1[free], (w0.astype(np.float64) - lr * dw)[free], rtol=0, atol=1e-15)
+            gnorm2 += float(np.sum(dw[free] ** 2))
+        for b0, b1, db in zip(wl.b, out["b"], ref["db"]):
+            assert np.allclose(b1, b0.astype(np.float64) - lr * db, rtol=0, atol=1e-15)
+            gnorm2 += float(np.sum(db ** 2))
+        after = CO.conv_backprop(out["w"], out["b"], wl.alphas, wl.s, wl.p, wl.x, wl.t)["loss"]
+        drop = ref["loss"] - after
+        assert drop > 0
+        assert abs(drop - lr * gnorm2) <= 0.05 * lr * gnorm2 + 1e-3 * lr   # first order in lr
+        for i, w1 in enumerate(out["w"]):
+            assert CO.is_submersive(w1, wl.s, wl.p, wl.sides[i])
+

@@ -139,3 +139,24 @@ def test_fp32_error_of_the_block_recurrence_stays_small_for_the_workload_recipe(
         m32 = FO.frag_moonwalk(wl.w, wl.b, wl.alphas, wl.x, wl.t, block, forced_masks=ref["masks"], dtype=np.float32)
         err = max(np.linalg.norm(np.asarray(a, dtype=np.float64) - b) / np.linalg.norm(b) for a, b in zip(m32["dW"], ref["dW"]))
         assert err < bound, (gain, block, err)
+
+
+def test_frag_sgd_step_is_a_projected_descent_step():
+    wl = make_fragnet(2, 16, 4, 2, block=4, gain=1.0, diag=(0.8, 1.2), seed=7)
+    ref = FO.conv1d_backprop(wl.w, wl.b, wl.alphas, wl.x, wl.t)
+    lr = 1e-3
+    out = FO.frag_sgd_step(wl.w, wl.b, wl.alphas, wl.x, wl.t, lr, 4)
+    gnorm2 = 0.0
+    for w0, w1, dw in zip(wl.w, out["w"], ref["dW"]):
+        free = np.ones(w0.shape, dtype=bool)
+        free[0] = np.tril(np.ones((4, 4), dtype=bool))
+        assert np.all(w1[~free] == 0.0) and FO.is_fragmental(w1)
+        assert np.allclose(w1[free], (w0.astype(np.float64) - lr * dw)[free], rtol=0, atol=1e-15)
+        gnorm2 += float(np.sum(dw[free] ** 2))
+    for b0, b1, db in zip(wl.b, out["b"], ref["db"]):
+        assert np.allclose(b1, b0.astype(np.float64) - lr * db, rtol=0, atol=1e-15)
+        gnorm2 += float(np.sum(db ** 2))
+    after = FO.conv1d_backprop(out["w"], out["b"], wl.alphas, wl.x, wl.t)["loss"]
+    drop = ref["loss"] - after
+    assert drop > 0 and abs(drop - lr * gnorm2) <= 0.05 * lr * gnorm2 + 1e-3 * lr
+

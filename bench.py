@@ -149,6 +149,19 @@ def bench_conv(args):
         mem_bp = {"bytes_residual": sb["bytes_bp_activations"], "bytes_input_cotangent": sb["bytes_input_cotangent"],
                   "bytes_scratch": sb["bytes_bp_scratch"] + sb["bytes_scratch"] + sb["bytes_patches"],
                   "bytes_packed_weights": sb["bytes_packed_weights"], "bytes_total": sb["bytes_peak"]}
+    train = {}
+    if not args.no_train:
+        # the training step in place (gradients applied in the weight-gradient reduction, constrained taps
+        # projected, derived matrices refreshed); a step that moves the weights by about 1e-4 of their size
+        net.close()
+        net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, plan=mw.PLAN_MOONWALK, input_cotangent=h0_mode)
+        gn = float(grads.double().norm().item()) if grads_probe is None else float(grads_probe.double().norm().item())
+        wn = float(torch.sqrt(sum((w.double() ** 2).sum() for w in net.ws)).item())
+        lr = 1e-4 * wn / max(gn, 1e-30)
+        ms_tr, _ = time_steps(lambda: net.sgd_step(net.x, net.t, lr, loss), args.steps, args.warmup)
+        train = {"ms_per_step": ms_tr, "steps_per_s": 1e3 / ms_tr, "lr": lr,
+                 "note": "moonwalk_conv_sgd_step: gradients applied in place, no gradient buffer; includes the refresh of the "
+                         "tap inverses and regrouped taps and its synchronisation"}
     achieved = flops_mw / (ms_mw * 1e-3) / 1e12
     residual_mw = st["bytes_masks"] + st["bytes_checkpoints"] + st["bytes_fragments"]
     if frag1d:
@@ -182,6 +195,7 @@ def bench_conv(args):
                    "backprop": mem_bp,
                    "bytes_input": int(wl.x.numel() if hasattr(wl.x, "numel") else wl.x.size) * 4},
         "backprop": bp,
+        "train_step": train,
     }
     net.close()
     if not args.no_cpu_baseline and frag1d:

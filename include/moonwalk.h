@@ -291,6 +291,18 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
                        void* hip_stream);
 int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
                        void* hip_stream);
+/* One training step in place (Algorithm 1 with "Apply g_i"): the phases of moonwalk_conv_grad, but each
+   layer's gradient goes straight onto that layer's own arrays, w_i -= lr dw_i and b_i -= lr db_i (a layer
+   given b = NULL has no bias to update), in the reduction that ends the weight-gradient product; the w and
+   b arrays given at setup are WRITTEN. The entries the method constrains to zero (above the diagonal of
+   the triangular tap, first C_out rows) are then put back to zero: a projected step, the layers stay
+   submersive / fragmental as long as no diagonal entry reaches zero. No gradient buffer exists at any
+   time. Ends with what moonwalk_conv_refresh does. Every layer must be on the gathered kernels and the
+   plan must hold MW_PLAN_MOONWALK (MW_ERR_NOT_PLANNED otherwise). loss_out: the loss BEFORE the update.
+   Synchronises (the refresh reads back its check of the taps); returns MW_ERR_NOT_SUBMERSIVE if a diagonal
+   entry has become zero. */
+int moonwalk_conv_sgd_step(mw_conv_handle_t* h, const float* x, const float* target, float lr, float* loss_out,
+                           void* hip_stream);
 int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
 int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out);
 /* what: MW_FETCH_MASK, MW_FETCH_H0 (whole or as read, see the config), MW_FETCH_P (here: T^{-1},

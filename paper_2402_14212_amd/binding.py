@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "mw_probe_operand_stream",
     "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
     "moonwalk_conv_grad_layout", "moonwalk_conv_memory_stats", "moonwalk_conv_fetch", "moonwalk_conv_destroy",
-    "mw_conv_im2col", "mw_conv_col2im", "mw_conv_forward", "mw_conv_input_cotangent", "mw_conv_weight_grad_work_floats",
+    "moonwalk_conv_sgd_step", "mw_conv_im2col", "mw_conv_col2im", "mw_conv_forward", "mw_conv_input_cotangent", "mw_conv_weight_grad_work_floats",
     "mw_conv_weight_grad",
 ]
 
@@ -133,6 +133,7 @@ def load_library() -> C.CDLL:
     lib.moonwalk_conv_setup.argtypes = [C.POINTER(vp), C.POINTER(_ConvLayer), i32, C.POINTER(_ConvConfig), vp]
     lib.moonwalk_conv_refresh.argtypes = [vp, vp]
     lib.moonwalk_conv_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.moonwalk_conv_sgd_step.argtypes = [vp, vp, vp, C.c_float, vp, vp]
     lib.backprop_conv_grad.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.moonwalk_conv_grad_layout.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     lib.moonwalk_conv_memory_stats.argtypes = [vp, C.POINTER(_ConvMemStats)]
@@ -498,6 +499,14 @@ class ConvMoonwalkNet:
     def refresh(self):
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_conv_refresh(self._handle, _stream()))
+
+    def sgd_step(self, x, target, lr: float, loss_out=None) -> torch.Tensor:
+        """One training step in place: self.ws / self.bs are updated; returns the loss before the update."""
+        loss = loss_out if loss_out is not None else torch.empty(1, dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self._lib.moonwalk_conv_sgd_step(self._handle, _ptr(_f32(x)), _ptr(_f32(target)), float(lr), _ptr(loss),
+                                                    _stream()))
+        return loss
 
     def memory_stats(self, check: bool = True) -> dict:
         st = _ConvMemStats()

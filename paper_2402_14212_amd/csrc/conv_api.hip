@@ -253,13 +253,14 @@ int conv_forward_layer(mw_conv_handle* h, const ConvLayer& l, const float* xin, 
 }
 
 // dW (+ db) of one layer from its input activation and ct_z, both for the whole batch
+// dW = scale * (parameter vjp) + beta0 * dW, likewise db (db may be NULL: not wanted)
 int conv_weight_grad(mw_conv_handle* h, const ConvLayer& l, const float* xin, const float* ctz, float scale, float* dW,
-                     float* db, hipStream_t s) {
+                     float* db, hipStream_t s, float beta0 = 0.f) {
   bool first = true;
   if (l.gather) {
     for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
       const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
-      CV_HIP(conv_dw(l.geom(), n_img, xin + img0 * l.in_img(), ctz + img0 * l.out_img(), l.Cout, scale, first ? 0.f : 1.f, dW,
+      CV_HIP(conv_dw(l.geom(), n_img, xin + img0 * l.in_img(), ctz + img0 * l.out_img(), l.Cout, scale, first ? beta0 : 1.f, dW,
                      h->dw_part, s));
       first = false;
     }
@@ -270,13 +271,16 @@ int conv_weight_grad(mw_conv_handle* h, const ConvLayer& l, const float* xin, co
       const int64_t r0 = img0 * per_img, R = n_img * per_img;
       CV_HIP(cv_im2col(xin, l.Hin, l.Win, l.Cin, l.Ho, l.Wo, l.k, l.s, l.p, r0, R, h->patches, s));
       CV_HIP(gemm_plain(OP_TN, TILE_AUTO, l.K, l.Cout, (int)R, scale, h->patches, l.K, ctz + r0 * l.Cout, l.Cout,
-                        first ? 0.f : 1.f, dW, l.Cout, nullptr, s));
+                        first ? beta0 : 1.f, dW, l.Cout, nullptr, s));
       first = false;
     }
   }
-  CV_HIP(ew_colsum_wide(ctz, l.rows, l.Cout, scale, 0.f, db, h->colsum_part, s));
+  if (db) CV_HIP(ew_colsum_wide(ctz, l.rows, l.Cout, scale, beta0, db, h->colsum_part, s));
   return MW_OK;
 }
+
+int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, bool apply,
+                      float lr, hipStream_t s);
 
 }  // namespace
 
@@ -498,7 +502,30 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   if (!h || !x || !target || !grads_out) return MW_ERR_INVALID_ARG;
   if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
   if (h->layers[0].gather && (reinterpret_cast<uintptr_t>(x) & 15)) return MW_ERR_INVALID_ARG;
+  return run_conv_moonwalk(h, x, target, grads_out, loss_out, false, 0.f, static_cast<hipStream_t>(hip_stream));
+}
+
+int moonwalk_conv_sgd_step(mw_conv_handle_t* h, const float* x, const float* target, float lr, float* loss_out,
+                           void* hip_stream) {
+  if (!h || !x || !target || !std::isfinite(lr)) return MW_ERR_INVALID_ARG;
+  if (!(h->plan & MW_PLAN_MOONWALK)) return MW_ERR_NOT_PLANNED;
+  // in the patch-buffer path a layer's forward and weight-gradient products alternate chunk by chunk, so its
+  // weights cannot change under it: the step needs every layer on the gathered kernels
+  for (const auto& l : h->layers)
+    if (!l.gather) return MW_ERR_NOT_PLANNED;
+  if (reinterpret_cast<uintptr_t>(x) & 15) return MW_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = run_conv_moonwalk(h, x, target, nullptr, loss_out, true, lr, s);
+  if (rc != MW_OK) return rc;
+  return build_from_weights(h, s);
+}
+
+}  // extern "C"
+
+namespace {
+
+int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, bool apply,
+                      float lr, hipStream_t s) {
   const int L = h->L;
   unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
   CV_HIP(ew_fill_u32(h->status, 0u, 2, s));
@@ -553,6 +580,10 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   }
   // ---------------- Phase III: forward vijp sweep
   const float inv_scale = 1.0f / h->loss_scale;
+  // Where the layer's gradient goes: into grads_out, or (training step) straight onto the layer's own
+  // weights as -lr * gradient, after which the entries the method constrains to zero are put back.
+  const float g_scale = apply ? -lr * inv_scale : inv_scale;
+  const float g_beta = apply ? 1.f : 0.f;
   float* hbuf[2] = {h->ha, h->hb};
   xin = x;
   const float* hin = h->h0;
@@ -577,7 +608,8 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
         CV_HIP(conv_vijp_given(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, h->ctz + o,
                                reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, mismatches, s));
       }
-      rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
+      rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
+                            apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
       if (rc != MW_OK) return rc;
     } else if (l.gather) {
       // one kernel per image chunk: recomputed forward, channel solve at the strided positions, vijp epilogue
@@ -588,9 +620,11 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
                                hin + img0 * (hin_as_read ? l.out_img() : l.in_img()), hin_as_read ? 1 : 0, l.Tinv, reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, h->ctz + o,
                                mismatches, s));
       }
-      int rc = conv_weight_grad(h, l, xin, h->ctz, inv_scale, grads_out + l.dW_off, grads_out + l.db_off, s);
+      int rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
+                                apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
       if (rc != MW_OK) return rc;
     } else {
+      if (apply) return MW_ERR_NOT_PLANNED;
       // vijp of the convolution: right-hand sides at the strided positions, then the channel solve as a product
       const float* rhs = hin;
       if (!hin_as_read) {
@@ -615,12 +649,18 @@ int moonwalk_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
       CV_HIP(ew_vijp_epilogue(h->zbuf, h->ctz, l.rows, l.Cout, l.alpha, l.mask, nullptr, nullptr, nullptr, 0, xout, hout,
                               mismatches, s));
     }
+    if (apply)  // the projected step: above the diagonal of the triangular tap the weights stay zero
+      CV_HIP(cv_zero_above_diagonal(const_cast<float*>(l.tri_tap()), l.Cout, l.Cout, s));
     xin = xout;
     hin = hout;
     hin_as_read = false;
   }
   return MW_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target, float* grads_out, float* loss_out,
                        void* hip_stream) {

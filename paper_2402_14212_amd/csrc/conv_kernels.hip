@@ -159,6 +159,52 @@ k_tri_inverse_lds(const float* __restrict__ T, int64_t ld, int n, float* __restr
   }
 }
 
+// Blocked inverse, first step: workgroup b inverts the 64 x 64 diagonal block b of T into the same
+// block of Tinv (row stride n) by the substitution above, 64 columns side by side in LDS.
+__global__ void __launch_bounds__(64)
+k_tri_inverse_diag64(const float* __restrict__ T, int64_t ld, int n, float* __restrict__ Tinv, int32_t* __restrict__ flag) {
+  __shared__ float xs[64 * 64];
+  const int lane = threadIdx.x;
+  const int o = blockIdx.x * 64;
+  const float* Tb = T + (int64_t)o * ld + o;
+  float* Ib = Tinv + (int64_t)o * n + o;
+  const int j = lane;
+  const bool bad = (Tb[(int64_t)j * ld + j] == 0.f);
+  if (bad) *flag = 1;
+  for (int i = 0; i < 64; ++i) {
+    float acc = 0.f;
+    for (int t = 0; t < i; ++t) acc += Tb[(int64_t)i * ld + t] * xs[t * 64 + lane];
+    float v;
+    if (i < j) v = 0.f;
+    else if (i == j) v = 1.f / Tb[(int64_t)i * ld + i];
+    else v = -acc / Tb[(int64_t)i * ld + i];
+    if (bad) v = (i == j) ? 1.f : 0.f;
+    xs[i * 64 + lane] = v;
+  }
+  for (int i = 0; i < 64; ++i) Ib[(int64_t)i * n + j] = xs[i * 64 + lane];
+}
+
+// Blocked inverse, last step: everything above the diagonal of Tinv is zero (the blocks there served as
+// scratch), and T itself must have been zero there (*flag raised otherwise).
+__global__ void __launch_bounds__(256)
+k_tri_inverse_finish(const float* __restrict__ T, int64_t ld, int n, float* __restrict__ Tinv, int32_t* __restrict__ flag) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)n * n) return;
+  const int c = (int)(i / n), cp = (int)(i % n);
+  if (c < cp) {
+    if (T[(int64_t)c * ld + cp] != 0.f) *flag = 1;
+    Tinv[(int64_t)c * n + cp] = 0.f;
+  }
+}
+
+// T[c][c'] = 0 for c < c' < n (row stride ld): the entries a training step must leave at zero
+__global__ void __launch_bounds__(256) k_zero_above_diagonal(float* __restrict__ T, int64_t ld, int n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (int64_t)n * n) return;
+  const int c = (int)(i / n), cp = (int)(i % n);
+  if (c < cp) T[(int64_t)c * ld + cp] = 0.f;
+}
+
 inline int cv_blocks(int64_t work_items) {
   int64_t b = (work_items + CV_THREADS - 1) / CV_THREADS;
   if (b < 1) b = 1;
@@ -256,8 +302,40 @@ hipError_t cv_copy_rows(const float* src, int64_t src_ld, float* dst, int64_t ds
   return hipGetLastError();
 }
 
+hipError_t cv_zero_above_diagonal(float* T, int64_t ld, int n, hipStream_t stream) {
+  if (n <= 1) return hipSuccess;
+  const int64_t total = (int64_t)n * n;
+  hipLaunchKernelGGL(k_zero_above_diagonal, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, T, ld, n);
+  return hipGetLastError();
+}
+
 hipError_t cv_tri_inverse(const float* T, int64_t ld, int n, float* Tinv, int32_t* flag, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
+  // n = 64 * 2^j, j >= 1: blocked. With T = [A 0; B D], T^{-1} = [A^{-1} 0; -D^{-1} B A^{-1}  D^{-1}]: the 64 x 64
+  // diagonal blocks first, then pairs of inverted blocks are joined, doubling the block size each time;
+  // X = D^{-1} B is parked in the top right quarter of Tinv, which no diagonal block of any step touches and
+  // which the last kernel clears with the rest of the upper triangle.
+  if (n >= 128 && n % 64 == 0 && ((n / 64) & (n / 64 - 1)) == 0) {
+    const int64_t total = (int64_t)n * n;
+    // the joined blocks are read whole: what lies above their diagonals must be zero from the start
+    hipLaunchKernelGGL(k_tri_inverse_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, T, ld, n, Tinv, flag);
+    hipLaunchKernelGGL(k_tri_inverse_diag64, dim3(n / 64), dim3(64), 0, stream, T, ld, n, Tinv, flag);
+    hipError_t e = hipGetLastError();
+    for (int m = 64; m < n && e == hipSuccess; m *= 2) {
+      for (int o = 0; o < n && e == hipSuccess; o += 2 * m) {
+        const float* Ainv = Tinv + (int64_t)o * n + o;
+        const float* Dinv = Tinv + (int64_t)(o + m) * n + (o + m);
+        const float* B = T + (int64_t)(o + m) * ld + o;
+        float* X = Tinv + (int64_t)(o / 2) * n + n / 2;    // pair o / (2 m) gets rows [o / 2, o / 2 + m) of the quarter
+        float* Low = Tinv + (int64_t)(o + m) * n + o;
+        e = gemm_plain(OP_NN, TILE_AUTO, m, m, m, 1.f, Dinv, n, B, ld, 0.f, X, n, nullptr, stream);
+        if (e == hipSuccess) e = gemm_plain(OP_NN, TILE_AUTO, m, m, m, -1.f, X, n, Ainv, n, 0.f, Low, n, nullptr, stream);
+      }
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_tri_inverse_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, T, ld, n, Tinv, flag);
+    return hipGetLastError();
+  }
   const size_t lds = (size_t)n * 64 * sizeof(float);
   if (lds <= 128 * 1024) {
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(k_tri_inverse_lds),

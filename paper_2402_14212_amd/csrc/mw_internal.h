@@ -221,6 +221,9 @@ hipError_t cv_pack_rev_weights(const float* w, int kh, int kw, int s, int Cin, i
 // rows x width floats from src (row stride src_ld) to dst (row stride dst_ld); all three multiples of 4, 16-byte aligned
 hipError_t cv_copy_rows(const float* src, int64_t src_ld, float* dst, int64_t dst_ld, int64_t rows, int width, hipStream_t stream);
 
+// T[c][c'] = 0 for c < c' < n
+hipError_t cv_zero_above_diagonal(float* T, int64_t ld, int n, hipStream_t stream);
+
 // records the text of a failed HIP call for moonwalk_strerror and returns MW_ERR_HIP (moonwalk_api.hip)
 int record_hip_failure(hipError_t e, const char* where);
 

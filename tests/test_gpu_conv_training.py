@@ -1,0 +1,110 @@
+"""GPU parity of the in-place training step on the convolutional chains (Algorithm 1 with the gradients
+applied) against the oracle's projected step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv_oracle as CO
+from oracle import frag_oracle as FO
+from oracle import moonwalk_oracle as O
+from workloads import make_convnet, make_fragnet
+from tests.parity import GRAD_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mw():
+    import paper_2402_14212_amd as m
+    m.load_library()
+    return m
+
+
+def _masks(net, shapes):
+    return [O.unpack_mask(net.fetch_mask(i), int(np.prod(s))).reshape(s) for i, s in enumerate(shapes)]
+
+
+def _lr_for(ws, ref_dW, rel_step):
+    """A learning rate that moves the weights by `rel_step` of their norm."""
+    wn = np.sqrt(sum(float(np.sum(np.square(w, dtype=np.float64))) for w in ws))
+    gn = np.sqrt(sum(float(np.sum(np.square(g))) for g in ref_dW))
+    return rel_step * wn / gn
+
+
+def _check_step(net, w_before, b_before, out, constrained_tap):
+    """Updates (new - old) against the oracle's, and the constrained entries exactly zero."""
+    for i, (w0, b0) in enumerate(zip(w_before, b_before)):
+        w1 = net.ws[i].cpu().numpy().astype(np.float64)
+        b1 = net.bs[i].cpu().numpy().astype(np.float64)
+        assert O.normwise_rel_err(w1 - w0, out["w"][i] - w0) <= GRAD_TOL, i
+        assert O.normwise_rel_err(b1 - b0, out["b"][i] - b0) <= GRAD_TOL, i
+        T = constrained_tap(w1)
+        assert np.all(np.triu(T, 1) == 0.0) and np.all(np.diag(T) != 0.0)
+
+
+@pytest.mark.parametrize("rel_step", [2e-3, 1e-2])
+def test_conv_sgd_steps_match_the_oracle(mw, rel_step):
+    wl = make_convnet(3, 32, 32, 3, alpha=0.3, seed=4)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=2, plan=mw.PLAN_MOONWALK, input_cotangent=mw.CONV_H0_AS_READ)
+    shapes = [(wl.batch, wl.sides[i + 1], wl.sides[i + 1], wl.channels) for i in range(wl.depth)]
+    ref0 = CO.conv_backprop(wl.w, wl.b, wl.alphas, wl.s, wl.p, wl.x, wl.t)
+    lr = _lr_for(wl.w, ref0["dW"], rel_step)
+    w = [np.asarray(a, dtype=np.float64) for a in wl.w]
+    b = [np.asarray(a, dtype=np.float64) for a in wl.b]
+    losses = []
+    for step in range(3):
+        w_before = [t.cpu().numpy().astype(np.float64) for t in net.ws]
+        b_before = [t.cpu().numpy().astype(np.float64) for t in net.bs]
+        loss = net.sgd_step(net.x, net.t, lr)
+        torch.cuda.synchronize()
+        assert net.memory_stats()["sign_mismatches"] == 0
+        masks = _masks(net, shapes)
+        out = CO.conv_sgd_step(w_before, b_before, wl.alphas, wl.s, wl.p, wl.x, wl.t, lr, forced_masks=masks)
+        assert abs(float(loss.item()) - out["loss"]) <= 1e-5 * abs(out["loss"])
+        _check_step(net, w_before, b_before, out, lambda w1: w1[wl.p, wl.p])
+        losses.append(float(loss.item()))
+    assert losses[2] < losses[1] < losses[0]
+    # the refresh at the end of a step left the handle ready for plain gradients of the new weights
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    w_now = [t.cpu().numpy() for t in net.ws]
+    b_now = [t.cpu().numpy() for t in net.bs]
+    ref = CO.conv_backprop(w_now, b_now, wl.alphas, wl.s, wl.p, wl.x, wl.t, forced_masks=_masks(net, shapes))
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    net.close()
+
+
+def test_frag_sgd_steps_match_the_oracle(mw):
+    wl = make_fragnet(2, 64, 32, 3, block=8, alpha=0.3, gain=1.0, diag=(0.8, 1.2), seed=6)
+    net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK)
+    shapes = [(wl.batch, wl.length, wl.channels)] * wl.depth
+    ref0 = FO.conv1d_backprop(wl.w, wl.b, wl.alphas, wl.x, wl.t)
+    lr = _lr_for(wl.w, ref0["dW"], 5e-3)
+    losses = []
+    for step in range(3):
+        w_before = [t.cpu().numpy().astype(np.float64) for t in net.ws]
+        b_before = [t.cpu().numpy().astype(np.float64) for t in net.bs]
+        loss = net.sgd_step(net.x, net.t, lr)
+        torch.cuda.synchronize()
+        assert net.memory_stats()["sign_mismatches"] == 0
+        out = FO.frag_sgd_step(w_before, b_before, wl.alphas, wl.x, wl.t, lr, wl.block, forced_masks=_masks(net, shapes))
+        assert abs(float(loss.item()) - out["loss"]) <= 1e-5 * abs(out["loss"])
+        _check_step(net, w_before, b_before, out, lambda w1: w1[0])
+        losses.append(float(loss.item()))
+    assert losses[2] < losses[1] < losses[0]
+    net.close()
+
+
+def test_sgd_step_needs_the_gathered_kernels_and_the_moonwalk_plan(mw):
+    wl = make_convnet(2, 16, 8, 1, seed=0)                   # 8 channels: the patch-buffer path
+    net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK)
+    with pytest.raises(mw.MoonwalkError) as e:
+        net.sgd_step(net.x, net.t, 1e-3)
+    assert e.value.code == -7
+    net.close()
+    wl = make_convnet(2, 16, 32, 1, seed=0)
+    net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_BACKPROP)
+    with pytest.raises(mw.MoonwalkError) as e:
+        net.sgd_step(net.x, net.t, 1e-3)
+    assert e.value.code == -7
+    net.close()

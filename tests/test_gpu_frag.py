@@ -72,6 +72,9 @@ def test_frag_moonwalk_matches_the_oracle(mw, name):
             got = net.fetch_fragments(i).reshape(want.shape).astype(np.float64)
             assert O.normwise_rel_err(got, want) <= 1e-4, i
             n_frag += want.size
+    for i in range(depth):                                   # the inverse of the triangular tap (blocked from 128 channels on)
+        T = wl.w[i][0].astype(np.float64)
+        assert O.normwise_rel_err(net.fetch_tap_inverse(i), np.linalg.inv(T)) < 1e-5
     assert st["bytes_fragments"] == 4 * n_frag
     assert st["bytes_masks"] == 8 * depth * ((B * N * C + 63) // 64)
     # the library's own backprop, same oracle

@@ -119,6 +119,7 @@ def bench_conv(args):
         flops_mw, flops_bp = frag_moonwalk_flops(wl), frag_backprop_flops(wl, True)
     else:
         wl = (make_convnet_on_device if on_device else make_convnet)(c["batch"], c["side"], c["channels"], c["depth"],
+                                                                     k=c.get("k", 3), s=c.get("s", 2), p=c.get("p", 1),
                                                                      alpha=c["alpha"], seed=0, name=args.config)
         h0_full = args.h0 == "full"
         flops_mw, flops_bp = conv_moonwalk_flops(wl, h0_full), conv_backprop_flops(wl, h0_full)
@@ -213,7 +214,7 @@ def bench_conv(args):
                                "gflops": fl / per / 1e9}
     elif not args.no_cpu_baseline:
         from oracle import conv_oracle as CO
-        sample = make_convnet(1, min(wl.side, 32), wl.channels, min(wl.depth, 3), alpha=c["alpha"], seed=0)
+        sample = make_convnet(1, min(wl.side, 32), wl.channels, min(wl.depth, 3), k=wl.k, s=wl.s, p=wl.p, alpha=c["alpha"], seed=0)
         t0, n = time.perf_counter(), 0
         while n < 1 or time.perf_counter() - t0 < 10.0:
             CO.conv_moonwalk(sample.w, sample.b, sample.alphas, sample.s, sample.p, sample.x, sample.t)

@@ -198,10 +198,14 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
  * spatial dimensions, and the loss J = 0.5 ||x_L - t||^2 / B. Setup checks the lemma's conditions:
  * k > p, s > p, n > s (n' - 1) in both dimensions, C_out <= C_in, and on the device that the tap
  * w[p][p] is channel-triangular (w[p][p][c][c'] = 0 for c < c') with non-zero diagonal
- * (MW_ERR_NOT_SUBMERSIVE otherwise). Only the fully parallel vijp is built: k <= p + s, so that no
- * other output position enters the equation of h[s i', s j', c'] (MW_ERR_INVALID_ARG otherwise);
- * alpha must be in (0, 1]. The vijp of the convolution is then, at every output position on its own,
- * the triangular solve T h'[i', j', :] = h[s i', s j', :C_out] with T = w[p][p][:C_out][:C_out]; the
+ * (MW_ERR_NOT_SUBMERSIVE otherwise); alpha must be in (0, 1]. For k <= p + s (the fully parallel case)
+ * no other output position enters the equation of h[s i', s j', c'] and the vijp of the convolution
+ * is, at every output position on its own, the triangular solve
+ * T h'[i', j', :] = h[s i', s j', :C_out] with T = w[p][p][:C_out][:C_out]. For wider kernels the
+ * equation also holds the earlier positions (i' - a, j' - b), a, b <= (k - 1 - p) / s, through the taps
+ * (p + a s, p + b s): those are subtracted in a sweep over the anti-diagonals of the output grid, one
+ * launch per diagonal. That sweep needs C_in and C_out to be multiples of 32, MW_CONV_KERNELS_AUTO and
+ * MW_CONV_H0_FULL (MW_ERR_INVALID_ARG otherwise), and its re-seed cotangents are kept whole. The
  * library keeps T^{-1} per layer, and for the layers on the gathered kernels a regrouped copy of the
  * taps that BOTH gradient paths use: after changing w call moonwalk_conv_refresh before either
  * moonwalk_conv_grad or backprop_conv_grad (it recomputes both, whatever the plan).

@@ -47,6 +47,10 @@ struct ConvLayer {
   int block = 0;                // fragmental layers: positions per block
   float* frag = nullptr;        // fragmental layers: [B W / block][k - 1][Cout], the first k - 1 positions of every block of ct_z
   float* Arec = nullptr;        // fragmental layers: [k - 1][Cout][Cout], T^{-1} w[u][:Cout] for u = 1 .. k - 1
+  int reach = 0;                // submersive layers: earlier output positions per dimension in a vijp equation, (k - 1 - p) / s;
+                                // 0 is the fully parallel case
+  float* Asweep = nullptr;      // reach > 0: [Cout][((reach + 1)^2 - 1) Cout], T^{-1} w[p + a s][p + b s][:Cout] by tap slot
+  bool whole_h() const { return kind == MW_CONV_FRAGMENTAL_1D || reach > 0; }  // the vijp reads more of h than sub(h)
   int Hin = 0, Win = 0, Ho = 0, Wo = 0;
   int K = 0;            // k k Cin: columns of the patch matrix
   int64_t rows = 0;     // B Ho Wo: rows of the patch matrix
@@ -128,6 +132,18 @@ int build_from_weights(mw_conv_handle* h, hipStream_t s) {
     if (l.wrev) CV_HIP(cv_pack_rev_weights(l.w, l.kh, l.kw, l.s, l.Cin, l.Cout, l.wrev, s));
     if (!l.Tinv) continue;
     CV_HIP(cv_tri_inverse(l.tri_tap(), l.Cout, l.Cout, l.Tinv, flag, s));
+    // general vijp: T^{-1} w[p + a s][p + b s][:Cout] for the earlier positions (a, b) != (0, 0), slot (reach - a, reach - b)
+    if (l.Asweep) {
+      const int n1 = l.reach + 1, Ktot = (n1 * n1 - 1) * l.Cout;
+      for (int ky = 0; ky < n1; ++ky)
+        for (int kx = 0; kx < n1; ++kx) {
+          if (ky == l.reach && kx == l.reach) continue;
+          const int u = l.p + (l.reach - ky) * l.s, v = l.p + (l.reach - kx) * l.s;
+          CV_HIP(gemm_plain(OP_NN, TILE_AUTO, l.Cout, l.Cout, l.Cout, 1.f, l.Tinv, l.Cout,
+                            l.w + ((size_t)(u * l.k + v) * l.Cin) * l.Cout, l.Cout, 0.f,
+                            l.Asweep + (size_t)(ky * n1 + kx) * l.Cout, Ktot, nullptr, s));
+        }
+    }
     // fragmental layers: the recurrence matrices T^{-1} w[u][:Cout], u = 1 .. k - 1
     for (int u = 1; l.Arec && u < l.k; ++u)
       CV_HIP(gemm_plain(OP_NN, TILE_AUTO, l.Cout, l.Cout, l.Cout, 1.f, l.Tinv, l.Cout, l.w + (size_t)u * l.Cin * l.Cout, l.Cout, 0.f,
@@ -322,8 +338,11 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     // conditions (i) of the lemma, and m' <= m
     if (!(l.k > l.pad && l.stride > l.pad && Hc > l.stride * (Ho - 1) && Wc > l.stride * (Wo - 1))) return MW_ERR_NOT_SUBMERSIVE;
     if (l.channels_out > l.channels_in) return MW_ERR_NOT_SUBMERSIVE;
-    // only the fully parallel vijp is built: no earlier position may enter an equation
-    if (l.k > l.pad + l.stride) return MW_ERR_INVALID_ARG;
+    // k > p + s: earlier output positions enter the equations of the vijp; that sweep exists for the
+    // gathered kernels only, and reads every position of the layer's input cotangent
+    if (l.k > l.pad + l.stride &&
+        (l.channels_in % 32 || l.channels_out % 32 || cfg->kernels != MW_CONV_KERNELS_AUTO || cfg->input_cotangent != MW_CONV_H0_FULL))
+      return MW_ERR_INVALID_ARG;
     if ((int64_t)l.k * l.k * l.channels_in * l.channels_out * 4 >= limit) return MW_ERR_INVALID_ARG;
     if ((int64_t)Ho * Wo * l.channels_out >= limit) return MW_ERR_INVALID_ARG;
     Hc = Ho;
@@ -356,6 +375,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     l.kind = layers[i].kind;
     l.block = layers[i].block;
     const bool frag1d = l.kind == MW_CONV_FRAGMENTAL_1D;
+    l.reach = frag1d ? 0 : (l.k - 1 - l.p) / l.s;
     l.kh = frag1d ? 1 : l.k;
     l.kw = l.k;
     l.ph = frag1d ? 0 : l.p;
@@ -406,6 +426,10 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
       any_patch_layer = true;
     }
     if (!l.gather || !l.gather_rev) need_patches = true;
+    if (l.reach > 0 && !l.gather) {  // the general vijp exists for the gathered kernels only
+      delete h;
+      return MW_ERR_INVALID_ARG;
+    }
     if (frag1d) {
       if (!l.gather || !l.gather_rev) {  // setup's checks should have made this impossible
         delete h;
@@ -439,6 +463,10 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   if (h->plan & MW_PLAN_MOONWALK) {
     for (auto& l : h->layers) {
       ok = ok && cv_alloc(h, &l.Tinv, (size_t)l.Cout * l.Cout, &st.bytes_tap_inverses);
+      if (l.reach > 0) {
+        const size_t n1 = (size_t)l.reach + 1;
+        ok = ok && cv_alloc(h, &l.Asweep, (n1 * n1 - 1) * l.Cout * l.Cout, &st.bytes_tap_inverses);
+      }
       if (l.kind == MW_CONV_FRAGMENTAL_1D && l.k > 1) {
         ok = ok && cv_alloc(h, &l.Arec, (size_t)(l.k - 1) * l.Cout * l.Cout, &st.bytes_tap_inverses);
         ok = ok && cv_alloc(h, &l.frag, (size_t)(l.rows / l.block) * (l.k - 1) * l.Cout, &st.bytes_fragments);
@@ -453,9 +481,9 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     if (!ok) return fail(MW_ERR_OOM);
     if (h->Kre > 0)
       for (int j = 1; j < n_layers; ++j)
-        if (j % h->Kre == 0)  // as the next layer reads it: a fragmental layer reads every position
+        if (j % h->Kre == 0)  // as the next layer reads it: whole where its vijp couples positions
           ok = ok && cv_alloc(h, &h->layers[j - 1].ckpt,
-                              h->layers[j].kind == MW_CONV_FRAGMENTAL_1D ? (size_t)h->layers[j].n_in
+                              h->layers[j].whole_h() ? (size_t)h->layers[j].n_in
                                                                          : (size_t)h->layers[j].rows * h->layers[j].Cout,
                               &st.bytes_checkpoints);
     // activations and cotangents alternate between an "even layer" and an "odd layer" buffer; the odd
@@ -561,8 +589,9 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
         int rc = frag_store(h, l, ct, s);
         if (rc != MW_OK) return rc;
       }
+      const bool whole = l.whole_h();
       float* kept = prev ? prev->ckpt : (h->h0_full ? nullptr : h->h0);
-      if (kept && !frag1d) {
+      if (kept && !whole) {
         int rc = conv_kept_cotangent(h, l, ct, kept, s);
         if (rc != MW_OK) return rc;
       }
@@ -572,7 +601,7 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
       // a layer that cannot scale in its epilogue leaves h in ha (free since the line above the loop)
       const bool can_fuse = l.gather_rev && prev && l.Cin % 32 == 0;
       float* raw = prev ? (can_fuse ? nullptr : h->ha) : h->h0;
-      if (frag1d && kept) raw = kept;  // a fragmental layer reads every position of its input cotangent
+      if (whole && kept) raw = kept;  // such a layer reads every position of its input cotangent
       int rc = conv_input_grad(h, l, ct, raw, ct_next, prev, &fused, s);
       if (rc != MW_OK) return rc;
       if (prev && !fused) CV_HIP(ew_rev_scale(raw, prev->mask, prev->n_out, prev->alpha, ct_next, s));
@@ -593,7 +622,7 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
     const bool frag1d = l.kind == MW_CONV_FRAGMENTAL_1D;
     if (i > 0 && h->layers[i - 1].ckpt) {  // re-seed
       hin = h->layers[i - 1].ckpt;
-      hin_as_read = !frag1d;
+      hin_as_read = !l.whole_h();
     }
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
@@ -610,6 +639,20 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
       }
       rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
                             apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
+      if (rc != MW_OK) return rc;
+    } else if (l.reach > 0) {
+      // the general vijp: right-hand sides solved for the (p, p) tap at all positions, then the sweep over the
+      // anti-diagonals of the output grid, then one kernel: the pre-activation again, the sign check, the activation's vijp
+      for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
+        const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
+        const int64_t o = img0 * l.out_img();
+        CV_HIP(conv_sub_solve(l.geom(), n_img, l.Cout, hin + img0 * l.in_img(), l.Tinv, h->ctz + o, s));
+        CV_HIP(conv_vijp_sweep(l.Ho, l.Wo, l.Cout, n_img, l.reach, h->ctz + o, l.Asweep, s));
+        CV_HIP(conv_vijp_given(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, h->ctz + o,
+                               reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, mismatches, s));
+      }
+      int rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
+                                apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
       if (rc != MW_OK) return rc;
     } else if (l.gather) {
       // one kernel per image chunk: recomputed forward, channel solve at the strided positions, vijp epilogue
@@ -742,7 +785,7 @@ int moonwalk_conv_fetch(mw_conv_handle_t* h, int32_t layer, int32_t what, void* 
     case MW_FETCH_CHECKPOINT:
       if (layer + 1 >= h->L) return MW_ERR_INVALID_ARG;
       src = h->layers[layer].ckpt;
-      bytes = (h->layers[layer + 1].kind == MW_CONV_FRAGMENTAL_1D ? (size_t)h->layers[layer + 1].n_in
+      bytes = (h->layers[layer + 1].whole_h() ? (size_t)h->layers[layer + 1].n_in
                                                                   : (size_t)h->layers[layer + 1].rows * h->layers[layer + 1].Cout) * 4;
       break;
     case MW_FETCH_FRAG:

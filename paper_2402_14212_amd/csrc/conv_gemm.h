@@ -55,6 +55,8 @@ struct AConvPatch {
   int s, py, px;     // stride, offsets (the padding) in y and x
   int c0, Csel;      // channels [c0, c0 + Csel) of every tap enter the patch
   int row_off;       // patch row of the A pointer's row 0 (set per split by the split-K task)
+  int xdiag;         // 1: rows run along an anti-diagonal of the image, x = ox*s - px - oy (columns along K only;
+                     // the grid is then Ho x 1 and oy counts the positions of the diagonal)
   uint32_t bytes;    // extent of the image chunk behind the A pointer
   uint32_t d1, d2;   // change of the row part of the offset (mod 2^32) when ox wraps to the next output
                      // row: (W - Wo) s C, and when oy wraps to the next image: (H - Ho s) W C
@@ -81,7 +83,8 @@ struct AConvPatch {
     __device__ __forceinline__ Dev(const AConvPatch& p, int, int, int64_t) : g(p), row_off(p.row_off) {}
 
     __device__ __forceinline__ uint32_t row_term(uint32_t b, uint32_t oy, uint32_t ox) const {  // mod 2^32
-      const uint32_t iy0 = oy * (uint32_t)g.s - (uint32_t)g.py, ix0 = ox * (uint32_t)g.s - (uint32_t)g.px;
+      const uint32_t iy0 = oy * (uint32_t)g.s - (uint32_t)g.py;
+      const uint32_t ix0 = ox * (uint32_t)g.s - (uint32_t)g.px - (uint32_t)g.xdiag * oy;
       return ((b * (uint32_t)g.H + iy0) * (uint32_t)g.W + ix0) * (uint32_t)g.C;
     }
     __device__ __forceinline__ void split_row(uint32_t row, uint32_t& b, uint32_t& oy, uint32_t& ox) const {
@@ -105,7 +108,7 @@ struct AConvPatch {
           split_row((uint32_t)(row + row_off), b, oy, ox);
           fterm[i] = row_term(b, oy, ox) + (uint32_t)kk;
           fy[i] = row < n_rows ? (int)oy * g.s - g.py : FAR;
-          fx[i] = (int)ox * g.s - g.px;
+          fx[i] = (int)ox * g.s - g.px - g.xdiag * (int)oy;
         }
         ky = 0; kx = 0; cb = 0;
         tterm = (uint32_t)g.c0;
@@ -358,6 +361,44 @@ struct EpiConvRev {
         }
       }
     }
+  };
+};
+
+// ---------------------------------------------------------------------------------------------
+// The general vijp of a submersive convolution (kernels wider than padding + stride): the equation of
+// h[s i', s j', :C_out] then also holds earlier output positions (i' - a, j' - b), 0 <= a, b <= reach,
+// through the taps (p + a s, p + b s) (constructive proof of the lemma on submersive convolutional
+// layers). With G = sub(h) T^{-T} computed for all positions at once,
+//     h'[i', j'] = G[i', j'] - sum_{(a, b) != (0, 0)} h'[i' - a, j' - b] (T^{-1} w[p + a s][p + b s][:C_out])^T,
+// and every position of an anti-diagonal i' + j' = d depends on earlier diagonals only: one launch per
+// diagonal, rows = (image, position on the diagonal), operand A gathered from the h' image itself.
+struct EpiDiagAccum {
+  float* OUT;          // the h' image chunk, [n_img][Ho][Wo][N]; the diagonal's entries hold G and get the sum subtracted
+  int n_d;             // positions on the diagonal
+  int img_pixels;      // Ho * Wo
+  int f0, step;        // flat pixel index of the diagonal's first position, and the step to the next (Wo - 1)
+  uint32_t bytes;
+  FastDiv d_nd;
+  struct Dev {
+    __amdgpu_buffer_rsrc_t ro;
+    const EpiDiagAccum& p;
+    __device__ __forceinline__ Dev(const EpiDiagAccum& e, int, int) : p(e) { ro = make_rsrc(e.OUT, e.bytes); }
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0, const float (&v)[1][CNT]) const {
+      uint32_t off[CNT];
+      float old[CNT];
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        const int row = row_base + acc_row(i0 + j, g);
+        const uint32_t b = p.d_nd.div((uint32_t)row), m = (uint32_t)row - b * (uint32_t)p.n_d;
+        const uint32_t pix = b * (uint32_t)p.img_pixels + (uint32_t)p.f0 + m * (uint32_t)p.step;
+        off[j] = (col < N && row < M) ? (pix * (uint32_t)N + (uint32_t)col) * 4u : OOB;
+        old[j] = buf_load_f32(ro, off[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) buf_store_f32(ro, off[j], old[j] - v[0][j]);
+    }
+    __device__ __forceinline__ void finish() const {}
   };
 };
 

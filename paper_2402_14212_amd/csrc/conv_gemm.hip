@@ -13,6 +13,7 @@ AConvPatch make_gather(const ConvGeom& g, int n_img, int kh, int kw, int s, int 
   a.H = g.H; a.W = g.W; a.C = g.C; a.Ho = g.Ho; a.Wo = g.Wo;
   a.kh = kh; a.kw = kw; a.s = s; a.py = ph; a.px = pw; a.c0 = c0; a.Csel = csel;
   a.row_off = 0;
+  a.xdiag = 0;
   a.bytes = (uint32_t)((int64_t)n_img * g.H * g.W * g.C * 4);
   a.d_howo = FastDiv((uint32_t)(g.Ho * g.Wo));
   a.d_wo = FastDiv((uint32_t)g.Wo);
@@ -54,7 +55,7 @@ hipError_t rev_t(const ConvGeom& g, int n_img, int Cout, const float* ctz, const
       a.kh = nty; a.kw = ntx; a.s = 1;
       // tap slot ky' holds ky = ry + s (nty - 1 - ky'): its source row is q - (nty - 1 - ky')
       a.py = nty - 1 - qy_lo; a.px = ntx - 1 - qx_lo;
-      a.c0 = 0; a.Csel = Cout; a.row_off = 0;
+      a.c0 = 0; a.Csel = Cout; a.row_off = 0; a.xdiag = 0;
       a.bytes = (uint32_t)((int64_t)n_img * g.Ho * g.Wo * Cout * 4);
       a.d_howo = FastDiv((uint32_t)(nqy * nqx));
       a.d_wo = FastDiv((uint32_t)nqx);
@@ -222,6 +223,76 @@ hipError_t conv_vijp_layer(const ConvGeom& g, int n_img, const float* x, const f
     case TILE_32K4: return vijp_t<Tile32K4>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
     default: return vijp_t<Tile64>(g, n_img, x, w, Cout, hin, hin_as_read, Tinv, epi, stream);
   }
+}
+
+// ct = sub(h) Tinv^T for all positions at once: the right-hand sides of the vijp, solved for the (p, p) tap alone
+template <class Cfg>
+hipError_t sub_solve_t(const ConvGeom& g, int n_img, int Cout, const float* hin, const float* Tinv, float* ct, hipStream_t stream) {
+  const int M = n_img * g.Ho * g.Wo;
+  const AConvPatch gh = make_gather(g, n_img, 1, 1, g.s, 0, 0, 0, Cout);
+  EpiStore epi{ct, Cout, 1.f, 0.f, nullptr};
+  auto t = make_gemm_task<Cfg, KCONTIG, KCONTIG, true, AConvPatch, EpiStore, false>(M, Cout, Cout, hin, 0, Tinv, Cout, gh, epi, nullptr,
+                                                                                  0.f);
+  return launch_task<Cfg::NT>(t, stream);
+}
+
+hipError_t conv_sub_solve(const ConvGeom& g, int n_img, int Cout, const float* hin, const float* Tinv, float* ct, hipStream_t stream) {
+  if (n_img <= 0) return hipSuccess;
+  const int M = n_img * g.Ho * g.Wo;
+  switch (gather_tile(M, Cout, Cout, Cout, Cout)) {
+    case TILE_128W8: return sub_solve_t<Tile128W8>(g, n_img, Cout, hin, Tinv, ct, stream);
+    case TILE_64X128: return sub_solve_t<Tile64x128>(g, n_img, Cout, hin, Tinv, ct, stream);
+    case TILE_64K2: return sub_solve_t<Tile64K2>(g, n_img, Cout, hin, Tinv, ct, stream);
+    case TILE_32K4: return sub_solve_t<Tile32K4>(g, n_img, Cout, hin, Tinv, ct, stream);
+    default: return sub_solve_t<Tile64>(g, n_img, Cout, hin, Tinv, ct, stream);
+  }
+}
+
+// One anti-diagonal d of the general vijp (see EpiDiagAccum). ct: the h' image chunk [n_img][Ho][Wo][Cout], G on the
+// diagonals not yet swept; Asweep: [Cout][K] with K = ((reach + 1)^2 - 1) Cout, tap slots in the gather's order.
+template <class Cfg>
+hipError_t sweep_t(int Ho, int Wo, int Cout, int n_img, int d, int reach, float* ct, const float* Asweep, hipStream_t stream) {
+  const int i0 = d - (Wo - 1) > 0 ? d - (Wo - 1) : 0;
+  const int i1 = d < Ho - 1 ? d : Ho - 1;
+  const int n_d = i1 - i0 + 1;
+  if (n_d <= 0) return hipSuccess;
+  const int taps = (reach + 1) * (reach + 1);
+  const int K = (taps - 1) * Cout, M = n_img * n_d;
+  AConvPatch a;
+  a.H = Ho; a.W = Wo; a.C = Cout; a.Ho = n_d; a.Wo = 1;
+  a.kh = reach + 1; a.kw = reach + 1; a.s = 1;
+  // slot (ky, kx) reads (i' - reach + ky, j' - reach + kx); the last slot is the position itself and is left out of K
+  a.py = reach - i0; a.px = reach + i0 - d; a.xdiag = 1;
+  a.c0 = 0; a.Csel = Cout; a.row_off = 0;
+  a.bytes = (uint32_t)((int64_t)n_img * Ho * Wo * Cout * 4);
+  a.d1 = 0; a.d2 = 0;
+  a.d_howo = FastDiv((uint32_t)n_d);
+  a.d_wo = FastDiv(1u);
+  a.d_csel = FastDiv((uint32_t)Cout);
+  a.d_kw = FastDiv((uint32_t)(reach + 1));
+  EpiDiagAccum epi{ct, n_d, Ho * Wo, i0 * Wo + d - i0, Wo - 1, a.bytes, FastDiv((uint32_t)n_d)};
+  auto t = make_gemm_task<Cfg, KCONTIG, KCONTIG, true, AConvPatch, EpiDiagAccum, false>(M, Cout, K, ct, 0, Asweep, K, a, epi, nullptr,
+                                                                                      0.f);
+  return launch_task<Cfg::NT>(t, stream);
+}
+
+hipError_t conv_vijp_sweep(int Ho, int Wo, int Cout, int n_img, int reach, float* ct, const float* Asweep, hipStream_t stream) {
+  if (n_img <= 0 || reach <= 0) return hipSuccess;
+  const int K = ((reach + 1) * (reach + 1) - 1) * Cout;
+  for (int d = 1; d <= Ho + Wo - 2; ++d) {  // diagonal 0 has no earlier position
+    const int i0 = d - (Wo - 1) > 0 ? d - (Wo - 1) : 0, i1 = d < Ho - 1 ? d : Ho - 1;
+    const int M = n_img * (i1 - i0 + 1);
+    hipError_t e;
+    switch (gather_tile(M, Cout, K, Cout, Cout)) {
+      case TILE_128W8: e = sweep_t<Tile128W8>(Ho, Wo, Cout, n_img, d, reach, ct, Asweep, stream); break;
+      case TILE_64X128: e = sweep_t<Tile64x128>(Ho, Wo, Cout, n_img, d, reach, ct, Asweep, stream); break;
+      case TILE_64K2: e = sweep_t<Tile64K2>(Ho, Wo, Cout, n_img, d, reach, ct, Asweep, stream); break;
+      case TILE_32K4: e = sweep_t<Tile32K4>(Ho, Wo, Cout, n_img, d, reach, ct, Asweep, stream); break;
+      default: e = sweep_t<Tile64>(Ho, Wo, Cout, n_img, d, reach, ct, Asweep, stream); break;
+    }
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 bool conv_rev_ok(const ConvGeom& g, int Cout) {

@@ -209,6 +209,11 @@ size_t conv_dw_part_floats(const ConvGeom& g, int n_img, int Cout);
 hipError_t conv_dw(const ConvGeom& g, int n_img, const float* x, const float* ctz, int Cout, float scale, float beta,
                    float* dW, float* part, hipStream_t stream);
 
+// ct [rows][Cout] = sub(hin) Tinv^T: hin [n_img][H][W][C] at the strided positions, first Cout channels
+hipError_t conv_sub_solve(const ConvGeom& g, int n_img, int Cout, const float* hin, const float* Tinv, float* ct, hipStream_t stream);
+// the general vijp's sweep over the anti-diagonals of the output grid, in place on ct (which holds sub(h) Tinv^T);
+// Asweep: [Cout][((reach + 1)^2 - 1) Cout], slot (ky, kx) = T^{-1} w[p + (reach - ky) s][p + (reach - kx) s][:Cout]
+hipError_t conv_vijp_sweep(int Ho, int Wo, int Cout, int n_img, int reach, float* ct, const float* Asweep, hipStream_t stream);
 // whether conv_input_cotangent can be used (stride classes fit the task, channels in fours)
 bool conv_rev_ok(const ConvGeom& g, int Cout);
 // input cotangent of the layer for n_img images from ct_z [n_img][Ho][Wo][Cout]: raw (may be NULL) = h,

@@ -85,6 +85,11 @@ CONV_CASES = {
     "gather_128":   (2, 128, 128, 2, 3, 2, 1, 0.3, 0, 0, 0),     # 8192 and 2048 rows, K = 1152: the split-K tiles
     "gather_tall":  (1, 512, 32, 2, 3, 2, 1, 0.3, 0, 0, 0),      # 65536 rows: the 128-row tile, then 16384 rows
     "gather_mid":   (2, 256, 32, 1, 3, 2, 1, 0.3, 0, 0, 0),      # 32768 rows: the 64 x 128 tile
+    # kernels wider than padding + stride: earlier positions enter the vijp, swept diagonal by diagonal
+    "general_k5":   (2, 32, 32, 2, 5, 2, 1, 0.3, 0, 0, 0),       # reach 1: sides 32 -> 15 -> 7
+    "general_k4":   (3, 29, 32, 3, 4, 2, 1, 0.3, 2, 0, 0),       # reach 1, even kernel, a re-seed kept whole
+    "general_s1":   (2, 12, 32, 2, 3, 1, 0, 0.3, 0, 0, 0),       # stride 1 without padding: reach 2, eight earlier positions
+    "general_wide": (2, 40, 64, 1, 5, 2, 1, 0.3, 0, 0, 0),       # non-square diagonals' worth of rows over several tiles
 }
 
 
@@ -116,7 +121,7 @@ def test_conv_moonwalk_matches_the_oracle(mw, name):
     if K > 0:
         for j in range(K, depth, K):
             side = wl.sides[j + 1]
-            want = ref["hs"][j][:, ::s, ::s, :C][:, :side, :side]
+            want = ref["hs"][j] if k > p + s else ref["hs"][j][:, ::s, ::s, :C][:, :side, :side]
             got = net.fetch_checkpoint(j - 1).reshape(want.shape).astype(np.float64)
             assert O.normwise_rel_err(got, want) <= 1e-4, j
     # the tap inverses
@@ -158,9 +163,15 @@ def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):
     with pytest.raises(mw.MoonwalkError) as e:            # stride must exceed the padding
         mw.ConvMoonwalkNet([w], [None], [0.3], 2, 16, 16, 1, 1)
     assert e.value.code == -2
-    with pytest.raises(mw.MoonwalkError) as e:            # k > p + s: coupled positions, not built
+    with pytest.raises(mw.MoonwalkError) as e:            # k > p + s: coupled positions need channels in 32s ...
         w5 = torch.zeros(5, 5, 8, 8, device=dev)
+        w5[1, 1] = torch.eye(8, device=dev)
         mw.ConvMoonwalkNet([w5], [None], [0.3], 2, 17, 17, 2, 1)
+    assert e.value.code == -1
+    with pytest.raises(mw.MoonwalkError) as e:            # ... and the whole input cotangent
+        w5 = torch.zeros(5, 5, 32, 32, device=dev)
+        w5[1, 1] = torch.eye(32, device=dev)
+        mw.ConvMoonwalkNet([w5], [None], [0.3], 2, 17, 17, 2, 1, input_cotangent=mw.CONV_H0_AS_READ)
     assert e.value.code == -1
     with pytest.raises(mw.MoonwalkError) as e:            # ReLU is not supported on this path
         mw.ConvMoonwalkNet([w], [None], [0.0], 2, 16, 16, 2, 1)

@@ -74,6 +74,29 @@ def test_conv_sgd_steps_match_the_oracle(mw, rel_step):
     net.close()
 
 
+def test_conv_sgd_steps_with_coupled_positions_match_the_oracle(mw):
+    """Kernels wider than padding + stride: the sweep's matrices are derived from the weights and must
+    follow every update."""
+    wl = make_convnet(2, 29, 32, 3, k=5, s=2, p=1, alpha=0.3, seed=8)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=2, plan=mw.PLAN_MOONWALK)
+    shapes = [(wl.batch, wl.sides[i + 1], wl.sides[i + 1], wl.channels) for i in range(wl.depth)]
+    ref0 = CO.conv_backprop(wl.w, wl.b, wl.alphas, wl.s, wl.p, wl.x, wl.t)
+    lr = _lr_for(wl.w, ref0["dW"], 1e-2)
+    losses = []
+    for step in range(3):
+        w_before = [t.cpu().numpy().astype(np.float64) for t in net.ws]
+        b_before = [t.cpu().numpy().astype(np.float64) for t in net.bs]
+        loss = net.sgd_step(net.x, net.t, lr)
+        torch.cuda.synchronize()
+        assert net.memory_stats()["sign_mismatches"] == 0
+        out = CO.conv_sgd_step(w_before, b_before, wl.alphas, wl.s, wl.p, wl.x, wl.t, lr, forced_masks=_masks(net, shapes))
+        assert abs(float(loss.item()) - out["loss"]) <= 1e-5 * abs(out["loss"])
+        _check_step(net, w_before, b_before, out, lambda w1: w1[wl.p, wl.p])
+        losses.append(float(loss.item()))
+    assert losses[2] < losses[1] < losses[0]
+    net.close()
+
+
 def test_frag_sgd_steps_match_the_oracle(mw):
     wl = make_fragnet(2, 64, 32, 3, block=8, alpha=0.3, gain=1.0, diag=(0.8, 1.2), seed=6)
     net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK)

@@ -73,12 +73,14 @@ def conv_moonwalk_flops(wl: ConvWorkload, h0_full: bool = True) -> int:
     """Algorithmic flops of one Moonwalk step. Per layer, with P = 2 rows' (k k C) C the flops of one
     product with the patch matrix: forward, recomputed forward and weight gradient (3 P), the input
     cotangent (P; not for the first layer unless h_0 is wanted for every input element), and the
-    channel solve of the vijp (2 rows' C C)."""
+    channel solve of the vijp (2 rows' C C), times the (reach + 1)^2 positions that enter an equation when
+    the kernel is wider than padding + stride (reach = (k - 1 - p) / s earlier positions per dimension)."""
     total = 0
+    reach = (wl.k - 1 - wl.p) // wl.s
     for i in range(wl.depth):
         rows = wl.batch * wl.sides[i + 1] ** 2
         P = 2 * rows * wl.k * wl.k * wl.channels * wl.channels
-        total += 3 * P + (P if (i > 0 or h0_full) else 0) + 2 * rows * wl.channels * wl.channels
+        total += 3 * P + (P if (i > 0 or h0_full) else 0) + 2 * rows * wl.channels * wl.channels * (reach + 1) ** 2
     return total
 
 
@@ -128,4 +130,6 @@ def make_convnet_on_device(batch: int, side: int, channels: int, depth: int, k: 
 CONV_CONFIGS = {
     "conv2d_small": dict(batch=8, side=64, channels=32, depth=4, alpha=0.3),
     "conv2d":       dict(batch=128, side=256, channels=128, depth=8, alpha=0.3),
+    # a kernel wider than padding + stride: three earlier output positions enter every equation of the vijp
+    "conv2d_k5":    dict(batch=32, side=128, channels=128, depth=6, alpha=0.3, k=5, s=2, p=1),
 }

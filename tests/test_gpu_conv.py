@@ -146,6 +146,56 @@ def test_conv_moonwalk_matches_the_oracle(mw, name):
     net.close()
 
 
+NARROWING_CASES = {
+    # name: (batch, side, channel counts input first, k, s, p, K, h_0 mode)
+    "patch":        (2, 16, [12, 8, 6], 3, 2, 1, 0, 0),          # through the patch buffer
+    "gather":       (3, 21, [96, 64, 32, 32], 3, 2, 1, 2, 0),    # gathered kernels; the re-seed keeps 32 of 64 channels
+    "gather_read":  (2, 32, [64, 32, 32], 3, 2, 1, 0, 1),        # h_0 as the first vijp reads it: 32 of 64 channels
+    "general":      (2, 29, [64, 32, 32], 5, 2, 1, 2, 0),        # coupled positions, re-seed kept whole
+}
+
+
+@pytest.mark.parametrize("name", sorted(NARROWING_CASES))
+def test_conv_moonwalk_with_fewer_output_than_input_channels(mw, name):
+    """C_out < C_in: the vijp's equations are those of the first C_out input channels at the strided positions."""
+    B, side, cs, k, s, p, K, h0_mode = NARROWING_CASES[name]
+    depth = len(cs) - 1
+    wl = make_convnet(B, side, cs, depth, k=k, s=s, p=p, alpha=0.3, seed=5, name=name)
+    print("conv narrowing", name, flush=True)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, input_cotangent=h0_mode)
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    shapes = [(B, wl.sides[i + 1], wl.sides[i + 1], cs[i + 1]) for i in range(depth)]
+    masks = [O.unpack_mask(net.fetch_mask(i), int(np.prod(sh))).reshape(sh) for i, sh in enumerate(shapes)]
+    _, zs, _ = CO.conv_forward(wl.w, wl.b, wl.alphas, s, p, wl.x, forced_masks=masks)
+    for z, m in zip(zs, masks):
+        sure = np.abs(z) > MASK_GUARD * np.sqrt(np.mean(z * z))
+        assert not ((m != (z > 0)) & sure).any()
+    ref = CO.conv_backprop(wl.w, wl.b, wl.alphas, s, p, wl.x, wl.t, forced_masks=masks)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    whole = k > p + s
+    if h0_mode == 0:
+        assert O.normwise_rel_err(net.fetch_h0().reshape(wl.x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    else:
+        want = ref["h0"][:, ::s, ::s, :cs[1]][:, :wl.sides[1], :wl.sides[1]]
+        assert O.normwise_rel_err(net.fetch_h0().reshape(want.shape).astype(np.float64), want) <= 1e-4
+    for j in range(K, depth, K) if K > 0 else ():
+        n = wl.sides[j + 1]
+        want = ref["hs"][j] if whole else ref["hs"][j][:, ::s, ::s, :cs[j + 1]][:, :n, :n]
+        assert O.normwise_rel_err(net.fetch_checkpoint(j - 1).reshape(want.shape).astype(np.float64), want) <= 1e-4, j
+    for i in range(depth):
+        T = wl.w[i][p, p, :cs[i + 1], :].astype(np.float64)
+        assert O.normwise_rel_err(net.fetch_tap_inverse(i), np.linalg.inv(T)) < 1e-5
+    if h0_mode == 0:
+        bp = net.backprop_grad(net.x, net.t)
+        torch.cuda.synchronize()
+        assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()
+
+
 def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):
     wl = make_convnet(2, 16, 8, 1, seed=0)
     dev = torch.device("cuda:0")

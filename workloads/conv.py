@@ -43,29 +43,34 @@ def conv_out_side(n: int, k: int, s: int, p: int) -> int:
     return (n + 2 * p - k) // s + 1
 
 
-def make_convnet(batch: int, side: int, channels: int, depth: int, k: int = 3, s: int = 2, p: int = 1,
+def make_convnet(batch: int, side: int, channels, depth: int, k: int = 3, s: int = 2, p: int = 1,
                  alpha: float = 0.1, seed: int = 0, name: str = "") -> ConvWorkload:
+    """`channels`: one count for the whole chain (the paper's setting), or depth + 1 counts, the input's
+    first, none larger than the one before (C_out <= C_in); `channels` of the result is then the input's."""
     rng = np.random.default_rng(seed)
-    C = int(channels)
+    cs = [int(channels)] * (depth + 1) if np.isscalar(channels) else [int(c) for c in channels]
+    if len(cs) != depth + 1 or any(b > a for a, b in zip(cs, cs[1:])):
+        raise ValueError("need depth + 1 channel counts, none larger than the one before")
     sides = [int(side)]
     ws, bs = [], []
-    for _ in range(depth):
+    for i in range(depth):
         n = sides[-1]
         no = conv_out_side(n, k, s, p)
         if no < 1 or not (k > p and s > p and n > s * (no - 1)):
             raise ValueError(f"layer with input side {n} violates the spatial bounds of the lemma")
-        w = rng.standard_normal((k, k, C, C)) / np.sqrt(k * k * C)
+        Ci, Co = cs[i], cs[i + 1]
+        w = rng.standard_normal((k, k, Ci, Co)) / np.sqrt(k * k * Ci)
         tap = np.tril(w[p, p])              # rows c, columns c': keep c >= c', zero for c < c'
-        d = rng.uniform(0.8, 1.2, size=C)
-        tap[np.arange(C), np.arange(C)] = d
+        d = rng.uniform(0.8, 1.2, size=Co)
+        tap[np.arange(Co), np.arange(Co)] = d
         w[p, p] = tap
-        bias = 0.01 * rng.standard_normal(C)
+        bias = 0.01 * rng.standard_normal(Co)
         ws.append(np.ascontiguousarray(w, dtype=np.float32))
         bs.append(np.ascontiguousarray(bias, dtype=np.float32))
         sides.append(no)
-    x = rng.standard_normal((batch, side, side, C)).astype(np.float32)
-    t = rng.standard_normal((batch, sides[-1], sides[-1], C)).astype(np.float32)
-    return ConvWorkload(batch=int(batch), side=int(side), channels=C, k=k, s=s, p=p, alphas=[float(alpha)] * depth,
+    x = rng.standard_normal((batch, side, side, cs[0])).astype(np.float32)
+    t = rng.standard_normal((batch, sides[-1], sides[-1], cs[-1])).astype(np.float32)
+    return ConvWorkload(batch=int(batch), side=int(side), channels=cs[0], k=k, s=s, p=p, alphas=[float(alpha)] * depth,
                         w=ws, b=bs, x=x, t=t, sides=sides, seed=int(seed), name=name)
 
 
@@ -79,8 +84,9 @@ def conv_moonwalk_flops(wl: ConvWorkload, h0_full: bool = True) -> int:
     reach = (wl.k - 1 - wl.p) // wl.s
     for i in range(wl.depth):
         rows = wl.batch * wl.sides[i + 1] ** 2
-        P = 2 * rows * wl.k * wl.k * wl.channels * wl.channels
-        total += 3 * P + (P if (i > 0 or h0_full) else 0) + 2 * rows * wl.channels * wl.channels * (reach + 1) ** 2
+        Ci, Co = wl.w[i].shape[2], wl.w[i].shape[3]
+        P = 2 * rows * wl.k * wl.k * Ci * Co
+        total += 3 * P + (P if (i > 0 or h0_full) else 0) + 2 * rows * Co * Co * (reach + 1) ** 2
     return total
 
 
@@ -90,7 +96,7 @@ def conv_backprop_flops(wl: ConvWorkload, h0_full: bool = True) -> int:
     total = 0
     for i in range(wl.depth):
         rows = wl.batch * wl.sides[i + 1] ** 2
-        P = 2 * rows * wl.k * wl.k * wl.channels * wl.channels
+        P = 2 * rows * wl.k * wl.k * wl.w[i].shape[2] * wl.w[i].shape[3]
         total += 2 * P + (P if (i > 0 or h0_full) else 0)
     return total
 

@@ -90,6 +90,33 @@ def test_frag_moonwalk_matches_the_oracle(mw, name):
     net.close()
 
 
+def test_frag_moonwalk_with_fewer_output_than_input_channels(mw):
+    """C_out < C_in: the rebuild reads the first C_out channels of the layer's input cotangent."""
+    cs, B, N, k, block = [96, 64, 32, 32], 2, 96, 3, 8
+    depth = len(cs) - 1
+    wl = make_fragnet(B, N, cs, depth, k=k, block=block, alpha=0.3, gain=1.0, diag=(0.8, 1.2), seed=7)
+    print("frag narrowing", flush=True)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=2)
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    masks = [O.unpack_mask(net.fetch_mask(i), B * N * cs[i + 1]).reshape(B, N, cs[i + 1]) for i in range(depth)]
+    ref = FO.conv1d_backprop(wl.w, wl.b, wl.alphas, wl.x, wl.t, forced_masks=masks)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    assert O.normwise_rel_err(net.fetch_h0().reshape(wl.x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    for i in range(depth):
+        want = FO.fragments_of(ref["ct_z"][i], k, block)
+        assert O.normwise_rel_err(net.fetch_fragments(i).reshape(want.shape).astype(np.float64), want) <= 1e-4, i
+        T = wl.w[i][0, :cs[i + 1], :].astype(np.float64)
+        assert O.normwise_rel_err(net.fetch_tap_inverse(i), np.linalg.inv(T)) < 1e-5
+    bp = net.backprop_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()
+
+
 def test_frag_setup_rejects_what_the_fragmental_update_cannot_take(mw):
     wl = make_fragnet(2, 32, 32, 1, block=4, seed=0)
     dev = torch.device("cuda:0")

@@ -42,28 +42,33 @@ class FragWorkload:
         return len(self.w)
 
 
-def make_fragnet(batch: int, length: int, channels: int, depth: int, k: int = 3, block: int = 4, alpha: float = 0.3,
+def make_fragnet(batch: int, length: int, channels, depth: int, k: int = 3, block: int = 4, alpha: float = 0.3,
                  gain: float = 0.5, diag=1.0, seed: int = 0, name: str = "") -> FragWorkload:
+    """`channels`: one count for the whole chain (the paper's setting), or depth + 1 counts, the input's
+    first, none larger than the one before; `channels` of the result is then the input's."""
     if k % 2 != 1 or length % block or block < k - 1:
         raise ValueError("odd kernel size, and a whole number of blocks of at least k - 1 positions")
     rng = np.random.default_rng(seed)
-    C = int(channels)
+    cs = [int(channels)] * (depth + 1) if np.isscalar(channels) else [int(c) for c in channels]
+    if len(cs) != depth + 1 or any(b > a for a, b in zip(cs, cs[1:])):
+        raise ValueError("need depth + 1 channel counts, none larger than the one before")
     ws, bs = [], []
-    for _ in range(depth):
-        w = gain * rng.standard_normal((k, C, C)) / np.sqrt(k * C)
+    for i in range(depth):
+        Ci, Co = cs[i], cs[i + 1]
+        w = gain * rng.standard_normal((k, Ci, Co)) / np.sqrt(k * Ci)
         tap = np.tril(w[0])
         if np.isscalar(diag):
-            d = np.full(C, float(diag))
+            d = np.full(Co, float(diag))
         else:
-            d = rng.uniform(diag[0], diag[1], size=C)
-        tap[np.arange(C), np.arange(C)] = d
+            d = rng.uniform(diag[0], diag[1], size=Co)
+        tap[np.arange(Co), np.arange(Co)] = d
         w[0] = tap
-        bias = 0.01 * rng.standard_normal(C)
+        bias = 0.01 * rng.standard_normal(Co)
         ws.append(np.ascontiguousarray(w, dtype=np.float32))
         bs.append(np.ascontiguousarray(bias, dtype=np.float32))
-    x = rng.standard_normal((batch, length, C)).astype(np.float32)
-    t = rng.standard_normal((batch, length, C)).astype(np.float32)
-    return FragWorkload(batch=int(batch), length=int(length), channels=C, k=k, block=int(block), alphas=[float(alpha)] * depth,
+    x = rng.standard_normal((batch, length, cs[0])).astype(np.float32)
+    t = rng.standard_normal((batch, length, cs[-1])).astype(np.float32)
+    return FragWorkload(batch=int(batch), length=int(length), channels=cs[0], k=k, block=int(block), alphas=[float(alpha)] * depth,
                         w=ws, b=bs, x=x, t=t, seed=int(seed), name=name)
 
 

@@ -196,6 +196,45 @@ def test_conv_moonwalk_with_fewer_output_than_input_channels(mw, name):
     net.close()
 
 
+@pytest.mark.parametrize("H,W,C,depth,k,s,p,K", [
+    (20, 13, 8, 2, 3, 2, 1, 0),       # patch buffer
+    (13, 37, 32, 2, 3, 2, 1, 0),      # gathered kernels, wide images
+    (29, 19, 32, 2, 5, 2, 1, 0),      # coupled positions: diagonals of a 14 x 9, then a 6 x 4 grid
+    (9, 14, 32, 2, 3, 1, 0, 1),       # reach 2, grids 7 x 12 and 5 x 10, every cotangent re-seeded
+    (17, 3, 32, 1, 5, 2, 1, 0),       # an 8 x 1 grid: every diagonal is one position
+])
+def test_conv_moonwalk_on_images_that_are_not_square(mw, H, W, C, depth, k, s, p, K):
+    B = 3
+    kernels = make_convnet(1, 64, C, depth, k=k, s=s, p=p, alpha=0.3, seed=11)   # the recipe's kernels and biases
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((B, H, W, C)).astype(np.float32)
+    hs, ws_ = [H], [W]
+    for _ in range(depth):
+        hs.append((hs[-1] + 2 * p - k) // s + 1)
+        ws_.append((ws_[-1] + 2 * p - k) // s + 1)
+        assert hs[-2] > s * (hs[-1] - 1) and ws_[-2] > s * (ws_[-1] - 1) and hs[-1] >= 1 and ws_[-1] >= 1
+    t = rng.standard_normal((B, hs[-1], ws_[-1], C)).astype(np.float32)
+    print("conv not square", H, W, k, s, p, flush=True)
+    dev = torch.device("cuda:0")
+    net = mw.ConvMoonwalkNet([torch.from_numpy(w).to(dev) for w in kernels.w], [torch.from_numpy(b).to(dev) for b in kernels.b],
+                             kernels.alphas, B, H, W, s, p, reseed_interval=K)
+    dx, dt = torch.from_numpy(x).to(dev), torch.from_numpy(t).to(dev)
+    res = net.moonwalk_grad(dx, dt)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    shapes = [(B, hs[i + 1], ws_[i + 1], C) for i in range(depth)]
+    masks = [O.unpack_mask(net.fetch_mask(i), int(np.prod(sh))).reshape(sh) for i, sh in enumerate(shapes)]
+    ref = CO.conv_backprop(kernels.w, kernels.b, kernels.alphas, s, p, x, t, forced_masks=masks)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    assert O.normwise_rel_err(net.fetch_h0().reshape(x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    bp = net.backprop_grad(dx, dt)
+    torch.cuda.synchronize()
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()
+
+
 def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):
     wl = make_convnet(2, 16, 8, 1, seed=0)
     dev = torch.device("cuda:0")

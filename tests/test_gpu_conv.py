@@ -265,6 +265,13 @@ def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):
     with pytest.raises(mw.MoonwalkError) as e:            # ReLU is not supported on this path
         mw.ConvMoonwalkNet([w], [None], [0.0], 2, 16, 16, 2, 1)
     assert e.value.code == -1
+    for shape in ((0, 16, 16), (2, 0, 16), (2, 16, 0)):  # an empty batch or image
+        with pytest.raises(mw.MoonwalkError) as e:
+            mw.ConvMoonwalkNet([w], [None], [0.3], *shape, 2, 1)
+        assert e.value.code == -1
+    with pytest.raises(mw.MoonwalkError) as e:            # an image too small for the kernel: no output position
+        mw.ConvMoonwalkNet([torch.zeros(5, 5, 8, 8, device=dev)], [None], [0.3], 2, 2, 2, 2, 1)
+    assert e.value.code in (-1, -2)
 
 
 def test_conv_refresh_follows_the_kernel(mw):

@@ -107,3 +107,74 @@ def test_binding_refuses_to_run_without_a_gpu():
         pytest.skip("GPU present")
     with pytest.raises(RuntimeError):
         mw.gemm_f32(mw.GEMM_NT, torch.zeros(2, 2), torch.zeros(2, 2))
+
+
+def test_conv_setup_validation_answers_without_a_gpu(lib):
+    """moonwalk_conv_setup checks shapes and the lemma's spatial conditions before it allocates or launches."""
+    from paper_2402_14212_amd.binding import _ConvLayer, _ConvConfig, _ALLOC_FN, _FREE_FN
+    handle = C.c_void_p()
+    fake = 0x1000  # never dereferenced: validation fails first
+
+    def cfg(batch=2, H=16, W=16, K=0, scale=1.0, plan=3, kernels=0, h0=0):
+        return _ConvConfig(batch, H, W, K, scale, plan, kernels, h0, 0, 0, _ALLOC_FN(0), _FREE_FN(0), None)
+
+    def lay(ci=8, co=8, k=3, s=2, p=1, alpha=0.3, kind=0, block=0):
+        return (_ConvLayer * 1)(_ConvLayer(ci, co, k, s, p, fake, None, alpha, kind, block))
+
+    def setup(layers, c, n=1):
+        return lib.moonwalk_conv_setup(C.byref(handle), layers, n, C.byref(c), None)
+
+    assert lib.moonwalk_conv_setup(None, lay(), 1, C.byref(cfg()), None) == -1
+    assert lib.moonwalk_conv_setup(C.byref(handle), None, 1, C.byref(cfg()), None) == -1
+    assert lib.moonwalk_conv_setup(C.byref(handle), lay(), 1, None, None) == -1
+    assert setup(lay(), cfg(), n=0) == -1
+    # the lemma on submersive convolutional layers: stride > padding, C_out <= C_in
+    assert setup(lay(s=1, p=1), cfg()) == -2
+    assert setup(lay(ci=8, co=9), cfg()) == -2
+    # kernels wider than padding + stride need channel counts in 32s and the whole input cotangent
+    assert setup(lay(k=5), cfg(H=17, W=17)) == -1
+    assert setup(lay(ci=32, co=32, k=5), cfg(H=17, W=17, h0=1)) == -1
+    # ReLU, empty batch or image, an image smaller than the kernel, a chain whose channel counts do not meet
+    assert setup(lay(alpha=0.0), cfg()) == -1
+    for c in (cfg(batch=0), cfg(H=0), cfg(W=0), cfg(K=-1), cfg(scale=0.0), cfg(plan=4), cfg(kernels=7), cfg(h0=5)):
+        assert setup(lay(), c) == -1
+    assert setup(lay(k=5), cfg(H=2, W=2)) == -1
+    chain = (_ConvLayer * 2)(_ConvLayer(8, 8, 3, 2, 1, fake, None, 0.3, 0, 0), _ConvLayer(6, 6, 3, 2, 1, fake, None, 0.3, 0, 0))
+    assert setup(chain, cfg(), n=2) == -1
+    # fragmental 1-D layers: a one-row image, whole blocks of at least k - 1 positions, channels in 32s, all of h_0
+    frag = dict(ci=32, co=32, k=3, s=1, p=1, kind=1)
+    assert setup(lay(block=4, **frag), cfg(H=2, W=32)) == -1
+    assert setup(lay(block=5, **frag), cfg(H=1, W=32)) == -1
+    assert setup(lay(block=1, **frag), cfg(H=1, W=32)) == -1
+    assert setup(lay(block=4, **(frag | dict(ci=24, co=24))), cfg(H=1, W=32)) == -1
+    assert setup(lay(block=4, **frag), cfg(H=1, W=32, h0=1)) == -1
+    assert setup(lay(block=4, **(frag | dict(p=0))), cfg(H=1, W=32)) == -1
+    assert handle.value is None
+
+
+def test_conv_failing_allocator_reports_oom(lib):
+    from paper_2402_14212_amd.binding import _ConvLayer, _ConvConfig, _ALLOC_FN, _FREE_FN
+    calls = []
+    alloc = _ALLOC_FN(lambda n, ctx: calls.append(n) or None)
+    free = _FREE_FN(lambda p, ctx: None)
+    cfg = _ConvConfig(2, 16, 16, 0, 1.0, 3, 0, 0, 0, 0, alloc, free, None)
+    handle = C.c_void_p()
+    layer = (_ConvLayer * 1)(_ConvLayer(8, 8, 3, 2, 1, 0x1000, None, 0.3, 0, 0))
+    assert lib.moonwalk_conv_setup(C.byref(handle), layer, 1, C.byref(cfg), None) == -3
+    assert calls and handle.value is None
+
+
+def test_conv_null_handles_and_shapes_are_rejected(lib):
+    from paper_2402_14212_amd.binding import _ConvShape
+    assert lib.moonwalk_conv_grad(None, None, None, None, None, None) == -1
+    assert lib.backprop_conv_grad(None, None, None, None, None, None) == -1
+    assert lib.moonwalk_conv_refresh(None, None) == -1
+    assert lib.moonwalk_conv_memory_stats(None, None) == -1
+    assert lib.moonwalk_conv_grad_layout(None, None, None, None) == -1
+    lib.moonwalk_conv_destroy(None)
+    # the scratch size of the stand-alone weight gradient is host arithmetic: positive for a shape, 0 for none
+    shape = _ConvShape(2, 16, 16, 32, 32, 3, 3, 2, 1, 1)
+    assert lib.mw_conv_weight_grad_work_floats(C.byref(shape)) > 0
+    assert lib.mw_conv_weight_grad_work_floats(None) == 0
+    empty = _ConvShape(0, 16, 16, 32, 32, 3, 3, 2, 1, 1)
+    assert lib.mw_conv_weight_grad_work_floats(C.byref(empty)) == 0

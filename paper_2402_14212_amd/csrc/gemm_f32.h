@@ -319,7 +319,7 @@ __device__ __forceinline__ void gemm_mainloop_chain(const float* __restrict__ A,
                                                     f32x16 (&acc)[Cfg::NACC], float (&asum)[Cfg::WTM],
                                                     TilePipe<Cfg, LA, LB, VEC, XfDev>& p,
                                                     const float* __restrict__ A2, const float* __restrict__ B2) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ST = Cfg::ST;
+  constexpr int BM = Cfg::BM, BK = Cfg::BK, ST = Cfg::ST;
   constexpr int A_FLOATS = lds_tile_floats<LA, BM, BK>();
   constexpr int STAGE = lds_stage_floats<Cfg, LA, LB>();
 

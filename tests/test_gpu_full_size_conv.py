@@ -142,3 +142,47 @@ def test_conv2d_full_benchmark_by_sampled_signs_and_properties(mw):
     print("conv2d full: Moonwalk vs backprop", rel, flush=True)
     assert rel <= 1e-4
     net.close()
+
+
+def test_conv2d_k5_full_benchmark_by_single_images_and_properties(mw):
+    """The benchmark with kernels wider than padding + stride (batch 32, six 5 x 5 layers, a sweep over up to
+    125 anti-diagonals per layer). Signs and the input cotangent of one image depend on that image alone, so
+    the oracle runs on single images: (1) every layer's sign bits of the first and the last image; (2) their
+    rows of h_0, which is 1/B of the single-image one; then (3) Phase III's recomputed signs equal Phase I's;
+    (4) Moonwalk's gradients equal the library's backprop's (no vijp, no sweep) to 1e-4; (5) bit-identical repeat."""
+    c = CONV_CONFIGS["conv2d_k5"]
+    wl = make_convnet_on_device(c["batch"], c["side"], c["channels"], c["depth"], k=c["k"], s=c["s"], p=c["p"],
+                                alpha=c["alpha"], seed=0)
+    net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, reseed_interval=2)
+    grads = net.new_grads()
+    net.moonwalk_grad(net.x, net.t, grads)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    B, C = wl.batch, wl.channels
+    masks = [_unpack(net, i, (B, wl.sides[i + 1], wl.sides[i + 1], C)) for i in range(wl.depth)]
+    h0 = net.fetch_h0().reshape(B, wl.side, wl.side, C)
+    ws = [w.cpu().numpy() for w in wl.w]
+    bs = [b.cpu().numpy() for b in wl.b]
+    for img in (0, B - 1):
+        print("conv2d_k5 full: image", img, flush=True)
+        x1 = wl.x[img:img + 1].cpu().numpy()
+        t1 = wl.t[img:img + 1].cpu().numpy()
+        own = [m[img:img + 1] for m in masks]
+        _, zs, _ = CO.conv_forward(ws, bs, wl.alphas, wl.s, wl.p, x1, forced_masks=own)
+        for z, m in zip(zs, own):
+            sure = np.abs(z) > MASK_GUARD * np.sqrt(np.mean(z * z))
+            assert not ((m != (z > 0)) & sure).any()
+        ref = CO.conv_backprop(ws, bs, wl.alphas, wl.s, wl.p, x1, t1, forced_masks=own)
+        assert O.normwise_rel_err(B * h0[img:img + 1].astype(np.float64), ref["h0"]) <= 1e-4
+    again = net.new_grads()
+    net.moonwalk_grad(net.x, net.t, again)
+    torch.cuda.synchronize()
+    assert torch.equal(grads, again)
+    net.close()
+    net = mw.ConvMoonwalkNet.from_workload(wl, plan=mw.PLAN_BACKPROP)
+    net.backprop_grad(net.x, net.t, again)
+    torch.cuda.synchronize()
+    rel = float(((again - grads).double().norm() / grads.double().norm()).item())
+    print("conv2d_k5 full: Moonwalk vs backprop", rel, flush=True)
+    assert rel <= 1e-4
+    net.close()

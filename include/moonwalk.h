@@ -259,7 +259,10 @@ typedef struct {
                                     computed and kept, [B][H'][W'][C_out] of layer 0 (the strided positions,
                                     the first C_out channels), and the first layer's reverse product is
                                     skipped                                                              */
-  int32_t reserved;
+  int32_t max_images_per_launch; /* the gathered kernels take the batch in launches of at most this many images
+                                    (0 = as many as the 2 GiB limit on a launch's operands allows; < 0:
+                                    MW_ERR_INVALID_ARG); the launches are of equal size up to the last one, and
+                                    the weight gradient's partial sums are sized for one launch             */
   size_t  patch_bytes;           /* size of the buffer the image chunks' patch matrices are gathered into
                                     (0 = 256 MiB); at least one image's patches are always taken        */
   void* (*dev_alloc)(size_t bytes, void* ctx);

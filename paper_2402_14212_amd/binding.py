@@ -68,7 +68,7 @@ class _ConvShape(C.Structure):
 class _ConvConfig(C.Structure):
     _fields_ = [("batch", C.c_int32), ("height", C.c_int32), ("width", C.c_int32), ("reseed_interval", C.c_int32),
                 ("loss_scale", C.c_float), ("plan", C.c_int32), ("kernels", C.c_int32), ("input_cotangent", C.c_int32),
-                ("reserved", C.c_int32), ("patch_bytes", C.c_size_t),
+                ("max_images_per_launch", C.c_int32), ("patch_bytes", C.c_size_t),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p)]
 
 
@@ -397,13 +397,16 @@ class ConvMoonwalkNet:
     allow it) or CONV_KERNELS_PATCH_MATRIX (always through the patch buffer).
     input_cotangent: CONV_H0_FULL (h_0 for every input element) or CONV_H0_AS_READ (only the entries
     the first layer's vijp reads; the first layer's reverse product is skipped).
+    max_images_per_launch: the gathered kernels take the batch in launches of at most this many images
+    (0 = bounded by the 2 GiB operand limit only).
     kind = CONV_FRAGMENTAL_1D: length-preserving 1-D layers with fragmental checkpointing; ws are
     [k][C_in][C_out], height must be 1, stride 1, pad (k - 1) / 2, block = positions per block."""
 
     def __init__(self, ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, height: int, width: int, stride: int, pad: int, reseed_interval: int = 0,
                  loss_scale: float = 1.0, plan: int = PLAN_MOONWALK | PLAN_BACKPROP, patch_bytes: int = 0,
-                 kernels: int = 0, input_cotangent: int = 0, kind: int = 0, block: int = 0):
+                 kernels: int = 0, input_cotangent: int = 0, kind: int = 0, block: int = 0,
+                 max_images_per_launch: int = 0):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -449,7 +452,8 @@ class ConvMoonwalkNet:
             layers[i] = _ConvLayer(w.shape[2], w.shape[3], w.shape[0], self.stride, self.pad, _ptr(w),
                                    _ptr(_f32(b)) if b is not None else None, a, int(kind), int(block))
         cfg = _ConvConfig(self.batch, self.height, self.width, int(reseed_interval), float(loss_scale), int(plan),
-                          int(kernels), int(input_cotangent), 0, int(patch_bytes), self._alloc_cb, self._free_cb, None)
+                          int(kernels), int(input_cotangent), int(max_images_per_launch), int(patch_bytes), self._alloc_cb,
+                          self._free_cb, None)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_conv_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()

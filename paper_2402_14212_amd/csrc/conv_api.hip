@@ -15,6 +15,9 @@
 // The vijp of a submersive convolution, in the fully parallel case k <= p + s, is a triangular
 // solve over channels at every output position, done as a product with the inverse of the
 // channel-triangular tap; the cotangents Phase III starts from are kept in the form it reads them.
+// Wider kernels couple each output position with earlier ones: the same solve for all positions,
+// then a sweep over the anti-diagonals of the output grid that subtracts the earlier positions'
+// contributions (one gathered product per diagonal), on cotangents kept whole.
 #include "../../include/moonwalk.h"
 
 #include <cmath>
@@ -312,6 +315,7 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
   if (cfg->kernels != MW_CONV_KERNELS_AUTO && cfg->kernels != MW_CONV_KERNELS_PATCH_MATRIX) return MW_ERR_INVALID_ARG;
   if (cfg->input_cotangent != MW_CONV_H0_FULL && cfg->input_cotangent != MW_CONV_H0_AS_READ) return MW_ERR_INVALID_ARG;
+  if (cfg->max_images_per_launch < 0) return MW_ERR_INVALID_ARG;
   int Hc = cfg->height, Wc = cfg->width;
   const int64_t limit = (int64_t)0x7FFFFFFF;
   for (int i = 0; i < n_layers; ++i) {
@@ -407,11 +411,12 @@ int moonwalk_conv_setup(mw_conv_handle_t** out, const mw_conv_layer_t* layers, i
     }
     l.chunk_images = (int)ci;
     const ConvGeom g = l.geom();
-    const int64_t gmax = conv_gather_max_images(g, l.Cout);
+    int64_t gmax = conv_gather_max_images(g, l.Cout);
     if (gmax < 1) {
       delete h;
       return MW_ERR_INVALID_ARG;  // a single image does not fit a GEMM operand
     }
+    if (cfg->max_images_per_launch > 0 && cfg->max_images_per_launch < gmax) gmax = cfg->max_images_per_launch;
     {
       // as few launches as the 2 GiB operand limit allows, of equal size
       const int64_t n_chunks = (h->B + gmax - 1) / gmax;

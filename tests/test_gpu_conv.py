@@ -95,10 +95,14 @@ CONV_CASES = {
 
 @pytest.mark.parametrize("name", sorted(CONV_CASES))
 def test_conv_moonwalk_matches_the_oracle(mw, name):
+    _parity_of_case(mw, name)
+
+
+def _parity_of_case(mw, name, **net_kw):
     B, side, C, depth, k, s, p, alpha, K, patch_bytes, kernels = CONV_CASES[name]
     wl = make_convnet(B, side, C, depth, k=k, s=s, p=p, alpha=alpha, seed=1, name=name)
-    print("conv", name, flush=True)
-    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels)
+    print("conv", name, net_kw, flush=True)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels, **net_kw)
     res = net.moonwalk_grad(net.x, net.t)
     torch.cuda.synchronize()
     st = net.memory_stats()
@@ -233,6 +237,17 @@ def test_conv_moonwalk_on_images_that_are_not_square(mw, H, W, C, depth, k, s, p
     torch.cuda.synchronize()
     assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
     net.close()
+
+
+@pytest.mark.parametrize("name,per_launch", [("gather_odd", 2), ("gather_deep", 1), ("general_k4", 2), ("general_s1", 1)])
+def test_conv_moonwalk_in_several_launches_per_layer(mw, name, per_launch):
+    """The batch taken in image chunks, as the 2 GiB operand limit forces at the benchmark's size: the same
+    parity with the oracle (chunks of two and one image, or one launch per image)."""
+    _parity_of_case(mw, name, max_images_per_launch=per_launch)
+    wl = make_convnet(2, 16, 32, 1, seed=0)
+    with pytest.raises(mw.MoonwalkError) as e:
+        mw.ConvMoonwalkNet.from_workload(wl, max_images_per_launch=-1)
+    assert e.value.code == -1
 
 
 def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):

@@ -43,10 +43,19 @@ FRAG_CASES = {
 
 @pytest.mark.parametrize("name", sorted(FRAG_CASES))
 def test_frag_moonwalk_matches_the_oracle(mw, name):
+    _parity_of_case(mw, name)
+
+
+def test_frag_moonwalk_in_several_launches_per_layer(mw):
+    """The batch taken in image chunks of two and one: the same parity with the oracle."""
+    _parity_of_case(mw, "block8", max_images_per_launch=2)
+
+
+def _parity_of_case(mw, name, **net_kw):
     B, N, C, depth, k, block, alpha, K, gain = FRAG_CASES[name]
     wl = make_fragnet(B, N, C, depth, k=k, block=block, alpha=alpha, gain=gain, diag=(0.8, 1.2), seed=1, name=name)
-    print("frag", name, flush=True)
-    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K)
+    print("frag", name, net_kw, flush=True)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, **net_kw)
     res = net.moonwalk_grad(net.x, net.t)
     torch.cuda.synchronize()
     st = net.memory_stats()

@@ -59,6 +59,40 @@ struct EpiStore::Dev {
   }
 };
 
+// C = alpha * acc + beta * D: D is another matrix of C's shape and row stride (or C itself, or NULL)
+struct EpiAxpby {
+  float* C;
+  const float* D;
+  int64_t ldc;
+  float alpha, beta;
+  struct Dev {
+    __amdgpu_buffer_rsrc_t rc, rd;
+    int64_t ldc;
+    float alpha, beta;
+    bool add;
+    __device__ __forceinline__ Dev(const EpiAxpby& p, int M, int N)
+        : ldc(p.ldc), alpha(p.alpha), beta(p.beta), add(p.D != nullptr && p.beta != 0.f) {
+      rc = make_rsrc(p.C, extent_bytes(M, N, p.ldc));
+      rd = make_rsrc(p.D, add ? extent_bytes(M, N, p.ldc) : 0u);
+    }
+    __device__ __forceinline__ void finish() const {}
+    template <int CNT>
+    __device__ __forceinline__ void part(int M, int N, int row_base, int col, int g, int i0,
+                                         const float (&v)[1][CNT]) const {
+      uint32_t off[CNT];
+      float old[CNT];
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) {
+        const int row = row_base + acc_row(i0 + j, g);
+        off[j] = (col < N && row < M) ? ((uint32_t)row * (uint32_t)ldc + (uint32_t)col) * 4u : OOB;
+        old[j] = buf_load_f32(rd, add ? off[j] : OOB);
+      }
+#pragma unroll
+      for (int j = 0; j < CNT; ++j) buf_store_f32(rc, off[j], alpha * v[0][j] + (add ? beta * old[j] : 0.f));
+    }
+  };
+};
+
 // Phase-I forward epilogue: z = acc + b, m = (z > 0), x = m ? z : alpha z. With MASK the 32
 // sign bits each half-wavefront holds for one output row go out as one 32-bit half of a packed
 // mask word (requires N % 32 == 0; the launcher checks).
@@ -373,6 +407,34 @@ struct GemmTask {
         }
       }
     }
+  }
+};
+
+// The same product for several independent operand sets of one shape, in one grid: set g takes
+// A[g], B[g], D[g] and writes C[g] (pointer tables in device memory). Small products that would
+// leave the chip half empty one at a time fill it together, with the tile a large product takes.
+template <class Cfg, int LA, int LB>
+struct GroupedGemmTask {
+  int n_sets, M, N, K;
+  const float* const* A;
+  int64_t lda;
+  const float* const* B;
+  int64_t ldb;
+  float* const* C;
+  const float* const* D;  // may be NULL: no addend
+  int64_t ldc;
+  float alpha, beta;
+  int tiles_m, tiles_n;
+  using One = GemmTask<Cfg, LA, LB, true, ANone, EpiAxpby, false>;
+  static constexpr int LDS_BYTES = One::LDS_BYTES;
+  __host__ __device__ int blocks() const { return n_sets * tiles_m * tiles_n; }
+
+  __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
+    const int per = tiles_m * tiles_n;
+    const int g = bid / per;
+    const One t{M, N, K, A[g], lda, B[g], ldb, ANone{}, EpiAxpby{C[g], D ? D[g] : nullptr, ldc, alpha, beta},
+                nullptr, 0.f, tiles_m, tiles_n};
+    t.run(bid - g * per, lds);
   }
 };
 

@@ -152,6 +152,14 @@ struct mw_handle {
   uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
   double* loss_scratch = nullptr;
   float* refresh_work = nullptr;  // incremental refresh of P: allocated on first use
+  const float** refresh_tab = nullptr;  // device table of pointers for the grouped products of that refresh:
+                                        // P of every layer, W of every layer, then the S and the Q slots
+  struct RefreshRun {             // consecutive layers of one shape
+    int l0, len, sets;            // first layer, layers, layers refreshed side by side (1: one at a time)
+    size_t tab_off;               // the run's S slot pointers in refresh_tab, its Q slot pointers `sets` further on
+    size_t slot, q_off;           // floats per slot of refresh_work, and where Q starts inside a slot
+  };
+  std::vector<RefreshRun> refresh_runs;
   // Phase III runs layer i's kernel and layer i-1's weight-gradient product in one launch: the
   // latter still reads ct_z_{i-1} and x_{i-2} while the former writes ct_z_i and x_i, so the
   // activation buffers rotate over three and the ct_z buffers over two.
@@ -692,35 +700,116 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
 //   P_0 = (P P^T) W            P P^T = (W_old W_old^T)^{-1}: a first-order guess whose rows lie in the
 //                              row space of the new W, so that every iterate stays the minimum-norm one
 //   P_{k+1} = (2 I - P_k W^T) P_k     Newton-Schulz; the residual I - P W^T squares per iteration
-// All products are the library's plain GEMMs; scratch (d_out^2 + d_out d_in floats of the largest
-// layer) is allocated on first use and kept.
-int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStream_t s) {
-  if (!h->refresh_work) {
-    size_t need = 0;
-    for (auto& l : h->layers) {
-      size_t w = (size_t)l.d_out * l.d_out + (size_t)l.d_out * l.d_in;
-      if (w > need) need = w;
+// Consecutive layers of one shape are refreshed side by side, as many (up to REFRESH_SETS) as it takes to
+// fill the chip with 128 x 128 tiles: each step is then one grouped product over all of them (a
+// 1024 x 1024 x 1024 product alone fills a quarter of the chip with the tile that suits it). Scratch
+// (d_out^2 + d_out d_in floats per layer in flight) and the pointer table are allocated on first use and kept.
+constexpr int REFRESH_SETS = 8;
+
+int refresh_one_layer(mw_handle* h, Layer& l, int iters, float* residual_out, hipStream_t s) {
+  const int n = l.d_out, m = l.d_in;
+  float* S = h->refresh_work;
+  float* Q = S + (((size_t)n * n + 63) / 64) * 64;
+  MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, l.P, m, l.P, m, 0.f, S, n, nullptr, s));
+  float* cur = (iters % 2 == 1) ? Q : l.P;
+  float* other = (cur == Q) ? l.P : Q;
+  MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, 1.f, S, n, l.W, m, 0.f, cur, m, nullptr, s));
+  for (int it = 0; it < iters; ++it) {
+    MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, cur, m, l.W, m, 0.f, S, n, nullptr, s));
+    if (residual_out && it == iters - 1) MW_HIP(ew_identity_residual(S, n, h->loss_scratch, residual_out, s));
+    MW_HIP(ew_copy(cur, other, (int64_t)n * m, s));
+    MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, -1.f, S, n, cur, m, 2.f, other, m, nullptr, s));
+    float* t = cur;
+    cur = other;
+    other = t;
+  }
+  return MW_OK;
+}
+
+int refresh_plan(mw_handle* h) {
+  auto round64 = [](size_t v) { return (v + 63) / 64 * 64; };  // slots start on 256-byte boundaries
+  const int L = h->L;
+  std::vector<mw_handle::RefreshRun> runs;
+  size_t total = 0, n_tab = 2 * (size_t)L;
+  for (int l0 = 0; l0 < L;) {
+    const int n = h->layers[l0].d_out, m = h->layers[l0].d_in;
+    int len = 0;
+    bool vec = n % 4 == 0 && m % 4 == 0;
+    while (l0 + len < L && h->layers[l0 + len].d_out == n && h->layers[l0 + len].d_in == m) {
+      vec = vec && ((reinterpret_cast<uintptr_t>(h->layers[l0 + len].P) | reinterpret_cast<uintptr_t>(h->layers[l0 + len].W)) & 15) == 0;
+      ++len;
     }
-    h->refresh_work = static_cast<float*>(h->alloc(need * sizeof(float), &h->st.bytes_mw_scratch));
-    if (!h->refresh_work) return MW_ERR_OOM;
+    // layers side by side: enough for two 128 x 128 tiles per CU in the smaller of the two products
+    const int64_t tiles = (int64_t)((n + 127) / 128) * ((n + 127) / 128);
+    int sets = (int)((512 + tiles - 1) / tiles);
+    if (sets > REFRESH_SETS) sets = REFRESH_SETS;
+    if (sets > len) sets = len;
+    if (!vec || sets < 2) sets = 1;
+    const size_t q_off = round64((size_t)n * n), slot = q_off + round64((size_t)n * m);
+    runs.push_back({l0, len, sets, n_tab, slot, q_off});
+    if ((size_t)sets * slot > total) total = (size_t)sets * slot;
+    if (sets > 1) n_tab += 2 * (size_t)sets;
+    l0 += len;
+  }
+  float* work = static_cast<float*>(h->alloc(total * sizeof(float), &h->st.bytes_mw_scratch));
+  if (!work) return MW_ERR_OOM;
+  const float** tab = static_cast<const float**>(h->alloc(n_tab * sizeof(float*), &h->st.bytes_mw_scratch));
+  if (!tab) return MW_ERR_OOM;
+  std::vector<const float*> host(n_tab);
+  for (int i = 0; i < L; ++i) {
+    host[i] = h->layers[i].P;
+    host[L + i] = h->layers[i].W;
+  }
+  for (auto& r : runs)
+    for (int j = 0; r.sets > 1 && j < r.sets; ++j) {
+      host[r.tab_off + j] = work + (size_t)j * r.slot;
+      host[r.tab_off + r.sets + j] = work + (size_t)j * r.slot + r.q_off;
+    }
+  MW_HIP(hipMemcpy(tab, host.data(), n_tab * sizeof(float*), hipMemcpyHostToDevice));
+  h->refresh_work = work;
+  h->refresh_tab = tab;
+  h->refresh_runs = std::move(runs);
+  return MW_OK;
+}
+
+int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStream_t s) {
+  const int L = h->L;
+  if (!h->refresh_work) {
+    int rc = refresh_plan(h);
+    if (rc != MW_OK) return rc;
   }
   if (residual_out) MW_HIP(ew_fill_f32(residual_out, iters >= 1 ? 0.f : -1.f, 1, s));
-  for (auto& l : h->layers) {
-    const int n = l.d_out, m = l.d_in;
-    float* S = h->refresh_work;
-    float* Q = S + (size_t)n * n;
-    MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, l.P, m, l.P, m, 0.f, S, n, nullptr, s));
-    float* cur = (iters % 2 == 1) ? Q : l.P;
-    float* other = (cur == Q) ? l.P : Q;
-    MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, 1.f, S, n, l.W, m, 0.f, cur, m, nullptr, s));
-    for (int it = 0; it < iters; ++it) {
-      MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, cur, m, l.W, m, 0.f, S, n, nullptr, s));
-      if (residual_out && it == iters - 1) MW_HIP(ew_identity_residual(S, n, h->loss_scratch, residual_out, s));
-      MW_HIP(ew_copy(cur, other, (int64_t)n * m, s));
-      MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, -1.f, S, n, cur, m, 2.f, other, m, nullptr, s));
-      float* t = cur;
-      cur = other;
-      other = t;
+  auto out = [](const float* const* t) { return reinterpret_cast<float* const*>(const_cast<float**>(const_cast<const float**>(t))); };
+  for (const auto& r : h->refresh_runs) {
+    const int n = h->layers[r.l0].d_out, m = h->layers[r.l0].d_in;
+    for (int l0 = r.l0; l0 < r.l0 + r.len;) {
+      const int g = (r.l0 + r.len - l0 < r.sets) ? r.l0 + r.len - l0 : r.sets;
+      if (r.sets < 2) {
+        int rc = refresh_one_layer(h, h->layers[l0], iters, residual_out, s);
+        if (rc != MW_OK) return rc;
+        l0 += 1;
+        continue;
+      }
+      const float* const* Pt = h->refresh_tab + l0;
+      const float* const* Wt = h->refresh_tab + L + l0;
+      const float* const* St = h->refresh_tab + r.tab_off;
+      const float* const* Qt = St + r.sets;
+      MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, Pt, m, Pt, m, 0.f, nullptr, out(St), n, s));
+      const float* const* cur = (iters % 2 == 1) ? Qt : Pt;
+      const float* const* other = (cur == Qt) ? Pt : Qt;
+      MW_HIP(gemm_grouped(OP_NN, g, n, m, n, 1.f, St, n, Wt, m, 0.f, nullptr, out(cur), m, s));
+      for (int it = 0; it < iters; ++it) {
+        MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, cur, m, Wt, m, 0.f, nullptr, out(St), n, s));
+        if (residual_out && it == iters - 1)
+          for (int j = 0; j < g; ++j)
+            MW_HIP(ew_identity_residual(h->refresh_work + (size_t)j * r.slot, n, h->loss_scratch, residual_out, s));
+        // other = 2 cur - S cur, the addend read from cur by the epilogue
+        MW_HIP(gemm_grouped(OP_NN, g, n, m, n, -1.f, St, n, cur, m, 2.f, cur, out(other), m, s));
+        const float* const* t = cur;
+        cur = other;
+        other = t;
+      }
+      l0 += g;
     }
   }
   return MW_OK;

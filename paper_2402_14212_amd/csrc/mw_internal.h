@@ -22,6 +22,13 @@ int pick_tile_dw(int M, int N, int K, int partner, bool phase3);
 
 // ---- GEMM launchers (gemm_*.hip). All enqueue on `stream` and return the launch status. ----
 
+// C[g] = alpha * op(A[g], B[g]) + beta * D[g], g < n_sets: the same NT or NN product on several operand sets of one
+// shape in one launch (gemm_grouped.hip). Pointer tables in device memory; D may be NULL; operands 16-byte aligned,
+// row strides multiples of 4 floats.
+hipError_t gemm_grouped(int op, int n_sets, int M, int N, int K, float alpha, const float* const* A, int64_t lda,
+                        const float* const* B, int64_t ldb, float beta, const float* const* D, float* const* C, int64_t ldc,
+                        hipStream_t stream);
+
 // C = alpha * op(A, B) + beta * C + bias (bias indexed by column, may be NULL)
 hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const float* A, int64_t lda,
                       const float* B, int64_t ldb, float beta, float* C, int64_t ldc, const float* bias,

@@ -55,6 +55,37 @@ def test_refresh_incremental_matches_the_oracle(mw, widths, rel):
     net.close()
 
 
+@pytest.mark.parametrize("widths", [[136] * 4, [64] * 12, [96, 96, 96, 40, 40, 40]])
+def test_refresh_incremental_of_layers_of_one_shape_side_by_side(mw, widths):
+    """Consecutive layers of one shape are refreshed by grouped products, eight layers at a time: every
+    layer's right inverse against the oracle's iteration, for even and odd iteration counts."""
+    wl = make_mlp(widths, 4, 0.1, seed=3)
+    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK)
+    L = len(widths) - 1
+    P_old = [net.fetch_P(i).astype(np.float64) for i in range(L)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(9)
+    W_old = [W.clone() for W in net.Ws]
+    for iters in (0, 1, 2, 3):
+        print("grouped refresh", widths, iters, flush=True)
+        for W, W0 in zip(net.Ws, W_old):
+            D = torch.randn(W.shape, device="cuda", generator=gen)
+            W.copy_(W0 + 3e-3 * float(W0.norm() / D.norm()) * D)
+        res = net.refresh_incremental(iters)
+        worst = 0.0
+        for i in range(L):
+            P_ref, res_ref = O.newton_schulz_refresh(_np64(net.Ws[i]), P_old[i], iters)
+            assert O.normwise_rel_err(net.fetch_P(i).astype(np.float64), P_ref) < 1e-5, (i, iters)
+            if iters >= 1:
+                worst = max(worst, res_ref[iters - 1])
+        if iters >= 1:   # the reported residual is the largest over the layers, measured before the last iteration
+            assert abs(float(res.item()) - worst) <= 0.02 * worst + 2e-5 * np.sqrt(max(widths)), (float(res.item()), worst)
+        for W, W0 in zip(net.Ws, W_old):
+            W.copy_(W0)
+        net.refresh()
+    net.close()
+
+
 TRAIN_CASES = {
     # name: (widths, batch, alpha, K, use_bias)
     "tiny":            ([64] * 5, 32, 0.1, 0, True),

@@ -717,6 +717,48 @@ k_identity_residual_final(const double* __restrict__ partial, int n_partial, flo
   }
 }
 
+// The same for several matrices `stride` floats apart (blockIdx.y selects one): partial sums of matrix j
+// in partial[j * gridDim.x ..]; the final kernel folds the largest of the residuals into *out.
+__global__ void __launch_bounds__(EW_THREADS)
+k_identity_residual_sets(const float* __restrict__ E, int64_t stride, int n, double* __restrict__ partial) {
+  __shared__ double red[EW_THREADS];
+  const float* Ej = E + (int64_t)blockIdx.y * stride;
+  const int64_t total = (int64_t)n * n;
+  double acc = 0.0;
+  for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < total; e += (int64_t)gridDim.x * EW_THREADS) {
+    const int64_t r = e / n, c = e - r * n;
+    const float d = Ej[e] - (r == c ? 1.f : 0.f);
+    acc += (double)d * (double)d;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = red[0];
+}
+
+__global__ void __launch_bounds__(EW_THREADS)
+k_identity_residual_sets_final(const double* __restrict__ partial, int n_partial, int n_sets, float* __restrict__ out) {
+  __shared__ double red[EW_THREADS];
+  for (int j = 0; j < n_sets; ++j) {
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n_partial; i += EW_THREADS) acc += partial[(int64_t)j * n_partial + i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
+      if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+      const float r = (float)sqrt(red[0]);
+      if (!(r <= *out)) *out = r;  // running maximum; a NaN residual is kept
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------- copy / fill
 __global__ void __launch_bounds__(EW_THREADS)
 k_copy(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
@@ -987,6 +1029,20 @@ hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* o
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_identity_residual_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, out);
+  return hipGetLastError();
+}
+
+hipError_t ew_identity_residual_sets(const float* E, int64_t stride, int n_sets, int n, double* scratch, float* out,
+                                     hipStream_t stream) {
+  if (n <= 0 || n_sets <= 0) return hipSuccess;
+  if (n_sets > LOSS_BLOCKS) return hipErrorInvalidValue;
+  int64_t want = ((int64_t)n * n + EW_THREADS - 1) / EW_THREADS;
+  const int64_t cap = LOSS_BLOCKS / n_sets;  // the scratch holds LOSS_BLOCKS doubles in all
+  const int blocks = (int)(want > cap ? cap : want);
+  hipLaunchKernelGGL(k_identity_residual_sets, dim3(blocks, n_sets), dim3(EW_THREADS), 0, stream, E, stride, n, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_identity_residual_sets_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, n_sets, out);
   return hipGetLastError();
 }
 

@@ -801,8 +801,7 @@ int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStrea
       for (int it = 0; it < iters; ++it) {
         MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, cur, m, Wt, m, 0.f, nullptr, out(St), n, s));
         if (residual_out && it == iters - 1)
-          for (int j = 0; j < g; ++j)
-            MW_HIP(ew_identity_residual(h->refresh_work + (size_t)j * r.slot, n, h->loss_scratch, residual_out, s));
+          MW_HIP(ew_identity_residual_sets(h->refresh_work, (int64_t)r.slot, g, n, h->loss_scratch, residual_out, s));
         // other = 2 cur - S cur, the addend read from cur by the epilogue
         MW_HIP(gemm_grouped(OP_NN, g, n, m, n, -1.f, St, n, cur, m, 2.f, cur, out(other), m, s));
         const float* const* t = cur;

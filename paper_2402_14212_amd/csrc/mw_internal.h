@@ -164,6 +164,9 @@ inline hipError_t ew_fill_f32(float* p, float value, int64_t n, hipStream_t stre
 hipError_t ew_scale_by_act_slope(const float* h, const float* act, int64_t n, float alpha, float* out, hipStream_t stream);
 // *out = max(*out, ||E - I||_F) for the n x n matrix E (row stride n); scratch: LOSS_BLOCKS doubles
 hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream);
+// the same for n_sets matrices `stride` floats apart, in two launches for all of them (the same scratch)
+hipError_t ew_identity_residual_sets(const float* E, int64_t stride, int n_sets, int n, double* scratch, float* out,
+                                     hipStream_t stream);
 // load-only model of a tiled product (measurement): sink gets (M/tile)*(N/tile)*256 floats
 hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
                              hipStream_t stream);

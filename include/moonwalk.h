@@ -427,6 +427,12 @@ int mw_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int32_t d, float
 
 /* Column sums: out[j] = scale * sum_r a[r][j], fixed summation order. */
 int mw_colsum(const float* a, int64_t rows, int32_t d, float scale, float* out, void* hip_stream);
+/* The same for tall matrices (the bias gradient of a convolutional layer: rows = B H' W'): the rows are cut
+   into ranges summed by separate workgroups (128-bit non-temporal loads when d % 4 == 0 and a, work are
+   16-byte aligned), and the ranges' sums are added in range order. work: mw_colsum_work_floats(d) device
+   floats. Fixed summation order, another one than mw_colsum's. */
+size_t mw_colsum_work_floats(int32_t d);
+int mw_colsum_wide(const float* a, int64_t rows, int32_t d, float scale, float* out, float* work, void* hip_stream);
 
 /* Loss step: h_L = scale (x_L - t) / rows and *loss = 0.5 ||x_L - t||_F^2 / rows (fixed-order
    reduction; partial sums in double). loss may be NULL. scratch: device doubles,

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
     "moonwalk_profile_filter", "moonwalk_profile_launches",
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
-    "mw_vijp_epilogue", "mw_colsum", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
+    "mw_vijp_epilogue", "mw_colsum", "mw_colsum_wide", "mw_colsum_work_floats", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
     "mw_probe_operand_stream",
     "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
     "moonwalk_conv_grad_layout", "moonwalk_conv_memory_stats", "moonwalk_conv_fetch", "moonwalk_conv_destroy",
@@ -125,6 +125,9 @@ def load_library() -> C.CDLL:
     lib.mw_frag_compact.argtypes = [vp, vp, vp, i64, vp, C.c_uint64, vp, vp]
     lib.mw_vijp_epilogue.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.mw_colsum.argtypes = [vp, i64, i32, f32, vp, vp]
+    lib.mw_colsum_wide.argtypes = [vp, i64, i32, f32, vp, vp, vp]
+    lib.mw_colsum_work_floats.argtypes = [i32]
+    lib.mw_colsum_work_floats.restype = C.c_size_t
     lib.mw_loss_grad.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp]
     lib.mw_loss_scratch_doubles.argtypes = []
     lib.mw_loss_scratch_doubles.restype = sz
@@ -714,6 +717,17 @@ def colsum(a: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
     rows, d = a.shape
     out = torch.empty(d, dtype=torch.float32, device=a.device)
     _check(load_library().mw_colsum(_ptr(_f32(a)), rows, d, scale, _ptr(out), _stream()))
+    return out
+
+
+def colsum_wide(a: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
+    """Column sums of a tall matrix, the rows cut into ranges summed side by side (mw_colsum_wide)."""
+    _require_gpu()
+    lib = load_library()
+    rows, d = a.shape
+    out = torch.empty(d, dtype=torch.float32, device=a.device)
+    work = torch.empty(int(lib.mw_colsum_work_floats(d)), dtype=torch.float32, device=a.device)
+    _check(lib.mw_colsum_wide(_ptr(_f32(a)), rows, d, scale, _ptr(out), _ptr(work), _stream()))
     return out
 
 

@@ -1044,6 +1044,14 @@ int mw_colsum(const float* a, int64_t rows, int32_t d, float scale, float* out, 
   return MW_OK;
 }
 
+size_t mw_colsum_work_floats(int32_t d) { return d > 0 ? (size_t)COLSUM_MAX_SLICES * (size_t)d : 0; }
+
+int mw_colsum_wide(const float* a, int64_t rows, int32_t d, float scale, float* out, float* work, void* hip_stream) {
+  if (rows < 0 || d <= 0 || !out || !work || (rows > 0 && !a)) return MW_ERR_INVALID_ARG;
+  MW_HIP(ew_colsum_wide(a, rows, d, scale, 0.f, out, work, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
 size_t mw_loss_scratch_doubles(void) { return (size_t)LOSS_BLOCKS; }
 
 int mw_loss_grad(const float* xL, const float* t, int64_t rows, int32_t d, float scale, float* hL, float* loss,

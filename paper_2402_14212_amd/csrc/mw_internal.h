@@ -143,8 +143,8 @@ hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* ou
 // the same for tall matrices: row ranges summed by separate workgroups into scratch
 // (ew_colsum_slices(rows, d) * d floats, at most COLSUM_MAX_SLICES * d), then combined in range order;
 // out = scale * sums + beta * out
-constexpr int COLSUM_MAX_SLICES = 512;
-int ew_colsum_slices(int64_t rows, int d);
+constexpr int COLSUM_MAX_SLICES = 2048;
+int ew_colsum_slices(int64_t rows, int d, bool vec);  // vec: the 128-bit kernel (d % 4 == 0, 16-byte aligned operands)
 hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, float beta, float* out, float* scratch,
                           hipStream_t stream);
 // out[i] = scale * (sum over the slices of part[.][i], in an order fixed by slices and n) + beta * out[i]; part is [slices][n]

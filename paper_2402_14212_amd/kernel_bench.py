@@ -93,6 +93,7 @@ def bench_elementwise(iters, max_log2):
         flag = torch.zeros(1, dtype=torch.int32, device="cuda")
         scratch = torch.empty(int(lib.mw_loss_scratch_doubles()), dtype=torch.float64, device="cuda")
         loss = torch.empty(1, device="cuda")
+        cswork = torch.empty(int(lib.mw_colsum_work_floats(128)), dtype=torch.float32, device="cuda")
         P = lambda t: t.data_ptr()
 
         def report(name, bytes_per_elt, t):
@@ -124,6 +125,9 @@ def bench_elementwise(iters, max_log2):
                timed(lambda i: lib.mw_vijp_epilogue(P(zs[i % pool]), P(hs[i % pool]), rows, dd, 0.1, None, None, None,
                                                     P(x), P(y), stream), iters))
         report("colsum", 4.0, timed(lambda i: lib.mw_colsum(P(hs[i % pool]), rows, dd, 1.0, P(bias), stream), iters))
+        # the tall-matrix form (bias gradient of a convolutional layer): as many rows as fit 128 columns
+        report("colsum tall, 128 columns", 4.0,
+               timed(lambda i: lib.mw_colsum_wide(P(hs[i % pool]), n // 128, 128, 1.0, P(bias), P(cswork), stream), iters))
         report("loss_grad", 12.0,
                timed(lambda i: lib.mw_loss_grad(P(zs[i % pool]), P(hs[i % pool]), rows, dd, 1.0, P(x), P(loss), P(scratch),
                                                 stream), iters))

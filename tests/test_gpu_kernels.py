@@ -184,6 +184,20 @@ def test_colsum_and_loss(mw):
         assert O.normwise_rel_err(hL.cpu().numpy(), h) < 1e-6
 
 
+@pytest.mark.parametrize("rows,d", [(1, 4), (7, 12), (300, 128), (5000, 32), (70001, 256), (2048, 1000), (1025, 130), (999, 7)])
+def test_colsum_of_tall_matrices(mw, rows, d):
+    """Row ranges summed side by side, then added in range order: the 128-bit kernel (d a multiple of 4) and
+    the scalar one, ragged row ranges, more than 128 columns; bit-identical on repetition."""
+    rng = np.random.default_rng(6)
+    a = rng.standard_normal((rows, d)).astype(np.float32)
+    got = mw.colsum_wide(dev(a), 0.25)
+    ref = 0.25 * a.astype(np.float64).sum(axis=0)
+    assert np.abs(got.cpu().numpy() - ref).max() <= 2e-6 * np.sqrt(rows) * max(1.0, np.abs(a).max())
+    assert torch.equal(got, mw.colsum_wide(dev(a), 0.25))
+    view = dev(np.concatenate([np.zeros(1, np.float32), a.ravel()]))[1:].view(rows, d)   # not 16-byte aligned
+    assert np.abs(mw.colsum_wide(view, 0.25).cpu().numpy() - ref).max() <= 2e-6 * np.sqrt(rows) * max(1.0, np.abs(a).max())
+
+
 def test_copy(mw):
     for n in (1, 5, 1024, 1_000_003):
         src = torch.arange(n, dtype=torch.float32, device="cuda")

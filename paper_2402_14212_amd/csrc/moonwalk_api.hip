@@ -206,12 +206,27 @@ bool alloc_t(mw_handle* h, T** out, size_t count, uint64_t* item) {
   return *out != nullptr;
 }
 
-// Right inverses for every layer; scratch is taken and given back within the call.
+// Right inverses for every layer; scratch is taken and given back within the call. Consecutive layers of
+// one shape are factored side by side, up to SETUP_GROUP of them and SETUP_GROUP_BYTES of scratch at a time.
+constexpr int SETUP_GROUP = 16;
+constexpr size_t SETUP_GROUP_BYTES = (size_t)1 << 30;
+
 int build_right_inverses(mw_handle* h, hipStream_t stream) {
+  const int L = (int)h->layers.size();
+  std::vector<int> group(L, 1);  // group[i]: layers factored together starting at layer i (0: inside a group)
   size_t work_floats = 0;
-  for (auto& l : h->layers) {
-    size_t w = setup_work_floats(l.d_out, l.d_in);
-    if (w > work_floats) work_floats = w;
+  for (int i = 0; i < L;) {
+    const Layer& f = h->layers[i];
+    const size_t w = setup_work_floats(f.d_out, f.d_in);
+    int most = (int)(SETUP_GROUP_BYTES / (w * sizeof(float)));
+    if (most > SETUP_GROUP) most = SETUP_GROUP;
+    if (most < 1) most = 1;
+    int g = 1;
+    while (i + g < L && g < most && h->layers[i + g].d_out == f.d_out && h->layers[i + g].d_in == f.d_in) ++g;
+    group[i] = g;
+    for (int j = 1; j < g; ++j) group[i + j] = 0;
+    if ((size_t)g * w > work_floats) work_floats = (size_t)g * w;
+    i += g;
   }
   uint64_t before = h->live;
   float* work = static_cast<float*>(h->alloc(work_floats * sizeof(float), nullptr));
@@ -221,9 +236,15 @@ int build_right_inverses(mw_handle* h, hipStream_t stream) {
   int32_t* bad = reinterpret_cast<int32_t*>(h->status + 3);
   int rc = MW_OK;
   hipError_t e = ew_fill_u32(h->status + 3, 0u, 1, stream);
-  for (size_t i = 0; e == hipSuccess && i < h->layers.size(); ++i) {
-    Layer& l = h->layers[i];
-    e = setup_right_inverse(l.W, l.d_out, l.d_in, l.P, work, bad, stream);
+  for (int i = 0; e == hipSuccess && i < L; ++i) {
+    if (group[i] == 0) continue;
+    const float* Ws[SETUP_GROUP];
+    float* Ps[SETUP_GROUP];
+    for (int j = 0; j < group[i]; ++j) {
+      Ws[j] = h->layers[i + j].W;
+      Ps[j] = h->layers[i + j].P;
+    }
+    e = setup_right_inverse_group(group[i], Ws, h->layers[i].d_out, h->layers[i].d_in, Ps, work, bad, stream);
   }
   int32_t bad_host = 0;
   if (e == hipSuccess) e = hipStreamSynchronize(stream);

@@ -249,5 +249,9 @@ int record_hip_failure(hipError_t e, const char* where);
 size_t setup_work_floats(int d_out, int d_in);
 hipError_t setup_right_inverse(const float* W, int d_out, int d_in, float* P, float* work, int32_t* bad_pivot,
                                hipStream_t stream);
+// the same for `count` layers of one shape side by side; work: count * setup_work_floats(d_out, d_in) floats,
+// W and P: host arrays of device pointers
+hipError_t setup_right_inverse_group(int count, const float* const* W, int d_out, int d_in, float* const* P, float* work,
+                                     int32_t* bad_pivot, hipStream_t stream);
 
 }  // namespace mw

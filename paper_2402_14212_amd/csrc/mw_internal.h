@@ -141,7 +141,7 @@ hipError_t ew_vijp_epilogue(const float* z, float* ct_z, int64_t rows, int d, fl
                             float* x, float* h_y, unsigned long long* mismatches, hipStream_t stream);
 hipError_t ew_colsum(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream);
 // the same for tall matrices: row ranges summed by separate workgroups into scratch
-// (ew_colsum_slices(rows, d) * d floats, at most COLSUM_MAX_SLICES * d), then combined in range order;
+// (ew_colsum_slices(rows, d, vec) * d floats, at most COLSUM_MAX_SLICES * d), then combined in range order;
 // out = scale * sums + beta * out
 constexpr int COLSUM_MAX_SLICES = 2048;
 int ew_colsum_slices(int64_t rows, int d, bool vec);  // vec: the 128-bit kernel (d % 4 == 0, 16-byte aligned operands)

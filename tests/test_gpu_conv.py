@@ -250,6 +250,61 @@ def test_conv_moonwalk_in_several_launches_per_layer(mw, name, per_launch):
     assert e.value.code == -1
 
 
+def _random_conv_cases(n_cases, seed):
+    """Seeded draws of valid chains: channel counts, kernel, stride, padding, image sides that meet the
+    lemma's spatial bounds, one or two layers, any re-seed interval."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n_cases:
+        k, s = int(rng.integers(1, 6)), int(rng.integers(1, 4))
+        p = int(rng.integers(0, min(s, k)))
+        depth = int(rng.integers(1, 3))
+        wide = k > p + s
+        pool = [32, 64] if wide else [4, 6, 8, 12, 32, 64]
+        cs = sorted((int(rng.choice(pool)) for _ in range(depth + 1)), reverse=True)
+        H, W = int(rng.integers(k, 27)), int(rng.integers(k, 27))
+        hs, ws_, ok = [H], [W], True
+        for _ in range(depth):
+            ho, wo = (hs[-1] + 2 * p - k) // s + 1, (ws_[-1] + 2 * p - k) // s + 1
+            ok = ok and hs[-1] + 2 * p >= k and ws_[-1] + 2 * p >= k and ho >= 1 and wo >= 1
+            ok = ok and hs[-1] > s * (ho - 1) and ws_[-1] > s * (wo - 1)
+            hs.append(ho)
+            ws_.append(wo)
+        if ok:
+            cases.append((int(rng.integers(1, 4)), H, W, cs, k, s, p, int(rng.integers(0, 2)), hs, ws_))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(24, 2024), ids=lambda c: "B%d_%dx%d_c%s_k%d_s%d_p%d_K%d" % (
+    c[0], c[1], c[2], "-".join(map(str, c[3])), c[4], c[5], c[6], c[7]))
+def test_conv_moonwalk_on_random_valid_chains(mw, case):
+    B, H, W, cs, k, s, p, K, hs, ws_ = case
+    depth = len(cs) - 1
+    kernels = make_convnet(1, 64, cs, depth, k=k, s=max(s, p + 1), p=p, alpha=0.3, seed=31)   # kernels and biases only
+    rng = np.random.default_rng(32)
+    x = rng.standard_normal((B, H, W, cs[0])).astype(np.float32)
+    t = rng.standard_normal((B, hs[-1], ws_[-1], cs[-1])).astype(np.float32)
+    print("conv random", case[:8], flush=True)
+    dev = torch.device("cuda:0")
+    net = mw.ConvMoonwalkNet([torch.from_numpy(w).to(dev) for w in kernels.w], [torch.from_numpy(b).to(dev) for b in kernels.b],
+                             kernels.alphas, B, H, W, s, p, reseed_interval=K)
+    dx, dt = torch.from_numpy(x).to(dev), torch.from_numpy(t).to(dev)
+    res = net.moonwalk_grad(dx, dt)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    shapes = [(B, hs[i + 1], ws_[i + 1], cs[i + 1]) for i in range(depth)]
+    masks = [O.unpack_mask(net.fetch_mask(i), int(np.prod(sh))).reshape(sh) for i, sh in enumerate(shapes)]
+    ref = CO.conv_backprop(kernels.w, kernels.b, kernels.alphas, s, p, x, t, forced_masks=masks)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    assert O.normwise_rel_err(net.fetch_h0().reshape(x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    bp = net.backprop_grad(dx, dt)
+    torch.cuda.synchronize()
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(bp.dW, ref["dW"])) <= 1e-4
+    net.close()
+
+
 def test_conv_setup_rejects_what_is_not_submersive_or_not_built(mw):
     wl = make_convnet(2, 16, 8, 1, seed=0)
     dev = torch.device("cuda:0")

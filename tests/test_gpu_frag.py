@@ -126,6 +126,42 @@ def test_frag_moonwalk_with_fewer_output_than_input_channels(mw):
     net.close()
 
 
+def _random_frag_cases(n_cases, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n_cases):
+        k = int(rng.choice([1, 3, 5, 7]))
+        block = int(rng.choice([b for b in (2, 4, 6, 8, 12, 16) if b >= k - 1 and b >= 1]))
+        depth = int(rng.integers(1, 4))
+        cs = sorted((int(rng.choice([32, 64, 96])) for _ in range(depth + 1)), reverse=True)
+        cases.append((int(rng.integers(1, 4)), block * int(rng.integers(1, 13)), cs, k, block, int(rng.integers(0, 3))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_frag_cases(12, 77), ids=lambda c: "B%d_N%d_c%s_k%d_b%d_K%d" % (
+    c[0], c[1], "-".join(map(str, c[2])), c[3], c[4], c[5]))
+def test_frag_moonwalk_on_random_valid_chains(mw, case):
+    B, N, cs, k, block, K = case
+    depth = len(cs) - 1
+    wl = make_fragnet(B, N, cs, depth, k=k, block=block, alpha=0.3, gain=0.7, diag=(0.8, 1.2), seed=41)
+    print("frag random", case, flush=True)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K)
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    assert net.memory_stats()["sign_mismatches"] == 0
+    masks = [O.unpack_mask(net.fetch_mask(i), B * N * cs[i + 1]).reshape(B, N, cs[i + 1]) for i in range(depth)]
+    ref = FO.conv1d_backprop(wl.w, wl.b, wl.alphas, wl.x, wl.t, forced_masks=masks)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.dW, ref["dW"])) <= GRAD_TOL
+    assert max(O.normwise_rel_err(g.cpu().numpy(), r) for g, r in zip(res.db, ref["db"])) <= GRAD_TOL
+    assert O.normwise_rel_err(net.fetch_h0().reshape(wl.x.shape).astype(np.float64), ref["h0"]) <= 1e-4
+    if k > 1:
+        for i in range(depth):
+            want = FO.fragments_of(ref["ct_z"][i], k, block)
+            assert O.normwise_rel_err(net.fetch_fragments(i).reshape(want.shape).astype(np.float64), want) <= 1e-4, i
+    net.close()
+
+
 def test_frag_setup_rejects_what_the_fragmental_update_cannot_take(mw):
     wl = make_fragnet(2, 32, 32, 1, block=4, seed=0)
     dev = torch.device("cuda:0")

@@ -54,6 +54,36 @@ def test_moonwalk_matches_oracle(mw, name, fuse):
     net.close()
 
 
+def _random_mlp_cases(n_cases, seed):
+    """Seeded draws of valid networks: non-increasing widths of any granularity, any batch, leaky and ReLU
+    layers mixed, with and without re-seeds (depth kept to what the error growth between re-seeds allows)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n_cases):
+        K = int(rng.integers(0, 4))
+        depth = int(rng.integers(1, 5 if K == 0 else 9))
+        gran = int(rng.choice([1, 4, 32, 64]))
+        widths = sorted((gran * int(rng.integers(1, max(2, 260 // gran))) for _ in range(depth + 1)), reverse=True)
+        alphas = [float(rng.choice([0.0, 0.1, 0.3, 1.0])) for _ in range(depth)]
+        cases.append((widths, int(rng.integers(1, 131)), alphas, K, bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_mlp_cases(16, 99), ids=lambda c: "w%s_B%d_K%d_f%d" % ("-".join(map(str, c[0])), c[1], c[3], c[4]))
+def test_moonwalk_on_random_valid_networks(mw, case):
+    widths, batch, alphas, K, fuse = case
+    print("mlp random", case, flush=True)
+    wl = make_mlp(widths, batch, alphas, seed=5, reseed_interval=K, name="random")
+    net = mw.MoonwalkNet.from_workload(wl, fuse=fuse)
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    print(f"   {check_moonwalk(net, wl, res)}", flush=True)
+    bp = net.backprop_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    check_gradients(wl, gpu_masks(net, wl), bp, tol=1e-4)
+    net.close()
+
+
 @pytest.mark.parametrize("name", ["tiny", "ragged", "multi_tile_relu", "mixed", "reseed4_scaled"])
 def test_fused_and_unfused_agree_bit_for_bit(mw, name):
     wl, fused = build(mw, name, fuse=True)

@@ -631,42 +631,33 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
     }
     float* xout = xbuf[i & 1];
     float* hout = hbuf[i & 1];
-    if (frag1d) {
-      // ct_z from the incoming cotangent and the fragments, then one kernel: the pre-activation again, the sign
-      // check and the vijp of the activation
-      int rc = frag_rebuild(h, l, hin, h->ctz, s);
-      if (rc != MW_OK) return rc;
-      for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
-        const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
-        const int64_t o = img0 * l.out_img();
-        CV_HIP(conv_vijp_given(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, h->ctz + o,
-                               reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, mismatches, s));
+    if (l.gather) {
+      // ct_z and the layer's outputs, image chunk by image chunk. Where the vijp couples positions, ct_z comes
+      // first (fragmental layers: rebuilt block-wise from the incoming cotangent and the fragments; wide kernels:
+      // solved for the (p, p) tap at all positions, then swept over the anti-diagonals of the output grid) and
+      // one kernel follows: the pre-activation again, the sign check, the vijp of the activation. In the fully
+      // parallel case one kernel does it all: recomputed forward, channel solve at the strided positions, epilogue.
+      if (frag1d) {
+        int rc = frag_rebuild(h, l, hin, h->ctz, s);
+        if (rc != MW_OK) return rc;
       }
-      rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
-                            apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
-      if (rc != MW_OK) return rc;
-    } else if (l.reach > 0) {
-      // the general vijp: right-hand sides solved for the (p, p) tap at all positions, then the sweep over the
-      // anti-diagonals of the output grid, then one kernel: the pre-activation again, the sign check, the activation's vijp
       for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
         const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
         const int64_t o = img0 * l.out_img();
-        CV_HIP(conv_sub_solve(l.geom(), n_img, l.Cout, hin + img0 * l.in_img(), l.Tinv, h->ctz + o, s));
-        CV_HIP(conv_vijp_sweep(l.Ho, l.Wo, l.Cout, n_img, l.reach, h->ctz + o, l.Asweep, s));
-        CV_HIP(conv_vijp_given(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout, h->ctz + o,
-                               reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, mismatches, s));
-      }
-      int rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
-                                apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);
-      if (rc != MW_OK) return rc;
-    } else if (l.gather) {
-      // one kernel per image chunk: recomputed forward, channel solve at the strided positions, vijp epilogue
-      for (int64_t img0 = 0; img0 < h->B; img0 += l.gchunk) {
-        const int n_img = (int)((img0 + l.gchunk <= h->B) ? l.gchunk : h->B - img0);
-        const int64_t o = img0 * l.out_img();
-        CV_HIP(conv_vijp_layer(l.geom(), n_img, xin + img0 * l.in_img(), l.w, l.b, l.alpha, l.Cout,
-                               hin + img0 * (hin_as_read ? l.out_img() : l.in_img()), hin_as_read ? 1 : 0, l.Tinv, reinterpret_cast<const uint32_t*>(l.mask) + o / 32, xout + o, hout + o, h->ctz + o,
-                               mismatches, s));
+        const uint32_t* mask32 = reinterpret_cast<const uint32_t*>(l.mask) + o / 32;
+        const float* xc = xin + img0 * l.in_img();
+        if (l.whole_h()) {
+          if (!frag1d) {
+            CV_HIP(conv_sub_solve(l.geom(), n_img, l.Cout, hin + img0 * l.in_img(), l.Tinv, h->ctz + o, s));
+            CV_HIP(conv_vijp_sweep(l.Ho, l.Wo, l.Cout, n_img, l.reach, h->ctz + o, l.Asweep, s));
+          }
+          CV_HIP(conv_vijp_given(l.geom(), n_img, xc, l.w, l.b, l.alpha, l.Cout, h->ctz + o, mask32, xout + o, hout + o,
+                                 mismatches, s));
+        } else {
+          CV_HIP(conv_vijp_layer(l.geom(), n_img, xc, l.w, l.b, l.alpha, l.Cout,
+                                 hin + img0 * (hin_as_read ? l.out_img() : l.in_img()), hin_as_read ? 1 : 0, l.Tinv, mask32,
+                                 xout + o, hout + o, h->ctz + o, mismatches, s));
+        }
       }
       int rc = conv_weight_grad(h, l, xin, h->ctz, g_scale, apply ? const_cast<float*>(l.w) : grads_out + l.dW_off,
                                 apply ? const_cast<float*>(l.b) : grads_out + l.db_off, s, g_beta);

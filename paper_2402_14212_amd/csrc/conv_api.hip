@@ -49,7 +49,7 @@ struct ConvLayer {
   int kh = 0, kw = 0, ph = 0, pw = 0;  // the kernel as the products see it: k x k with padding p, or 1 x k for a 1-D layer
   int block = 0;                // fragmental layers: positions per block
   float* frag = nullptr;        // fragmental layers: [B W / block][k - 1][Cout], the first k - 1 positions of every block of ct_z
-  float* Arec = nullptr;        // fragmental layers: [k - 1][Cout][Cout], T^{-1} w[u][:Cout] for u = 1 .. k - 1
+  float* Arec = nullptr;        // fragmental layers: [Cout][(k - 1) Cout], T^{-1} w[u][:Cout] side by side for u = k - 1 .. 1
   int reach = 0;                // submersive layers: earlier output positions per dimension in a vijp equation, (k - 1 - p) / s;
                                 // 0 is the fully parallel case
   float* Asweep = nullptr;      // reach > 0: [Cout][((reach + 1)^2 - 1) Cout], T^{-1} w[p + a s][p + b s][:Cout] by tap slot
@@ -147,10 +147,11 @@ int build_from_weights(mw_conv_handle* h, hipStream_t s) {
                             l.Asweep + (size_t)(ky * n1 + kx) * l.Cout, Ktot, nullptr, s));
         }
     }
-    // fragmental layers: the recurrence matrices T^{-1} w[u][:Cout], u = 1 .. k - 1
+    // fragmental layers: the recurrence matrices T^{-1} w[u][:Cout] side by side, u = k - 1 .. 1, in the
+    // order of the positions j - k + 1 .. j - 1 they multiply: one [Cout][(k - 1) Cout] matrix
     for (int u = 1; l.Arec && u < l.k; ++u)
       CV_HIP(gemm_plain(OP_NN, TILE_AUTO, l.Cout, l.Cout, l.Cout, 1.f, l.Tinv, l.Cout, l.w + (size_t)u * l.Cin * l.Cout, l.Cout, 0.f,
-                        l.Arec + (size_t)(u - 1) * l.Cout * l.Cout, l.Cout, nullptr, s));
+                        l.Arec + (size_t)(l.k - 1 - u) * l.Cout, (int64_t)(l.k - 1) * l.Cout, nullptr, s));
   }
   int32_t bad = 0;
   CV_HIP(hipStreamSynchronize(s));
@@ -234,9 +235,10 @@ int frag_rebuild(mw_conv_handle* h, const ConvLayer& l, const float* hin, float*
     for (int j = l.k - 1; j < l.block; ++j) {
       CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, 1.f, hi + (int64_t)(j - l.p) * l.Cin, ld_h, l.Tinv, l.Cout, 0.f,
                         ct + (int64_t)j * l.Cout, ld_ct, nullptr, s));
-      for (int u = 1; u < l.k; ++u)
-        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, l.Cout, -1.f, ct + (int64_t)(j - u) * l.Cout, ld_ct,
-                          l.Arec + (size_t)(u - 1) * l.Cout * l.Cout, l.Cout, 1.f, ct + (int64_t)j * l.Cout, ld_ct, nullptr, s));
+      // the k - 1 positions before j are neighbours in a row of ct: one product over all of them
+      if (l.k > 1)
+        CV_HIP(gemm_plain(OP_NT, TILE_AUTO, (int)R, l.Cout, (l.k - 1) * l.Cout, -1.f, ct + (int64_t)(j - l.k + 1) * l.Cout, ld_ct,
+                          l.Arec, (int64_t)(l.k - 1) * l.Cout, 1.f, ct + (int64_t)j * l.Cout, ld_ct, nullptr, s));
     }
   }
   return MW_OK;

@@ -148,3 +148,21 @@ def test_sgd_step_is_a_projected_descent_step():
         for i, w1 in enumerate(out["w"]):
             assert CO.is_submersive(w1, wl.s, wl.p, wl.sides[i])
 
+
+
+def test_loss_and_cotangent_by_hand():
+    """J = 0.5 * (sum over every entry of (x_L - t)^2) / batch, h_L = scale (x_L - t) / batch: two 1 x 2 x 1
+    images, residuals (1, -2) and (0, 3): J = 0.5 (1 + 4 + 0 + 9) / 2 = 3.5. A mean over all entries, a
+    missing half, or a division by the entries per image gives 1.75, 7 or another value."""
+    x = np.array([[[[2.0], [0.0]]], [[[1.0], [4.0]]]])          # [2][1][2][1]
+    t = np.array([[[[1.0], [2.0]]], [[[1.0], [1.0]]]])
+    J, h = CO.loss_and_cotangent(x, t, loss_scale=8.0)
+    assert J == 3.5
+    np.testing.assert_array_equal(h, 8.0 * np.array([[[[1.0], [-2.0]]], [[[0.0], [3.0]]]]) / 2.0)
+    # the cotangent is the gradient of J: central difference on one entry
+    eps = 1e-6
+    xp, xm = x.copy(), x.copy()
+    xp[1, 0, 1, 0] += eps
+    xm[1, 0, 1, 0] -= eps
+    fd = (CO.loss_and_cotangent(xp, t)[0] - CO.loss_and_cotangent(xm, t)[0]) / (2 * eps)
+    assert fd == pytest.approx(CO.loss_and_cotangent(x, t)[1][1, 0, 1, 0], rel=1e-8)

@@ -160,3 +160,20 @@ def test_frag_sgd_step_is_a_projected_descent_step():
     drop = ref["loss"] - after
     assert drop > 0 and abs(drop - lr * gnorm2) <= 0.05 * lr * gnorm2 + 1e-3 * lr
 
+
+
+def test_loss_and_cotangent_by_hand():
+    """J = 0.5 * (sum over every entry of (x_L - t)^2) / samples, h_L = scale (x_L - t) / samples: two
+    samples of length 2 with one channel, residuals (1, -2) and (0, 3): J = 0.5 * 14 / 2 = 3.5 (a mean over all
+    entries would give 1.75, a missing half 7)."""
+    x = np.array([[[2.0], [0.0]], [[1.0], [4.0]]])          # [2][2][1]
+    t = np.array([[[1.0], [2.0]], [[1.0], [1.0]]])
+    J, h = FO.loss_and_cotangent(x, t, loss_scale=0.5)
+    assert J == 3.5
+    np.testing.assert_array_equal(h, 0.5 * np.array([[[1.0], [-2.0]], [[0.0], [3.0]]]) / 2.0)
+    eps = 1e-6
+    xp, xm = x.copy(), x.copy()
+    xp[0, 1, 0] += eps
+    xm[0, 1, 0] -= eps
+    fd = (FO.loss_and_cotangent(xp, t)[0] - FO.loss_and_cotangent(xm, t)[0]) / (2 * eps)
+    assert fd == pytest.approx(FO.loss_and_cotangent(x, t)[1][0, 1, 0], rel=1e-8)

@@ -387,3 +387,37 @@ def test_adaptive_reseed_keeps_fp32_moonwalk_accurate_where_none_does_not():
     assert seeds == [4, 8, 12, 16, 20]
     assert O.max_layer_err(seeded["dW"], ref["dW"]) < 1e-3
     assert O.max_layer_err(plain["dW"], ref["dW"]) > 1e-1
+
+
+# ----------------------------------------------------------------------------- the error measure
+def test_normwise_relative_error_on_hand_computed_vectors():
+    """||a - ref|| / ||ref||, worked by hand. a = (3, 4), ref = (0, 5): a - ref = (3, -1), so
+    sqrt(10) / 5. Swapping the arguments divides by ||a|| = 5 too, so a second pair with different
+    norms tells the two apart: a = (1, 0), ref = (0, 2): sqrt(5) / 2 one way, sqrt(5) / 1 the other.
+    Dividing by the squared norm, or taking the max norm instead of the Frobenius norm, fails too."""
+    assert O.normwise_rel_err([3.0, 4.0], [0.0, 5.0]) == pytest.approx(np.sqrt(10.0) / 5.0, rel=1e-15)
+    assert O.normwise_rel_err([1.0, 0.0], [0.0, 2.0]) == pytest.approx(np.sqrt(5.0) / 2.0, rel=1e-15)
+    assert O.normwise_rel_err([0.0, 2.0], [1.0, 0.0]) == pytest.approx(np.sqrt(5.0), rel=1e-15)
+    # Frobenius over all entries of a matrix, not per row and not the spectral norm
+    a = np.array([[1.0, 2.0], [3.0, 4.0]])
+    ref = np.array([[1.0, 0.0], [0.0, 4.0]])
+    assert O.normwise_rel_err(a, ref) == pytest.approx(np.sqrt(4.0 + 9.0) / np.sqrt(17.0), rel=1e-15)
+    # scale invariance and exactness
+    assert O.normwise_rel_err(1e30 * a, 1e30 * ref) == pytest.approx(np.sqrt(13.0 / 17.0), rel=1e-12)
+    assert O.normwise_rel_err(ref, ref) == 0.0
+    # 0 / 0 is 0 (an all-zero gradient reproduced exactly); x / 0 is infinite
+    assert O.normwise_rel_err(np.zeros(3), np.zeros(3)) == 0.0
+    assert O.normwise_rel_err([0.0, 1e-3], np.zeros(2)) == np.inf
+    # float32 inputs are promoted before the difference is taken: 1 + 2^-24 is not lost
+    got = O.normwise_rel_err(np.array([1.0], dtype=np.float32), np.array([1.0 + 2.0 ** -30]))
+    assert got == pytest.approx(2.0 ** -30, rel=1e-6)
+
+
+def test_max_layer_error_picks_the_worst_tensor():
+    got = [np.array([1.0, 0.0]), np.array([[3.0, 4.0]]), np.array([2.0])]
+    ref = [np.array([1.0, 0.0]), np.array([[0.0, 5.0]]), np.array([1.0])]
+    # per layer: 0, sqrt(10)/5 = 0.632.., |2 - 1| / 1 = 1
+    assert O.max_layer_err(got, ref) == pytest.approx(1.0, rel=1e-15)
+    assert O.max_layer_err(got[:2], ref[:2]) == pytest.approx(np.sqrt(10.0) / 5.0, rel=1e-15)
+    # a global norm over all layers would give sqrt(10 + 1) / sqrt(1 + 25 + 1) = 0.638: not this
+    assert abs(O.max_layer_err(got, ref) - np.sqrt(11.0 / 27.0)) > 0.3

@@ -72,7 +72,10 @@ typedef struct {
                                inside the segment (masks, fragment index), reverse, Phase III. Masks,
                                fragments and their index exist for one segment only; costs one more forward
                                pass. Needs fuse = 1. 0 or >= n_layers: off.                               */
-  int32_t reserved;
+  int32_t debug_keep;       /* 0: nothing extra. 1: a debugging aid for moonwalk_debug_fetch: every layer's Phase-I
+                               pre-activations z_i, Phase-II cotangent at its output and Phase-III cotangent at
+                               its output are kept in buffers of their own (3 x 4 B d_i bytes per layer, itemised
+                               as bytes_debug). The results of the gradient calls do not change by a bit.   */
 } mw_config_t;
 
 /* Itemised device bytes held by a handle (closed forms are in the design notes). */
@@ -92,6 +95,7 @@ typedef struct {
   uint64_t sign_mismatches;     /* phase-III signs that differed from the stored masks (must be 0)    */
   int32_t  frag_overflow;       /* 1 if the last moonwalk_grad overflowed the fragment store          */
   int32_t  reserved;
+  uint64_t bytes_debug;         /* cfg.debug_keep: the kept z_i and cotangents                          */
 } mw_memstats_t;
 
 /*
@@ -181,6 +185,15 @@ int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out);
 #define MW_FETCH_H0            5  /* float[B d_0]              input cotangent (scaled by loss_scale); layer ignored */
 #define MW_FETCH_P             6  /* float[d_out d_in]         right inverse                         */
 #define MW_FETCH_CHECKPOINT    7  /* float[B d_i]              kept cotangent at the OUTPUT of layer i (error if not kept) */
+/* The next three need cfg.debug_keep = 1 (MW_ERR_INVALID_ARG otherwise):                                   */
+#define MW_FETCH_Z             8  /* float[B d_i]              z_i = x_{i-1} W_i^T + b_i as Phase I computed it (the mask
+                                                               bits are z_i > 0; Residual Impact section)              */
+#define MW_FETCH_H             9  /* float[B d_i]              Phase-II cotangent at the OUTPUT of layer i, scaled by
+                                                               loss_scale, before the activation slope is applied: the
+                                                               tensor whose erased entries are the layer's fragments
+                                                               (Fragmental Gradient Checkpointing section)             */
+#define MW_FETCH_H_FORWARD    10  /* float[B d_i]              Phase-III cotangent at the OUTPUT of layer i (Eq. h_i:
+                                                               the vijp of layer i applied to the cotangent below it)  */
 /* Synchronous copy of library state after the last step to host_dst (host, cap bytes).
    layer is 0-based. *n_bytes (host, may be NULL) receives the size. host_dst == NULL with
    cap == 0 is a size query (returns MW_OK); if cap is too small nothing is copied and
@@ -350,25 +363,6 @@ size_t mw_conv_weight_grad_work_floats(const mw_conv_shape_t* shape);
 int mw_conv_weight_grad(const mw_conv_shape_t* shape, const float* x, const float* ctz, float scale, float* dw, float* db,
                         float* work, void* hip_stream);
 
-/* Measurement aid: run the gradient drivers with only ONE class of kernel launches enabled, so
-   that a caller can time that class alone between two events on its stream (the launches then run
-   back to back over the handle's real buffers, layer after layer, with the real shapes and cold
-   weights; the numbers they produce are meaningless). Classes: the Phase-I forward GEMM, the
-   Phase-II reverse GEMM, the Phase-III layer kernel alone (recompute + vijp + epilogue), the
-   weight-gradient GEMM alone, every elementwise/integer kernel, and the Phase-III launches as the
-   step really issues them (layer i's kernel and layer i-1's weight gradient in one launch). */
-#define MW_KCLASS_FWD    0
-#define MW_KCLASS_REV    1
-#define MW_KCLASS_VIJP   2
-#define MW_KCLASS_DW     3
-#define MW_KCLASS_EW     4
-#define MW_KCLASS_PHASE3 5
-#define MW_KCLASS_COUNT  6
-/* kclass = -1 restores normal operation. Does not synchronise. */
-int moonwalk_profile_filter(mw_handle_t* h, int32_t kclass);
-/* Number of launches of the class made by the last moonwalk_grad / backprop_grad call. launches: host. */
-int moonwalk_profile_launches(const mw_handle_t* h, int32_t kclass, uint64_t* launches);
-
 /* Frees every device buffer through dev_free. NULL is allowed. Synchronises the device first. */
 void moonwalk_destroy(mw_handle_t* h);
 
@@ -440,20 +434,6 @@ int mw_colsum_wide(const float* a, int64_t rows, int32_t d, float scale, float* 
 int mw_loss_grad(const float* xL, const float* t, int64_t rows, int32_t d, float scale,
                  float* hL, float* loss, double* scratch, void* hip_stream);
 size_t mw_loss_scratch_doubles(void);
-
-/* Plain device-to-device copy kernel of n floats (bandwidth yardstick for the profiles). */
-int mw_copy_f32(const float* src, float* dst, int64_t n, void* hip_stream);
-
-/* Load-only model of a tiled NT product (measurement aid, computes nothing): one workgroup per
-   tile x tile output tile of an M x N product reads its two operand row panels, A[M][K] and
-   B[N][K] (device, row stride K, 16-byte aligned), the way the GEMM kernels do, and writes one
-   checksum per thread to sink (device, at least (M/tile)*(N/tile)*256 floats). Its run time gives
-   the rate at which the CUs can pull operand panels through their L1 caches, the bound of the
-   small-batch products. The kernel is launched `repeats` (>= 1) times back to back, so that a
-   caller timing the call is not bound by its own launch rate. tile is 16, 32 or 64; M and N must
-   be multiples of tile, K of 256. MW_ERR_INVALID_ARG otherwise. */
-int mw_probe_operand_stream(int32_t M, int32_t N, int32_t K, int32_t tile, const float* A, const float* B,
-                            float* sink, int32_t repeats, void* hip_stream);
 
 #ifdef __cplusplus
 }

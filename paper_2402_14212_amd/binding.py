@@ -13,6 +13,7 @@ GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 TILE_AUTO, TILE_128, TILE_64, TILE_32K4, TILE_32K8, TILE_64K2, TILE_128W8, TILE_64X128 = 0, 1, 2, 3, 4, 5, 6, 7
 PLAN_MOONWALK, PLAN_BACKPROP = 1, 2
 FETCH_MASK, FETCH_FRAG, FETCH_FRAG_OFFSETS, FETCH_FRAG_BASE, FETCH_H0, FETCH_P, FETCH_CHECKPOINT = range(1, 8)
+FETCH_Z, FETCH_H, FETCH_H_FORWARD = 8, 9, 10
 
 EXPORTED_SYMBOLS = [
     "moonwalk_setup", "moonwalk_refresh", "moonwalk_refresh_incremental", "moonwalk_sgd_step", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
@@ -51,7 +52,7 @@ class _Config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("reseed_interval", C.c_int32), ("loss_scale", C.c_float),
                 ("plan", C.c_int32), ("fuse", C.c_int32), ("frag_capacity_factor", C.c_double),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p),
-                ("segment_length", C.c_int32), ("reserved", C.c_int32)]
+                ("segment_length", C.c_int32), ("debug_keep", C.c_int32)]
 
 
 class _ConvLayer(C.Structure):
@@ -83,7 +84,8 @@ class _MemStats(C.Structure):
         "bytes_P", "bytes_masks", "bytes_fragments", "bytes_frag_index", "bytes_checkpoints",
         "bytes_mw_scratch", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak",
         "bytes_setup_peak", "frag_used", "sign_mismatches")] + [("frag_overflow", C.c_int32),
-                                                                 ("reserved", C.c_int32)]
+                                                                 ("reserved", C.c_int32),
+                                                                 ("bytes_debug", C.c_uint64)]
 
 
 _lib = None
@@ -196,7 +198,7 @@ class MoonwalkNet:
     def __init__(self, Ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, reseed_interval: int = 0, loss_scale: float = 1.0,
                  plan: int = PLAN_MOONWALK | PLAN_BACKPROP, fuse: bool = True,
-                 frag_capacity_factor: float = 1.0, segment_length: int = 0):
+                 frag_capacity_factor: float = 1.0, segment_length: int = 0, debug_keep: bool = False):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -234,7 +236,7 @@ class MoonwalkNet:
                 raise ValueError("W must be [d_out][d_in]")
             layers[i] = _Layer(w.shape[1], w.shape[0], _ptr(w), _ptr(_f32(b)) if b is not None else None, a)
         cfg = _Config(self.batch, int(reseed_interval), float(loss_scale), int(plan), 1 if fuse else 0,
-                      float(frag_capacity_factor), self._alloc_cb, self._free_cb, None, int(segment_length), 0)
+                      float(frag_capacity_factor), self._alloc_cb, self._free_cb, None, int(segment_length), 1 if debug_keep else 0)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()
@@ -373,6 +375,18 @@ class MoonwalkNet:
 
     def fetch_checkpoint(self, layer: int) -> np.ndarray:
         return self._fetch(layer, FETCH_CHECKPOINT, np.float32).reshape(self.batch, -1)
+
+    def fetch_z(self, layer: int) -> np.ndarray:
+        """Phase-I pre-activations of a layer (needs debug_keep)."""
+        return self._fetch(layer, FETCH_Z, np.float32).reshape(self.batch, -1)
+
+    def fetch_h(self, layer: int) -> np.ndarray:
+        """Phase-II cotangent at the output of a layer, scaled by loss_scale (needs debug_keep)."""
+        return self._fetch(layer, FETCH_H, np.float32).reshape(self.batch, -1)
+
+    def fetch_h_forward(self, layer: int) -> np.ndarray:
+        """Phase-III cotangent at the output of a layer, scaled by loss_scale (needs debug_keep)."""
+        return self._fetch(layer, FETCH_H_FORWARD, np.float32).reshape(self.batch, -1)
 
     def close(self):
         if getattr(self, "_handle", None) is not None and self._handle.value:

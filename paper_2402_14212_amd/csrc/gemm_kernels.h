@@ -102,14 +102,17 @@ struct EpiFwdAct {
   const float* bias;
   float alpha;
   uint32_t* mask32;
+  float* Z = nullptr;  // debugging aid: the pre-activations themselves, [M][N]; NULL (the normal case): not kept
   struct Dev {
-    __amdgpu_buffer_rsrc_t rx, rbias, rmask;
+    __amdgpu_buffer_rsrc_t rx, rbias, rmask, rz;
     float alpha;
-    bool bias;
-    __device__ __forceinline__ Dev(const EpiFwdAct& p, int M, int N) : alpha(p.alpha), bias(p.bias != nullptr) {
+    bool bias, keep_z;
+    __device__ __forceinline__ Dev(const EpiFwdAct& p, int M, int N)
+        : alpha(p.alpha), bias(p.bias != nullptr), keep_z(p.Z != nullptr) {
       rx = make_rsrc(p.X, extent_bytes(M, N, N));
       rbias = make_rsrc(p.bias, p.bias ? (uint32_t)N * 4u : 0u);
       rmask = make_rsrc(p.mask32, MASK ? (uint32_t)(((int64_t)M * N + 63) / 64) * 8u : 0u);
+      rz = make_rsrc(p.Z, p.Z ? extent_bytes(M, N, N) : 0u);
     }
     __device__ __forceinline__ void finish() const {}
     template <int CNT>
@@ -127,6 +130,7 @@ struct EpiFwdAct {
         if (bias) z += bv;
         bool bit = valid && (z > 0.f);
         buf_store_f32(rx, valid ? e * 4u : OOB, bit ? z : alpha * z);
+        if (keep_z) buf_store_f32(rz, valid ? e * 4u : OOB, z);  // uniform branch: nothing is issued normally
         if (MASK) {
           unsigned long long bal = __ballot(bit);
           uint32_t word = g ? (uint32_t)(bal >> 32) : (uint32_t)bal;
@@ -576,6 +580,12 @@ inline GemmTask<Cfg, LA, LB, VEC, Xf, Epi, COLSUM> make_gemm_task(int M, int N, 
                                                       ceil_div(M, Cfg::BM), ceil_div(N, Cfg::BN)};
 }
 
+// Row stride (floats) of the matrix an epilogue writes: its own ldc where it has one, else N (a dense output).
+template <class Epi>
+inline auto epi_row_stride(const Epi& e, int /*N*/, int) -> decltype((int64_t)e.ldc) { return (int64_t)e.ldc; }
+template <class Epi>
+inline int64_t epi_row_stride(const Epi&, int N, long) { return N > 0 ? N : 1; }
+
 template <class Cfg, int LA, int LB, class Xf, class Epi, bool COLSUM>
 inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb,
                               const Xf& xf, const Epi& epi, bool xf_vec_ok, float* colsum_out, float colsum_scale,
@@ -583,7 +593,7 @@ inline hipError_t launch_gemm(int M, int N, int K, const float* A, int64_t lda, 
   if (M <= 0 || N <= 0) return hipSuccess;
   const bool a_k = (LA == KCONTIG), b_k = (LB == KCONTIG);
   if (!extent_ok(a_k ? M : K, a_k ? K : M, lda) || !extent_ok(b_k ? N : K, b_k ? K : N, ldb) ||
-      !extent_ok(M, N, (int64_t)N > 0 ? N : 1))
+      !extent_ok(M, N, epi_row_stride(epi, N, 0)))
     return hipErrorInvalidValue;
   const bool vec = xf_vec_ok && operand_vec_ok(A, lda, a_k ? K : M) && operand_vec_ok(B, ldb, b_k ? K : N);
   if (vec) {

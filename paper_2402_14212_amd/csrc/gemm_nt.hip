@@ -10,13 +10,13 @@ hipError_t gemm_plain_nt(int tile, int M, int N, int K, float alpha, const float
 }
 
 hipError_t gemm_fwd_act(int tile, int M, int N, int K, const float* X, const float* W, const float* bias,
-                        float alpha, float* Xout, uint64_t* mask, hipStream_t stream) {
+                        float alpha, float* Xout, uint64_t* mask, hipStream_t stream, float* Zkeep) {
   if (mask) {
     if (N % 32 != 0) return hipErrorInvalidValue;
-    EpiFwdAct<true> epi{Xout, bias, alpha, reinterpret_cast<uint32_t*>(mask)};
+    EpiFwdAct<true> epi{Xout, bias, alpha, reinterpret_cast<uint32_t*>(mask), Zkeep};
     return dispatch_gemm<KCONTIG, KCONTIG, false>(tile, M, N, K, X, K, W, K, ANone{}, epi, true, nullptr, 0.f, stream);
   }
-  EpiFwdAct<false> epi{Xout, bias, alpha, nullptr};
+  EpiFwdAct<false> epi{Xout, bias, alpha, nullptr, Zkeep};
   return dispatch_gemm<KCONTIG, KCONTIG, false>(tile, M, N, K, X, K, W, K, ANone{}, epi, true, nullptr, 0.f, stream);
 }
 

@@ -3,6 +3,7 @@
 // Everything here is host code that enqueues kernels; the only synchronising calls are setup,
 // refresh, memory_stats, debug_fetch and destroy.
 #include "../../include/moonwalk.h"
+#include "../../include/moonwalk_bench.h"
 
 #include <cmath>
 #include <cstdio>
@@ -119,6 +120,9 @@ struct Layer {
   float* ckpt = nullptr;        // kept cotangent at this layer's OUTPUT (h_i), if any
   float* xck = nullptr;         // kept activation at this layer's OUTPUT (x_i): segment boundaries only
   float* act = nullptr;         // backprop: stored x_i
+  // cfg.debug_keep only: this layer's Phase-I pre-activations z_i, the Phase-II cotangent at its output
+  // (NULL where ckpt already holds it), and the Phase-III cotangent at its output
+  float *dbg_z = nullptr, *dbg_h = nullptr, *dbg_h3 = nullptr;
   size_t dW_off = 0, db_off = 0;
 };
 
@@ -128,6 +132,7 @@ struct mw_handle {
   std::vector<Layer> layers;
   int B = 0, L = 0, K = 0, fuse = 1, plan = 0;
   int S = 0;                        // segment length (0: the whole network is one run)
+  int debug_keep = 0;               // per-layer z, Phase-II and Phase-III cotangents kept for moonwalk_debug_fetch
   float* hseg[2] = {nullptr, nullptr};  // cotangents at segment boundaries, alternating
   float loss_scale = 1.f;
   double frag_factor = 1.0;
@@ -262,6 +267,7 @@ int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_
   if (!(cfg->loss_scale > 0.f) || !std::isfinite(cfg->loss_scale)) return MW_ERR_INVALID_ARG;
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
+  if (cfg->debug_keep != 0 && cfg->debug_keep != 1) return MW_ERR_INVALID_ARG;
   for (int i = 0; i < n_layers; ++i) {
     const mw_layer_t& l = layers[i];
     if (l.d_in <= 0 || l.d_out <= 0 || !l.W) return MW_ERR_INVALID_ARG;
@@ -300,6 +306,7 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
   h->K = cfg->reseed_interval;
   h->S = (cfg->segment_length > 0 && cfg->segment_length < n_layers) ? cfg->segment_length : 0;
   h->fuse = cfg->fuse ? 1 : 0;
+  h->debug_keep = cfg->debug_keep;
   h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
   h->loss_scale = cfg->loss_scale;
   h->frag_factor = cfg->frag_capacity_factor > 0.0 ? cfg->frag_capacity_factor : 1.0;
@@ -445,6 +452,12 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
          alloc_t(h, &h->ctz, nmax, &st.bytes_mw_scratch) &&
          alloc_t(h, &h->h0, B * (size_t)h->layers[0].d_in, &st.bytes_mw_scratch);
     if (!h->fuse) ok = ok && alloc_t(h, &h->zbuf, nmax, &st.bytes_mw_scratch);
+    if (h->debug_keep)
+      for (auto& l : h->layers) {
+        const size_t n = B * (size_t)l.d_out;
+        ok = ok && alloc_t(h, &l.dbg_z, n, &st.bytes_debug) && alloc_t(h, &l.dbg_h3, n, &st.bytes_debug);
+        if (!l.ckpt) ok = ok && alloc_t(h, &l.dbg_h, n, &st.bytes_debug);
+      }
     if (h->fuse) ok = ok && alloc_t(h, &h->xc, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->ctz2, nmax, &st.bytes_mw_scratch);
     if (h->S > 0) ok = ok && alloc_t(h, &h->hseg[0], nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->hseg[1], nmax, &st.bytes_mw_scratch);
     if (!ok) return fail(MW_ERR_OOM);
@@ -501,15 +514,16 @@ int forward_range(const Step& c, int lo, int hi, const float* xin, int mask_from
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_fill_u32(reinterpret_cast<uint32_t*>(l.mask + l.mask_words - 1), 0u, 2, s));
     if (h->fuse) {
       if (want_mask && l.d_out % 32 == 0) {
-        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, l.mask, s));
+        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, l.mask, s, l.dbg_z));
       } else {
-        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, nullptr, s));
+        MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_fwd_act(TILE_AUTO, B, l.d_out, l.d_in, xin, l.W, l.b, l.alpha, xout, nullptr, s, l.dbg_z));
         if (want_mask) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_mask_from_act(xout, (int64_t)B * l.d_out, l.mask, s));
       }
     } else {
-      MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
+      float* z = l.dbg_z ? l.dbg_z : h->zbuf;
+      MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, z, l.d_out,
                         l.b, s));
-      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(h->zbuf, nullptr, B, l.d_out, l.alpha, xout, want_mask ? l.mask : nullptr, s));
+      MW_LAUNCH(h, s, MW_KCLASS_EW, ew_bias_act_mask(z, nullptr, B, l.d_out, l.alpha, xout, want_mask ? l.mask : nullptr, s));
     }
     xin = xout;
   }
@@ -542,6 +556,10 @@ int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) 
   const int B = h->B;
   int32_t* overflow = reinterpret_cast<int32_t*>(h->status + 2);
   float* hbuf[2] = {h->ha, h->hb};
+  {
+    Layer& top = h->layers[hi - 1];  // debugging aid: the raw cotangent at the top of the run
+    if (top.dbg_h) MW_LAUNCH(h, s, MW_KCLASS_EW, ew_copy(h_top, top.dbg_h, (int64_t)B * top.d_out, s));
+  }
   if (h->fuse) {
     // The top layer's slope (and fragments) are applied by the elementwise kernels; every
     // reverse product then applies the slope of the layer below it in its own epilogue.
@@ -563,7 +581,7 @@ int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) 
         Layer& below = h->layers[i - 1];
         float* ctout = (ctcur == hbuf[0]) ? hbuf[1] : hbuf[0];
         const bool relu = below.alpha == 0.f;
-        RevArgs r{ctout, below.ckpt, below.mask, below.alpha, below.offsets, h->frag,
+        RevArgs r{ctout, below.ckpt ? below.ckpt : below.dbg_h, below.mask, below.alpha, below.offsets, h->frag,
                   relu ? h->frag_bases + below.relu_slot : nullptr, h->frag_capacity, overflow};
         MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_fused(TILE_AUTO, B, l.d_in, l.d_out, ctcur, l.W, r, s));
         ctcur = ctout;
@@ -580,6 +598,7 @@ int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) 
       float* hout;
       if (i == lo) hout = h_bottom;
       else if (h->layers[i - 1].ckpt) hout = h->layers[i - 1].ckpt;
+      else if (h->layers[i - 1].dbg_h) hout = h->layers[i - 1].dbg_h;
       else hout = (hcur == hbuf[0]) ? hbuf[1] : hbuf[0];
       MW_LAUNCH(h, s, MW_KCLASS_EW, ew_rev_scale(hcur, l.mask, n, l.alpha, h->ctz, s));
       MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, h->ctz, l.d_out, l.W, l.d_in, 0.f,
@@ -616,7 +635,7 @@ int phase3_range(const Step& c, int lo, int hi, const float* xin, const float* h
       if (i > lo && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
       float* xout = xrot[i % 3];
       float* ctz = crot[i & 1];
-      float* hout = hbuf[i & 1];
+      float* hout = l.dbg_h3 ? l.dbg_h3 : hbuf[i & 1];
       const bool relu = (l.alpha == 0.f);
       VijpArgs a{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
                  relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xout, hout, ctz, mismatches};
@@ -650,7 +669,7 @@ int phase3_range(const Step& c, int lo, int hi, const float* xin, const float* h
       Layer& l = h->layers[i];
       if (i > lo && h->layers[i - 1].ckpt) hin = h->layers[i - 1].ckpt;  // re-seed
       float* xout = xbuf[i & 1];
-      float* hout = hbuf[i & 1];
+      float* hout = l.dbg_h3 ? l.dbg_h3 : hbuf[i & 1];
       const bool relu = (l.alpha == 0.f);
       MW_LAUNCH(h, s, MW_KCLASS_FWD, gemm_plain(OP_NT, TILE_AUTO, B, l.d_out, l.d_in, 1.f, xin, l.d_in, l.W, l.d_in, 0.f, h->zbuf, l.d_out,
                         l.b, s));
@@ -965,6 +984,12 @@ int moonwalk_debug_fetch(mw_handle_t* h, int32_t layer, int32_t what, void* host
       src = l->P; bytes = (size_t)l->d_out * l->d_in * 4; break;
     case MW_FETCH_CHECKPOINT:
       src = l->ckpt; bytes = B * l->d_out * 4; break;
+    case MW_FETCH_Z:
+      src = l->dbg_z; bytes = B * l->d_out * 4; break;
+    case MW_FETCH_H:
+      src = h->debug_keep ? (l->ckpt ? l->ckpt : l->dbg_h) : nullptr; bytes = B * l->d_out * 4; break;
+    case MW_FETCH_H_FORWARD:
+      src = l->dbg_h3; bytes = B * l->d_out * 4; break;
     default:
       return MW_ERR_INVALID_ARG;
   }
@@ -1018,6 +1043,13 @@ int mw_gemm_f32(int32_t op, int32_t tile, int32_t M, int32_t N, int32_t K, float
   // leading dimensions must cover the fast index of each operand
   const int a_fast = (op == MW_GEMM_TN) ? M : K, b_fast = (op == MW_GEMM_NT) ? K : N;
   if (lda < a_fast || ldb < b_fast || ldc < N) return MW_ERR_INVALID_ARG;
+  // the kernels address every operand with 31-bit byte offsets, row strides included
+  auto too_large = [](int64_t n_outer, int64_t n_inner, int64_t ld) {
+    return n_outer > 0 && n_inner > 0 && ((n_outer - 1) * ld + n_inner) * 4 >= (int64_t)0x7FFFFFFF;
+  };
+  if (too_large(op == MW_GEMM_TN ? K : M, a_fast, lda) || too_large(op == MW_GEMM_NT ? N : K, b_fast, ldb) ||
+      too_large(M, N, ldc))
+    return MW_ERR_INVALID_ARG;
   MW_HIP(gemm_plain(op, tile, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, nullptr, static_cast<hipStream_t>(hip_stream)));
   return MW_OK;
 }

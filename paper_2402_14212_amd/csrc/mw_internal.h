@@ -35,9 +35,9 @@ hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const 
                       hipStream_t stream);
 
 // Xout[M][N] = act(X[M][K] W[N][K]^T + bias); mask (may be NULL) receives the packed signs and
-// then requires N % 32 == 0.
+// then requires N % 32 == 0. Zkeep (may be NULL; a debugging aid) receives the pre-activations.
 hipError_t gemm_fwd_act(int tile, int M, int N, int K, const float* X, const float* W, const float* bias,
-                        float alpha, float* Xout, uint64_t* mask, hipStream_t stream);
+                        float alpha, float* Xout, uint64_t* mask, hipStream_t stream, float* Zkeep = nullptr);
 
 // Phase-II product with the NEXT step's slope folded into the epilogue:
 //   h = CTin[M][K] W[K][N];  CT = h .* slope(mask, alpha)  (mask/alpha of the layer whose OUTPUT h is);

@@ -8,6 +8,9 @@ Protocol
   piece), per tensor, normwise relative error <= GRAD_TOL.
 * integers (packed words, erased offsets, fragment bases and counts): bit-exact against the
   oracle's own packing/compaction applied to the GPU's masks.
+* with the library's own pre-activations and Phase-II cotangents kept (debug_keep): the mask words
+  are the oracle's packing of (z_gpu > 0) and the fragment store is the oracle's compaction of
+  h_gpu, both bit for bit, inside the running network (check_kept_tensors).
 """
 import numpy as np
 
@@ -91,3 +94,35 @@ def check_moonwalk(net, wl, res, tol=GRAD_TOL, check_h0=True):
             want = O.compact_fragments(ref["h"][i + 1], masks[i])
             assert O.normwise_rel_err(got, want) <= 1e-4
     return {"max_dW_err": eW, "max_db_err": eb, "guard_band": in_band}
+
+
+def check_kept_tensors(net, wl, ref, masks, h_tol=1e-4, hf_tol=1e-3):
+    """A network built with debug_keep: the GPU's own z, Phase-II h and Phase-III h of every layer.
+
+    Integer and copy steps, bit-exact against the oracle's definitions applied to the GPU's OWN tensors:
+    mask words = pack(z_gpu > 0); for a ReLU layer the stored fragments = compaction of h_gpu at the
+    erased entries; for a layer with a re-seed checkpoint the checkpoint is h_gpu itself. Floating
+    point, against the mask-forced fp64 oracle: z (given the GPU's masks below), Phase-II h, and the
+    Phase-III h, whose error is the one that grows between re-seeds.
+    Returns the per-layer normwise errors of the Phase-III cotangent.
+    """
+    xs, zs, _ = O.forward(wl.W, wl.b, wl.alphas, wl.x, forced_masks=masks)
+    hf_err = []
+    for i in range(wl.depth):
+        n = wl.batch * wl.widths[i + 1]
+        z = net.fetch_z(i)
+        np.testing.assert_array_equal(O.pack_mask(O.sign_mask(z)), net.fetch_mask(i))
+        assert O.normwise_rel_err(z, zs[i]) <= 2e-5, f"layer {i}: pre-activations"
+        h = net.fetch_h(i)
+        assert h.size == n
+        assert O.normwise_rel_err(h / wl.loss_scale, ref["h"][i + 1]) <= h_tol, f"layer {i}: Phase-II cotangent"
+        if wl.alphas[i] == 0.0:
+            np.testing.assert_array_equal(net.fetch_fragments(i), O.compact_fragments(h, masks[i]))
+        hf = net.fetch_h_forward(i)
+        if wl.alphas[i] == 0.0:
+            # restored entries are copies of the Phase-II cotangent
+            erased = ~masks[i]
+            np.testing.assert_array_equal(hf[erased], h[erased])
+        hf_err.append(O.normwise_rel_err(hf / wl.loss_scale, ref["h"][i + 1]))
+    assert max(hf_err) <= hf_tol, f"Phase-III cotangent errors per layer: {hf_err}"
+    return hf_err

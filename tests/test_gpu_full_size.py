@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from workloads import make_config
+from workloads import make_config, workload_to_host
 
 from parity import check_moonwalk, check_gradients, gpu_masks
 
@@ -41,4 +41,30 @@ def test_large_layer_shapes_at_reduced_depth(mw, name, depth):
     torch.cuda.synchronize()
     info = check_moonwalk(net, wl, res)
     print(name, info, flush=True)
+    net.close()
+
+
+@pytest.mark.parametrize("name,depth", [("relu_frag", 48), ("narrowing", 32), ("very_deep", 16)])
+def test_large_configurations_at_the_stated_depth(mw, name, depth):
+    """relu_frag (48 ReLU layers of 2048, batch 512: a fragment store with 48 layer bases) and narrowing
+    (32 layers, 4096 -> 512, batch 512, every tile choice of the taper) whole; very_deep's layers (4096 x 4096,
+    batch 1024, loss scale 2^64, a re-seed every 4 layers) at depth 16, three re-seeds taken. The weights are
+    drawn on the device (the host QR of these sizes takes minutes) and the same fp32 arrays go to the oracle.
+    Everything check_moonwalk checks: masks, every dW and db, h_0, fragment index, bases and values."""
+    print(f"full depth: {name} L={depth}", flush=True)
+    dev = make_config(name, depth=depth, device="cuda:0")
+    net = mw.MoonwalkNet.from_workload(dev, plan=1)
+    wl = workload_to_host(dev)
+    del dev
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    info = check_moonwalk(net, wl, res)
+    print(name, depth, info, flush=True)
+    stats = net.memory_stats()
+    kept = [j for j in range(1, depth) if wl.reseed_interval and j % wl.reseed_interval == 0]
+    assert stats["bytes_checkpoints"] == 4 * wl.batch * sum(wl.widths[j] for j in kept)
+    if name == "very_deep":
+        assert len(kept) == 3
+        # the scaled cotangent really is far outside what fp32 would hold unscaled at full depth
+        assert float(np.abs(net.fetch_h0()).max()) > 2.0 ** 40
     net.close()

@@ -7,11 +7,11 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "moonwalk.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("moonwalk.h", "moonwalk_bench.h")]
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b((?:moonwalk|backprop|mw)_[a-z0-9_]+)\s*\(", text)
     return sorted(set(n for n in names if not n.endswith("_t")))
@@ -178,3 +178,18 @@ def test_conv_null_handles_and_shapes_are_rejected(lib):
     assert lib.mw_conv_weight_grad_work_floats(None) == 0
     empty = _ConvShape(0, 16, 16, 32, 32, 3, 3, 2, 1, 1)
     assert lib.mw_conv_weight_grad_work_floats(C.byref(empty)) == 0
+
+
+def test_gemm_rejects_operands_whose_strided_extent_passes_2_gib(lib):
+    """31-bit byte offsets: (rows - 1) * row stride + columns must stay below 2^31 bytes for A, B and C
+    alike; a C with few columns but a long row stride used to pass the check and wrap."""
+    lib.mw_gemm_f32.argtypes = [C.c_int32] * 5 + [C.c_float, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float,
+                                                  C.c_void_p, C.c_int32, C.c_void_p]
+    fake = 0x1000  # never dereferenced: validation fails first
+    big = 1 << 20
+    # C: 1024 rows with a row stride of 2^20 floats = 4 GiB
+    assert lib.mw_gemm_f32(0, 0, 1024, 64, 64, 1.0, fake, 64, fake, 64, 0.0, fake, big, None) == -1
+    # A and B likewise
+    assert lib.mw_gemm_f32(0, 0, 1024, 64, 64, 1.0, fake, big, fake, 64, 0.0, fake, 64, None) == -1
+    assert lib.mw_gemm_f32(0, 0, 64, 1024, 64, 1.0, fake, 64, fake, big, 0.0, fake, 1024, None) == -1
+    assert lib.mw_gemm_f32(2, 0, 64, 64, 1024, 1.0, fake, big, fake, 64, 0.0, fake, 64, None) == -1

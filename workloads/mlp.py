@@ -94,9 +94,9 @@ def make_mlp_on_device(widths: Sequence[int], batch: int, alpha, seed: int = 0, 
     """The same recipe drawn with torch on `device` (fp64 QR on the GPU, then rounded to fp32).
 
     For the large configurations, whose hundreds of 4096 x 4096 QR factorisations would take the
-    host most of an hour. Same distribution, different random stream than make_mlp: use it for
-    throughput and memory runs; parity runs feed the oracle from make_mlp. W, b, x, t are torch
-    tensors on the device.
+    host most of an hour. Same distribution, different random stream than make_mlp. W, b, x, t are
+    torch tensors on the device; workload_to_host copies them for the CPU oracle, so that both sides
+    consume the same fp32 values (the full-depth parity runs of the large configurations do that).
     """
     import torch
     widths = [int(w) for w in widths]
@@ -129,6 +129,16 @@ def make_mlp_on_device(widths: Sequence[int], batch: int, alpha, seed: int = 0, 
     return MLPWorkload(widths=widths, batch=int(batch), alphas=alphas, W=Ws, b=bs, x=x, t=t,
                        reseed_interval=int(reseed_interval), loss_scale=float(loss_scale), seed=int(seed),
                        name=name, factors=None)
+
+
+def workload_to_host(wl: MLPWorkload) -> MLPWorkload:
+    """The same workload with every tensor as a numpy array on the host (for the CPU oracle): the values
+    a device-drawn workload holds, bit for bit."""
+    def host(a):
+        return a if isinstance(a, np.ndarray) else a.detach().cpu().numpy()
+    return MLPWorkload(widths=list(wl.widths), batch=wl.batch, alphas=list(wl.alphas), W=[host(w) for w in wl.W],
+                       b=[host(b) for b in wl.b], x=host(wl.x), t=host(wl.t), reseed_interval=wl.reseed_interval,
+                       loss_scale=wl.loss_scale, seed=wl.seed, name=wl.name, factors=None)
 
 
 def _narrowing_widths() -> List[int]:

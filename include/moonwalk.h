@@ -33,6 +33,7 @@ extern "C" {
 #define MW_ERR_HIP              (-5)  /* a HIP call failed; text available from moonwalk_strerror      */
 #define MW_ERR_SIGN_MISMATCH    (-6)  /* phase-III recomputed signs differ from the phase-I masks      */
 #define MW_ERR_NOT_PLANNED      (-7)  /* entry point called on a handle planned without it             */
+#define MW_ERR_TOO_LARGE        (-8)  /* input beyond the fixed scratch of an entry point that allocates nothing */
 
 typedef struct mw_handle mw_handle_t;   /* opaque; owned by the library */
 
@@ -427,6 +428,20 @@ int mw_colsum(const float* a, int64_t rows, int32_t d, float scale, float* out, 
    floats. Fixed summation order, another one than mw_colsum's. */
 size_t mw_colsum_work_floats(int32_t d);
 int mw_colsum_wide(const float* a, int64_t rows, int32_t d, float scale, float* out, float* work, void* hip_stream);
+
+/* mw_colsum_wide for callers that cannot allocate and have no workspace to pass: code under HIP graph
+   capture, tight serving loops, harnesses that forbid hipMalloc. Same result as mw_colsum_wide with a
+   256-byte aligned workspace, bit for bit (same kernels, same row ranges, same summation order). The
+   row-range partial sums go to a fixed array inside the library's code object, mw_colsum_noalloc_max_floats()
+   floats (4 MiB) on every GPU the library is loaded on, held until the process ends; the call makes no
+   hipMalloc / hipFree and calls no allocating routine. It needs (number of row ranges) * d floats of
+   that array: always enough for d <= 4096, and for any d up to the array's size when rows is small
+   enough for one range; beyond it MW_ERR_TOO_LARGE is returned and nothing is launched. All calls
+   on one GPU share the array, which keeps the last call's contents (nothing needs clearing: every
+   slot a call reads it has written first): calls that overlap on one GPU, from different streams or
+   threads, race; order them. Asynchronous on hip_stream like the others. */
+size_t mw_colsum_noalloc_max_floats(void);
+int mw_colsum_wide_noalloc(const float* a, int64_t rows, int32_t d, float scale, float* out, void* hip_stream);
 
 /* Loss step: h_L = scale (x_L - t) / rows and *loss = 0.5 ||x_L - t||_F^2 / rows (fixed-order
    reduction; partial sums in double). loss may be NULL. scratch: device doubles,

@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
     "moonwalk_profile_filter", "moonwalk_profile_launches",
     "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
-    "mw_vijp_epilogue", "mw_colsum", "mw_colsum_wide", "mw_colsum_work_floats", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
+    "mw_vijp_epilogue", "mw_colsum", "mw_colsum_wide", "mw_colsum_work_floats", "mw_colsum_wide_noalloc", "mw_colsum_noalloc_max_floats", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
     "mw_probe_operand_stream",
     "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
     "moonwalk_conv_grad_layout", "moonwalk_conv_memory_stats", "moonwalk_conv_fetch", "moonwalk_conv_destroy",
@@ -35,8 +35,8 @@ class MoonwalkError(RuntimeError):
         self.code = code
 
 
-ERR_INVALID_ARG, ERR_NOT_SUBMERSIVE, ERR_OOM, ERR_FRAG_OVERFLOW, ERR_HIP, ERR_SIGN_MISMATCH, ERR_NOT_PLANNED = \
-    -1, -2, -3, -4, -5, -6, -7
+ERR_INVALID_ARG, ERR_NOT_SUBMERSIVE, ERR_OOM, ERR_FRAG_OVERFLOW, ERR_HIP, ERR_SIGN_MISMATCH, ERR_NOT_PLANNED, ERR_TOO_LARGE = \
+    -1, -2, -3, -4, -5, -6, -7, -8
 
 
 class _Layer(C.Structure):
@@ -130,6 +130,9 @@ def load_library() -> C.CDLL:
     lib.mw_colsum_wide.argtypes = [vp, i64, i32, f32, vp, vp, vp]
     lib.mw_colsum_work_floats.argtypes = [i32]
     lib.mw_colsum_work_floats.restype = C.c_size_t
+    lib.mw_colsum_wide_noalloc.argtypes = [vp, i64, i32, f32, vp, vp]
+    lib.mw_colsum_noalloc_max_floats.argtypes = []
+    lib.mw_colsum_noalloc_max_floats.restype = sz
     lib.mw_loss_grad.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp]
     lib.mw_loss_scratch_doubles.argtypes = []
     lib.mw_loss_scratch_doubles.restype = sz
@@ -742,6 +745,18 @@ def colsum_wide(a: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
     out = torch.empty(d, dtype=torch.float32, device=a.device)
     work = torch.empty(int(lib.mw_colsum_work_floats(d)), dtype=torch.float32, device=a.device)
     _check(lib.mw_colsum_wide(_ptr(_f32(a)), rows, d, scale, _ptr(out), _ptr(work), _stream()))
+    return out
+
+
+def colsum_wide_noalloc(a: torch.Tensor, out: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
+    """mw_colsum_wide_noalloc: the same sums into the caller's `out`, the partial sums in the library's own
+    fixed array; neither the library nor this wrapper allocates. Raises MoonwalkError (ERR_TOO_LARGE) when
+    the partial sums would not fit."""
+    _require_gpu()
+    rows, d = a.shape
+    if out.numel() != d:
+        raise ValueError("out must have one element per column")
+    _check(load_library().mw_colsum_wide_noalloc(_ptr(_f32(a)), rows, d, scale, _ptr(_f32(out)), _stream()))
     return out
 
 

@@ -6,6 +6,8 @@
 // (256 B per wavefront per access) and the integer work is a ballot or a popcount per word.
 #include "mw_internal.h"
 
+#include <mutex>
+
 namespace mw {
 
 namespace {
@@ -1059,6 +1061,56 @@ hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, floa
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return ew_reduce_slices(scratch, slices, d, scale, beta, out, stream);
+}
+
+// ---------------------------------------------------------------- column sums without a workspace argument
+// The row-range partial sums of ew_colsum_wide in an array that belongs to the library's code object
+// instead of a buffer somebody allocated: for callers that cannot allocate. Every GPU holds its own
+// copy of the array from the moment the library is loaded there until the process ends; its address on
+// a GPU is looked up once, with that GPU current, and kept. In host code the array's name is only a
+// handle for that lookup: kernels, and anything else that touches the memory, get the looked-up pointer.
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)1 << 20;  // 4 MiB per GPU
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static float* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];
+static std::mutex g_scratch_lock;
+
+static hipError_t static_scratch_ptr(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+size_t ew_colsum_static_floats() { return STATIC_SCRATCH_FLOATS; }
+
+hipError_t ew_colsum_wide_static(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream,
+                                 bool* too_large) {
+  *too_large = false;
+  if (d <= 0) return hipSuccess;
+  // the partial sums take slices * d floats; the array is 256-byte aligned, so the choice of kernel (and with
+  // it the slice count and the summation order) is the one ew_colsum_wide makes for an aligned workspace
+  const bool vec = d % 4 == 0 && al16(a);
+  if ((size_t)ew_colsum_slices(rows, d, vec) * (size_t)d > STATIC_SCRATCH_FLOATS) {
+    *too_large = true;
+    return hipSuccess;
+  }
+  float* work = nullptr;
+  hipError_t e = static_scratch_ptr(&work);
+  if (e != hipSuccess) return e;
+  // every slot the reduction reads is written by this call's first kernel: nothing has to start at zero
+  return ew_colsum_wide(a, rows, d, scale, 0.f, out, work, stream);
 }
 
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream) {

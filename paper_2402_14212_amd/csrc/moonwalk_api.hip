@@ -1030,6 +1030,7 @@ const char* moonwalk_strerror(int code) {
     case MW_ERR_HIP: return g_hip_error_text.c_str();
     case MW_ERR_SIGN_MISMATCH: return "recomputed activation signs differ from the stored masks";
     case MW_ERR_NOT_PLANNED: return "handle was planned without this entry point";
+    case MW_ERR_TOO_LARGE: return "input larger than the fixed scratch array of an entry point that allocates nothing";
     default: return "unknown error code";
   }
 }
@@ -1102,6 +1103,16 @@ size_t mw_colsum_work_floats(int32_t d) { return d > 0 ? (size_t)COLSUM_MAX_SLIC
 int mw_colsum_wide(const float* a, int64_t rows, int32_t d, float scale, float* out, float* work, void* hip_stream) {
   if (rows < 0 || d <= 0 || !out || !work || (rows > 0 && !a)) return MW_ERR_INVALID_ARG;
   MW_HIP(ew_colsum_wide(a, rows, d, scale, 0.f, out, work, static_cast<hipStream_t>(hip_stream)));
+  return MW_OK;
+}
+
+size_t mw_colsum_noalloc_max_floats(void) { return ew_colsum_static_floats(); }
+
+int mw_colsum_wide_noalloc(const float* a, int64_t rows, int32_t d, float scale, float* out, void* hip_stream) {
+  if (rows < 0 || d <= 0 || !out || (rows > 0 && !a)) return MW_ERR_INVALID_ARG;
+  bool too_large = false;
+  MW_HIP(ew_colsum_wide_static(a, rows, d, scale, out, static_cast<hipStream_t>(hip_stream), &too_large));
+  if (too_large) return MW_ERR_TOO_LARGE;
   return MW_OK;
 }
 

@@ -147,6 +147,11 @@ constexpr int COLSUM_MAX_SLICES = 2048;
 int ew_colsum_slices(int64_t rows, int d, bool vec);  // vec: the 128-bit kernel (d % 4 == 0, 16-byte aligned operands)
 hipError_t ew_colsum_wide(const float* a, int64_t rows, int d, float scale, float beta, float* out, float* scratch,
                           hipStream_t stream);
+// ew_colsum_wide (beta = 0) with the partial sums in an array of the library's own code object (ew_colsum_static_floats()
+// floats per GPU) instead of a workspace: allocates nothing. *too_large: the partial sums would not fit, nothing was launched.
+size_t ew_colsum_static_floats();
+hipError_t ew_colsum_wide_static(const float* a, int64_t rows, int d, float scale, float* out, hipStream_t stream,
+                                 bool* too_large);
 // out[i] = scale * (sum over the slices of part[.][i], in an order fixed by slices and n) + beta * out[i]; part is [slices][n]
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream);
 constexpr int LOSS_BLOCKS = 2048;  // most workgroups (and scratch doubles) the loss reduction uses

@@ -46,6 +46,10 @@ def parse():
                          "layers before the chain needs it; backprop then computes it too), or only what the first vijp reads")
     ap.add_argument("--segment", type=int, default=0,
                     help="segment length S of Moonwalk with rematerialisation (0 = off: the metric's configuration)")
+    ap.add_argument("--group", type=int, default=0,
+                    help="Phase III side by side: most stretches between re-seed points per launch (1: off, 0: chosen by the library)")
+    ap.add_argument("--overlap", type=int, default=1, choices=[0, 1],
+                    help="1: the grouped Phase-III sweeps run on the library's second stream while Phase II goes on")
     ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
     ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
     ap.add_argument("--gen", choices=["numpy", "torch"], default="numpy",
@@ -251,7 +255,8 @@ def main():
 
     # --- Moonwalk handle only (so that its peak memory is its own)
     t0 = time.perf_counter()
-    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused, segment_length=args.segment)
+    net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused, segment_length=args.segment,
+                                       phase3_parallel_segments=args.group, phase3_overlap=bool(args.overlap))
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
     grads = net.new_grads()
@@ -355,7 +360,9 @@ def main():
         "config": {"workload": f"{wl.name}: depth {L}, widths {widths[0]}->{widths[-1]}, batch {B}, "
                                f"alpha {wl.alphas[0]}, reseed K={wl.reseed_interval}, loss_scale {wl.loss_scale:g}, "
                                f"{'unfused' if args.unfused else 'fused'} kernels"
-                               + (f", segments of {args.segment} layers" if args.segment else "")},
+                               + (f", segments of {args.segment} layers" if args.segment else "")
+                               + (f", Phase III of up to {args.group if args.group else 'auto'} stretches side by side"
+                                  f"{' on a second stream under Phase II' if args.overlap else ''}" if args.group != 1 else "")},
         "tflops": flops_mw / (ms_mw * 1e-3) / 1e12,
         "flop_per_step": flops_mw,
         "mfma_frac_whole_step": flops_mw / (ms_mw * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS,

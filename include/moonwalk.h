@@ -77,6 +77,22 @@ typedef struct {
                                pre-activations z_i, Phase-II cotangent at its output and Phase-III cotangent at
                                its output are kept in buffers of their own (3 x 4 B d_i bytes per layer, itemised
                                as bytes_debug). The results of the gradient calls do not change by a bit.   */
+  int32_t phase3_parallel_segments; /* Phase III side by side. The re-seed points (reseed_interval) cut the network into
+                               stretches whose forward sweeps do not depend on each other once the activation at a
+                               stretch's first layer is kept as well (Table 1, "Moonwalk + checkpoint": Phase I
+                               writes it there on its way, B d_i floats per re-seed point). Up to this many
+                               consecutive stretches of one shape are swept in ONE launch per layer position,
+                               which fills the chip when one small-batch layer cannot. 1: off (one layer per
+                               launch, nothing extra kept). 0: chosen by the library (enough stretches to give
+                               every CU a 64 x 64 tile; off where one layer fills the chip already, or with fewer
+                               than two stretches). 2..16: at most that many. Each stretch in flight has its own 7
+                               rotating buffers of B max d floats. Needs fuse = 1 and segment_length = 0 (else
+                               ignored). Gradients, masks and h_0 are the same bit for bit whatever the value.     */
+  int32_t phase3_overlap;   /* 1: the grouped sweeps of phase3_parallel_segments are issued on a second stream of
+                               the library (default priority), each as soon as Phase II has passed its lowest
+                               re-seed point, and share the machine with the rest of Phase II; the caller's stream
+                               waits for them at the end of the call, so the call still looks asynchronous on
+                               hip_stream alone. 0: everything on hip_stream, Phase III after Phase II.           */
 } mw_config_t;
 
 /* Itemised device bytes held by a handle (closed forms are in the design notes). */

@@ -52,7 +52,8 @@ class _Config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("reseed_interval", C.c_int32), ("loss_scale", C.c_float),
                 ("plan", C.c_int32), ("fuse", C.c_int32), ("frag_capacity_factor", C.c_double),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p),
-                ("segment_length", C.c_int32), ("debug_keep", C.c_int32)]
+                ("segment_length", C.c_int32), ("debug_keep", C.c_int32),
+                ("phase3_parallel_segments", C.c_int32), ("phase3_overlap", C.c_int32)]
 
 
 class _ConvLayer(C.Structure):
@@ -201,7 +202,8 @@ class MoonwalkNet:
     def __init__(self, Ws: Sequence[torch.Tensor], bs: Sequence[Optional[torch.Tensor]], alphas: Sequence[float],
                  batch: int, reseed_interval: int = 0, loss_scale: float = 1.0,
                  plan: int = PLAN_MOONWALK | PLAN_BACKPROP, fuse: bool = True,
-                 frag_capacity_factor: float = 1.0, segment_length: int = 0, debug_keep: bool = False):
+                 frag_capacity_factor: float = 1.0, segment_length: int = 0, debug_keep: bool = False,
+                 phase3_parallel_segments: int = 0, phase3_overlap: bool = False):
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -239,7 +241,8 @@ class MoonwalkNet:
                 raise ValueError("W must be [d_out][d_in]")
             layers[i] = _Layer(w.shape[1], w.shape[0], _ptr(w), _ptr(_f32(b)) if b is not None else None, a)
         cfg = _Config(self.batch, int(reseed_interval), float(loss_scale), int(plan), 1 if fuse else 0,
-                      float(frag_capacity_factor), self._alloc_cb, self._free_cb, None, int(segment_length), 1 if debug_keep else 0)
+                      float(frag_capacity_factor), self._alloc_cb, self._free_cb, None, int(segment_length), 1 if debug_keep else 0,
+                      int(phase3_parallel_segments), 1 if phase3_overlap else 0)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()

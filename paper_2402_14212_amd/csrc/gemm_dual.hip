@@ -79,6 +79,90 @@ hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs
   return hipSuccess;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Phase III of several stretches side by side (GroupedVijpTask / GroupedDwTask).
+
+static_assert(MAX_GROUP == MAX_PHASE3_GROUP, "the task's set table and the driver's argument arrays");
+
+bool phase3_group_ok(int M, int N, int K) {
+  // layers whose Phase-I product takes the 32 x 32 tile with K split over four wavefronts (outputs too small to
+  // fill the chip with larger tiles); pairs of whole 128-wide K tiles, so that the split falls on the same
+  // boundaries and every set has an even number of 32-wide slices
+  return M > 0 && N > 0 && K > 0 && K % 256 == 0 && N % 32 == 0 && pick_tile(M, N, K) == TILE_32K4 && extent_ok(M, K, K) &&
+         extent_ok(N, K, K) && extent_ok(M, N, N);
+}
+
+template <bool RELU>
+static GroupedVijpTask<Tile64, RELU, 4> make_grouped_vijp(int n, const VijpArgs* v, int M, int N, int K) {
+  GroupedVijpTask<Tile64, RELU, 4> t{};
+  t.n_sets = n;
+  t.M = M; t.N = N; t.K = K;
+  t.alpha = v[0].alpha;
+  t.inv_alpha = v[0].alpha > 0.f ? 1.0f / v[0].alpha : 0.f;
+  t.frag = v[0].frag;
+  t.frag_capacity = v[0].frag_capacity;
+  t.mismatches = v[0].mismatches;
+  t.tiles_m = ceil_div(M, Tile64::BM);
+  t.tiles_n = ceil_div(N, Tile64::BN);
+  for (int g = 0; g < n; ++g)
+    t.set[g] = VijpSet{v[g].X, v[g].W, v[g].Hin, v[g].P, v[g].bias, v[g].mask, v[g].offsets, v[g].frag_base,
+                       v[g].Xout, v[g].Hout, v[g].CTZ};
+  return t;
+}
+
+template <class CfgD>
+static GroupedDwTask<CfgD> make_grouped_dw(int n, const DwArgs* d) {
+  GroupedDwTask<CfgD> t{};
+  t.n_sets = n;
+  t.M = d[0].M; t.N = d[0].N; t.K = d[0].K;
+  t.scale = d[0].scale;
+  t.beta = d[0].beta;
+  t.tiles_m = ceil_div(t.M, CfgD::BM);
+  t.tiles_n = ceil_div(t.N, CfgD::BN);
+  for (int g = 0; g < n; ++g) t.set[g] = DwSet{d[g].CTZ, d[g].X, d[g].dW, d[g].db};
+  return t;
+}
+
+template <bool RELU, class CfgD, int MIN_WG>
+static hipError_t group_t(int n_v, const VijpArgs* v, int M, int N, int K, int n_d, const DwArgs* d, hipStream_t stream) {
+  static_assert(CfgD::NT == Tile64::NT, "both tasks run in workgroups of the same size");
+  // MIN_WG workgroups of the layer task must fit a CU side by side (one's loads under the others' matrix
+  // work): the register count is held to that share of a SIMD's file. Two is what measures best: the layer task
+  // takes 182 registers by itself; squeezed into a third of the file (168) it spills inside its main loop
+  if (n_v > 0 && n_d > 0)
+    return launch_task_pair_resident<Tile64::NT, MIN_WG>(make_grouped_vijp<RELU>(n_v, v, M, N, K),
+                                                         make_grouped_dw<CfgD>(n_d, d), stream);
+  if (n_v > 0) return launch_task_resident<Tile64::NT, MIN_WG>(make_grouped_vijp<RELU>(n_v, v, M, N, K), stream);
+  return launch_task<CfgD::NT>(make_grouped_dw<CfgD>(n_d, d), stream);
+}
+
+hipError_t gemm_phase3_group(int n_v, const VijpArgs* v, int M, int N, int K, int n_d, const DwArgs* d, hipStream_t stream) {
+  if (n_v < 0 || n_d < 0 || n_v > MAX_GROUP || n_d > MAX_GROUP || (n_v == 0 && n_d == 0)) return hipErrorInvalidValue;
+  if (n_v > 0) {
+    if (!phase3_group_ok(M, N, K)) return hipErrorInvalidValue;
+    for (int g = 0; g < n_v; ++g)
+      if (!vijp_vec_ok(K, v[g].X, v[g].W, v[g].Hin, v[g].P) || v[g].alpha != v[0].alpha) return hipErrorInvalidValue;
+  }
+  int tile_d = TILE_64;
+  if (n_d > 0) {
+    // the tile the weight gradient takes next to a layer kernel of the 32 x 32 K-split tile (the same product
+    // launched with one layer gets the same tile, hence the same bits)
+    tile_d = pick_tile_dw(d[0].M, d[0].N, d[0].K, TILE_32K4, true);
+    if (!extent_ok(d[0].K, d[0].M, d[0].M) || !extent_ok(d[0].K, d[0].N, d[0].N) || !extent_ok(d[0].M, d[0].N, d[0].N))
+      return hipErrorInvalidValue;
+    for (int g = 0; g < n_d; ++g) {
+      if (d[g].M != d[0].M || d[g].N != d[0].N || d[g].K != d[0].K || d[g].scale != d[0].scale || d[g].beta != d[0].beta)
+        return hipErrorInvalidValue;
+      if (!operand_vec_ok(d[g].CTZ, d[g].M, d[g].M) || !operand_vec_ok(d[g].X, d[g].N, d[g].N)) return hipErrorInvalidValue;
+    }
+  }
+  const bool relu = n_v > 0 && v[0].alpha == 0.f;
+  if (tile_d == TILE_128)
+    return relu ? group_t<true, Tile128, 2>(n_v, v, M, N, K, n_d, d, stream)
+                : group_t<false, Tile128, 2>(n_v, v, M, N, K, n_d, d, stream);
+  return relu ? group_t<true, Tile64, 2>(n_v, v, M, N, K, n_d, d, stream) : group_t<false, Tile64, 2>(n_v, v, M, N, K, n_d, d, stream);
+}
+
 template <class CfgD, class CfgR>
 static hipError_t bp_pair_t(const BpLayerArgs& a, hipStream_t stream) {
   static_assert(CfgD::NT == CfgR::NT, "both tasks run in workgroups of the same size");

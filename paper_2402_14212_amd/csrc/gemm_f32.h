@@ -408,6 +408,108 @@ __device__ __forceinline__ void gemm_mainloop(const float* __restrict__ A, int64
                                                            nullptr, nullptr);
 }
 
+// The same product with the summation order of a tile whose K tile is KSETS times as wide and split over
+// KSETS wavefronts (WK = KSETS): there wavefront w adds up the K slices w, w + KSETS, w + 2 KSETS, ... (32 wide
+// each) and the KSETS sums are then added in the order 0, 1, 2, ... Here one wavefront owns the whole K range
+// (Cfg::WK == 1) and walks it in that order: first every slice of set 0 into `acc`, then every slice of set 1,
+// ...; a finished set is added to the running total `sum` (set 0 starts it). Every accumulator therefore sees the
+// same sequence of matrix instructions on the same operand values as the split tile's, and the sums are added in
+// the same order: the result has the same bits. (A larger tile with that property lets a product that must
+// reproduce the split tile's bits -- the pre-activations of Phase III against Phase I -- run with more operand
+// reuse. Walking the sets one after the other instead of keeping KSETS accumulators costs 16 registers, not
+// 16 KSETS.) K must be a multiple of KSETS * ST * BK (the launcher checks); CHAIN as in gemm_mainloop_chain; the
+// result is left in `sum`.
+template <class Cfg, int LA, int LB, bool VEC, int KSETS, int CHAIN, class XfDev>
+__device__ __forceinline__ void gemm_mainloop_sets(const float* __restrict__ A, int64_t lda, const float* __restrict__ B,
+                                                   int64_t ldb, int M, int N, int K, int m0, int n0,
+                                                   float* __restrict__ lds, XfDev& xf, f32x16 (&sum)[Cfg::NACC],
+                                                   TilePipe<Cfg, LA, LB, VEC, XfDev>& p,
+                                                   const float* __restrict__ A2, const float* __restrict__ B2) {
+  static_assert(Cfg::WK == 1, "the walk over the sets stands in for the K split");
+  static_assert(Cfg::ST == 2, "two tiles in flight");
+  constexpr int BM = Cfg::BM, BK = Cfg::BK, ST = Cfg::ST;
+  constexpr int A_FLOATS = lds_tile_floats<LA, BM, BK>();
+  constexpr int STAGE = lds_stage_floats<Cfg, LA, LB>();
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int wn = wave % Cfg::WN;
+  const int wm = wave / Cfg::WN;
+  const int r = lane & 31, g = lane >> 5;
+
+  const uint32_t bytes_a = LA == KCONTIG ? xf.extent(M, K, lda) : xf.extent(K, M, lda);
+  const uint32_t bytes_b = LB == KCONTIG ? extent_bytes(N, K, ldb) : extent_bytes(K, N, ldb);
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, bytes_a);
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, bytes_b);
+  const __amdgpu_buffer_rsrc_t ra2 = make_rsrc(CHAIN == CHAIN_FIRST ? A2 : A, bytes_a);
+  const __amdgpu_buffer_rsrc_t rb2 = make_rsrc(CHAIN == CHAIN_FIRST ? B2 : B, bytes_b);
+  const ANone::Dev none;
+  float unused[Cfg::WTM];
+
+  const int per_set = K / (BK * KSETS);  // K tiles per set: a multiple of ST
+  // the tile to request next: slice `rt` of set `rset` starts at k = (rt * KSETS + rset) * BK; past the last set
+  // come the first tiles of the next product (CHAIN_FIRST) or nothing (loads beyond K return zeros untouched)
+  int rt = 0, rset = 0;
+#define MW_REQUEST(slot)                                                             \
+  do {                                                                               \
+    const int k0_ = (rt * KSETS + (rset < KSETS ? rset : 0)) * BK;                   \
+    if (CHAIN == CHAIN_FIRST && rset >= KSETS) {                                     \
+      p.a[slot].load(ra2, lda, m0, k0_, M, K, xf);                                   \
+      p.b[slot].load(rb2, ldb, n0, k0_, N, K, none);                                 \
+    } else {                                                                         \
+      p.a[slot].load(ra, lda, m0, rset < KSETS ? k0_ : K, M, K, xf);                 \
+      p.b[slot].load(rb, ldb, n0, rset < KSETS ? k0_ : K, N, K, none);               \
+    }                                                                                \
+    xf.template advance<LA, BK>();                                                   \
+    if (++rt == per_set) {                                                           \
+      rt = 0;                                                                        \
+      ++rset;                                                                        \
+    }                                                                                \
+  } while (0)
+#define MW_TO_LDS(slot, stage)                                  \
+  do {                                                          \
+    p.a[slot].store(lds + (stage) * STAGE, xf);                 \
+    p.b[slot].store(lds + (stage) * STAGE + A_FLOATS, none);    \
+  } while (0)
+
+  if (CHAIN != CHAIN_SECOND) {
+    xf.template prepare<LA, BM, BK, Cfg::NT>(m0, M, K);
+#pragma unroll
+    for (int j = 0; j < ST; ++j) MW_REQUEST(j);
+    MW_TO_LDS(0, 0);
+    __syncthreads();
+  } else {
+    rt = ST;  // tiles 0 .. ST-1 of this product were requested by the product before
+    if (rt == per_set) {
+      rt = 0;
+      rset = 1;
+    }
+  }
+  for (int set = 0; set < KSETS; ++set) {
+    f32x16 acc[Cfg::NACC];
+#pragma unroll
+    for (int a = 0; a < Cfg::NACC; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    for (int t = 0; t < per_set; t += ST) {
+#pragma unroll
+      for (int u = 0; u < ST; ++u) {
+        // the tile to multiply is in LDS stage u; register slot u is free, slot u ^ 1 holds the tile after it
+        MW_REQUEST(u);
+        mma_stage<Cfg, LA, LB, false>(lds + u * STAGE, lds + u * STAGE + A_FLOATS, wm, wn, 0, r, g, acc, unused);
+        MW_TO_LDS(u ^ 1, u ^ 1);
+        __syncthreads();
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < Cfg::NACC; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum[a][i] = (set == 0) ? acc[a][i] : sum[a][i] + acc[a][i];
+  }
+#undef MW_REQUEST
+#undef MW_TO_LDS
+}
+
 // Position of this lane's 16 accumulator values inside a 32x32 tile: value i sits in row
 // 8*(i/4) + 4*(lane>>5) + i%4 and column lane & 31.
 __device__ __forceinline__ int acc_row(int i, int g) { return 8 * (i / 4) + 4 * g + (i % 4); }

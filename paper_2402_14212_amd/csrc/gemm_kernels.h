@@ -396,7 +396,7 @@ struct GemmTask {
     reduce_and_finish<Cfg, 1>(lds, M, N, m0, n0, acc, asum, ed);
     ed.finish();
 
-    if (COLSUM && n0 == 0) {
+    if (COLSUM && n0 == 0 && colsum_out) {
       const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
       const int wk = wave % Cfg::WK, wn = (wave / Cfg::WK) % Cfg::WN, wm = wave / (Cfg::WK * Cfg::WN);
       if (wk == 0 && wn == 0 && lane < 32) {
@@ -490,6 +490,103 @@ struct VijpTask {
   }
 };
 
+// Phase III for several independent stretches of the network at once. Between two re-seed points the forward
+// sweep needs nothing but the kept activation and the kept cotangent at the stretch's first layer, so the
+// stretches can be swept side by side: set g of a launch is one layer of stretch g (all of one shape). What a
+// 256-row batch cannot give one layer -- enough 64 x 64 output tiles to fill the chip -- several layers give
+// together. The tile is 64 x 64 and walks K in the order that reproduces the bits of the 32 x 32 tile with
+// K split over KSETS wavefronts that Phase I takes for such a layer (gemm_mainloop_sets): the recomputed signs
+// agree with the stored ones, and gradients do not depend on how many stretches ran together.
+constexpr int MAX_GROUP = 16;
+
+struct VijpSet {
+  const float *X, *W, *Hin, *P, *bias;
+  const uint64_t* mask;
+  const uint32_t* offsets;     // ReLU only
+  const uint64_t* frag_base;   // ReLU only
+  float *Xout, *Hout, *CTZ;
+};
+
+template <class Cfg, bool RELU, int KSETS>
+struct GroupedVijpTask {
+  int n_sets, M, N, K;
+  float alpha, inv_alpha;
+  const float* frag;
+  uint64_t frag_capacity;
+  unsigned long long* mismatches;
+  int tiles_m, tiles_n;
+  VijpSet set[MAX_GROUP];
+  static constexpr int LDS_BYTES = lds_bytes<Cfg, KCONTIG, KCONTIG, 2>();
+  __host__ __device__ int blocks() const { return n_sets * tiles_m * tiles_n; }
+
+  __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
+    // XCD-aware over the whole launch, row tiles fastest: an XCD works on whole column panels of one set's weights
+    const int per = tiles_m * tiles_n;
+    const int id = xcd_remap(bid, n_sets * per);
+    const int g = id / per, local = id - g * per;
+    const int m0 = (local % tiles_m) * Cfg::BM, n0 = (local / tiles_m) * Cfg::BN;
+    const VijpSet& q = set[g];
+
+    f32x16 acc[2][Cfg::NACC];
+    ANone::Dev none;
+    TilePipe<Cfg, KCONTIG, KCONTIG, true, ANone::Dev> pipe;
+    gemm_mainloop_sets<Cfg, KCONTIG, KCONTIG, true, KSETS, CHAIN_FIRST>(q.X, K, q.W, K, M, N, K, m0, n0, lds, none, acc[0],
+                                                                       pipe, q.Hin, q.P);
+    gemm_mainloop_sets<Cfg, KCONTIG, KCONTIG, true, KSETS, CHAIN_SECOND>(q.Hin, K, q.P, K, M, N, K, m0, n0, lds, none, acc[1],
+                                                                        pipe, nullptr, nullptr);
+    const EpiVijp<RELU> epi{q.bias, alpha, inv_alpha, q.mask, q.offsets, frag, q.frag_base, frag_capacity,
+                            q.Xout, q.Hout, q.CTZ, mismatches};
+    typename EpiVijp<RELU>::Dev ed(epi, M, N);
+    // the epilogue in quarters of a 32 x 32 tile (four accumulator registers at a time): its index and mask
+    // arrays then take a quarter of the registers, which is what lets a third wavefront share a SIMD
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wn = wave % Cfg::WN, wm = wave / Cfg::WN, gl = lane >> 5;
+#pragma unroll
+    for (int tm = 0; tm < Cfg::WTM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < Cfg::WTN; ++tn)
+#pragma unroll
+        for (int i0 = 0; i0 < 16; i0 += 4) {
+          float v[2][4];
+#pragma unroll
+          for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[q][j] = acc[q][tm * Cfg::WTN + tn][i0 + j];
+          ed.template part<4>(M, N, m0 + (wm * Cfg::WTM + tm) * 32, n0 + (wn * Cfg::WTN + tn) * 32 + (lane & 31), gl, i0, v);
+        }
+    ed.finish();
+  }
+};
+
+// The weight gradients (and bias gradients) of several layers of one shape in one grid: set g is the
+// product GemmTask<Cfg, RCONTIG, RCONTIG, .., COLSUM> would compute alone, with the same bits.
+struct DwSet {
+  const float *CTZ, *X;
+  float *dW, *db;
+};
+
+template <class Cfg>
+struct GroupedDwTask {
+  int n_sets, M, N, K;   // d_out, d_in, batch
+  float scale, beta;
+  int tiles_m, tiles_n;
+  DwSet set[MAX_GROUP];
+  using One = GemmTask<Cfg, RCONTIG, RCONTIG, true, ANone, EpiStore, true>;
+  static constexpr int LDS_BYTES = One::LDS_BYTES;
+  __host__ __device__ int blocks() const { return n_sets * tiles_m * tiles_n; }
+
+  __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
+    const int per = tiles_m * tiles_n;
+    // blocks of one set are consecutive, so that bid % 8 inside the set is still the XCD the block runs on
+    // whenever `per` is a multiple of 8 (the set's own tile order then keeps a column panel on one XCD)
+    const int g = bid / per;
+    const DwSet& q = set[g];
+    One t{M, N, K, q.CTZ, M, q.X, N, ANone{}, EpiStore{q.dW, N, scale, beta, nullptr}, q.db, scale, tiles_m, tiles_n};
+    t.colsum_beta = beta;
+    t.run(bid - g * per, lds);
+  }
+};
+
 template <int NT, class Task>
 __global__ void __launch_bounds__(NT) task_kernel(Task t) {
   extern __shared__ __align__(16) float lds[];
@@ -511,6 +608,18 @@ task_kernel_resident(Task t) {
 // any cross-queue dependency.
 template <int NT, class TaskA, class TaskB>
 __global__ void __launch_bounds__(NT) task_pair_kernel(TaskA a, TaskB b, int first) {
+  extern __shared__ __align__(16) float lds[];
+  const int bid = (int)blockIdx.x;
+  if (bid < first) {
+    if (bid < a.blocks()) a.run(bid, lds);
+  } else {
+    b.run(bid - first, lds);
+  }
+}
+
+template <int NT, int MIN_WG, class TaskA, class TaskB>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(MIN_WG * NT / 256, 8)))
+task_pair_kernel_resident(TaskA a, TaskB b, int first) {
   extern __shared__ __align__(16) float lds[];
   const int bid = (int)blockIdx.x;
   if (bid < first) {
@@ -563,6 +672,17 @@ inline hipError_t launch_task_resident(const Task& t, hipStream_t stream) {
 template <int NT, class TaskA, class TaskB>
 inline hipError_t launch_task_pair(const TaskA& a, const TaskB& b, hipStream_t stream) {
   auto kernel = task_pair_kernel<NT, TaskA, TaskB>;
+  constexpr int bytes = TaskA::LDS_BYTES > TaskB::LDS_BYTES ? TaskA::LDS_BYTES : TaskB::LDS_BYTES;
+  static hipError_t attr = ensure_lds(kernel, bytes);
+  if (attr != hipSuccess) return attr;
+  const int first = (a.blocks() + 7) / 8 * 8;
+  hipLaunchKernelGGL(kernel, dim3(first + b.blocks()), dim3(NT), bytes, stream, a, b, first);
+  return hipGetLastError();
+}
+
+template <int NT, int MIN_WG, class TaskA, class TaskB>
+inline hipError_t launch_task_pair_resident(const TaskA& a, const TaskB& b, hipStream_t stream) {
+  auto kernel = task_pair_kernel_resident<NT, MIN_WG, TaskA, TaskB>;
   constexpr int bytes = TaskA::LDS_BYTES > TaskB::LDS_BYTES ? TaskA::LDS_BYTES : TaskB::LDS_BYTES;
   static hipError_t attr = ensure_lds(kernel, bytes);
   if (attr != hipSuccess) return attr;

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <string>
 #include <utility>
 #include <vector>
@@ -172,6 +173,19 @@ struct mw_handle {
   // backprop workspace
   float *bp_ha = nullptr, *bp_hb = nullptr;
 
+  // Phase III side by side (cfg.phase3_parallel_segments): the stretches between re-seed points, top first,
+  // and how they are taken: `count` > 1 consecutive stretches of one signature in grouped launches, or one
+  // stretch through the ordinary sweep.
+  struct Stretch { int lo, hi; };
+  struct StretchGroup { int first, count; };   // indices into `stretches`
+  std::vector<Stretch> stretches;
+  std::vector<StretchGroup> groups;
+  int group_width = 0;                          // most stretches in one launch (0: grouping off)
+  int overlap = 0;                              // grouped stretches run on `side` while Phase II goes on
+  std::vector<float*> gx, gh, gc;               // per group slot: 3 activation, 2 cotangent, 2 ct_z buffers
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> events;               // one per group, and one to join
+
   // measurement aid: run only the launches of one kernel class (-1 = all), count launches
   int class_filter = -1;
   uint64_t launches[MW_KCLASS_COUNT] = {0, 0, 0, 0, 0, 0};
@@ -200,6 +214,10 @@ struct mw_handle {
     for (auto& a : allocs) dev_free(a.first, alloc_ctx);
     allocs.clear();
     live = 0;
+    for (auto e : events) (void)hipEventDestroy(e);
+    events.clear();
+    if (side) (void)hipStreamDestroy(side);
+    side = nullptr;
   }
 };
 
@@ -260,6 +278,67 @@ int build_right_inverses(mw_handle* h, hipStream_t stream) {
   return rc;
 }
 
+// Phase III side by side. The re-seed points cut the network into stretches that Phase III can sweep
+// independently of each other once the activation at a stretch's first layer is kept too (Phase I writes it
+// there anyway; with a plan it is kept for every stretch). Consecutive stretches (top first, the order in which Phase II releases them) with the same
+// layer shapes and slopes, all of them shapes the grouped kernel takes, are swept in one launch per layer
+// position, at most `width` of them; everything else goes through the ordinary sweep, one stretch at a time.
+// width 0 (automatic): as many as it takes to give every CU one 64 x 64 tile of the layer kernel.
+void plan_stretches(mw_handle* h, int width) {
+  const int L = h->L, B = h->B;
+  h->stretches.clear();
+  h->groups.clear();
+  h->group_width = 0;
+  if (!h->fuse || h->S > 0 || width == 1) return;
+  std::vector<int> bounds;  // 0 = b_0 < b_1 < ... < L
+  bounds.push_back(0);
+  for (int j = 1; j < L; ++j)
+    if (h->layers[j - 1].ckpt) bounds.push_back(j);
+  bounds.push_back(L);
+  if (bounds.size() < 3) return;  // one stretch: nothing to run side by side
+  for (size_t k = bounds.size() - 1; k >= 1; --k) h->stretches.push_back({bounds[k - 1], bounds[k]});
+  auto eligible = [&](const mw_handle::Stretch& st) {
+    for (int i = st.lo; i < st.hi; ++i) {
+      const Layer& l = h->layers[i];
+      if (!phase3_group_ok(B, l.d_out, l.d_in)) return false;
+      if ((reinterpret_cast<uintptr_t>(l.W) | reinterpret_cast<uintptr_t>(l.P)) & 15) return false;
+    }
+    return true;
+  };
+  auto same = [&](const mw_handle::Stretch& a, const mw_handle::Stretch& b) {
+    if (a.hi - a.lo != b.hi - b.lo) return false;
+    for (int j = 0; j < a.hi - a.lo; ++j) {
+      const Layer &p = h->layers[a.lo + j], &q = h->layers[b.lo + j];
+      if (p.d_in != q.d_in || p.d_out != q.d_out || p.alpha != q.alpha) return false;
+    }
+    return true;
+  };
+  const int n = (int)h->stretches.size();
+  int widest = 0;
+  for (int k = 0; k < n;) {
+    int count = 1;
+    if (eligible(h->stretches[k])) {
+      int most = width;
+      if (most == 0) {
+        const Layer& l = h->layers[h->stretches[k].lo];
+        const int tiles = ((B + 63) / 64) * ((l.d_out + 63) / 64);
+        most = (256 + tiles - 1) / tiles;
+      }
+      if (most > 16) most = 16;
+      while (k + count < n && count < most && same(h->stretches[k], h->stretches[k + count])) ++count;
+    }
+    h->groups.push_back({k, count});
+    if (count > widest) widest = count;
+    k += count;
+  }
+  if (widest < 2) {  // nothing to gain: the ordinary sweep, no kept activations
+    h->stretches.clear();
+    h->groups.clear();
+    return;
+  }
+  h->group_width = widest;
+}
+
 int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_t* cfg) {
   if (!layers || n_layers <= 0 || !cfg || cfg->batch <= 0) return MW_ERR_INVALID_ARG;
   if (cfg->reseed_interval < -1 || cfg->segment_length < 0) return MW_ERR_INVALID_ARG;
@@ -268,6 +347,8 @@ int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return MW_ERR_INVALID_ARG;
   if (cfg->plan & ~(MW_PLAN_MOONWALK | MW_PLAN_BACKPROP)) return MW_ERR_INVALID_ARG;
   if (cfg->debug_keep != 0 && cfg->debug_keep != 1) return MW_ERR_INVALID_ARG;
+  if (cfg->phase3_parallel_segments < 0 || cfg->phase3_parallel_segments > 16) return MW_ERR_INVALID_ARG;
+  if (cfg->phase3_overlap < 0 || cfg->phase3_overlap > 1) return MW_ERR_INVALID_ARG;
   for (int i = 0; i < n_layers; ++i) {
     const mw_layer_t& l = layers[i];
     if (l.d_in <= 0 || l.d_out <= 0 || !l.W) return MW_ERR_INVALID_ARG;
@@ -445,6 +526,31 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
         if (boundary) ok = ok && alloc_t(h, &h->layers[j - 1].xck, B * h->layers[j - 1].d_out, &st.bytes_checkpoints);
       }
     }
+    // Phase III side by side: the plan, the activations kept at the first layer of every stretch that is
+    // swept in a group, the groups' own rotating buffers, and the side stream with its events
+    plan_stretches(h, cfg->phase3_parallel_segments);
+    if (h->group_width > 0) {
+      const size_t nmax = B * (size_t)h->dmax;
+      for (const auto& sg : h->stretches)
+        if (sg.lo > 0) ok = ok && alloc_t(h, &h->layers[sg.lo - 1].xck, B * h->layers[sg.lo - 1].d_out, &st.bytes_checkpoints);
+      h->gx.assign((size_t)3 * h->group_width, nullptr);
+      h->gh.assign((size_t)2 * h->group_width, nullptr);
+      h->gc.assign((size_t)2 * h->group_width, nullptr);
+      for (auto& p : h->gx) ok = ok && alloc_t(h, &p, nmax, &st.bytes_mw_scratch);
+      for (auto& p : h->gh) ok = ok && alloc_t(h, &p, nmax, &st.bytes_mw_scratch);
+      for (auto& p : h->gc) ok = ok && alloc_t(h, &p, nmax, &st.bytes_mw_scratch);
+      if (!ok) return fail(MW_ERR_OOM);
+      h->overlap = cfg->phase3_overlap;
+      if (h->overlap) {
+        e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);  // default priority
+        if (e != hipSuccess) return fail(hip_fail(e, "side stream"));
+        h->events.resize(h->groups.size() + 2, nullptr);
+        for (auto& ev : h->events) {
+          e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+          if (e != hipSuccess) return fail(hip_fail(e, "event"));
+        }
+      }
+    }
     // ping-pong buffers
     const size_t nmax = B * (size_t)h->dmax;
     ok = ok && alloc_t(h, &h->xa, nmax, &st.bytes_mw_scratch) && alloc_t(h, &h->xb, nmax, &st.bytes_mw_scratch) &&
@@ -490,6 +596,12 @@ namespace {
 // keeps x at every S-th layer boundary and no masks, and the segments are then finished one by
 // one from the top: forward again inside the segment (masks, fragment index), reverse through
 // it, Phase III through it. Only one segment's masks and fragments exist at a time.
+#define MW_TRY_RC(expr)          \
+  do {                           \
+    int rc__ = (expr);           \
+    if (rc__ != MW_OK) return rc__; \
+  } while (0)
+
 struct Step {
   mw_handle* h;
   hipStream_t s;
@@ -550,7 +662,10 @@ int frag_index_range(const Step& c, int lo, int hi) {
 
 // Phase II through layers [lo, hi): h_top holds the raw cotangent at the output of layer hi-1
 // (overwritten), the cotangent at the input of layer lo goes to h_bottom.
-int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) {
+// `released` (may be empty) is called after the launch that produced the cotangent at layer boundary i
+// (the input of layer i), for every i in [lo, hi), top down.
+int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom,
+                  const std::function<int(int)>& released = nullptr) {
   mw_handle* h = c.h;
   hipStream_t s = c.s;
   const int B = h->B;
@@ -586,6 +701,7 @@ int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) 
         MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_rev_fused(TILE_AUTO, B, l.d_in, l.d_out, ctcur, l.W, r, s));
         ctcur = ctout;
       }
+      if (released) MW_TRY_RC(released(i));
     }
   } else {
     const float* hcur = h_top;
@@ -604,6 +720,7 @@ int reverse_range(const Step& c, int lo, int hi, float* h_top, float* h_bottom) 
       MW_LAUNCH(h, s, MW_KCLASS_REV, gemm_plain(OP_NN, TILE_AUTO, B, l.d_in, l.d_out, 1.f, h->ctz, l.d_out, l.W, l.d_in, 0.f,
                                                 hout, l.d_in, nullptr, s));
       hcur = hout;
+      if (released) MW_TRY_RC(released(i));
     }
   }
   return MW_OK;
@@ -689,11 +806,107 @@ int phase3_range(const Step& c, int lo, int hi, const float* xin, const float* h
   return MW_OK;
 }
 
-#define MW_TRY_RC(expr)          \
-  do {                           \
-    int rc__ = (expr);           \
-    if (rc__ != MW_OK) return rc__; \
-  } while (0)
+// Phase III of the stretches [first, first + count) of the plan, side by side on stream `s`: position j of all of
+// them in one launch, which also carries the weight gradients of position j - 1 (the rotation of phase3_range,
+// per stretch, over the group's own buffers). A stretch starts from the activation and the cotangent kept at
+// its first layer.
+int phase3_group(const Step& c, int first, int count, hipStream_t s) {
+  mw_handle* h = c.h;
+  const int B = h->B;
+  unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
+  const float inv_scale = 1.0f / h->loss_scale;
+  const bool paired = h->class_filter < 0 || h->class_filter == MW_KCLASS_PHASE3;
+  const int len = h->stretches[first].hi - h->stretches[first].lo;
+  VijpArgs v[MAX_PHASE3_GROUP];
+  DwArgs pending[MAX_PHASE3_GROUP], fresh[MAX_PHASE3_GROUP];
+  bool have_pending = false;
+  for (int j = 0; j < len; ++j) {
+    for (int g = 0; g < count; ++g) {
+      const int lo = h->stretches[first + g].lo, i = lo + j;
+      Layer& l = h->layers[i];
+      float* const* xrot = &h->gx[(size_t)3 * g];
+      float* const* hrot = &h->gh[(size_t)2 * g];
+      float* const* crot = &h->gc[(size_t)2 * g];
+      const float* xin = j > 0 ? xrot[(j - 1) % 3] : (lo == 0 ? c.x : h->layers[lo - 1].xck);
+      const float* hin = j > 0 ? (h->layers[i - 1].dbg_h3 ? h->layers[i - 1].dbg_h3 : hrot[(j - 1) & 1])
+                               : (lo == 0 ? h->h0 : h->layers[lo - 1].ckpt);
+      float* hout = l.dbg_h3 ? l.dbg_h3 : hrot[j & 1];
+      const bool relu = (l.alpha == 0.f);
+      v[g] = VijpArgs{xin, l.W, l.b, hin, l.P, l.alpha, l.mask, l.offsets, h->frag,
+                      relu ? h->frag_bases + l.relu_slot : nullptr, h->frag_capacity, xrot[j % 3], hout, crot[j & 1], mismatches};
+      DwArgs d{l.d_out, l.d_in, B, crot[j & 1], xin, inv_scale, nullptr, nullptr};
+      if (c.apply_lr != 0.f) {
+        d.scale = -c.apply_lr * inv_scale;
+        d.dW = const_cast<float*>(l.W);
+        d.db = const_cast<float*>(l.b);
+        d.beta = 1.f;
+      } else {
+        d.dW = c.grads_out + l.dW_off;
+        d.db = c.grads_out + l.db_off;
+      }
+      fresh[g] = d;
+    }
+    const Layer& l0 = h->layers[h->stretches[first].lo + j];
+    if (paired) {
+      MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_group(count, v, B, l0.d_out, l0.d_in, have_pending ? count : 0, pending, s));
+    } else {
+      MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_phase3_group(count, v, B, l0.d_out, l0.d_in, 0, nullptr, s));
+      MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_phase3_group(0, nullptr, 0, 0, 0, count, fresh, s));
+    }
+    for (int g = 0; g < count; ++g) pending[g] = fresh[g];
+    have_pending = true;
+  }
+  if (paired && have_pending) MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_group(0, nullptr, 0, 0, 0, count, pending, s));
+  return MW_OK;
+}
+
+// Phases II and III with the plan of plan_stretches. Phase II runs on `s`. A group of stretches can be swept as
+// soon as Phase II has passed its lowest boundary: with overlap it is then issued on the side stream (behind an
+// event) and shares the machine with the rest of Phase II; otherwise, and for stretches taken one at a time
+// (they use the buffers Phase II uses), it is issued on `s` after Phase II, top first.
+int reverse_and_sweep(const Step& c) {
+  mw_handle* h = c.h;
+  hipStream_t s = c.s;
+  const int L = h->L;
+  const bool overlap = h->overlap && h->class_filter < 0;
+  size_t next = 0;  // next group Phase II will release
+  int side_used = 0;
+  auto released = [&](int boundary) -> int {
+    while (next < h->groups.size()) {
+      const auto& g = h->groups[next];
+      if (h->stretches[g.first + g.count - 1].lo != boundary) break;
+      if (overlap && g.count > 1) {
+        MW_HIP(hipEventRecord(h->events[next], s));
+        MW_HIP(hipStreamWaitEvent(h->side, h->events[next], 0));
+        MW_TRY_RC(phase3_group(c, g.first, g.count, h->side));
+        side_used = 1;
+      }
+      ++next;
+    }
+    return MW_OK;
+  };
+  if (overlap) {
+    // the side stream must not run ahead of what the caller's stream has done before this call
+    MW_HIP(hipEventRecord(h->events[h->groups.size()], s));
+    MW_HIP(hipStreamWaitEvent(h->side, h->events[h->groups.size()], 0));
+  }
+  MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0, released));
+  for (size_t k = 0; k < h->groups.size(); ++k) {
+    const auto& g = h->groups[k];
+    if (g.count > 1) {
+      if (!overlap) MW_TRY_RC(phase3_group(c, g.first, g.count, s));
+    } else {
+      const auto& st = h->stretches[g.first];
+      MW_TRY_RC(phase3_range(c, st.lo, st.hi, st.lo == 0 ? c.x : h->layers[st.lo - 1].xck,
+                             st.lo == 0 ? h->h0 : h->layers[st.lo - 1].ckpt));
+    }
+  }
+  if (side_used) {
+    MW_HIP(hipEventRecord(h->events[h->groups.size() + 1], h->side));
+    MW_HIP(hipStreamWaitEvent(s, h->events[h->groups.size() + 1], 0));
+  }
+  return MW_OK;
+}
 
 int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads_out, float* loss_out, hipStream_t s,
                  float apply_lr) {
@@ -708,6 +921,7 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
     MW_TRY_RC(forward_range(c, 0, L, x, 0, &x_L));
     MW_TRY_RC(frag_index_range(c, 0, L));
     MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+    if (h->group_width > 0) return reverse_and_sweep(c);
     MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0));
     return phase3_range(c, 0, L, x, h->h0);
   }

@@ -99,6 +99,15 @@ struct DwArgs {
 };
 hipError_t gemm_phase3_pair(const VijpArgs* v, int M, int N, int K, const DwArgs* d, hipStream_t stream);
 
+// Phase III for several independent stretches of the network in one launch: n_v layer kernels of one shape
+// (M x N x K each, the same alpha) and n_d weight-gradient products of one shape (the same scale and beta; a
+// NULL db is skipped), either count may be 0, at most 16 each. Every product gets the bits it gets from
+// gemm_phase3_pair. Only for shapes phase3_group_ok accepts and 16-byte aligned operands (else an error,
+// nothing launched).
+constexpr int MAX_PHASE3_GROUP = 16;
+bool phase3_group_ok(int M, int N, int K);
+hipError_t gemm_phase3_group(int n_v, const VijpArgs* v, int M, int N, int K, int n_d, const DwArgs* d, hipStream_t stream);
+
 // Backprop's two products of one layer in one launch (both read h .* slope(act)):
 //   dW[dout][din] = scale (Hy .* slope)^T Xprev, db = scale * column sums;   Hout[B][din] = (Hy .* slope) W
 // Hout == NULL skips the second product (first layer).

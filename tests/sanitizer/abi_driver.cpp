@@ -85,7 +85,7 @@ static void validation() {
 
 // One dense network through every entry point. widths: d_0 .. d_L.
 static void dense_network(const std::vector<int>& widths, int batch, const std::vector<float>& alphas, int K, int S, int fuse,
-                          int debug_keep, int plan) {
+                          int debug_keep, int plan, int group = 1, int overlap = 0) {
   const int L = (int)widths.size() - 1;
   std::vector<std::vector<float>> W(L), b(L);
   std::vector<mw_layer_t> layers(L);
@@ -100,6 +100,8 @@ static void dense_network(const std::vector<int>& widths, int batch, const std::
   cfg.fuse = fuse;
   cfg.debug_keep = debug_keep;
   cfg.plan = plan;
+  cfg.phase3_parallel_segments = group;
+  cfg.phase3_overlap = overlap;
   mw_handle_t* h = nullptr;
   const int rc = moonwalk_setup(&h, layers.data(), L, &cfg, nullptr);
   EXPECT(rc == MW_OK && h != nullptr);
@@ -240,6 +242,12 @@ int main() {
   dense_network({40, 24}, 3, {0.1f}, 0, 0, 1, 0, MW_PLAN_BACKPROP);
   // shapes of the large configurations (host arithmetic in size_t / int64): 1024-wide, batch 256, 9 layers of one shape
   dense_network(std::vector<int>(10, 1024), 256, std::vector<float>(9, 0.1f), 4, 0, 1, 0, MW_PLAN_MOONWALK);
+  // Phase III side by side: stretches of 4, 4, 4 and 2 layers (the short one alone), two or three or all at a
+  // time, on one stream and with the side stream; a ReLU layer at the same place of every stretch; kept tensors
+  for (int group : {0, 2, 3, 16})
+    for (int overlap = 0; overlap <= 1; ++overlap)
+      dense_network(std::vector<int>(15, 256), 64, std::vector<float>(14, 0.1f), 4, 0, 1, 0, MW_PLAN_MOONWALK, group, overlap);
+  dense_network(std::vector<int>(13, 256), 77, {0.1f, 0.f, 0.1f, 0.3f, 0.1f, 0.f, 0.1f, 0.3f, 0.1f, 0.f, 0.1f, 0.3f}, 4, 0, 1, 1, 0, 3, 1);
   dense_allocation_failures();
   // convolutional chains: gathered kernels and patch buffer, as-read input cotangent, image chunks of 3,
   // a kernel wider than padding + stride (the sweep), 1-D fragmental layers in blocks of 4

@@ -51,6 +51,27 @@ hipError_t hipMemcpy(void* dst, const void* src, size_t bytes, hipMemcpyKind) {
   memmove(dst, src, bytes);
   return hipSuccess;
 }
+// streams and events are tokens: everything "runs" at once, in program order
+hipError_t hipStreamCreateWithFlags(hipStream_t* stream, unsigned) {
+  if (!stream) return hipErrorInvalidValue;
+  *stream = reinterpret_cast<hipStream_t>(malloc(8));
+  return *stream ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipStreamDestroy(hipStream_t stream) {
+  free(stream);
+  return hipSuccess;
+}
+hipError_t hipEventCreateWithFlags(hipEvent_t* event, unsigned) {
+  if (!event) return hipErrorInvalidValue;
+  *event = reinterpret_cast<hipEvent_t>(malloc(8));
+  return *event ? hipSuccess : hipErrorOutOfMemory;
+}
+hipError_t hipEventDestroy(hipEvent_t event) {
+  free(event);
+  return hipSuccess;
+}
+hipError_t hipEventRecord(hipEvent_t event, hipStream_t) { return event ? hipSuccess : hipErrorInvalidHandle; }
+hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t event, unsigned) { return event ? hipSuccess : hipErrorInvalidHandle; }
 hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
 hipError_t hipDeviceSynchronize() { return hipSuccess; }
 hipError_t hipGetLastError() {

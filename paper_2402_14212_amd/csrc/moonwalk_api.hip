@@ -809,8 +809,21 @@ int phase3_range(const Step& c, int lo, int hi, const float* xin, const float* h
 // Phase III of the stretches [first, first + count) of the plan, side by side on stream `s`: position j of all of
 // them in one launch, which also carries the weight gradients of position j - 1 (the rotation of phase3_range,
 // per stretch, over the group's own buffers). A stretch starts from the activation and the cotangent kept at
-// its first layer.
-int phase3_group(const Step& c, int first, int count, hipStream_t s) {
+// its first layer. The weight gradients of a group's last position would need a launch of their own: they are
+// handed on in `carry` instead and ride in the next group's first launch (the caller flushes what is left),
+// unless they read a buffer that launch writes (the groups share their rotating buffers).
+struct CarriedDw {
+  DwArgs d[MAX_PHASE3_GROUP];
+  int n = 0;
+};
+
+int flush_carried(const Step& c, CarriedDw* carry, hipStream_t s) {
+  if (carry->n > 0) MW_LAUNCH(c.h, s, MW_KCLASS_PHASE3, gemm_phase3_group(0, nullptr, 0, 0, 0, carry->n, carry->d, s));
+  carry->n = 0;
+  return MW_OK;
+}
+
+int phase3_group(const Step& c, int first, int count, hipStream_t s, CarriedDw* carry) {
   mw_handle* h = c.h;
   const int B = h->B;
   unsigned long long* mismatches = reinterpret_cast<unsigned long long*>(h->status);
@@ -819,7 +832,12 @@ int phase3_group(const Step& c, int first, int count, hipStream_t s) {
   const int len = h->stretches[first].hi - h->stretches[first].lo;
   VijpArgs v[MAX_PHASE3_GROUP];
   DwArgs pending[MAX_PHASE3_GROUP], fresh[MAX_PHASE3_GROUP];
-  bool have_pending = false;
+  int n_pending = 0;
+  if (paired) {
+    for (int g = 0; g < carry->n; ++g) pending[g] = carry->d[g];
+    n_pending = carry->n;
+    carry->n = 0;
+  }
   for (int j = 0; j < len; ++j) {
     for (int g = 0; g < count; ++g) {
       const int lo = h->stretches[first + g].lo, i = lo + j;
@@ -848,15 +866,21 @@ int phase3_group(const Step& c, int first, int count, hipStream_t s) {
     }
     const Layer& l0 = h->layers[h->stretches[first].lo + j];
     if (paired) {
-      MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_group(count, v, B, l0.d_out, l0.d_in, have_pending ? count : 0, pending, s));
+      MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_group(count, v, B, l0.d_out, l0.d_in, n_pending, pending, s));
     } else {
       MW_LAUNCH(h, s, MW_KCLASS_VIJP, gemm_phase3_group(count, v, B, l0.d_out, l0.d_in, 0, nullptr, s));
       MW_LAUNCH(h, s, MW_KCLASS_DW, gemm_phase3_group(0, nullptr, 0, 0, 0, count, fresh, s));
     }
     for (int g = 0; g < count; ++g) pending[g] = fresh[g];
-    have_pending = true;
+    n_pending = count;
   }
-  if (paired && have_pending) MW_LAUNCH(h, s, MW_KCLASS_PHASE3, gemm_phase3_group(0, nullptr, 0, 0, 0, count, pending, s));
+  if (!paired) return MW_OK;
+  // The last position's weight gradients read ct_z buffer (len - 1) & 1 and activation buffer (len - 2) % 3 of
+  // their slot (the kept activation when len == 1); the next group's first launch writes buffers 0 of each.
+  const bool safe_to_carry = len >= 2 && ((len - 1) & 1) != 0 && ((len - 2) % 3) != 0;
+  for (int g = 0; g < count; ++g) carry->d[g] = pending[g];
+  carry->n = count;
+  if (!safe_to_carry) return flush_carried(c, carry, s);
   return MW_OK;
 }
 
@@ -871,6 +895,7 @@ int reverse_and_sweep(const Step& c) {
   const bool overlap = h->overlap && h->class_filter < 0;
   size_t next = 0;  // next group Phase II will release
   int side_used = 0;
+  CarriedDw carry;
   auto released = [&](int boundary) -> int {
     while (next < h->groups.size()) {
       const auto& g = h->groups[next];
@@ -878,7 +903,7 @@ int reverse_and_sweep(const Step& c) {
       if (overlap && g.count > 1) {
         MW_HIP(hipEventRecord(h->events[next], s));
         MW_HIP(hipStreamWaitEvent(h->side, h->events[next], 0));
-        MW_TRY_RC(phase3_group(c, g.first, g.count, h->side));
+        MW_TRY_RC(phase3_group(c, g.first, g.count, h->side, &carry));
         side_used = 1;
       }
       ++next;
@@ -891,16 +916,19 @@ int reverse_and_sweep(const Step& c) {
     MW_HIP(hipStreamWaitEvent(h->side, h->events[h->groups.size()], 0));
   }
   MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0, released));
+  if (side_used) MW_TRY_RC(flush_carried(c, &carry, h->side));
   for (size_t k = 0; k < h->groups.size(); ++k) {
     const auto& g = h->groups[k];
     if (g.count > 1) {
-      if (!overlap) MW_TRY_RC(phase3_group(c, g.first, g.count, s));
+      if (!overlap) MW_TRY_RC(phase3_group(c, g.first, g.count, s, &carry));
     } else {
+      MW_TRY_RC(flush_carried(c, &carry, s));
       const auto& st = h->stretches[g.first];
       MW_TRY_RC(phase3_range(c, st.lo, st.hi, st.lo == 0 ? c.x : h->layers[st.lo - 1].xck,
                              st.lo == 0 ? h->h0 : h->layers[st.lo - 1].ckpt));
     }
   }
+  MW_TRY_RC(flush_carried(c, &carry, s));
   if (side_used) {
     MW_HIP(hipEventRecord(h->events[h->groups.size() + 1], h->side));
     MW_HIP(hipStreamWaitEvent(s, h->events[h->groups.size() + 1], 0));

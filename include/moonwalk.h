@@ -418,8 +418,11 @@ int mw_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, f
                  void* hip_stream);
 
 /* Erased-element index of a mask: offsets[w] = number of zero bits among elements < 64 w,
-   offsets[n_words] = n0 (uint32[n_words + 1]). Deterministic integer scan. */
-int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, void* hip_stream);
+   offsets[n_words] = n0 (uint32[n_words + 1]). Deterministic integer scan in two levels (two launches: the
+   erased counts of chunks of 2048 mask words, then the offsets); every mask word is read twice whatever n is.
+   work: mw_frag_offsets_work_words(n) device words of scratch (one per chunk). */
+size_t mw_frag_offsets_work_words(int64_t n);
+int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, uint32_t* work, void* hip_stream);
 
 /* Stream compaction of the erased cotangents: frag[offsets[e/64] + rank of e within its word] =
    h[e] for every e with mask bit 0, ascending e. capacity in floats; on overflow nothing past

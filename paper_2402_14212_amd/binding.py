@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "moonwalk_setup", "moonwalk_refresh", "moonwalk_refresh_incremental", "moonwalk_sgd_step", "moonwalk_grad", "backprop_grad", "moonwalk_grad_layout",
     "moonwalk_memory_stats", "moonwalk_debug_fetch", "moonwalk_destroy", "moonwalk_strerror",
     "moonwalk_profile_filter", "moonwalk_profile_launches",
-    "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_compact",
+    "mw_gemm_f32", "mw_bias_act_mask", "mw_rev_scale", "mw_frag_offsets", "mw_frag_offsets_work_words", "mw_frag_compact",
     "mw_vijp_epilogue", "mw_colsum", "mw_colsum_wide", "mw_colsum_work_floats", "mw_colsum_wide_noalloc", "mw_colsum_noalloc_max_floats", "mw_loss_grad", "mw_loss_scratch_doubles", "mw_copy_f32",
     "mw_probe_operand_stream",
     "moonwalk_conv_setup", "moonwalk_conv_refresh", "moonwalk_conv_grad", "backprop_conv_grad",
@@ -124,7 +124,9 @@ def load_library() -> C.CDLL:
     lib.mw_gemm_f32.argtypes = [i32, i32, i32, i32, i32, f32, vp, i32, vp, i32, f32, vp, i32, vp]
     lib.mw_bias_act_mask.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
     lib.mw_rev_scale.argtypes = [vp, vp, i64, f32, vp, vp]
-    lib.mw_frag_offsets.argtypes = [vp, i64, vp, vp]
+    lib.mw_frag_offsets.argtypes = [vp, i64, vp, vp, vp]
+    lib.mw_frag_offsets_work_words.argtypes = [i64]
+    lib.mw_frag_offsets_work_words.restype = sz
     lib.mw_frag_compact.argtypes = [vp, vp, vp, i64, vp, C.c_uint64, vp, vp]
     lib.mw_vijp_epilogue.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.mw_colsum.argtypes = [vp, i64, i32, f32, vp, vp]
@@ -706,8 +708,10 @@ def rev_scale(h: torch.Tensor, mask: torch.Tensor, alpha: float) -> torch.Tensor
 
 def frag_offsets(mask: torch.Tensor, n: int) -> torch.Tensor:
     _require_gpu()
+    lib = load_library()
     off = torch.empty(_n_words(n) + 1, dtype=torch.int32, device=mask.device)
-    _check(load_library().mw_frag_offsets(_ptr(mask), n, _ptr(off), _stream()))
+    work = torch.empty(int(lib.mw_frag_offsets_work_words(n)), dtype=torch.int32, device=mask.device)
+    _check(lib.mw_frag_offsets(_ptr(mask), n, _ptr(off), _ptr(work), _stream()))
     return off
 
 

@@ -157,11 +157,15 @@ k_rev_scale_v4(const float* __restrict__ h, const uint64_t* __restrict__ mask, i
   }
 }
 
+// A wavefront's 256 elements hold a contiguous run of the store (about half of them are erased). The erased
+// values are first put in order into the wavefront's own LDS slot, then written out 64 at a time, lane k next
+// to lane k + 1: full 256-byte stores instead of four scattered ones per lane.
 __global__ void __launch_bounds__(EW_THREADS)
 k_frag_compact_v4(const float* __restrict__ h, const uint64_t* __restrict__ mask, const uint32_t* __restrict__ offsets,
                   int64_t n, float* __restrict__ frag, const uint64_t* __restrict__ base_ptr, uint64_t capacity,
                   int32_t* __restrict__ overflow_flag) {
-  const int lane = threadIdx.x & 63;
+  __shared__ float stage[EW_WAVES][VUNROLL][256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t n_words = (n + 63) >> 6, n_groups = (n + 255) >> 8;
   const int64_t stride = total_waves() * VUNROLL;
   const uint64_t base = base_ptr ? *base_ptr : 0ull;
@@ -169,29 +173,42 @@ k_frag_compact_v4(const float* __restrict__ h, const uint64_t* __restrict__ mask
   for (int64_t g0 = global_wave() * VUNROLL; g0 < n_groups; g0 += stride) {
     float4 v[VUNROLL];
     uint64_t m[VUNROLL];
-    uint32_t off[VUNROLL];
+    uint32_t off[VUNROLL], first[VUNROLL], end[VUNROLL];
 #pragma unroll
     for (int u = 0; u < VUNROLL; ++u) {
       v[u] = ld4(h, (g0 + u) * 256 + 4 * lane, n);
-      const int64_t wi = (g0 + u) * 4 + (lane >> 4);
+      const int64_t w0 = (g0 + u) * 4, wi = w0 + (lane >> 4);
       m[u] = wi < n_words ? mask[wi] : ~0ull;
       off[u] = wi < n_words ? offsets[wi] : 0u;
+      // the group's run of the store: [first, end)
+      first[u] = w0 < n_words ? offsets[w0] : 0u;
+      end[u] = w0 < n_words ? offsets[w0 + 4 < n_words ? w0 + 4 : n_words] : 0u;
     }
 #pragma unroll
     for (int u = 0; u < VUNROLL; ++u) {
       const int64_t e = (g0 + u) * 256 + 4 * lane;
       // erased elements of this word below this lane's first position, then one by one
-      uint64_t idx = base + off[u] + (uint64_t)__popcll(~m[u] & ((1ull << pos0) - 1ull));
+      uint32_t idx = off[u] - first[u] + (uint32_t)__popcll(~m[u] & ((1ull << pos0) - 1ull));
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const bool erased = (e + j < n) && !((m[u] >> (pos0 + j)) & 1ull);
-        if (erased) {
-          if (idx < capacity) frag[idx] = pick(v[u], j);
-          else if (overflow_flag) *overflow_flag = 1;
-          ++idx;
-        }
+        if (erased) stage[wave][u][idx++] = pick(v[u], j);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int u = 0; u < VUNROLL; ++u) {
+      const uint32_t count = end[u] - first[u];
+      const uint64_t dst = base + first[u];
+      for (uint32_t k = lane; k < count; k += 64) {
+        if (dst + k < capacity) __builtin_nontemporal_store(stage[wave][u][k], frag + dst + k);
+        else if (overflow_flag) *overflow_flag = 1;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -345,7 +362,6 @@ k_rev_scale(const float* __restrict__ h, const uint64_t* __restrict__ mask, int6
 // Integer arithmetic only: the result does not depend on scheduling.
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_WORDS_PER_THREAD = 8;
-constexpr int SCAN_MAX_BLOCKS = 64;
 
 __device__ __forceinline__ uint32_t erased_in_word(uint64_t w, int64_t word_index, int64_t n) {
   int64_t valid = n - word_index * 64;
@@ -367,25 +383,48 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* red) {
   return t;
 }
 
-__device__ __forceinline__ void frag_offsets_chunk(const uint64_t* __restrict__ mask, int64_t n,
-                                                   uint32_t* __restrict__ offsets, int64_t chunk, uint32_t* red) {
+// Two-level scan over chunks of SCAN_CHUNK_WORDS mask words. First launch: one workgroup per chunk counts the
+// erased bits of its chunk into sums[chunk]. Second launch: workgroup c adds up sums[0 .. c) (at most a few
+// thousand values, whatever the layer's size), then scans its own chunk and writes the offsets. Every mask word is
+// read twice and nothing is counted more often than that, so the scan stays bound by memory for any size.
+constexpr int64_t SCAN_CHUNK_WORDS = (int64_t)SCAN_THREADS * SCAN_WORDS_PER_THREAD;
+
+__device__ __forceinline__ void frag_chunk_sum(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ sums,
+                                               uint32_t* red) {
   const int64_t n_words = (n + 63) >> 6;
-  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  const int64_t c0 = (int64_t)blockIdx.x * SCAN_CHUNK_WORDS;
+  if (c0 >= n_words) return;
+  const int64_t c1 = c0 + SCAN_CHUNK_WORDS < n_words ? c0 + SCAN_CHUNK_WORDS : n_words;
+  uint32_t cnt = 0;
+  for (int64_t w = c0 + threadIdx.x; w < c1; w += SCAN_THREADS) cnt += erased_in_word(mask[w], w, n);
+  cnt = block_sum(cnt, red);
+  if (threadIdx.x == 0) sums[blockIdx.x] = cnt;
+}
+
+__device__ __forceinline__ void frag_offsets_chunk(const uint64_t* __restrict__ mask, int64_t n,
+                                                   uint32_t* __restrict__ offsets, const uint32_t* __restrict__ sums,
+                                                   uint32_t* red) {
+  const int64_t n_words = (n + 63) >> 6;
+  const int64_t c0 = (int64_t)blockIdx.x * SCAN_CHUNK_WORDS;
   if (c0 >= n_words) {  // nothing to scan here; an empty mask still gets its total
     if (n_words == 0 && blockIdx.x == 0 && threadIdx.x == 0) offsets[0] = 0u;
     return;
   }
-  const int64_t c1 = c0 + chunk < n_words ? c0 + chunk : n_words;
+  const int64_t c1 = c0 + SCAN_CHUNK_WORDS < n_words ? c0 + SCAN_CHUNK_WORDS : n_words;
   // erased bits before this chunk
   uint32_t before = 0;
-  for (int64_t w = threadIdx.x; w < c0; w += SCAN_THREADS) before += erased_in_word(mask[w], w, n);
+  for (int64_t c = threadIdx.x; c < (int64_t)blockIdx.x; c += SCAN_THREADS) before += sums[c];
   before = block_sum(before, red);
   // this chunk: each thread takes a contiguous run of words
-  const int64_t per = (chunk + SCAN_THREADS - 1) / SCAN_THREADS;
-  const int64_t lo = c0 + (int64_t)threadIdx.x * per;
-  const int64_t hi = lo + per < c1 ? lo + per : c1;
+  const int64_t lo = c0 + (int64_t)threadIdx.x * SCAN_WORDS_PER_THREAD;
+  const int64_t hi = lo + SCAN_WORDS_PER_THREAD < c1 ? lo + SCAN_WORDS_PER_THREAD : c1;
+  uint32_t each[SCAN_WORDS_PER_THREAD];
   uint32_t cnt = 0;
-  for (int64_t w = lo; w < hi; ++w) cnt += erased_in_word(mask[w], w, n);
+#pragma unroll
+  for (int j = 0; j < SCAN_WORDS_PER_THREAD; ++j) {
+    each[j] = lo + j < hi ? erased_in_word(mask[lo + j], lo + j, n) : 0u;
+    cnt += each[j];
+  }
   red[threadIdx.x] = cnt;
   __syncthreads();
   for (int off = 1; off < SCAN_THREADS; off <<= 1) {  // inclusive Hillis-Steele scan
@@ -395,25 +434,37 @@ __device__ __forceinline__ void frag_offsets_chunk(const uint64_t* __restrict__ 
     __syncthreads();
   }
   uint32_t run = before + red[threadIdx.x] - cnt;
-  for (int64_t w = lo; w < hi; ++w) {
-    offsets[w] = run;
-    run += erased_in_word(mask[w], w, n);
+#pragma unroll
+  for (int j = 0; j < SCAN_WORDS_PER_THREAD; ++j) {
+    if (lo + j < hi) offsets[lo + j] = run;
+    run += each[j];
   }
   if (c1 == n_words && threadIdx.x == SCAN_THREADS - 1) offsets[n_words] = before + red[SCAN_THREADS - 1];
 }
 
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets, int64_t chunk) {
+k_frag_chunk_sums(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ sums) {
   __shared__ uint32_t red[SCAN_THREADS];
-  frag_offsets_chunk(mask, n, offsets, chunk, red);
+  frag_chunk_sum(mask, n, sums, red);
 }
 
-// The same for several layers in one launch: blockIdx.y selects the layer.
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_frag_offsets_layers(const FragLayer* __restrict__ layers, int64_t chunk) {
+k_frag_offsets(const uint64_t* __restrict__ mask, int64_t n, uint32_t* __restrict__ offsets, const uint32_t* __restrict__ sums) {
+  __shared__ uint32_t red[SCAN_THREADS];
+  frag_offsets_chunk(mask, n, offsets, sums, red);
+}
+
+// The same for several layers in one launch each: blockIdx.y selects the layer.
+__global__ void __launch_bounds__(SCAN_THREADS) k_frag_chunk_sums_layers(const FragLayer* __restrict__ layers) {
   __shared__ uint32_t red[SCAN_THREADS];
   const FragLayer l = layers[blockIdx.y];
-  frag_offsets_chunk(l.mask, l.n, l.offsets, chunk, red);
+  frag_chunk_sum(l.mask, l.n, l.sums, red);
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) k_frag_offsets_layers(const FragLayer* __restrict__ layers) {
+  __shared__ uint32_t red[SCAN_THREADS];
+  const FragLayer l = layers[blockIdx.y];
+  frag_offsets_chunk(l.mask, l.n, l.offsets, l.sums, red);
 }
 
 // Layer bases: exclusive scan of the erased counts in the order given (reverse-pass order).
@@ -565,33 +616,33 @@ k_colsum(const float* __restrict__ a, int64_t rows, int64_t rows_per_block, int 
 }
 
 // The same with 128-bit accesses, for d % 4 == 0 and a 16-byte aligned matrix: a workgroup takes 128
-// columns (32 lanes x 4) and splits its row range over 8 lanes of rows; each thread has four rows in
+// columns (32 lanes x 4) and splits its row range over 8 lanes of rows; each thread has eight rows in
 // flight and adds them in row order; the 8 partial sums are combined in LDS in a fixed order.
-constexpr int COLSUM4_QUADS = 32, COLSUM4_SPLIT = 8;
+constexpr int COLSUM4_QUADS = 32, COLSUM4_SPLIT = 8, COLSUM4_ROWS = 8;
+constexpr int COLSUM4_BLOCK_ROWS = COLSUM4_SPLIT * COLSUM4_ROWS;  // rows one workgroup takes per trip
+// Workgroup (bx, by) takes the row blocks by, by + gridDim.y, ... of COLSUM4_BLOCK_ROWS rows each (so the
+// workgroups running at one time read one compact stretch of the matrix); inside a block row lane s takes the
+// rows s, s + 8, ... (the two row lanes of a wavefront read neighbouring rows), eight of them in flight, added in
+// row order. rows_per_block is unused here (the slice count alone fixes the order of the sums).
 __global__ void __launch_bounds__(COLSUM4_QUADS* COLSUM4_SPLIT)
-k_colsum_v4(const float* __restrict__ a, int64_t rows, int64_t rows_per_block, int d, float scale, float* __restrict__ out) {
+k_colsum_v4(const float* __restrict__ a, int64_t rows, int64_t /*rows_per_block*/, int d, float scale, float* __restrict__ out) {
   __shared__ f4v part[COLSUM4_SPLIT][COLSUM4_QUADS];
   const int q = threadIdx.x % COLSUM4_QUADS, s = threadIdx.x / COLSUM4_QUADS;
   const int col = 4 * (blockIdx.x * COLSUM4_QUADS + q);
-  const int64_t first = (int64_t)blockIdx.y * rows_per_block;
-  const int64_t last = first + rows_per_block < rows ? first + rows_per_block : rows;
-  const int64_t per = (last - first + COLSUM4_SPLIT - 1) / COLSUM4_SPLIT;
-  const int64_t lo = first + s * per, hi = lo + per < last ? lo + per : last;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   if (col < d) {
     const float* p = a + col;
-    int64_t r = lo;
-    for (; r + 4 <= hi; r += 4) {
-      const f4v v0 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + r * d));
-      const f4v v1 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + (r + 1) * d));
-      const f4v v2 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + (r + 2) * d));
-      const f4v v3 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + (r + 3) * d));
-      acc += v0;
-      acc += v1;
-      acc += v2;
-      acc += v3;
+    for (int64_t r0 = (int64_t)blockIdx.y * COLSUM4_BLOCK_ROWS; r0 < rows; r0 += (int64_t)gridDim.y * COLSUM4_BLOCK_ROWS) {
+      f4v v[COLSUM4_ROWS];
+#pragma unroll
+      for (int j = 0; j < COLSUM4_ROWS; ++j) {
+        const int64_t r = r0 + s + (int64_t)j * COLSUM4_SPLIT;
+        v[j] = f4v{0.f, 0.f, 0.f, 0.f};
+        if (r < rows) v[j] = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + r * d));
+      }
+#pragma unroll
+      for (int j = 0; j < COLSUM4_ROWS; ++j) acc += v[j];
     }
-    for (; r < hi; ++r) acc += __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p + r * d));
   }
   part[s][q] = acc;
   __syncthreads();
@@ -607,15 +658,24 @@ k_colsum_v4(const float* __restrict__ a, int64_t rows, int64_t rows_per_block, i
 // one memory round trip at a time: REDUCE_GROUPS threads share an element, thread g adds the slices
 // g, g + REDUCE_GROUPS, ... and the group sums are added in group order. (A different, equally fixed,
 // association of the same terms.)
-constexpr int REDUCE_ELEMS = 16, REDUCE_GROUPS = 16;
+constexpr int REDUCE_ELEMS = 4, REDUCE_GROUPS = 64;
 __global__ void __launch_bounds__(REDUCE_ELEMS* REDUCE_GROUPS)
 k_reduce_slices_short(const float* __restrict__ part, int slices, int64_t n, float scale, float beta, float* __restrict__ out) {
   __shared__ float sums[REDUCE_GROUPS][REDUCE_ELEMS];
   const int e = threadIdx.x % REDUCE_ELEMS, g = threadIdx.x / REDUCE_ELEMS;
   const int64_t i = (int64_t)blockIdx.x * REDUCE_ELEMS + e;
   float t = 0.f;
-  if (i < n)
-    for (int k = g; k < slices; k += REDUCE_GROUPS) t += part[(int64_t)k * n + i];
+  if (i < n) {
+    int k = g;
+    for (; k + 7 * REDUCE_GROUPS < slices; k += 8 * REDUCE_GROUPS) {  // eight slices in flight, added in slice order
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = part[(int64_t)(k + j * REDUCE_GROUPS) * n + i];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) t += v[j];
+    }
+    for (; k < slices; k += REDUCE_GROUPS) t += part[(int64_t)k * n + i];
+  }
   sums[g][e] = t;
   __syncthreads();
   if (g == 0 && i < n) {
@@ -657,40 +717,40 @@ k_reduce_slices(const float* __restrict__ part, int slices, int64_t n, float sca
 }
 
 // ---------------------------------------------------------------- loss value and output cotangent
+constexpr int LOSS_UNROLL = 4;
 __global__ void __launch_bounds__(EW_THREADS)
 k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n, float cot_scale,
             float* __restrict__ hL, double* __restrict__ partial, int vec) {
-  __shared__ double red[EW_THREADS];
+  __shared__ double red[EW_WAVES];
   double acc = 0.0;
   const int64_t tid = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x, stride = (int64_t)gridDim.x * EW_THREADS;
   int64_t done = 0;
   if (vec) {  // all three arrays 16-byte aligned
     const int64_t n4 = n >> 2;
-    // two quads in flight per thread, taken in the order q, q + stride, ...: the sum a thread forms does
-    // not depend on how many are in flight
-    for (int64_t q = tid; q < n4; q += 2 * stride) {
-      const int64_t q1 = q + stride;
-      const bool two = q1 < n4;
-      const f4v a0 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(xL + 4 * q));
-      const f4v b0 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(t + 4 * q));
-      f4v a1 = {0.f, 0.f, 0.f, 0.f}, b1 = a1;
-      if (two) {
-        a1 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(xL + 4 * q1));
-        b1 = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(t + 4 * q1));
+    // a wavefront takes LOSS_UNROLL KiB of each array per trip (one contiguous stretch: a thread's quads are 64
+    // quads apart), all of it in flight before the first use; the trips of all wavefronts interleave
+    const int lane = threadIdx.x & 63;
+    for (int64_t q = global_wave() * (64 * LOSS_UNROLL) + lane; q - lane < n4; q += total_waves() * (64 * LOSS_UNROLL)) {
+      f4v a[LOSS_UNROLL], b[LOSS_UNROLL];
+#pragma unroll
+      for (int u = 0; u < LOSS_UNROLL; ++u) {
+        const int64_t qu = q + u * 64;
+        a[u] = f4v{0.f, 0.f, 0.f, 0.f};
+        b[u] = a[u];
+        if (qu < n4) {
+          a[u] = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(xL + 4 * qu));
+          b[u] = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(t + 4 * qu));
+        }
       }
-      const f4v r = a0 - b0;
-      __builtin_nontemporal_store(r * cot_scale, reinterpret_cast<f4v*>(hL + 4 * q));
-      acc += (double)r.x * (double)r.x;
-      acc += (double)r.y * (double)r.y;
-      acc += (double)r.z * (double)r.z;
-      acc += (double)r.w * (double)r.w;
-      if (two) {
-        const f4v r1 = a1 - b1;
-        __builtin_nontemporal_store(r1 * cot_scale, reinterpret_cast<f4v*>(hL + 4 * q1));
-        acc += (double)r1.x * (double)r1.x;
-        acc += (double)r1.y * (double)r1.y;
-        acc += (double)r1.z * (double)r1.z;
-        acc += (double)r1.w * (double)r1.w;
+#pragma unroll
+      for (int u = 0; u < LOSS_UNROLL; ++u) {
+        const int64_t qu = q + u * 64;
+        if (qu < n4) {
+          const f4v r = a[u] - b[u];
+          __builtin_nontemporal_store(r * cot_scale, reinterpret_cast<f4v*>(hL + 4 * qu));
+          acc += (double)r.x * (double)r.x + (double)r.y * (double)r.y;
+          acc += (double)r.z * (double)r.z + (double)r.w * (double)r.w;
+        }
       }
     }
     done = n4 << 2;
@@ -700,13 +760,16 @@ k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n
     hL[e] = cot_scale * r;
     acc += (double)r * (double)r;
   }
-  red[threadIdx.x] = acc;
+  // fixed tree: lanes of a wavefront by halving distances, then the wavefronts in order
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
   __syncthreads();
-  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
-    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = red[0];
+    for (int w = 1; w < EW_WAVES; ++w) s += red[w];
+    partial[blockIdx.x] = s;
   }
-  if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
 // Sum of the per-workgroup partials in a fixed order (thread t takes partials t, t + 256, ...;
@@ -953,26 +1016,32 @@ hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float a
   return hipGetLastError();
 }
 
-hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream) {
+size_t ew_frag_scan_words(int64_t n) {
+  const int64_t n_words = n > 0 ? (n + 63) >> 6 : 0;
+  const int64_t chunks = (n_words + SCAN_CHUNK_WORDS - 1) / SCAN_CHUNK_WORDS;
+  return (size_t)(chunks < 1 ? 1 : chunks);
+}
+
+hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, uint32_t* sums, hipStream_t stream) {
   if (n < 0) return hipErrorInvalidValue;
-  const int64_t n_words = (n + 63) >> 6;
-  int64_t chunk = (int64_t)SCAN_THREADS * SCAN_WORDS_PER_THREAD;
-  if (chunk * SCAN_MAX_BLOCKS < n_words) chunk = (n_words + SCAN_MAX_BLOCKS - 1) / SCAN_MAX_BLOCKS;
-  int blocks = (int)((n_words + chunk - 1) / chunk);
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(k_frag_offsets, dim3(blocks), dim3(SCAN_THREADS), 0, stream, mask, n, offsets, chunk);
+  const size_t chunks = ew_frag_scan_words(n);
+  if (chunks > 0x7FFFFFFFu) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_frag_chunk_sums, dim3((unsigned)chunks), dim3(SCAN_THREADS), 0, stream, mask, n, sums);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_frag_offsets, dim3((unsigned)chunks), dim3(SCAN_THREADS), 0, stream, mask, n, offsets, sums);
   return hipGetLastError();
 }
 
 hipError_t ew_frag_offsets_layers(const FragLayer* layers, int n_layers, int64_t max_n, hipStream_t stream) {
   if (n_layers <= 0) return hipSuccess;
   if (max_n < 0 || n_layers > 65535) return hipErrorInvalidValue;
-  const int64_t n_words = (max_n + 63) >> 6;
-  int64_t chunk = (int64_t)SCAN_THREADS * SCAN_WORDS_PER_THREAD;
-  if (chunk * SCAN_MAX_BLOCKS < n_words) chunk = (n_words + SCAN_MAX_BLOCKS - 1) / SCAN_MAX_BLOCKS;
-  int blocks = (int)((n_words + chunk - 1) / chunk);
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(k_frag_offsets_layers, dim3(blocks, n_layers), dim3(SCAN_THREADS), 0, stream, layers, chunk);
+  const size_t chunks = ew_frag_scan_words(max_n);
+  if (chunks > 0x7FFFFFFFu) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_frag_chunk_sums_layers, dim3((unsigned)chunks, n_layers), dim3(SCAN_THREADS), 0, stream, layers);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_frag_offsets_layers, dim3((unsigned)chunks, n_layers), dim3(SCAN_THREADS), 0, stream, layers);
   return hipGetLastError();
 }
 
@@ -1115,7 +1184,7 @@ hipError_t ew_colsum_wide_static(const float* a, int64_t rows, int d, float scal
 
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream) {
   if (n <= 0 || slices <= 0) return hipSuccess;
-  if (n <= 8192 && slices >= 2 * REDUCE_GROUPS) {
+  if (n <= 8192 && slices >= 32) {
     hipLaunchKernelGGL(k_reduce_slices_short, dim3((unsigned)((n + REDUCE_ELEMS - 1) / REDUCE_ELEMS)),
                        dim3(REDUCE_ELEMS * REDUCE_GROUPS), 0, stream, part, slices, n, scale, beta, out);
     return hipGetLastError();
@@ -1135,7 +1204,8 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
   // correctly rounded scale/rows either way
   float cot_scale = scale / (float)rows;
   const int vec = al16(xL) && al16(t) && al16(hL);
-  int64_t want = ((vec ? (n + 3) / 4 : n) + EW_THREADS - 1) / EW_THREADS;
+  // one workgroup per LOSS_UNROLL quads per thread, up to LOSS_BLOCKS of them (64 per CU)
+  int64_t want = ((vec ? (n + 3) / 4 : n) + (int64_t)EW_THREADS * LOSS_UNROLL - 1) / ((int64_t)EW_THREADS * LOSS_UNROLL);
   const int blocks = (int)(want < 1 ? 1 : (want > LOSS_BLOCKS ? LOSS_BLOCKS : want));
   hipLaunchKernelGGL(k_loss_grad, dim3(blocks), dim3(EW_THREADS), 0, stream, xL, t, n, cot_scale, hL, scratch, vec);
   hipError_t e = hipGetLastError();

@@ -489,10 +489,13 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
             l.relu_slot = slot++;
             ptrs.push_back(l.offsets + l.mask_words);
             const int64_t n = (int64_t)(B * l.d_out);
-            table.push_back(FragLayer{l.mask, l.offsets, n});
+            uint32_t* sums = nullptr;
+            ok = ok && alloc_t(h, &sums, ew_frag_scan_words(n), &st.bytes_frag_index);
+            table.push_back(FragLayer{l.mask, l.offsets, n, sums});
             if (n > h->frag_max_n) h->frag_max_n = n;
           }
         }
+        if (!ok) return fail(MW_ERR_OOM);
         e = hipMemcpy(h->count_ptrs, ptrs.data(), ptrs.size() * sizeof(ptrs[0]), hipMemcpyHostToDevice);
         if (e == hipSuccess) e = hipMemcpy(h->frag_layers, table.data(), table.size() * sizeof(table[0]), hipMemcpyHostToDevice);
         if (e != hipSuccess) return fail(hip_fail(e, "fragment index init"));
@@ -1310,10 +1313,12 @@ int mw_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, f
   return MW_OK;
 }
 
-int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, void* hip_stream) {
-  if (n < 0 || !offsets || (n > 0 && !mask)) return MW_ERR_INVALID_ARG;
+size_t mw_frag_offsets_work_words(int64_t n) { return ew_frag_scan_words(n); }
+
+int mw_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, uint32_t* work, void* hip_stream) {
+  if (n < 0 || !offsets || !work || (n > 0 && !mask)) return MW_ERR_INVALID_ARG;
   if (n > (int64_t)0xFFFFFFFFll) return MW_ERR_INVALID_ARG;
-  MW_HIP(ew_frag_offsets(mask, n, offsets, static_cast<hipStream_t>(hip_stream)));
+  MW_HIP(ew_frag_offsets(mask, n, offsets, work, static_cast<hipStream_t>(hip_stream)));
   return MW_OK;
 }
 

@@ -131,12 +131,15 @@ hipError_t ew_bias_act_mask(const float* zin, const float* bias, int64_t rows, i
 hipError_t ew_mask_from_act(const float* x, int64_t n, uint64_t* mask, hipStream_t stream);
 hipError_t ew_rev_scale(const float* h, const uint64_t* mask, int64_t n, float alpha, float* ct_z,
                         hipStream_t stream);
-hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, hipStream_t stream);
-// the same scan for several layers in one launch; `layers` is a device array, max_n the largest n in it
+// a two-level scan (two launches); sums: ew_frag_scan_words(n) device words of scratch
+size_t ew_frag_scan_words(int64_t n);
+hipError_t ew_frag_offsets(const uint64_t* mask, int64_t n, uint32_t* offsets, uint32_t* sums, hipStream_t stream);
+// the same scan for several layers in the same two launches; `layers` is a device array, max_n the largest n in it
 struct FragLayer {
   const uint64_t* mask;
   uint32_t* offsets;   // [ceil(n / 64) + 1]
   int64_t n;
+  uint32_t* sums;      // [ew_frag_scan_words(n)] scratch
 };
 hipError_t ew_frag_offsets_layers(const FragLayer* layers, int n_layers, int64_t max_n, hipStream_t stream);
 // base[i] for the ReLU layers in reverse-pass order: order[j] lists layer slots, counts[slot] points at
@@ -163,7 +166,7 @@ hipError_t ew_colsum_wide_static(const float* a, int64_t rows, int d, float scal
                                  bool* too_large);
 // out[i] = scale * (sum over the slices of part[.][i], in an order fixed by slices and n) + beta * out[i]; part is [slices][n]
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream);
-constexpr int LOSS_BLOCKS = 2048;  // most workgroups (and scratch doubles) the loss reduction uses
+constexpr int LOSS_BLOCKS = 16384;  // most workgroups (and scratch doubles) the loss reduction uses
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
                         double* scratch, hipStream_t stream);
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);

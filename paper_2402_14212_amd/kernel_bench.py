@@ -108,10 +108,11 @@ def bench_elementwise(iters, max_log2):
         # Phase II scaling: read h and 1 bit, write ct_z
         report("rev_scale", 8.125, timed(lambda i: lib.mw_rev_scale(P(hs[i % pool]), P(mask), n, 0.1, P(x), stream), iters))
         # fragment index (integer scan over the mask words only)
-        if n <= (1 << 24):   # fragment kernels: up to the largest layer of the configurations (B * d = 2^22)
-            lib.mw_frag_offsets(P(mask), n, P(off), stream)
+        if n <= (1 << 28):   # fragment kernels (the largest layer of the configurations has B * d = 2^22)
+            swork = torch.empty(int(lib.mw_frag_offsets_work_words(n)), dtype=torch.int32, device="cuda")
+            lib.mw_frag_offsets(P(mask), n, P(off), P(swork), stream)
             report("frag_offsets", 0.125 + 0.0625,
-                   timed(lambda i: lib.mw_frag_offsets(P(mask), n, P(off), stream), max(3, iters // 4)))
+                   timed(lambda i: lib.mw_frag_offsets(P(mask), n, P(off), P(swork), stream), iters))
             # compaction: read h, 1 bit, offsets; write the erased half
             frac0 = 1.0 - float(torch.mean((zs[0] > 0).float()))
             report("frag_compact", 4 + 0.125 + 0.0625 + 4 * frac0,

@@ -140,6 +140,7 @@ int moonwalk_refresh(mw_handle_t* h, void* hip_stream);
  *   P_0 = (P P^T) W_new            (P P^T = (W_old W_old^T)^{-1}: first-order guess whose rows lie
  *                                   in the row space of W_new, so every iterate below is the
  *                                   minimum-norm right inverse of its own residual equation)
+ *                                   (a square layer has one inverse and no row space to stay in: P_0 = P)
  *   P_{k+1} = (2 I - P_k W_new^T) P_k,  k = 0 .. iters-1   (Newton-Schulz: I - P W^T squares each time)
  * Plain GEMMs on the given stream; does not synchronise. iters in 0..16. residual_out (device float
  * or NULL) receives max over layers of ||I - P W^T||_F measured BEFORE the last iteration (after it

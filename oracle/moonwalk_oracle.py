@@ -161,13 +161,16 @@ def newton_schulz_refresh(W_new, P_old, iters: int):
 
     Every iterate is a left multiple of W_new, so the limit is the minimum-norm right inverse
     (W_new W_new^T)^{-1} W_new, and the residual R_k = I - P_k W_new^T obeys R_{k+1} = R_k^2.
+    A square layer has one inverse only and no row space to stay in: there the iteration starts from
+    P_0 = P_old itself (residual -P_old dW^T, of the size of the update), which saves the two products
+    of the start.
     Returns (P, residuals) with residuals[k] = ||I - P_k W_new^T||_F for k = 0 .. iters.
     """
     W = _as64(W_new)
     P_old = _as64(P_old)
     n = W.shape[0]
     eye = np.eye(n)
-    P = (P_old @ P_old.T) @ W
+    P = P_old.copy() if W.shape[0] == W.shape[1] else (P_old @ P_old.T) @ W
     residuals = [float(np.linalg.norm(eye - P @ W.T))]
     for _ in range(int(iters)):
         E = P @ W.T

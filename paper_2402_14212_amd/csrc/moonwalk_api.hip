@@ -984,6 +984,7 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
 // P <- right inverse of the CURRENT W, starting from the P held (right inverse of nearby weights):
 //   P_0 = (P P^T) W            P P^T = (W_old W_old^T)^{-1}: a first-order guess whose rows lie in the
 //                              row space of the new W, so that every iterate stays the minimum-norm one
+//                              (a square layer has one inverse only: there P_0 = P, no start products)
 //   P_{k+1} = (2 I - P_k W^T) P_k     Newton-Schulz; the residual I - P W^T squares per iteration
 // Consecutive layers of one shape are refreshed side by side, as many (up to REFRESH_SETS) as it takes to
 // fill the chip with 128 x 128 tiles: each step is then one grouped product over all of them (a
@@ -995,10 +996,14 @@ int refresh_one_layer(mw_handle* h, Layer& l, int iters, float* residual_out, hi
   const int n = l.d_out, m = l.d_in;
   float* S = h->refresh_work;
   float* Q = S + (((size_t)n * n + 63) / 64) * 64;
-  MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, l.P, m, l.P, m, 0.f, S, n, nullptr, s));
   float* cur = (iters % 2 == 1) ? Q : l.P;
   float* other = (cur == Q) ? l.P : Q;
-  MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, 1.f, S, n, l.W, m, 0.f, cur, m, nullptr, s));
+  if (n == m) {  // a square layer starts from the inverse it has
+    if (cur != l.P) MW_HIP(ew_copy(l.P, cur, (int64_t)n * m, s));
+  } else {
+    MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, l.P, m, l.P, m, 0.f, S, n, nullptr, s));
+    MW_HIP(gemm_plain(OP_NN, TILE_AUTO, n, m, n, 1.f, S, n, l.W, m, 0.f, cur, m, nullptr, s));
+  }
   for (int it = 0; it < iters; ++it) {
     MW_HIP(gemm_plain(OP_NT, TILE_AUTO, n, n, m, 1.f, cur, m, l.W, m, 0.f, S, n, nullptr, s));
     if (residual_out && it == iters - 1) MW_HIP(ew_identity_residual(S, n, h->loss_scratch, residual_out, s));
@@ -1079,10 +1084,16 @@ int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStrea
       const float* const* Wt = h->refresh_tab + L + l0;
       const float* const* St = h->refresh_tab + r.tab_off;
       const float* const* Qt = St + r.sets;
-      MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, Pt, m, Pt, m, 0.f, nullptr, out(St), n, s));
       const float* const* cur = (iters % 2 == 1) ? Qt : Pt;
       const float* const* other = (cur == Qt) ? Pt : Qt;
-      MW_HIP(gemm_grouped(OP_NN, g, n, m, n, 1.f, St, n, Wt, m, 0.f, nullptr, out(cur), m, s));
+      if (n == m) {  // square layers start from the inverses they have
+        if (cur != Pt)
+          for (int j = 0; j < g; ++j)
+            MW_HIP(ew_copy(h->layers[l0 + j].P, h->refresh_work + (size_t)j * r.slot + r.q_off, (int64_t)n * m, s));
+      } else {
+        MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, Pt, m, Pt, m, 0.f, nullptr, out(St), n, s));
+        MW_HIP(gemm_grouped(OP_NN, g, n, m, n, 1.f, St, n, Wt, m, 0.f, nullptr, out(cur), m, s));
+      }
       for (int it = 0; it < iters; ++it) {
         MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, cur, m, Wt, m, 0.f, nullptr, out(St), n, s));
         if (residual_out && it == iters - 1)

@@ -331,6 +331,24 @@ def test_newton_schulz_refresh_squares_the_residual_and_reaches_the_pseudo_inver
     assert np.linalg.norm(P0 @ proj_null) < 1e-12
 
 
+def test_newton_schulz_refresh_of_a_square_layer_starts_from_the_old_inverse():
+    """Square W: P_0 = P_old, residual -P_old dW^T (first order in the update), squared by every iteration,
+    limit = the inverse (library routine inv)."""
+    rng = np.random.default_rng(8)
+    wl = make_mlp([16, 16], batch=4, alpha=0.1, seed=12)
+    W_old = wl.W[0].astype(np.float64)
+    dW = 1e-2 * rng.standard_normal(W_old.shape) / np.sqrt(W_old.shape[1])
+    W_new = W_old + dW
+    P_old = O.right_inverse(W_old)
+    P0, res0 = O.newton_schulz_refresh(W_new, P_old, iters=0)
+    assert np.array_equal(P0, P_old)
+    assert res0[0] == pytest.approx(np.linalg.norm(P_old @ dW.T), rel=1e-9)
+    P, res = O.newton_schulz_refresh(W_new, P_old, iters=4)
+    for k in range(3):
+        assert res[k + 1] <= res[k] ** 2 * (1 + 1e-9) + 1e-15
+    assert np.allclose(P, np.linalg.inv(W_new).T, atol=1e-12, rtol=0)
+
+
 def test_newton_schulz_zero_iterations_is_first_order_accurate():
     """P_0 - P_new = O(||dW||): halving the perturbation halves the error."""
     rng = np.random.default_rng(6)

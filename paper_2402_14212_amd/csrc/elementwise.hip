@@ -850,41 +850,70 @@ k_identity_residual_final(const double* __restrict__ partial, int n_partial, flo
 // in partial[j * gridDim.x ..]; the final kernel folds the largest of the residuals into *out.
 __global__ void __launch_bounds__(EW_THREADS)
 k_identity_residual_sets(const float* __restrict__ E, int64_t stride, int n, double* __restrict__ partial) {
-  __shared__ double red[EW_THREADS];
+  __shared__ double red[EW_WAVES];
   const float* Ej = E + (int64_t)blockIdx.y * stride;
   const int64_t total = (int64_t)n * n;
   double acc = 0.0;
-  for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < total; e += (int64_t)gridDim.x * EW_THREADS) {
-    const int64_t r = e / n, c = e - r * n;
-    const float d = Ej[e] - (r == c ? 1.f : 0.f);
-    acc += (double)d * (double)d;
+  // whole rows are dealt to the threads in runs of four elements when the rows allow it (no division per element)
+  if (n % 4 == 0 && ((uintptr_t)Ej & 15) == 0 && total < ((int64_t)1 << 31)) {
+    const uint32_t quads = (uint32_t)(total >> 2), per_row = (uint32_t)n >> 2;
+    for (uint32_t q = blockIdx.x * EW_THREADS + threadIdx.x; q < quads; q += gridDim.x * EW_THREADS) {
+      const uint32_t r = q / per_row, c = 4u * (q - r * per_row);
+      const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(Ej) + q);
+      const float d0 = v.x - (r == c ? 1.f : 0.f), d1 = v.y - (r == c + 1 ? 1.f : 0.f), d2 = v.z - (r == c + 2 ? 1.f : 0.f),
+                  d3 = v.w - (r == c + 3 ? 1.f : 0.f);
+      acc += (double)d0 * (double)d0 + (double)d1 * (double)d1;
+      acc += (double)d2 * (double)d2 + (double)d3 * (double)d3;
+    }
+  } else {
+    for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < total; e += (int64_t)gridDim.x * EW_THREADS) {
+      const int64_t r = e / n, c = e - r * n;
+      const float d = Ej[e] - (r == c ? 1.f : 0.f);
+      acc += (double)d * (double)d;
+    }
   }
-  red[threadIdx.x] = acc;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
   __syncthreads();
-  for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
-    if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = red[0];
+    for (int w = 1; w < EW_WAVES; ++w) t += red[w];
+    partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = t;
   }
-  if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = red[0];
 }
 
+// one wavefront per matrix (in turns), a fixed tree inside it
 __global__ void __launch_bounds__(EW_THREADS)
 k_identity_residual_sets_final(const double* __restrict__ partial, int n_partial, int n_sets, float* __restrict__ out) {
-  __shared__ double red[EW_THREADS];
-  for (int j = 0; j < n_sets; ++j) {
+  __shared__ float worst[EW_WAVES];
+  __shared__ int any_nan[EW_WAVES];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float w = 0.f;
+  int bad = 0;
+  for (int j = wave; j < n_sets; j += EW_WAVES) {
     double acc = 0.0;
-    for (int i = threadIdx.x; i < n_partial; i += EW_THREADS) acc += partial[(int64_t)j * n_partial + i];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = EW_THREADS / 2; s > 0; s >>= 1) {
-      if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
-      __syncthreads();
+    for (int i = lane; i < n_partial; i += 64) acc += partial[(int64_t)j * n_partial + i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off);
+    const float r = (float)sqrt(acc);
+    if (r != r) bad = 1;
+    else if (r > w) w = r;
+  }
+  if (lane == 0) {
+    worst[wave] = w;
+    any_nan[wave] = bad;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float r = worst[0];
+    int nan = any_nan[0];
+    for (int k = 1; k < EW_WAVES; ++k) {
+      if (worst[k] > r) r = worst[k];
+      nan |= any_nan[k];
     }
-    if (threadIdx.x == 0) {
-      const float r = (float)sqrt(red[0]);
-      if (!(r <= *out)) *out = r;  // running maximum; a NaN residual is kept
-    }
-    __syncthreads();
+    if (nan) r = __builtin_nanf("");
+    if (!(r <= *out)) *out = r;  // running maximum; a NaN residual is kept
   }
 }
 
@@ -1241,7 +1270,8 @@ hipError_t ew_identity_residual_sets(const float* E, int64_t stride, int n_sets,
   if (n <= 0 || n_sets <= 0) return hipSuccess;
   if (n_sets > LOSS_BLOCKS) return hipErrorInvalidValue;
   int64_t want = ((int64_t)n * n + EW_THREADS - 1) / EW_THREADS;
-  const int64_t cap = LOSS_BLOCKS / n_sets;  // the scratch holds LOSS_BLOCKS doubles in all
+  int64_t cap = LOSS_BLOCKS / n_sets;  // the scratch holds LOSS_BLOCKS doubles in all
+  if (cap > 256) cap = 256;            // a workgroup per CU and matrix is plenty; the final kernel reads them all
   const int blocks = (int)(want > cap ? cap : want);
   hipLaunchKernelGGL(k_identity_residual_sets, dim3(blocks, n_sets), dim3(EW_THREADS), 0, stream, E, stride, n, scratch);
   hipError_t e = hipGetLastError();

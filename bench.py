@@ -22,11 +22,12 @@ sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
 
-# Bytes that cross the L2 per Phase-III launch (layer kernel + previous layer's weight gradient), from
-# the two rocprofv3 --pmc runs summarised in profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE
-# 17147.5 KiB scaled x2.0 by the copy-kernel calibration, WRITE_SIZE 7172.0 KiB scaled x1.0). Offline
-# counters: known only for the default workload with its default re-seed interval, null otherwise.
-PHASE3_TRAFFIC_BYTES = {"deep_square": int(17147.5 * 1024 * 2.0 + 7172.0 * 1024 * 1.0)}
+# Bytes that cross the L2 per Phase-III launch (the layer kernels of four stretches + the weight gradients of the
+# position before; average over the 17 launches of a step), from the two rocprofv3 --pmc runs summarised in
+# profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE 40748.4 KiB scaled x2.0 by the copy-kernel calibration,
+# WRITE_SIZE 27000.5 KiB scaled x1.0). Offline counters: known only for the default workload in its default
+# launch configuration (re-seed interval, group width), null otherwise.
+PHASE3_TRAFFIC_BYTES = {"deep_square": int(40748.4 * 1024 * 2.0 + 27000.5 * 1024 * 1.0)}
 
 
 def parse():
@@ -296,7 +297,11 @@ def main():
     # dominant kernel: the paired Phase-III launch; in unfused runs (no layer kernel at all) the plain
     # GEMM that serves Phase I and both Phase-III products, three launches per layer
     if per_class["phase3"]["launches_per_step"]:
+        grouped = net.memory_stats()["phase3_group_width"]
         dom, dom_flops, dom_name = "phase3", class_flops["phase3"], (
+            ("task_pair_kernel_resident<GroupedVijpTask, GroupedDwTask> (Phase-III launch: one layer position of up to %d "
+             "stretches side by side = recompute + vijp + epilogue each, plus the weight-gradient GEMMs of the position "
+             "before)" % grouped) if grouped > 1 else
             "task_pair_kernel (Phase-III launch: layer kernel = recompute + vijp + epilogue, plus the previous "
             "layer's weight-gradient GEMM)")
     elif per_class["vijp"]["launches_per_step"]:
@@ -312,7 +317,7 @@ def main():
                 "kernel": dom_name,
                 "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_F32_PEAK_TFLOPS,
-                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and not args.segment and dom == "phase3" else None,
+                "traffic": PHASE3_TRAFFIC_BYTES.get(args.config) if args.depth is None and args.reseed is None and not args.segment and dom == "phase3" and args.group == 0 else None,
                 "avg_launch_ms": avg_ms, "launches": n_v * prof_steps,
                 "flop_per_launch": flop_per_launch}
     # --- training step in place (gradients applied as Phase III produces them, then the right inverses

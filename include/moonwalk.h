@@ -111,7 +111,7 @@ typedef struct {
   uint64_t frag_used;           /* erased cotangents stored by the last moonwalk_grad                 */
   uint64_t sign_mismatches;     /* phase-III signs that differed from the stored masks (must be 0)    */
   int32_t  frag_overflow;       /* 1 if the last moonwalk_grad overflowed the fragment store          */
-  int32_t  reserved;
+  int32_t  phase3_group_width;  /* most stretches Phase III sweeps in one launch (cfg.phase3_parallel_segments as planned); 0: one layer per launch */
   uint64_t bytes_debug;         /* cfg.debug_keep: the kept z_i and cotangents                          */
 } mw_memstats_t;
 

@@ -85,7 +85,7 @@ class _MemStats(C.Structure):
         "bytes_P", "bytes_masks", "bytes_fragments", "bytes_frag_index", "bytes_checkpoints",
         "bytes_mw_scratch", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak",
         "bytes_setup_peak", "frag_used", "sign_mismatches")] + [("frag_overflow", C.c_int32),
-                                                                 ("reserved", C.c_int32),
+                                                                 ("phase3_group_width", C.c_int32),
                                                                  ("bytes_debug", C.c_uint64)]
 
 

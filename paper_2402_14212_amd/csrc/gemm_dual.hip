@@ -96,6 +96,7 @@ template <bool RELU>
 static GroupedVijpTask<Tile64, RELU, 4> make_grouped_vijp(int n, const VijpArgs* v, int M, int N, int K) {
   GroupedVijpTask<Tile64, RELU, 4> t{};
   t.n_sets = n;
+  if (n <= 0) return t;  // no workgroups
   t.M = M; t.N = N; t.K = K;
   t.alpha = v[0].alpha;
   t.inv_alpha = v[0].alpha > 0.f ? 1.0f / v[0].alpha : 0.f;
@@ -114,6 +115,7 @@ template <class CfgD>
 static GroupedDwTask<CfgD> make_grouped_dw(int n, const DwArgs* d) {
   GroupedDwTask<CfgD> t{};
   t.n_sets = n;
+  if (n <= 0) return t;  // no workgroups
   t.M = d[0].M; t.N = d[0].N; t.K = d[0].K;
   t.scale = d[0].scale;
   t.beta = d[0].beta;
@@ -129,11 +131,10 @@ static hipError_t group_t(int n_v, const VijpArgs* v, int M, int N, int K, int n
   // MIN_WG workgroups of the layer task must fit a CU side by side (one's loads under the others' matrix
   // work): the register count is held to that share of a SIMD's file. Two is what measures best: the layer task
   // takes 182 registers by itself; squeezed into a third of the file (168) it spills inside its main loop
-  if (n_v > 0 && n_d > 0)
-    return launch_task_pair_resident<Tile64::NT, MIN_WG>(make_grouped_vijp<RELU>(n_v, v, M, N, K),
-                                                         make_grouped_dw<CfgD>(n_d, d), stream);
-  if (n_v > 0) return launch_task_resident<Tile64::NT, MIN_WG>(make_grouped_vijp<RELU>(n_v, v, M, N, K), stream);
-  return launch_task<CfgD::NT>(make_grouped_dw<CfgD>(n_d, d), stream);
+  // one kernel for every launch of the sweep: a group's first launch has no weight gradients yet, the last one
+  // of the step no layer kernels left (an empty task takes no workgroups)
+  return launch_task_pair_resident<Tile64::NT, MIN_WG>(make_grouped_vijp<RELU>(n_v, v, M, N, K),
+                                                       make_grouped_dw<CfgD>(n_d, d), stream);
 }
 
 hipError_t gemm_phase3_group(int n_v, const VijpArgs* v, int M, int N, int K, int n_d, const DwArgs* d, hipStream_t stream) {

@@ -1200,6 +1200,7 @@ int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out) {
   out->frag_used = frag_total;
   out->sign_mismatches = (uint64_t)status[0] | ((uint64_t)status[1] << 32);
   out->frag_overflow = status[2] ? 1 : 0;
+  out->phase3_group_width = h->group_width;
   if (out->frag_overflow) return MW_ERR_FRAG_OVERFLOW;
   if (out->sign_mismatches) return MW_ERR_SIGN_MISMATCH;
   return MW_OK;

@@ -366,8 +366,9 @@ def main():
                                f"alpha {wl.alphas[0]}, reseed K={wl.reseed_interval}, loss_scale {wl.loss_scale:g}, "
                                f"{'unfused' if args.unfused else 'fused'} kernels"
                                + (f", segments of {args.segment} layers" if args.segment else "")
-                               + (f", Phase III of up to {args.group if args.group else 'auto'} stretches side by side"
-                                  f"{' on a second stream under Phase II' if args.overlap else ''}" if args.group != 1 else "")},
+                               + (f", Phase III of up to {st['phase3_group_width']} stretches side by side"
+                                  f"{' on a second stream under Phase II' if args.overlap else ''}"
+                                  if st["phase3_group_width"] > 1 else "")},
         "tflops": flops_mw / (ms_mw * 1e-3) / 1e12,
         "flop_per_step": flops_mw,
         "mfma_frac_whole_step": flops_mw / (ms_mw * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS,

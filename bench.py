@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--overlap", type=int, default=1, choices=[0, 1],
                     help="1: the grouped Phase-III sweeps run on the library's second stream while Phase II goes on")
     ap.add_argument("--no-train", action="store_true", help="skip the timing of the in-place training step")
+    ap.add_argument("--refresh", choices=["fp32", "bf16"], default="bf16",
+                    help="training step only: operand precision of the correction product of the Schulz refresh "
+                         "(the residual it corrects is formed in fp32 either way; the gradient step is fp32 always)")
     ap.add_argument("--unfused", action="store_true", help="plain GEMMs + stand-alone elementwise kernels")
     ap.add_argument("--gen", choices=["numpy", "torch"], default="numpy",
                     help="numpy: host generator (the one the parity tests use); torch: same recipe drawn on the GPU "
@@ -257,7 +260,8 @@ def main():
     # --- Moonwalk handle only (so that its peak memory is its own)
     t0 = time.perf_counter()
     net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, fuse=not args.unfused, segment_length=args.segment,
-                                       phase3_parallel_segments=args.group, phase3_overlap=bool(args.overlap))
+                                       phase3_parallel_segments=args.group, phase3_overlap=bool(args.overlap),
+                                       refresh_bf16=args.refresh == "bf16")
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
     grads = net.new_grads()
@@ -335,11 +339,22 @@ def main():
         torch.cuda.synchronize()
         full_ms = (time.perf_counter() - t0) * 1e3
         train = {"ms_per_step": ms_train, "steps_per_s": 1e3 / ms_train, "refresh_iters": 2,
+                 "refresh_correction_operands": args.refresh,
                  "ms_grad_and_apply": ms_apply, "ms_refresh_incremental": ms_ref, "ms_refresh_full": full_ms,
                  "residual_before_last_iteration": float(resid.item()),
                  "gradient_buffer_bytes_saved": int(net.total_floats) * 4}
     net.close()
     del net
+    if train is not None and args.refresh == "bf16":
+        # the same step with every product of the refresh in fp32, on a handle of its own
+        net = mw.MoonwalkNet.from_workload(wl, plan=mw.PLAN_MOONWALK, segment_length=args.segment,
+                                           phase3_parallel_segments=args.group, phase3_overlap=bool(args.overlap))
+        ms32, _ = time_steps(lambda: net.sgd_step(net.x, net.t, 1e-7, 2, loss, resid), tsteps, 2)
+        ms_ref32, _ = time_steps(lambda: net.refresh_incremental(2, resid), tsteps, 1)
+        train["fp32_refresh"] = {"ms_per_step": ms32, "ms_refresh_incremental": ms_ref32,
+                                 "residual_before_last_iteration": float(resid.item())}
+        net.close()
+        del net
 
     # --- the library's own backprop, timed the same way on a handle of its own
     bp = {}

@@ -93,6 +93,15 @@ typedef struct {
                                re-seed point, and share the machine with the rest of Phase II; the caller's stream
                                waits for them at the end of the call, so the call still looks asynchronous on
                                hip_stream alone. 0: everything on hip_stream, Phase III after Phase II.           */
+  int32_t refresh_precision; /* moonwalk_refresh_incremental / moonwalk_sgd_step. 0: every product of a Schulz iteration in
+                               fp32. 1: the residual R = I - P W^T in fp32 (that difference is where digits are lost),
+                               the correction R P that is then added to P with its operands rounded to bf16 (to nearest
+                               even) in front of the matrix unit, sums and the addition in fp32: the correction is
+                               ||R|| times the size of P, so its 2^-8 relative error is 2^-8 ||R|| of P, and the next
+                               iteration (which measures its residual in fp32 again) takes it out; the residual then
+                               shrinks like R^2 + 2^-8 R per iteration instead of R^2. About three times faster for the
+                               correction product. Layers whose operands are not 16-byte aligned or whose widths are
+                               not multiples of four stay in fp32.                                                   */
 } mw_config_t;
 
 /* Itemised device bytes held by a handle (closed forms are in the design notes). */

@@ -150,9 +150,18 @@ def right_inverse(W) -> np.ndarray:
     return scipy.linalg.solve_triangular(Lc.T, Y, lower=False)        # Lc^T P = Y
 
 
-# --------------------------------------------------------------------------- packed masks and fragments
+# --------------------------------------------------------------------------- training step and refresh
 
-def newton_schulz_refresh(W_new, P_old, iters: int):
+def round_to_bf16(a):
+    """Every element rounded to the nearest number with an 8-bit significand (bfloat16's: 1 implicit + 7
+    stored bits), ties to the even significand. Returned in fp64; bfloat16's exponent range is fp32's, and
+    values beyond it (or below its normal range) are not treated specially here."""
+    a = _as64(a)
+    mant, exp = np.frexp(a)                     # a = mant * 2^exp with 0.5 <= |mant| < 1
+    return np.ldexp(np.rint(mant * 256.0) / 256.0, exp)      # rint rounds halves to even
+
+
+def newton_schulz_refresh(W_new, P_old, iters: int, correction: str = "exact"):
     """Right inverse of W_new from the right inverse P_old = (W_old W_old^T)^{-1} W_old of nearby
     weights, without a factorisation (the library's incremental refresh, written out):
 
@@ -164,8 +173,17 @@ def newton_schulz_refresh(W_new, P_old, iters: int):
     A square layer has one inverse only and no row space to stay in: there the iteration starts from
     P_0 = P_old itself (residual -P_old dW^T, of the size of the update), which saves the two products
     of the start.
+    correction="bf16" is the library's mixed-precision variant: the iteration written as
+    P_{k+1} = P_k + R_k P_k, with both operands of the correction product R_k P_k rounded to bfloat16
+    and everything else as before. With relative roundings dR, dP of at most 2^-8 per element the
+    residual obeys R_{k+1} = R_k^2 - dR (I - R_k) - (R_k + dR) dP W_new^T: it shrinks by a factor of order
+    2^-8 per iteration once R_k is below that, to the same limit P W_new^T = I. The rounding of P_k leaves
+    the row space of W_new, so for a non-square layer the limit is a right inverse within
+    2^-8 ||R_0|| ||P|| of the minimum-norm one rather than that one exactly.
     Returns (P, residuals) with residuals[k] = ||I - P_k W_new^T||_F for k = 0 .. iters.
     """
+    if correction not in ("exact", "bf16"):
+        raise ValueError(f"unknown correction {correction!r}")
     W = _as64(W_new)
     P_old = _as64(P_old)
     n = W.shape[0]
@@ -174,7 +192,10 @@ def newton_schulz_refresh(W_new, P_old, iters: int):
     residuals = [float(np.linalg.norm(eye - P @ W.T))]
     for _ in range(int(iters)):
         E = P @ W.T
-        P = (2.0 * eye - E) @ P
+        if correction == "bf16":
+            P = P + round_to_bf16(eye - E) @ round_to_bf16(P)
+        else:
+            P = (2.0 * eye - E) @ P
         residuals.append(float(np.linalg.norm(eye - P @ W.T)))
     return P, residuals
 
@@ -187,6 +208,8 @@ def sgd_step(Ws, bs, alphas, x0, t, lr: float, forced_masks=None):
     new_b = [_as64(b) - lr * db for b, db in zip(bs, g["db"])]
     return new_W, new_b, g["loss"], g["masks"]
 
+
+# --------------------------------------------------------------------------- packed masks and fragments
 
 def pack_mask(m: np.ndarray) -> np.ndarray:
     """Pack a bool array (any shape, flattened row-major) into uint64 words, LSB first.

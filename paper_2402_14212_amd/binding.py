@@ -53,7 +53,8 @@ class _Config(C.Structure):
                 ("plan", C.c_int32), ("fuse", C.c_int32), ("frag_capacity_factor", C.c_double),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("alloc_ctx", C.c_void_p),
                 ("segment_length", C.c_int32), ("debug_keep", C.c_int32),
-                ("phase3_parallel_segments", C.c_int32), ("phase3_overlap", C.c_int32)]
+                ("phase3_parallel_segments", C.c_int32), ("phase3_overlap", C.c_int32),
+                ("refresh_precision", C.c_int32)]
 
 
 class _ConvLayer(C.Structure):
@@ -205,7 +206,9 @@ class MoonwalkNet:
                  batch: int, reseed_interval: int = 0, loss_scale: float = 1.0,
                  plan: int = PLAN_MOONWALK | PLAN_BACKPROP, fuse: bool = True,
                  frag_capacity_factor: float = 1.0, segment_length: int = 0, debug_keep: bool = False,
-                 phase3_parallel_segments: int = 0, phase3_overlap: bool = False):
+                 phase3_parallel_segments: int = 0, phase3_overlap: bool = False, refresh_bf16: bool = False):
+        """refresh_bf16: refresh_incremental / sgd_step form the residual I - P W^T in fp32 and round the operands of
+        the correction product that is added to P to bfloat16 (mw_config_t.refresh_precision = 1)."""
         _require_gpu()
         self._lib = load_library()
         self._handle = C.c_void_p()
@@ -244,7 +247,7 @@ class MoonwalkNet:
             layers[i] = _Layer(w.shape[1], w.shape[0], _ptr(w), _ptr(_f32(b)) if b is not None else None, a)
         cfg = _Config(self.batch, int(reseed_interval), float(loss_scale), int(plan), 1 if fuse else 0,
                       float(frag_capacity_factor), self._alloc_cb, self._free_cb, None, int(segment_length), 1 if debug_keep else 0,
-                      int(phase3_parallel_segments), 1 if phase3_overlap else 0)
+                      int(phase3_parallel_segments), 1 if phase3_overlap else 0, 1 if refresh_bf16 else 0)
         with torch.cuda.device(self.device):
             _check(self._lib.moonwalk_setup(C.byref(self._handle), layers, n, C.byref(cfg), _stream()))
         total = C.c_size_t()

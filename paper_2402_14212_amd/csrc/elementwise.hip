@@ -849,7 +849,7 @@ k_identity_residual_final(const double* __restrict__ partial, int n_partial, flo
 // The same for several matrices `stride` floats apart (blockIdx.y selects one): partial sums of matrix j
 // in partial[j * gridDim.x ..]; the final kernel folds the largest of the residuals into *out.
 __global__ void __launch_bounds__(EW_THREADS)
-k_identity_residual_sets(const float* __restrict__ E, int64_t stride, int n, double* __restrict__ partial) {
+k_identity_residual_sets(const float* __restrict__ E, int64_t stride, int n, double* __restrict__ partial, float eye) {
   __shared__ double red[EW_WAVES];
   const float* Ej = E + (int64_t)blockIdx.y * stride;
   const int64_t total = (int64_t)n * n;
@@ -860,15 +860,15 @@ k_identity_residual_sets(const float* __restrict__ E, int64_t stride, int n, dou
     for (uint32_t q = blockIdx.x * EW_THREADS + threadIdx.x; q < quads; q += gridDim.x * EW_THREADS) {
       const uint32_t r = q / per_row, c = 4u * (q - r * per_row);
       const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(Ej) + q);
-      const float d0 = v.x - (r == c ? 1.f : 0.f), d1 = v.y - (r == c + 1 ? 1.f : 0.f), d2 = v.z - (r == c + 2 ? 1.f : 0.f),
-                  d3 = v.w - (r == c + 3 ? 1.f : 0.f);
+      const float d0 = v.x - (r == c ? eye : 0.f), d1 = v.y - (r == c + 1 ? eye : 0.f), d2 = v.z - (r == c + 2 ? eye : 0.f),
+                  d3 = v.w - (r == c + 3 ? eye : 0.f);
       acc += (double)d0 * (double)d0 + (double)d1 * (double)d1;
       acc += (double)d2 * (double)d2 + (double)d3 * (double)d3;
     }
   } else {
     for (int64_t e = (int64_t)blockIdx.x * EW_THREADS + threadIdx.x; e < total; e += (int64_t)gridDim.x * EW_THREADS) {
       const int64_t r = e / n, c = e - r * n;
-      const float d = Ej[e] - (r == c ? 1.f : 0.f);
+      const float d = Ej[e] - (r == c ? eye : 0.f);
       acc += (double)d * (double)d;
     }
   }
@@ -1266,14 +1266,15 @@ hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* o
 }
 
 hipError_t ew_identity_residual_sets(const float* E, int64_t stride, int n_sets, int n, double* scratch, float* out,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, bool minus_identity) {
   if (n <= 0 || n_sets <= 0) return hipSuccess;
   if (n_sets > LOSS_BLOCKS) return hipErrorInvalidValue;
   int64_t want = ((int64_t)n * n + EW_THREADS - 1) / EW_THREADS;
   int64_t cap = LOSS_BLOCKS / n_sets;  // the scratch holds LOSS_BLOCKS doubles in all
   if (cap > 256) cap = 256;            // a workgroup per CU and matrix is plenty; the final kernel reads them all
   const int blocks = (int)(want > cap ? cap : want);
-  hipLaunchKernelGGL(k_identity_residual_sets, dim3(blocks, n_sets), dim3(EW_THREADS), 0, stream, E, stride, n, scratch);
+  hipLaunchKernelGGL(k_identity_residual_sets, dim3(blocks, n_sets), dim3(EW_THREADS), 0, stream, E, stride, n, scratch,
+                     minus_identity ? 1.f : 0.f);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_identity_residual_sets_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, n_sets, out);

@@ -22,6 +22,7 @@
 namespace mw {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -29,9 +30,13 @@ constexpr int KCONTIG = 0;
 constexpr int RCONTIG = 1;
 constexpr int NUM_XCD = 8;
 
-template <int WTM_, int WTN_, int WM_, int WN_, int WK_, int ST_ = 2>
+// PREC_: 0 = fp32 matrix instructions (v_mfma_f32_32x32x2_f32); 1 = the operands are rounded to bf16 (to nearest
+// even) on their way from LDS to the matrix unit and multiplied by v_mfma_f32_32x32x16_bf16, sums in fp32: for
+// products whose result is a small correction to something held in fp32 (2^-9 relative error per operand).
+template <int WTM_, int WTN_, int WM_, int WN_, int WK_, int ST_ = 2, int PREC_ = 0>
 struct TileCfg {
   static constexpr int WTM = WTM_, WTN = WTN_, WM = WM_, WN = WN_, WK = WK_;
+  static constexpr int PREC = PREC_;
   // operand tiles in flight in registers (even). Two is what measures best on every tile here:
   // with four, the extra registers cost more than the longer lead time gains.
   static constexpr int ST = ST_;
@@ -49,6 +54,9 @@ using Tile32K8 = TileCfg<1, 1, 1, 1, 8>;  //  32 x  32, K tile 256 split over 8 
 using Tile64K2 = TileCfg<1, 1, 2, 2, 2>;  //  64 x  64, K tile 64 split over 2 groups of 4 wavefronts
 using Tile128W8 = TileCfg<1, 2, 4, 2, 1>;  // 128 x 128, K tile 32, 8 wavefronts of 32 x 64
 using Tile64x128 = TileCfg<1, 1, 2, 4, 1>;  //  64 x 128, K tile 32, 8 wavefronts of 32 x 32
+using Tile128W8B = TileCfg<1, 2, 4, 2, 1, 2, 1>;   // the same three with bf16 matrix instructions
+using Tile64x128B = TileCfg<1, 1, 2, 4, 1, 2, 1>;
+using Tile64B = TileCfg<1, 1, 2, 2, 1, 2, 1>;
 
 // LDS footprint (floats) of one operand tile of R rows.
 template <int LAYOUT, int R, int BK>
@@ -269,15 +277,36 @@ __device__ __forceinline__ void mma_stage(const float* __restrict__ sa, const fl
 #pragma unroll
     for (int tn = 0; tn < Cfg::WTN; ++tn)
       read_frag8<LB, Cfg::BN, Cfg::BK>(sb, (wn * Cfg::WTN + tn) * 32 + r, kbase, fb[tn]);
+    if (Cfg::PREC == 1) {
+      // one 32x32x16 instruction per half: lane group g supplies the eight k values 16 g + 8 half + 0..7 of its
+      // row for both operands (which k a slot stands for does not matter as long as A and B agree)
+      static_assert(!(COLSUM && Cfg::PREC == 1), "column sums are taken from the fp32 operands");
+      bf16x8 va[Cfg::WTM], vb[Cfg::WTN];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+      for (int tm = 0; tm < Cfg::WTM; ++tm)
 #pragma unroll
-      for (int tm = 0; tm < Cfg::WTM; ++tm) {
-        if (COLSUM) asum[tm] += fa[tm][j];
+        for (int j = 0; j < 8; ++j) va[tm][j] = (__bf16)fa[tm][j];
+#pragma unroll
+      for (int tn = 0; tn < Cfg::WTN; ++tn)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vb[tn][j] = (__bf16)fb[tn][j];
+#pragma unroll
+      for (int tm = 0; tm < Cfg::WTM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < Cfg::WTN; ++tn)
           acc[tm * Cfg::WTN + tn] =
-              __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][j], fb[tn][j], acc[tm * Cfg::WTN + tn], 0, 0, 0);
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[tm], vb[tn], acc[tm * Cfg::WTN + tn], 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int tm = 0; tm < Cfg::WTM; ++tm) {
+          if (COLSUM) asum[tm] += fa[tm][j];
+#pragma unroll
+          for (int tn = 0; tn < Cfg::WTN; ++tn)
+            acc[tm * Cfg::WTN + tn] =
+                __builtin_amdgcn_mfma_f32_32x32x2f32(fa[tm][j], fb[tn][j], acc[tm * Cfg::WTN + tn], 0, 0, 0);
+        }
       }
     }
   }

@@ -59,19 +59,20 @@ struct EpiStore::Dev {
   }
 };
 
-// C = alpha * acc + beta * D: D is another matrix of C's shape and row stride (or C itself, or NULL)
+// C = alpha * acc + beta * D + eye * I: D is another matrix of C's shape and row stride (or C itself, or NULL)
 struct EpiAxpby {
   float* C;
   const float* D;
   int64_t ldc;
   float alpha, beta;
+  float eye = 0.f;
   struct Dev {
     __amdgpu_buffer_rsrc_t rc, rd;
     int64_t ldc;
-    float alpha, beta;
+    float alpha, beta, eye;
     bool add;
     __device__ __forceinline__ Dev(const EpiAxpby& p, int M, int N)
-        : ldc(p.ldc), alpha(p.alpha), beta(p.beta), add(p.D != nullptr && p.beta != 0.f) {
+        : ldc(p.ldc), alpha(p.alpha), beta(p.beta), eye(p.eye), add(p.D != nullptr && p.beta != 0.f) {
       rc = make_rsrc(p.C, extent_bytes(M, N, p.ldc));
       rd = make_rsrc(p.D, add ? extent_bytes(M, N, p.ldc) : 0u);
     }
@@ -88,7 +89,11 @@ struct EpiAxpby {
         old[j] = buf_load_f32(rd, add ? off[j] : OOB);
       }
 #pragma unroll
-      for (int j = 0; j < CNT; ++j) buf_store_f32(rc, off[j], alpha * v[0][j] + (add ? beta * old[j] : 0.f));
+      for (int j = 0; j < CNT; ++j) {
+        float r = alpha * v[0][j] + (add ? beta * old[j] : 0.f);
+        if (eye != 0.f && row_base + acc_row(i0 + j, g) == col) r += eye;
+        buf_store_f32(rc, off[j], r);
+      }
     }
   };
 };
@@ -429,6 +434,7 @@ struct GroupedGemmTask {
   int64_t ldc;
   float alpha, beta;
   int tiles_m, tiles_n;
+  float eye = 0.f;  // C[g] += eye * I
   using One = GemmTask<Cfg, LA, LB, true, ANone, EpiAxpby, false>;
   static constexpr int LDS_BYTES = One::LDS_BYTES;
   __host__ __device__ int blocks() const { return n_sets * tiles_m * tiles_n; }
@@ -436,7 +442,7 @@ struct GroupedGemmTask {
   __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
     const int per = tiles_m * tiles_n;
     const int g = bid / per;
-    const One t{M, N, K, A[g], lda, B[g], ldb, ANone{}, EpiAxpby{C[g], D ? D[g] : nullptr, ldc, alpha, beta},
+    const One t{M, N, K, A[g], lda, B[g], ldb, ANone{}, EpiAxpby{C[g], D ? D[g] : nullptr, ldc, alpha, beta, eye},
                 nullptr, 0.f, tiles_m, tiles_n};
     t.run(bid - g * per, lds);
   }

@@ -134,6 +134,7 @@ struct mw_handle {
   int B = 0, L = 0, K = 0, fuse = 1, plan = 0;
   int S = 0;                        // segment length (0: the whole network is one run)
   int debug_keep = 0;               // per-layer z, Phase-II and Phase-III cotangents kept for moonwalk_debug_fetch
+  int refresh_bf16 = 0;             // incremental refresh: the correction product of a Schulz iteration in bf16 matrix instructions
   float* hseg[2] = {nullptr, nullptr};  // cotangents at segment boundaries, alternating
   float loss_scale = 1.f;
   double frag_factor = 1.0;
@@ -161,7 +162,8 @@ struct mw_handle {
   const float** refresh_tab = nullptr;  // device table of pointers for the grouped products of that refresh:
                                         // P of every layer, W of every layer, then the S and the Q slots
   struct RefreshRun {             // consecutive layers of one shape
-    int l0, len, sets;            // first layer, layers, layers refreshed side by side (1: one at a time)
+    int l0, len, sets;            // first layer, layers, layers refreshed side by side
+    bool vec;                     // grouped products (16-byte aligned operands, widths in fours); else one plain layer at a time
     size_t tab_off;               // the run's S slot pointers in refresh_tab, its Q slot pointers `sets` further on
     size_t slot, q_off;           // floats per slot of refresh_work, and where Q starts inside a slot
   };
@@ -349,6 +351,7 @@ int validate_layers(const mw_layer_t* layers, int32_t n_layers, const mw_config_
   if (cfg->debug_keep != 0 && cfg->debug_keep != 1) return MW_ERR_INVALID_ARG;
   if (cfg->phase3_parallel_segments < 0 || cfg->phase3_parallel_segments > 16) return MW_ERR_INVALID_ARG;
   if (cfg->phase3_overlap < 0 || cfg->phase3_overlap > 1) return MW_ERR_INVALID_ARG;
+  if (cfg->refresh_precision < 0 || cfg->refresh_precision > 1) return MW_ERR_INVALID_ARG;
   for (int i = 0; i < n_layers; ++i) {
     const mw_layer_t& l = layers[i];
     if (l.d_in <= 0 || l.d_out <= 0 || !l.W) return MW_ERR_INVALID_ARG;
@@ -388,6 +391,7 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
   h->S = (cfg->segment_length > 0 && cfg->segment_length < n_layers) ? cfg->segment_length : 0;
   h->fuse = cfg->fuse ? 1 : 0;
   h->debug_keep = cfg->debug_keep;
+  h->refresh_bf16 = cfg->refresh_precision;
   h->plan = cfg->plan ? cfg->plan : (MW_PLAN_MOONWALK | MW_PLAN_BACKPROP);
   h->loss_scale = cfg->loss_scale;
   h->frag_factor = cfg->frag_capacity_factor > 0.0 ? cfg->frag_capacity_factor : 1.0;
@@ -1034,11 +1038,11 @@ int refresh_plan(mw_handle* h) {
     int sets = (int)((512 + tiles - 1) / tiles);
     if (sets > REFRESH_SETS) sets = REFRESH_SETS;
     if (sets > len) sets = len;
-    if (!vec || sets < 2) sets = 1;
+    if (!vec || sets < 1) sets = 1;
     const size_t q_off = round64((size_t)n * n), slot = q_off + round64((size_t)n * m);
-    runs.push_back({l0, len, sets, n_tab, slot, q_off});
+    runs.push_back({l0, len, sets, vec, n_tab, slot, q_off});
     if ((size_t)sets * slot > total) total = (size_t)sets * slot;
-    if (sets > 1) n_tab += 2 * (size_t)sets;
+    if (vec) n_tab += 2 * (size_t)sets;
     l0 += len;
   }
   float* work = static_cast<float*>(h->alloc(total * sizeof(float), &h->st.bytes_mw_scratch));
@@ -1051,7 +1055,7 @@ int refresh_plan(mw_handle* h) {
     host[L + i] = h->layers[i].W;
   }
   for (auto& r : runs)
-    for (int j = 0; r.sets > 1 && j < r.sets; ++j) {
+    for (int j = 0; r.vec && j < r.sets; ++j) {
       host[r.tab_off + j] = work + (size_t)j * r.slot;
       host[r.tab_off + r.sets + j] = work + (size_t)j * r.slot + r.q_off;
     }
@@ -1074,7 +1078,7 @@ int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStrea
     const int n = h->layers[r.l0].d_out, m = h->layers[r.l0].d_in;
     for (int l0 = r.l0; l0 < r.l0 + r.len;) {
       const int g = (r.l0 + r.len - l0 < r.sets) ? r.l0 + r.len - l0 : r.sets;
-      if (r.sets < 2) {
+      if (!r.vec) {
         int rc = refresh_one_layer(h, h->layers[l0], iters, residual_out, s);
         if (rc != MW_OK) return rc;
         l0 += 1;
@@ -1095,6 +1099,18 @@ int refresh_newton_schulz(mw_handle* h, int iters, float* residual_out, hipStrea
         MW_HIP(gemm_grouped(OP_NN, g, n, m, n, 1.f, St, n, Wt, m, 0.f, nullptr, out(cur), m, s));
       }
       for (int it = 0; it < iters; ++it) {
+        if (h->refresh_bf16) {
+          // S = I - cur W^T in fp32 (the difference is where the digits are lost); other = cur + S cur, the small
+          // correction S cur with its operands rounded to bf16 in front of the matrix unit, summed and added in fp32
+          MW_HIP(gemm_grouped(OP_NT, g, n, n, m, -1.f, cur, m, Wt, m, 0.f, nullptr, out(St), n, s, 1.f));
+          if (residual_out && it == iters - 1)
+            MW_HIP(ew_identity_residual_sets(h->refresh_work, (int64_t)r.slot, g, n, h->loss_scratch, residual_out, s, false));
+          MW_HIP(gemm_grouped(OP_NN, g, n, m, n, 1.f, St, n, cur, m, 1.f, cur, out(other), m, s, 0.f, true));
+          const float* const* t = cur;
+          cur = other;
+          other = t;
+          continue;
+        }
         MW_HIP(gemm_grouped(OP_NT, g, n, n, m, 1.f, cur, m, Wt, m, 0.f, nullptr, out(St), n, s));
         if (residual_out && it == iters - 1)
           MW_HIP(ew_identity_residual_sets(h->refresh_work, (int64_t)r.slot, g, n, h->loss_scratch, residual_out, s));

@@ -25,9 +25,10 @@ int pick_tile_dw(int M, int N, int K, int partner, bool phase3);
 // C[g] = alpha * op(A[g], B[g]) + beta * D[g], g < n_sets: the same NT or NN product on several operand sets of one
 // shape in one launch (gemm_grouped.hip). Pointer tables in device memory; D may be NULL; operands 16-byte aligned,
 // row strides multiples of 4 floats.
+// + eye * I (eye != 0 needs M == N); bf16 (NN only): operands rounded to bf16 in front of the matrix unit
 hipError_t gemm_grouped(int op, int n_sets, int M, int N, int K, float alpha, const float* const* A, int64_t lda,
                         const float* const* B, int64_t ldb, float beta, const float* const* D, float* const* C, int64_t ldc,
-                        hipStream_t stream);
+                        hipStream_t stream, float eye = 0.f, bool bf16 = false);
 
 // C = alpha * op(A, B) + beta * C + bias (bias indexed by column, may be NULL)
 hipError_t gemm_plain(int op, int tile, int M, int N, int K, float alpha, const float* A, int64_t lda,
@@ -182,8 +183,9 @@ hipError_t ew_scale_by_act_slope(const float* h, const float* act, int64_t n, fl
 // *out = max(*out, ||E - I||_F) for the n x n matrix E (row stride n); scratch: LOSS_BLOCKS doubles
 hipError_t ew_identity_residual(const float* E, int n, double* scratch, float* out, hipStream_t stream);
 // the same for n_sets matrices `stride` floats apart, in two launches for all of them (the same scratch)
+// (minus_identity = false: ||E||_F itself, for matrices that already hold the residual)
 hipError_t ew_identity_residual_sets(const float* E, int64_t stride, int n_sets, int n, double* scratch, float* out,
-                                     hipStream_t stream);
+                                     hipStream_t stream, bool minus_identity = true);
 // load-only model of a tiled product (measurement): sink gets (M/tile)*(N/tile)*256 floats
 hipError_t ew_operand_stream(const float* A, const float* B, int M, int N, int K, int tile, float* sink,
                              hipStream_t stream);

@@ -70,6 +70,9 @@ static void validation() {
   bad.debug_keep = 3;
   EXPECT(moonwalk_setup(&h, &ok, 1, &bad, nullptr) == MW_ERR_INVALID_ARG);
   bad = cfg;
+  bad.refresh_precision = 2;
+  EXPECT(moonwalk_setup(&h, &ok, 1, &bad, nullptr) == MW_ERR_INVALID_ARG);
+  bad = cfg;
   bad.batch = 1 << 30;
   EXPECT(moonwalk_setup(&h, &ok, 1, &bad, nullptr) == MW_ERR_INVALID_ARG);
   EXPECT(h == nullptr);
@@ -85,7 +88,7 @@ static void validation() {
 
 // One dense network through every entry point. widths: d_0 .. d_L.
 static void dense_network(const std::vector<int>& widths, int batch, const std::vector<float>& alphas, int K, int S, int fuse,
-                          int debug_keep, int plan, int group = 1, int overlap = 0) {
+                          int debug_keep, int plan, int group = 1, int overlap = 0, int refresh_precision = 0) {
   const int L = (int)widths.size() - 1;
   std::vector<std::vector<float>> W(L), b(L);
   std::vector<mw_layer_t> layers(L);
@@ -102,6 +105,7 @@ static void dense_network(const std::vector<int>& widths, int batch, const std::
   cfg.plan = plan;
   cfg.phase3_parallel_segments = group;
   cfg.phase3_overlap = overlap;
+  cfg.refresh_precision = refresh_precision;
   mw_handle_t* h = nullptr;
   const int rc = moonwalk_setup(&h, layers.data(), L, &cfg, nullptr);
   EXPECT(rc == MW_OK && h != nullptr);
@@ -248,6 +252,9 @@ int main() {
     for (int overlap = 0; overlap <= 1; ++overlap)
       dense_network(std::vector<int>(15, 256), 64, std::vector<float>(14, 0.1f), 4, 0, 1, 0, MW_PLAN_MOONWALK, group, overlap);
   dense_network(std::vector<int>(13, 256), 77, {0.1f, 0.f, 0.1f, 0.3f, 0.1f, 0.f, 0.1f, 0.3f, 0.1f, 0.f, 0.1f, 0.3f}, 4, 0, 1, 1, 0, 3, 1);
+  // the refresh with the correction product in bf16: square and narrowing runs of layers, a ragged layer that stays in fp32
+  dense_network({200, 136, 136, 136, 96, 96, 70, 50}, 9, {0.1f, 0.1f, 0.1f, 0.1f, 0.1f, 0.1f, 0.1f}, 2, 0, 1, 0, MW_PLAN_MOONWALK, 1, 0, 1);
+  dense_network(std::vector<int>(12, 1024), 64, std::vector<float>(11, 0.1f), 4, 0, 1, 0, MW_PLAN_MOONWALK, 0, 0, 1);
   dense_allocation_failures();
   // convolutional chains: gathered kernels and patch buffer, as-read input cotangent, image chunks of 3,
   // a kernel wider than padding + stride (the sweep), 1-D fragmental layers in blocks of 4

@@ -349,6 +349,67 @@ def test_newton_schulz_refresh_of_a_square_layer_starts_from_the_old_inverse():
     assert np.allclose(P, np.linalg.inv(W_new).T, atol=1e-12, rtol=0)
 
 
+def test_round_to_bf16_against_hand_cases_and_the_library_conversion():
+    """8-bit significand, ties to even: hand-written cases, then torch's float32 -> bfloat16 conversion
+    (a library routine of its own) on random float32 values, which double rounding cannot touch."""
+    import torch
+    cases = [(1.0, 1.0), (1.0 + 2.0 ** -8, 1.0),                 # tie, even significand below
+             (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6),             # tie, even significand above
+             (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -7),    # just above the tie
+             (-3.0 - 2.0 ** -7, -3.0), (-3.0 - 3 * 2.0 ** -7, -3.0 - 2.0 ** -5),   # ties in the next binade (spacing 2^-6)
+             (-3.0 - 2.0 ** -6, -3.0 - 2.0 ** -6),               # held exactly
+             (255.5, 256.0), (0.0, 0.0), (2.0 ** -40 * 1.2345, float(np.ldexp(np.rint(1.2345 * 128) / 128, -40)))]
+    for x, want in cases:
+        assert float(O.round_to_bf16(np.array([x]))[0]) == want, (x, want)
+    rng = np.random.default_rng(17)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x), want)
+    # idempotent, odd, and within half a unit in the last place: |r(x) - x| <= 2^-8 |x|
+    r = O.round_to_bf16(x)
+    np.testing.assert_array_equal(O.round_to_bf16(r), r)
+    np.testing.assert_array_equal(O.round_to_bf16(-x.astype(np.float64)), -r)
+    assert np.all(np.abs(r - x) <= 2.0 ** -8 * np.abs(x))
+
+
+@pytest.mark.parametrize("widths", [[24, 16], [16, 16]])
+def test_newton_schulz_refresh_with_the_bf16_correction(widths):
+    """Operands that bfloat16 holds exactly give the exact iteration bit for bit; otherwise the residual obeys
+    R_{k+1} = R_k^2 - dR (I - R_k) - (R_k + dR) dP W^T with |dR| <= 2^-8 |R_k|, |dP| <= 2^-8 |P_k| per element,
+    and the limit is still a right inverse, within 2^-8 ||R_0|| ||P|| of the minimum-norm one."""
+    rng = np.random.default_rng(23)
+    # (a) one iteration on bf16-exact data: P_0 = P_old (square) and R_0 = I - P_old W^T made of small dyadic numbers
+    n = 8
+    W = np.eye(n) + rng.integers(-2, 3, (n, n)) / 16.0
+    P_old = np.eye(n) + rng.integers(-2, 3, (n, n)) / 16.0
+    Pe, _ = O.newton_schulz_refresh(W, P_old, 1)
+    Pb, _ = O.newton_schulz_refresh(W, P_old, 1, correction="bf16")
+    np.testing.assert_array_equal(Pe, Pb)
+    # (b) general data
+    wl = make_mlp(widths, batch=4, alpha=0.1, seed=11)
+    W_old = wl.W[0].astype(np.float64)
+    W_new = W_old + 2e-2 * rng.standard_normal(W_old.shape) / np.sqrt(W_old.shape[1])
+    P_old = O.right_inverse(W_old)
+    iters = 10
+    P, res = O.newton_schulz_refresh(W_new, P_old, iters, correction="bf16")
+    _, res_exact = O.newton_schulz_refresh(W_new, P_old, 1)
+    assert res[0] == res_exact[0]
+    assert res[1] != res_exact[1]                                         # the rounding is really there
+    Pk = [O.newton_schulz_refresh(W_new, P_old, k, correction="bf16")[0] for k in range(iters)]
+    eps = 2.0 ** -8
+    w2 = np.linalg.norm(W_new, 2)
+    for k in range(iters):
+        bound = res[k] ** 2 + eps * res[k] * (1 + res[k]) + (1 + eps) * res[k] * eps * np.linalg.norm(Pk[k]) * w2
+        assert res[k + 1] <= bound * (1 + 1e-9) + 1e-15, (k, res[k + 1], bound)
+    assert res[iters] < 1e-13                                             # still a right inverse in the limit
+    exact = O.right_inverse(W_new)
+    assert np.linalg.norm(P - exact) <= eps * res[0] * np.linalg.norm(exact) * 1.5
+    if widths[0] == widths[1]:                                            # a square matrix has one inverse only
+        assert np.allclose(P, np.linalg.inv(W_new).T, atol=1e-11, rtol=0)
+    with pytest.raises(ValueError):
+        O.newton_schulz_refresh(W_new, P_old, 1, correction="fp8")
+
+
 def test_newton_schulz_zero_iterations_is_first_order_accurate():
     """P_0 - P_new = O(||dW||): halving the perturbation halves the error."""
     rng = np.random.default_rng(6)

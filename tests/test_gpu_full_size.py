@@ -18,9 +18,11 @@ def mw():
 
 
 def test_deep_square_full_size(mw):
-    """Depth 64, width 1024, batch 256, leaky 0.1, re-seed every 4 layers: every gradient tensor."""
+    """Depth 64, width 1024, batch 256, leaky 0.1, re-seed every 4 layers: every gradient tensor, with Phase III
+    as bench.py runs it (the library's choice of stretches side by side, on its second stream)."""
     wl = make_config("deep_square")
-    net = mw.MoonwalkNet.from_workload(wl)
+    net = mw.MoonwalkNet.from_workload(wl, phase3_parallel_segments=0, phase3_overlap=True)
+    assert net.memory_stats()["phase3_group_width"] == 4
     res = net.moonwalk_grad(net.x, net.t)
     torch.cuda.synchronize()
     info = check_moonwalk(net, wl, res)

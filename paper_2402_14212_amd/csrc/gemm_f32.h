@@ -32,7 +32,7 @@ constexpr int NUM_XCD = 8;
 
 // PREC_: 0 = fp32 matrix instructions (v_mfma_f32_32x32x2_f32); 1 = the operands are rounded to bf16 (to nearest
 // even) on their way from LDS to the matrix unit and multiplied by v_mfma_f32_32x32x16_bf16, sums in fp32: for
-// products whose result is a small correction to something held in fp32 (2^-9 relative error per operand).
+// products whose result is a small correction to something held in fp32 (2^-8 relative error per operand).
 template <int WTM_, int WTN_, int WM_, int WN_, int WK_, int ST_ = 2, int PREC_ = 0>
 struct TileCfg {
   static constexpr int WTM = WTM_, WTN = WTN_, WM = WM_, WN = WN_, WK = WK_;

@@ -17,6 +17,8 @@ What follows which passage of the Moonwalk paper:
 
 * `backprop`            ordinary reverse mode; it is the plain definition of the result, since
                         the method yields the exact gradient (Moonwalk identity, Eq. ifp-main).
+                        `forward_layerwise` / `backprop_layerwise`: the same, one layer in memory at a
+                        time (for the 256-layer configuration), pinned to be `backprop` bit for bit.
 * `right_inverse`       the (.)^+ of the vijp definition (Notation section) for a dense layer:
                         the Moore-Penrose right inverse of W, kept as P = (W W^T)^{-1} W so that
                         the vijp of the affine map is ct_z = ct_x P^T.  P W^T = I.
@@ -130,6 +132,39 @@ def backprop(Ws, bs, alphas, x0, t, forced_masks=None) -> Dict[str, object]:
         db[i] = ct_z.sum(axis=0)                        # vjp w.r.t. b
         hs[i] = ct_z @ _as64(Ws[i])                     # vjp w.r.t. the layer input
     return {"dW": dW, "db": db, "loss": loss, "masks": masks, "h": hs, "zs": zs, "xs": xs}
+
+
+def forward_layerwise(layer, depth: int, alphas, x0, mask_for=None):
+    """`forward` for networks whose parameters are fetched one layer at a time: `layer(i)` returns (W_i, b_i)
+    (any dtype; used as fp64 and dropped), `mask_for(i, z)` returns the sign decisions to impose on layer i
+    given its pre-activation (None, or a None result: the signs of z). Returns (xs = [x_0..x_L], masks)."""
+    xs, masks = [_as64(x0)], []
+    for i in range(depth):
+        W, b = layer(i)
+        z = xs[-1] @ _as64(W).T + _as64(b)
+        m = mask_for(i, z) if mask_for is not None else None
+        m = sign_mask(z) if m is None else np.asarray(m, dtype=bool)
+        xs.append(activation(z, m, alphas[i]))
+        masks.append(m)
+    return xs, masks
+
+
+def backprop_layerwise(layer, alphas, xs, masks, t):
+    """`backprop` for networks whose gradients do not fit in memory at once: a generator over the layers from the
+    last to the first, given the activations and masks of `forward_layerwise`. Yields first (L, loss, None, h_L),
+    then (i, dW_i, db_i, h_i) for i = L-1 .. 0 with h_i = dJ/dx_i the cotangent at layer i's INPUT (0-based i: the
+    paper's layer i+1); xs[i+1] is released once used. Same arithmetic, in the same order, as `backprop`."""
+    L = len(masks)
+    loss, h = loss_and_output_cotangent(xs[L], _as64(t))
+    yield L, loss, None, h
+    for i in range(L - 1, -1, -1):
+        ct_z = h * activation_slope(masks[i], alphas[i])
+        dW = ct_z.T @ xs[i]
+        db = ct_z.sum(axis=0)
+        W, _ = layer(i)
+        h = ct_z @ _as64(W)
+        xs[i + 1] = None
+        yield i, dW, db, h
 
 
 # --------------------------------------------------------------------------- right inverse

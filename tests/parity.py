@@ -96,6 +96,50 @@ def check_moonwalk(net, wl, res, tol=GRAD_TOL, check_h0=True):
     return {"max_dW_err": eW, "max_db_err": eb, "guard_band": in_band}
 
 
+def check_moonwalk_layerwise(net, wl, res, say=print, tol=GRAD_TOL):
+    """check_moonwalk for a network too large to hold the oracle's whole state (256 layers of 4096 x 4096): the same
+    protocol (GPU masks forced, guard band, loss, every dW and db, h_0), one layer in host memory at a time. `wl`
+    may hold device tensors; each layer's parameters come to the host when the oracle asks for them. `say` reports
+    progress (a long silent test looks hung)."""
+    def host(a):
+        return a if isinstance(a, np.ndarray) else a.detach().cpu().numpy()
+
+    def layer(i):
+        return host(wl.W[i]), host(wl.b[i])
+
+    state = {"in_band": 0}
+
+    def gpu_mask(i, z):
+        words = net.fetch_mask(i)
+        assert words.size == (z.size + 63) // 64
+        m = O.unpack_mask(words, z.size).reshape(z.shape)
+        rms = float(np.sqrt(np.mean(z * z)))
+        sure = np.abs(z) > MASK_GUARD * rms
+        bad = (m != O.sign_mask(z)) & sure
+        assert not bad.any(), f"layer {i}: {int(bad.sum())} sign bits differ outside the guard band"
+        state["in_band"] += int((~sure).sum())
+        if i % 32 == 31:
+            say(f"  oracle forward: {i + 1} layers")
+        return m
+
+    xs, masks = O.forward_layerwise(layer, wl.depth, wl.alphas, host(wl.x), gpu_mask)
+    eW, eb = [], []
+    for i, dW, db, h in O.backprop_layerwise(layer, wl.alphas, xs, masks, host(wl.t)):
+        if i == wl.depth:
+            loss = float(res.loss.item())
+            assert abs(loss - dW) <= 1e-5 * abs(dW) + 1e-30, (loss, dW)
+            continue
+        eW.append(O.normwise_rel_err(res.dW[i].detach().cpu().numpy(), dW))
+        eb.append(O.normwise_rel_err(res.db[i].detach().cpu().numpy(), db))
+        assert eW[-1] <= tol and eb[-1] <= tol, f"layer {i}: dW {eW[-1]:.3e}, db {eb[-1]:.3e}"
+        if i % 32 == 0:
+            say(f"  oracle reverse: down to layer {i}, worst so far dW {max(eW):.2e} db {max(eb):.2e}")
+    assert O.normwise_rel_err(net.fetch_h0() / wl.loss_scale, h) <= 1e-4
+    stats = net.memory_stats()
+    assert stats["sign_mismatches"] == 0 and stats["frag_overflow"] == 0
+    return {"max_dW_err": max(eW), "max_db_err": max(eb), "guard_band": state["in_band"]}
+
+
 def check_kept_tensors(net, wl, ref, masks, h_tol=1e-4, hf_tol=1e-3):
     """A network built with debug_keep: the GPU's own z, Phase-II h and Phase-III h of every layer.
 

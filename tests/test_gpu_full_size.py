@@ -5,7 +5,7 @@ import torch
 
 from workloads import make_config, workload_to_host
 
-from parity import check_moonwalk, check_gradients, gpu_masks
+from parity import check_moonwalk, check_moonwalk_layerwise, check_gradients, gpu_masks
 
 pytestmark = pytest.mark.gpu
 
@@ -69,4 +69,28 @@ def test_large_configurations_at_the_stated_depth(mw, name, depth):
         assert len(kept) == 3
         # the scaled cotangent really is far outside what fp32 would hold unscaled at full depth
         assert float(np.abs(net.fetch_h0()).max()) > 2.0 ** 40
+    net.close()
+
+
+def test_very_deep_whole(mw, capsys):
+    """very_deep at its stated depth: 256 layers of 4096 x 4096, batch 1024, loss scale 2^64, a re-seed every 4
+    layers. Every dW and db, the loss and h_0 against the fp64 oracle with the GPU's masks forced, one layer in host
+    memory at a time (about 26 TFLOP of fp64 on the host: a minute or two, with progress lines)."""
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+
+    say("very_deep L=256: drawing the weights on the device")
+    dev = make_config("very_deep", device="cuda:0")
+    net = mw.MoonwalkNet.from_workload(dev, plan=1)
+    say("very_deep L=256: gradient step")
+    res = net.moonwalk_grad(net.x, net.t)
+    torch.cuda.synchronize()
+    info = check_moonwalk_layerwise(net, dev, res, say)
+    say(f"very_deep L=256: {info}")
+    stats = net.memory_stats()
+    assert stats["bytes_checkpoints"] == 4 * dev.batch * 4096 * 63
+    # what the scale is for: at this depth the unscaled input cotangent lies below fp32's normal range
+    top = float(np.abs(net.fetch_h0()).max())
+    assert 0.0 < top / dev.loss_scale < 2.0 ** -126 < top
     net.close()

@@ -311,6 +311,43 @@ def test_tiny_golden_fixture_is_reproduced():
     np.testing.assert_array_equal(wl.x[0, :4], np.float32(g["x_head"]))
 
 
+def test_layerwise_backprop_is_backprop_bit_for_bit():
+    """The one-layer-at-a-time form used for the deepest configuration: same loss, gradients, cotangents and masks
+    as `backprop`, exactly, with free and with forced masks; activations are released on the way."""
+    wl = make_mlp([20, 16, 16, 12, 7], batch=9, alpha=[0.1, 0.0, 0.5, 0.0], seed=13)
+    rng = np.random.default_rng(3)
+    forced = [rng.random((9, d)) < 0.5 for d in wl.widths[1:]]
+    for masks_in in (None, forced):
+        ref = O.backprop(wl.W, wl.b, wl.alphas, wl.x, wl.t, forced_masks=masks_in)
+        asked = []
+        def layer(i):
+            asked.append(i)
+            return wl.W[i], wl.b[i]
+        xs, masks = O.forward_layerwise(layer, wl.depth, wl.alphas, wl.x,
+                                        None if masks_in is None else (lambda i, z: masks_in[i]))
+        assert asked == list(range(wl.depth))
+        for a, b in zip(xs, ref["xs"]):
+            np.testing.assert_array_equal(a, b)
+        for a, b in zip(masks, ref["masks"]):
+            np.testing.assert_array_equal(a, b)
+        seen = []
+        for i, dW, db, h in O.backprop_layerwise(layer, wl.alphas, xs, masks, wl.t):
+            seen.append(i)
+            if i == wl.depth:
+                assert dW == ref["loss"] and db is None
+            else:
+                np.testing.assert_array_equal(dW, ref["dW"][i])
+                np.testing.assert_array_equal(db, ref["db"][i])
+                assert xs[i + 1] is None
+            np.testing.assert_array_equal(h, ref["h"][i])
+        assert seen == list(range(wl.depth, -1, -1))
+    # a mask_for that declines (returns None) leaves the sign of z in charge
+    xs2, masks2 = O.forward_layerwise(lambda i: (wl.W[i], wl.b[i]), wl.depth, wl.alphas, wl.x, lambda i, z: None)
+    free = O.backprop(wl.W, wl.b, wl.alphas, wl.x, wl.t)
+    for a, b in zip(masks2, free["masks"]):
+        np.testing.assert_array_equal(a, b)
+
+
 # ----------------------------------------------------------------------------- training step and refresh
 def test_newton_schulz_refresh_squares_the_residual_and_reaches_the_pseudo_inverse():
     """Schulz iteration: R_{k+1} = R_k^2, limit = Moore-Penrose right inverse (library routine pinv)."""

@@ -24,10 +24,10 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix peak (256 CU
 
 # Bytes that cross the L2 per Phase-III launch (the layer kernels of four stretches + the weight gradients of the
 # position before; average over the 17 launches of a step), from the two rocprofv3 --pmc runs summarised in
-# profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE 40748.4 KiB scaled x2.0 by the copy-kernel calibration,
+# profiles/bench_deep_square_hbm_traffic.txt (FETCH_SIZE 33096.8 KiB scaled x2.0 by the copy-kernel calibration,
 # WRITE_SIZE 27000.5 KiB scaled x1.0). Offline counters: known only for the default workload in its default
 # launch configuration (re-seed interval, group width), null otherwise.
-PHASE3_TRAFFIC_BYTES = {"deep_square": int(40748.4 * 1024 * 2.0 + 27000.5 * 1024 * 1.0)}
+PHASE3_TRAFFIC_BYTES = {"deep_square": int(33096.8 * 1024 * 2.0 + 27000.5 * 1024 * 1.0)}
 
 
 def parse():

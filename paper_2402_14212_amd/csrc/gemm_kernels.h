@@ -378,6 +378,10 @@ struct GemmTask {
   __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
     int tm_i, tn_i;
     tile_coords(bid, tiles_m, tiles_n, tm_i, tn_i);
+    run_tile(tm_i, tn_i, lds);
+  }
+
+  __device__ __forceinline__ void run_tile(int tm_i, int tn_i, float* __restrict__ lds) const {
     const int m0 = tm_i * Cfg::BM, n0 = tn_i * Cfg::BN;
 
     f32x16 acc[1][Cfg::NACC];
@@ -583,13 +587,14 @@ struct GroupedDwTask {
 
   __device__ __forceinline__ void run(int bid, float* __restrict__ lds) const {
     const int per = tiles_m * tiles_n;
-    // blocks of one set are consecutive, so that bid % 8 inside the set is still the XCD the block runs on
-    // whenever `per` is a multiple of 8 (the set's own tile order then keeps a column panel on one XCD)
-    const int g = bid / per;
+    // every XCD takes a contiguous range of the launch's tiles in set-major, column-panel order: a set's weight
+    // gradient sits on 8 / n_sets XCDs, so its ct_z and x cross into that many L2s instead of all eight
+    const int id = xcd_remap(bid, n_sets * per);
+    const int g = id / per, tile = id - g * per;
     const DwSet& q = set[g];
     One t{M, N, K, q.CTZ, M, q.X, N, ANone{}, EpiStore{q.dW, N, scale, beta, nullptr}, q.db, scale, tiles_m, tiles_n};
     t.colsum_beta = beta;
-    t.run(bid - g * per, lds);
+    t.run_tile(tile % tiles_m, tile / tiles_m, lds);
   }
 };
 

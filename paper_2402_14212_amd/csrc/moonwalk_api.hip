@@ -917,11 +917,8 @@ int reverse_and_sweep(const Step& c) {
     }
     return MW_OK;
   };
-  if (overlap) {
-    // the side stream must not run ahead of what the caller's stream has done before this call
-    MW_HIP(hipEventRecord(h->events[h->groups.size()], s));
-    MW_HIP(hipStreamWaitEvent(h->side, h->events[h->groups.size()], 0));
-  }
+  // (every launch on the side stream follows a wait for an event recorded on the caller's stream inside this call,
+  // and the last call ended with the caller's stream waiting for the side stream: no further fence is needed here)
   MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0, released));
   if (side_used) MW_TRY_RC(flush_carried(c, &carry, h->side));
   for (size_t k = 0; k < h->groups.size(); ++k) {

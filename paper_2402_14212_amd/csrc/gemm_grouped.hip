@@ -42,6 +42,7 @@ hipError_t gemm_grouped(int op, int n_sets, int M, int N, int K, float alpha, co
   if (n_sets <= 0 || M <= 0 || N <= 0) return hipSuccess;
   const bool b_k = op == OP_NT;
   if (!extent_ok(M, K, lda) || !extent_ok(b_k ? N : K, b_k ? K : N, ldb) || !extent_ok(M, N, ldc)) return hipErrorInvalidValue;
+  if (eye != 0.f && M != N) return hipErrorInvalidValue;
   if (lda % 4 || ldb % 4 || ldc % 4 || (int64_t)n_sets * ceil_div(M, 64) * ceil_div(N, 64) > 0x7FFFFFFF) return hipErrorInvalidValue;
   switch (op) {
     case OP_NT:

@@ -34,6 +34,7 @@ extern "C" {
 #define MW_ERR_SIGN_MISMATCH    (-6)  /* phase-III recomputed signs differ from the phase-I masks      */
 #define MW_ERR_NOT_PLANNED      (-7)  /* entry point called on a handle planned without it             */
 #define MW_ERR_TOO_LARGE        (-8)  /* input beyond the fixed scratch of an entry point that allocates nothing */
+#define MW_ERR_NONFINITE        (-9)  /* the loss of the last gradient step was NaN or infinite         */
 
 typedef struct mw_handle mw_handle_t;   /* opaque; owned by the library */
 
@@ -122,6 +123,9 @@ typedef struct {
   int32_t  frag_overflow;       /* 1 if the last moonwalk_grad overflowed the fragment store          */
   int32_t  phase3_group_width;  /* most stretches Phase III sweeps in one launch (cfg.phase3_parallel_segments as planned); 0: one layer per launch */
   uint64_t bytes_debug;         /* cfg.debug_keep: the kept z_i and cotangents                          */
+  int32_t  nonfinite_loss;      /* 1 if the loss of the last moonwalk_grad / sgd_step / backprop_grad was NaN or
+                                   infinite (inputs, weights or activations out of range): its gradients are void */
+  int32_t  reserved;
 } mw_memstats_t;
 
 /*
@@ -200,8 +204,8 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target,
 int moonwalk_grad_layout(const mw_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
 
 /* Itemised memory and the sticky device-side conditions of the last step. out: host.
-   Synchronises the device (reads two counters back). Returns MW_ERR_FRAG_OVERFLOW or
-   MW_ERR_SIGN_MISMATCH if the last step raised one, after filling *out. */
+   Synchronises the device (reads the flags back). Returns MW_ERR_FRAG_OVERFLOW, MW_ERR_NONFINITE or
+   MW_ERR_SIGN_MISMATCH (in this order) if the last step raised one, after filling *out. */
 int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out);
 
 /* What moonwalk_debug_fetch can copy to the host (element type, count for layer i):          */

@@ -35,8 +35,8 @@ class MoonwalkError(RuntimeError):
         self.code = code
 
 
-ERR_INVALID_ARG, ERR_NOT_SUBMERSIVE, ERR_OOM, ERR_FRAG_OVERFLOW, ERR_HIP, ERR_SIGN_MISMATCH, ERR_NOT_PLANNED, ERR_TOO_LARGE = \
-    -1, -2, -3, -4, -5, -6, -7, -8
+ERR_INVALID_ARG, ERR_NOT_SUBMERSIVE, ERR_OOM, ERR_FRAG_OVERFLOW, ERR_HIP, ERR_SIGN_MISMATCH, ERR_NOT_PLANNED, ERR_TOO_LARGE, \
+    ERR_NONFINITE = -1, -2, -3, -4, -5, -6, -7, -8, -9
 
 
 class _Layer(C.Structure):
@@ -87,7 +87,8 @@ class _MemStats(C.Structure):
         "bytes_mw_scratch", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak",
         "bytes_setup_peak", "frag_used", "sign_mismatches")] + [("frag_overflow", C.c_int32),
                                                                  ("phase3_group_width", C.c_int32),
-                                                                 ("bytes_debug", C.c_uint64)]
+                                                                 ("bytes_debug", C.c_uint64),
+                                                                 ("nonfinite_loss", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None

@@ -775,7 +775,8 @@ k_loss_grad(const float* __restrict__ xL, const float* __restrict__ t, int64_t n
 // Sum of the per-workgroup partials in a fixed order (thread t takes partials t, t + 256, ...;
 // then a fixed tree), so the loss does not depend on scheduling.
 __global__ void __launch_bounds__(EW_THREADS)
-k_loss_final(const double* __restrict__ partial, int n_partial, double factor, float* __restrict__ loss) {
+k_loss_final(const double* __restrict__ partial, int n_partial, double factor, float* __restrict__ loss,
+             uint32_t* __restrict__ nonfinite) {
   __shared__ double red[EW_THREADS];
   double acc = 0.0;
   for (int i = threadIdx.x; i < n_partial; i += EW_THREADS) acc += partial[i];
@@ -785,7 +786,11 @@ k_loss_final(const double* __restrict__ partial, int n_partial, double factor, f
     if (threadIdx.x < (unsigned)s) red[threadIdx.x] += red[threadIdx.x + s];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *loss = (float)(factor * red[0]);
+  if (threadIdx.x == 0) {
+    const float v = (float)(factor * red[0]);
+    if (loss) *loss = v;
+    if (nonfinite) *nonfinite = (fabsf(v) <= 3.402823466e38f) ? 0u : 1u;  // NaN or infinity
+  }
 }
 
 // ---------------------------------------------------------------- slope from a stored activation
@@ -1226,7 +1231,7 @@ hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scal
 }
 
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
-                        double* scratch, hipStream_t stream) {
+                        double* scratch, hipStream_t stream, uint32_t* nonfinite) {
   int64_t n = rows * d;
   if (n <= 0 || rows <= 0) return hipErrorInvalidValue;
   // scale and 1/rows are folded into one fp32 factor; with a power-of-two scale this is the
@@ -1239,8 +1244,8 @@ hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, fl
   hipLaunchKernelGGL(k_loss_grad, dim3(blocks), dim3(EW_THREADS), 0, stream, xL, t, n, cot_scale, hL, scratch, vec);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (loss) {
-    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, 0.5 / (double)rows, loss);
+  if (loss || nonfinite) {
+    hipLaunchKernelGGL(k_loss_final, dim3(1), dim3(EW_THREADS), 0, stream, scratch, blocks, 0.5 / (double)rows, loss, nonfinite);
     e = hipGetLastError();
   }
   return e;

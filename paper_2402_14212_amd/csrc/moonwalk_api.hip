@@ -156,7 +156,7 @@ struct mw_handle {
   const uint32_t** count_ptrs = nullptr;  // device array [n_relu]
   FragLayer* frag_layers = nullptr;       // device array [n_relu]: mask, offsets and size of every ReLU layer
   int64_t frag_max_n = 0;                 // largest B * d_out among them
-  uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] bad pivot
+  uint32_t* status = nullptr;             // [0..1] sign mismatches (u64), [2] fragment overflow, [3] non-finite loss, [4] bad pivot
   double* loss_scratch = nullptr;
   float* refresh_work = nullptr;  // incremental refresh of P: allocated on first use
   const float** refresh_tab = nullptr;  // device table of pointers for the grouped products of that refresh:
@@ -258,9 +258,9 @@ int build_right_inverses(mw_handle* h, hipStream_t stream) {
   if (!work) return MW_ERR_OOM;
   if (h->live > h->setup_peak) h->setup_peak = h->live;
   (void)before;
-  int32_t* bad = reinterpret_cast<int32_t*>(h->status + 3);
+  int32_t* bad = reinterpret_cast<int32_t*>(h->status + 4);
   int rc = MW_OK;
-  hipError_t e = ew_fill_u32(h->status + 3, 0u, 1, stream);
+  hipError_t e = ew_fill_u32(h->status + 4, 0u, 1, stream);
   for (int i = 0; e == hipSuccess && i < L; ++i) {
     if (group[i] == 0) continue;
     const float* Ws[SETUP_GROUP];
@@ -422,9 +422,9 @@ int moonwalk_setup(mw_handle_t** out, const mw_layer_t* layers, int32_t n_layers
     return code;
   };
   mw_memstats_t& st = h->st;
-  bool ok = alloc_t(h, &h->status, 4, &st.bytes_mw_scratch);
+  bool ok = alloc_t(h, &h->status, 5, &st.bytes_mw_scratch);
   if (!ok) return fail(MW_ERR_OOM);
-  hipError_t e = ew_fill_u32(h->status, 0u, 4, stream);
+  hipError_t e = ew_fill_u32(h->status, 0u, 5, stream);
   if (e != hipSuccess) return fail(hip_fail(e, "status init"));
 
   if (h->plan & MW_PLAN_MOONWALK) {
@@ -952,7 +952,7 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
     // Phase I: forward, keep sign masks only; loss and output cotangent; Phase II; Phase III
     MW_TRY_RC(forward_range(c, 0, L, x, 0, &x_L));
     MW_TRY_RC(frag_index_range(c, 0, L));
-    MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+    MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->ha, loss_out, h->loss_scratch, s, h->status + 3));
     if (h->group_width > 0) return reverse_and_sweep(c);
     MW_TRY_RC(reverse_range(c, 0, L, h->ha, h->h0));
     return phase3_range(c, 0, L, x, h->h0);
@@ -965,7 +965,7 @@ int run_moonwalk(mw_handle* h, const float* x, const float* target, float* grads
   const int S = h->S, nseg = (L + S - 1) / S;
   MW_TRY_RC(forward_range(c, 0, L, x, (nseg - 1) * S, &x_L));
   MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(x_L, target, B, h->layers[L - 1].d_out, h->loss_scale, h->hseg[(nseg - 1) & 1], loss_out,
-                                             h->loss_scratch, s));
+                                             h->loss_scratch, s, h->status + 3));
   for (int k = nseg - 1; k >= 0; --k) {
     const int lo = k * S, hi = (lo + S < L) ? lo + S : L;
     const float* x_seg = (lo == 0) ? x : h->layers[lo - 1].xck;
@@ -1165,7 +1165,8 @@ int backprop_grad(mw_handle_t* h, const float* x, const float* target, float* gr
     xin = l.act;
   }
   float* hbuf[2] = {h->bp_ha, h->bp_hb};
-  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s));
+  MW_LAUNCH(h, s, MW_KCLASS_EW, ew_loss_grad(xin, target, B, h->layers[L - 1].d_out, h->loss_scale, hbuf[0], loss_out, h->loss_scratch, s,
+                                             h->status + 3));
   const float inv_scale = 1.0f / h->loss_scale;
   int sel = 0;
   for (int i = L - 1; i >= 0; --i) {
@@ -1200,7 +1201,7 @@ int moonwalk_grad_layout(const mw_handle_t* h, size_t* total_floats, size_t* dW_
 
 int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out) {
   if (!h || !out) return MW_ERR_INVALID_ARG;
-  uint32_t status[4] = {0, 0, 0, 0};
+  uint32_t status[4] = {0, 0, 0, 0};  // the words a gradient step writes
   uint64_t frag_total = 0;
   MW_HIP(hipDeviceSynchronize());
   MW_HIP(hipMemcpy(status, h->status, sizeof(status), hipMemcpyDeviceToHost));
@@ -1213,8 +1214,10 @@ int moonwalk_memory_stats(mw_handle_t* h, mw_memstats_t* out) {
   out->frag_used = frag_total;
   out->sign_mismatches = (uint64_t)status[0] | ((uint64_t)status[1] << 32);
   out->frag_overflow = status[2] ? 1 : 0;
+  out->nonfinite_loss = status[3] ? 1 : 0;
   out->phase3_group_width = h->group_width;
   if (out->frag_overflow) return MW_ERR_FRAG_OVERFLOW;
+  if (out->nonfinite_loss) return MW_ERR_NONFINITE;
   if (out->sign_mismatches) return MW_ERR_SIGN_MISMATCH;
   return MW_OK;
 }
@@ -1301,6 +1304,7 @@ const char* moonwalk_strerror(int code) {
     case MW_ERR_SIGN_MISMATCH: return "recomputed activation signs differ from the stored masks";
     case MW_ERR_NOT_PLANNED: return "handle was planned without this entry point";
     case MW_ERR_TOO_LARGE: return "input larger than the fixed scratch array of an entry point that allocates nothing";
+    case MW_ERR_NONFINITE: return "the loss of the last gradient step was NaN or infinite";
     default: return "unknown error code";
   }
 }

@@ -168,8 +168,9 @@ hipError_t ew_colsum_wide_static(const float* a, int64_t rows, int d, float scal
 // out[i] = scale * (sum over the slices of part[.][i], in an order fixed by slices and n) + beta * out[i]; part is [slices][n]
 hipError_t ew_reduce_slices(const float* part, int slices, int64_t n, float scale, float beta, float* out, hipStream_t stream);
 constexpr int LOSS_BLOCKS = 16384;  // most workgroups (and scratch doubles) the loss reduction uses
+// (nonfinite, may be NULL: a device word that receives 1 when the loss is NaN or infinite, else 0)
 hipError_t ew_loss_grad(const float* xL, const float* t, int64_t rows, int d, float scale, float* hL, float* loss,
-                        double* scratch, hipStream_t stream);
+                        double* scratch, hipStream_t stream, uint32_t* nonfinite = nullptr);
 hipError_t ew_copy(const float* src, float* dst, int64_t n, hipStream_t stream);
 hipError_t ew_fill_u32(uint32_t* p, uint32_t value, int64_t n, hipStream_t stream);
 inline hipError_t ew_fill_f32(float* p, float value, int64_t n, hipStream_t stream) {

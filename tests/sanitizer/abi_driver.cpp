@@ -138,6 +138,7 @@ static void dense_network(const std::vector<int>& widths, int batch, const std::
   mw_memstats_t st;
   EXPECT(moonwalk_memory_stats(h, &st) == MW_OK);
   EXPECT(st.bytes_live <= st.bytes_peak);
+  EXPECT(st.nonfinite_loss == 0 && st.reserved == 0);
   EXPECT((st.bytes_debug != 0) == (debug_keep != 0 && mw_planned));
   // every kind of fetch on every layer: size query, exact buffer, buffer one byte short
   for (int i = 0; i < L; ++i)

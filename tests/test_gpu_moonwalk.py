@@ -159,6 +159,31 @@ def test_fragment_overflow_is_reported(mw):
     net.close()
 
 
+def test_nonfinite_loss_is_reported(mw):
+    """An input (or target) out of range makes the loss NaN or infinite: both gradient paths raise the flag for that
+    step, memory_stats reports it, and the next good step lowers it again."""
+    wl = make_mlp([64, 64, 32], 8, 0.1, seed=0)
+    net = mw.MoonwalkNet.from_workload(wl)
+    for bad in (float("nan"), float("inf"), 3e38):          # 3e38: finite input, squared error beyond fp32
+        for step in (net.moonwalk_grad, net.backprop_grad):
+            x = net.x.clone()
+            t = net.t.clone()
+            if bad == 3e38:
+                t[3, 5] = bad
+            else:
+                x[3, 5] = bad
+            res = step(x, t)
+            st = net.memory_stats(check=False)
+            assert st["nonfinite_loss"] == 1 and st["status"] == mw.binding.ERR_NONFINITE, (bad, st["status"])
+            assert not np.isfinite(float(res.loss.item())) or bad == 3e38
+            with pytest.raises(mw.MoonwalkError):
+                net.memory_stats()
+            step(net.x, net.t)
+            st = net.memory_stats()
+            assert st["nonfinite_loss"] == 0 and st["status"] == 0
+    net.close()
+
+
 def test_refresh_after_weight_update(mw):
     wl, net = build(mw, "tiny")
     with torch.no_grad():

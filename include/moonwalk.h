@@ -330,6 +330,7 @@ typedef struct {
   uint64_t bytes_bp_scratch;       /* backprop: cotangent ping-pong (when planned without Moonwalk)      */
   uint64_t bytes_live, bytes_peak;
   uint64_t sign_mismatches;        /* Phase-III signs that differed from the stored masks (must be 0)    */
+  uint64_t nonfinite_loss;         /* 1 if the loss of the last gradient step was NaN or infinite         */
 } mw_conv_memstats_t;
 
 /* Same contracts as the dense entry points of the same names (setup synchronises; grad calls only
@@ -355,6 +356,7 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
 int moonwalk_conv_sgd_step(mw_conv_handle_t* h, const float* x, const float* target, float lr, float* loss_out,
                            void* hip_stream);
 int moonwalk_conv_grad_layout(const mw_conv_handle_t* h, size_t* total_floats, size_t* dW_off, size_t* db_off);
+/* Synchronises; returns MW_ERR_NONFINITE or MW_ERR_SIGN_MISMATCH if the last gradient step raised one, after filling *out. */
 int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out);
 /* what: MW_FETCH_MASK, MW_FETCH_H0 (whole or as read, see the config), MW_FETCH_P (here: T^{-1},
    float[C_out^2]), MW_FETCH_FRAG (fragmental layers: float[B N / block][k - 1][C_out]) or MW_FETCH_CHECKPOINT (the cotangent kept at the output of `layer`, in the

@@ -78,7 +78,8 @@ class _ConvConfig(C.Structure):
 class _ConvMemStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "bytes_masks", "bytes_tap_inverses", "bytes_packed_weights", "bytes_fragments", "bytes_checkpoints", "bytes_input_cotangent",
-        "bytes_scratch", "bytes_patches", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak", "sign_mismatches")]
+        "bytes_scratch", "bytes_patches", "bytes_bp_activations", "bytes_bp_scratch", "bytes_live", "bytes_peak", "sign_mismatches",
+        "nonfinite_loss")]
 
 
 class _MemStats(C.Structure):

@@ -99,7 +99,7 @@ struct mw_conv_handle {
   float *patches = nullptr, *zbuf = nullptr, *ctz = nullptr, *hsub = nullptr;
   float *dw_part = nullptr, *colsum_part = nullptr;
   float *xa = nullptr, *xb = nullptr, *ha = nullptr, *hb = nullptr, *h0 = nullptr;
-  uint32_t* status = nullptr;  // [0..1] sign mismatches (u64), [2] kernel not triangular / zero diagonal
+  uint32_t* status = nullptr;  // [0..1] sign mismatches (u64), [2] kernel not triangular / zero diagonal, [3] non-finite loss
   double* loss_scratch = nullptr;
 
   void* alloc(size_t bytes, uint64_t* item) {
@@ -578,7 +578,7 @@ int run_conv_moonwalk(mw_conv_handle* h, const float* x, const float* target, fl
   // ---------------- loss and output cotangent
   {
     const ConvLayer& last = h->layers[L - 1];
-    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s, h->status + 3));
   }
   // ---------------- Phase II: reverse, input cotangent only. ct_z of layer i lives in ctbuf[i % 2]; the
   // cotangent h itself is kept only where Phase III starts from it (h_0 and the re-seed points), and
@@ -720,7 +720,7 @@ int backprop_conv_grad(mw_conv_handle_t* h, const float* x, const float* target,
   }
   {
     const ConvLayer& last = h->layers[L - 1];
-    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s));
+    CV_HIP(ew_loss_grad(xin, target, h->B, (int)(last.n_out / h->B), h->loss_scale, h->ha, loss_out, h->loss_scratch, s, h->status + 3));
   }
   const float inv_scale = 1.0f / h->loss_scale;
   float* hbuf[2] = {h->ha, h->hb};
@@ -761,9 +761,12 @@ int moonwalk_conv_memory_stats(mw_conv_handle_t* h, mw_conv_memstats_t* out) {
   *out = h->st;
   out->bytes_live = h->live;
   out->bytes_peak = h->peak;
-  unsigned long long mm = 0;
-  CV_HIP(hipMemcpy(&mm, h->status, sizeof(mm), hipMemcpyDeviceToHost));
+  uint32_t status[4] = {0, 0, 0, 0};
+  CV_HIP(hipMemcpy(status, h->status, sizeof(status), hipMemcpyDeviceToHost));
+  const unsigned long long mm = (unsigned long long)status[0] | ((unsigned long long)status[1] << 32);
   out->sign_mismatches = mm;
+  out->nonfinite_loss = status[3] ? 1 : 0;
+  if (out->nonfinite_loss) return MW_ERR_NONFINITE;
   return mm ? MW_ERR_SIGN_MISMATCH : MW_OK;
 }
 

@@ -98,6 +98,23 @@ def test_conv_moonwalk_matches_the_oracle(mw, name):
     _parity_of_case(mw, name)
 
 
+def test_conv_nonfinite_loss_is_reported(mw):
+    """A NaN in the input: the step's loss is not finite, memory_stats says so; the next good step lowers the flag."""
+    B, side, C, depth, k, s, p, alpha, K, patch_bytes, kernels = CONV_CASES[sorted(CONV_CASES)[0]]
+    wl = make_convnet(B, side, C, depth, k=k, s=s, p=p, alpha=alpha, seed=1)
+    net = mw.ConvMoonwalkNet.from_workload(wl, reseed_interval=K, patch_bytes=patch_bytes, kernels=kernels)
+    for step in (net.moonwalk_grad, net.backprop_grad):
+        x = net.x.clone()
+        x.view(-1)[7] = float("nan")
+        step(x, net.t)
+        st = net.memory_stats(check=False)
+        assert st["nonfinite_loss"] == 1 and st["status"] == mw.binding.ERR_NONFINITE
+        step(net.x, net.t)
+        st = net.memory_stats()
+        assert st["nonfinite_loss"] == 0 and st["status"] == 0
+    net.close()
+
+
 def _parity_of_case(mw, name, **net_kw):
     B, side, C, depth, k, s, p, alpha, K, patch_bytes, kernels = CONV_CASES[name]
     wl = make_convnet(B, side, C, depth, k=k, s=s, p=p, alpha=alpha, seed=1, name=name)
